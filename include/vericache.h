@@ -1,0 +1,184 @@
+/*
+ * vericache.h - C ABI of the MI355X (gfx950) draft / verify / accept / swap-in hot path of
+ * VeriCache (arXiv 2605.17613): draft tokens against a compressed KV cache, verify them against
+ * the full KV cache, accept greedily.
+ *
+ * Conventions that hold for every call
+ *   - "device" pointers are HIP device memory of the GPU the context was created on, "host"
+ *     pointers are ordinary process memory.  Every data pointer is borrowed: the library neither
+ *     frees nor keeps it beyond the call (vc_swap_in keeps src/dst until the tickets complete).
+ *   - Scratch memory is a caller-provided device workspace, sized by the *_workspace_bytes query.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls enqueue work
+ *     and return; they never synchronise the device and never allocate device memory.
+ *   - Errors are return codes; vc_last_error() gives a message for the last failing call on the
+ *     calling thread.  Arguments are validated on the host in O(1) (null pointers, 16-byte
+ *     alignment, head_dim == 128, group geometry); data-dependent contents (index ranges,
+ *     sortedness) are the caller's contract and are not read by the host.
+ *   - head_dim is 128.  n_q_heads must be a multiple of n_kv_heads with a ratio of at most 16;
+ *     query head h uses KV head h / (n_q_heads / n_kv_heads).
+ *   - bf16 tensors are raw 16-bit patterns.  A "bf16 pool" is token-major: row (token t, KV
+ *     head h) is 128 consecutive bf16 at element offset (t * n_kv_heads + h) * 128.
+ *   - Ragged batches use prefix-sum arrays cu_x of n_seqs + 1 int32 on the DEVICE; the matching
+ *     max_x is the largest per-sequence count, given on the host so grids can be sized without
+ *     a device round trip.  max_x may over-estimate; it must not under-estimate.
+ */
+#ifndef VERICACHE_H
+#define VERICACHE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  VC_OK = 0,
+  VC_ERR_INVALID_ARG = 1,  /* null / misaligned pointer, negative size, bad geometry          */
+  VC_ERR_UNSUPPORTED = 2,  /* head_dim != 128, GQA ratio > 16, window > 64, bits not 16/4/2   */
+  VC_ERR_WORKSPACE = 3,    /* workspace missing or smaller than the query says                */
+  VC_ERR_HIP = 4,          /* a HIP runtime call failed (message holds hipGetErrorString)     */
+  VC_ERR_NOT_READY = 5     /* vc_swap_query: the ticket's copy has not finished yet           */
+} vc_status;
+
+typedef struct vc_ctx vc_ctx; /* opaque: owns one copy stream and the chunk events, nothing else */
+
+/* Create / destroy a context bound to HIP device `device`. */
+vc_status vc_create(int device, vc_ctx** out);
+vc_status vc_destroy(vc_ctx* ctx);
+/* Message of the last failing call on this thread (static storage, never freed by the caller). */
+const char* vc_last_error(void);
+/* Library version, "major.minor". */
+const char* vc_version(void);
+
+/* ------------------------------------------------------------------------------------------
+ * Compressed KV of one attention layer for a ragged batch (paper section 6: a compressed cache
+ * is "which positions are dropped" plus "bits per element").  The drafted token of sequence b
+ * attends to the union of three sources, each of which may be absent or empty:
+ *
+ *  (1) bf16 rows of a pool, either all rows of the sequence or the rows a kept-index list names
+ *      (token dropping, bit scheme 16; every KV head of a sequence keeps the same count).
+ *        pool_k, pool_v  device bf16 pools; sequence b owns rows cu_ctx[b] .. cu_ctx[b+1]-1
+ *        keep_idx        device int32 or NULL.  List (b, h) is keep_idx[(cu_keep[b]*n_kv_heads
+ *                        + h*nk) + i], i < nk = cu_keep[b+1]-cu_keep[b]; entries are positions
+ *                        relative to the sequence start, in [0, length).  NULL = every row.
+ *        max_keep        host: max over b of nk (of the length when keep_idx is NULL)
+ *
+ *  (2) group-quantised block records (bit scheme 4 or 2; keys quantised per channel over the TB
+ *      tokens of a block, values per token over groups of TB channels; TB = 32 for 4 bit, 64 for
+ *      2 bit; x = scale * code + zero with fp16 scale and zero).
+ *        blocks          device, 5120-byte records.  (b, h) owns records cu_blk[b]*n_kv_heads +
+ *                        h*nb + i, i < nb = cu_blk[b+1]-cu_blk[b]; record i holds tokens
+ *                        i*TB .. i*TB+TB-1 of whatever token list was compressed.
+ *      Record layout (all multi-byte fields little endian):
+ *        bytes    0..2047  key codes, token-major: (token t, channel d) is the `bits`-wide field
+ *                          at bit  bits*(d mod (8/bits))  of byte  t*(16*bits) + d*bits/8
+ *        bytes 2048..4095  value codes, 128 slots of 16 bytes; slot 64*c + 16*j + n (c<2, j<4,
+ *                          n<16) holds 32-bit words q<4; word q is channel d = 64*c + 16*q + n
+ *                          and carries tokens (32/bits)*j + i in the field at bit bits*i
+ *        bytes 4096..4607  key scale[128] then key zero[128] (fp16, per channel)
+ *        bytes 4608..5119  value scale[g][t] then value zero[g][t] (fp16; g = d / TB < 128/TB,
+ *                          t < TB), 128 + 128 values
+ *
+ *  (3) a bf16 tail of recent tokens (tokens drafted in this horizon, and the remainder of a
+ *      context that does not fill a whole block): pools tail_k, tail_v, rows cu_tail[b] ..
+ *      cu_tail[b+1]-1.
+ * ------------------------------------------------------------------------------------------ */
+typedef struct {
+  int32_t n_seqs, n_q_heads, n_kv_heads, head_dim;
+  int32_t bits;            /* bit scheme of `blocks`: 4 or 2 (ignored when blocks is NULL) */
+  int32_t max_keep, max_blk, max_tail;
+  const void* pool_k;      /* (1) */
+  const void* pool_v;
+  const int32_t* cu_ctx;
+  const int32_t* keep_idx;
+  const int32_t* cu_keep;  /* required when keep_idx is given */
+  const void* blocks;      /* (2) */
+  const int32_t* cu_blk;
+  const void* tail_k;      /* (3) */
+  const void* tail_v;
+  const int32_t* cu_tail;
+} vc_comp_kv;
+
+/* Draft attention (paper section 4.1 step 1; section 4.2.1: bounded by HBM bandwidth).
+ * For every sequence b and query head h:  s_j = softmax_scale * <q, K_j>, p = softmax(s),
+ * out = sum_j p_j V_j over the keys described above, accumulated in fp32.
+ *   q    device bf16 [n_seqs, n_q_heads, 128]
+ *   out  device bf16 [n_seqs, n_q_heads, 128]
+ *   lse  device fp32 [n_seqs, n_q_heads] or NULL: natural-log sum of exp(s_j)
+ * A sequence with no keys at all gets out = 0 and lse = -inf. */
+vc_status vc_draft_workspace_bytes(const vc_comp_kv* kv, size_t* bytes);
+vc_status vc_draft_attn(vc_ctx* ctx, const vc_comp_kv* kv, const void* q, float softmax_scale,
+                        void* out, float* lse, void* workspace, size_t workspace_bytes,
+                        void* stream);
+
+/* Full KV of one layer, resident on the device (the destination of vc_swap_in). */
+typedef struct {
+  int32_t n_seqs, n_q_heads, n_kv_heads, head_dim;
+  int32_t max_ctx, max_win;
+  const void* k;           /* device bf16 pools; sequence b owns rows cu_ctx[b] .. cu_ctx[b+1]-1 */
+  const void* v;
+  const int32_t* cu_ctx;
+} vc_full_kv;
+
+/* Verify attention (paper section 4.1 step 2).  Sequence b brings w_b = cu_win[b+1]-cu_win[b]
+ * drafted positions (1 <= w_b <= 64 or 0).  Window row i of head h attends to the sequence's
+ * full KV and to window rows 0..i (its own position included):
+ *   q_win         device bf16 [sum w, n_q_heads, 128]
+ *   k_win, v_win  device bf16 pools [sum w, n_kv_heads, 128]
+ *   out           device bf16 [sum w, n_q_heads, 128];  lse device fp32 [sum w, n_q_heads] or NULL
+ * bf16 MFMA, fp32 accumulation. */
+vc_status vc_verify_workspace_bytes(const vc_full_kv* kv, int32_t total_win, size_t* bytes);
+vc_status vc_verify_attn(vc_ctx* ctx, const vc_full_kv* kv, const void* q_win, const void* k_win,
+                         const void* v_win, const int32_t* cu_win, int32_t total_win,
+                         float softmax_scale, void* out, float* lse, void* workspace,
+                         size_t workspace_bytes, void* stream);
+
+/* Greedy acceptance (paper section 4.1 step 3).
+ *   logits      device fp32 [total_rows, vocab]; sequence b owns rows cu_rows[b]..cu_rows[b+1]-1:
+ *               w_b rows (row j = full-KV prediction for drafted position j), or w_b + 1 when the
+ *               bonus row is supplied.  Values are finite or -inf.
+ *   draft_ids   device int32 [sum w], sequence b owns cu_win[b]..cu_win[b+1]-1
+ *   argmax_ids  device int32 [total_rows] (required, written): arg-max of each row, the lowest
+ *               index wins a tie
+ *   accept_len  device int32 [n_seqs]: first j with draft_ids[j] != argmax(row j), else w_b
+ *   next_token  device int32 [n_seqs]: argmax(row accept_len) - the correction, or the bonus
+ *               token when everything matched and the bonus row exists; -1 if that row is absent */
+vc_status vc_accept_len(vc_ctx* ctx, const float* logits, int32_t vocab, const int32_t* cu_rows,
+                        int32_t total_rows, const int32_t* draft_ids, const int32_t* cu_win,
+                        int32_t n_seqs, int32_t* accept_len, int32_t* next_token,
+                        int32_t* argmax_ids, void* stream);
+
+/* Full-KV reload (paper section 4.2.1 and section 5.2 step (i): the full KV lives in CPU memory
+ * and is reloaded asynchronously, overlapped with draft forward passes).
+ * One hipMemcpyAsync and one event per chunk, on the context's own copy stream.
+ *   host_src  pinned host memory (hipHostMalloc); pageable memory is rejected
+ *   dev_dst   device memory
+ *   chunks    host array of n_chunks {src_off, dst_off, bytes} (byte offsets from the bases)
+ *   first_ticket  receives the ticket of chunks[0]; chunk i has ticket first_ticket + i.
+ * Tickets complete in issue order.  At most 65536 tickets may be outstanding. */
+typedef struct { size_t src_off, dst_off, bytes; } vc_chunk;
+vc_status vc_swap_in(vc_ctx* ctx, const void* host_src, void* dev_dst, const vc_chunk* chunks,
+                     int32_t n_chunks, int64_t* first_ticket);
+/* Make `stream` wait (on the device, the host does not block) until `ticket` has landed. */
+vc_status vc_swap_wait(vc_ctx* ctx, int64_t ticket, void* stream);
+/* VC_OK once `ticket` has landed, VC_ERR_NOT_READY before. */
+vc_status vc_swap_query(vc_ctx* ctx, int64_t ticket);
+/* Block the host until every issued chunk has landed. */
+vc_status vc_swap_sync(vc_ctx* ctx);
+
+/* Kept-index lists from the compressor's dropped-index lists (section 6,
+ * CompressedKV.dropped_indices): keep = [0, len_b) minus dropped, ascending.
+ *   dropped  device int32: list (b, h) is dropped[(cu_drop[b]*n_kv_heads + h*nd) + i], ascending,
+ *            i < nd = cu_drop[b+1]-cu_drop[b]
+ *   cu_ctx   device int32 [n_seqs+1]: len_b = cu_ctx[b+1]-cu_ctx[b];  max_ctx host
+ *   keep_idx device int32, written in the layout vc_comp_kv.keep_idx describes
+ *   cu_keep  device int32 [n_seqs+1], written: prefix sums of len_b - nd */
+vc_status vc_keep_from_dropped(vc_ctx* ctx, const int32_t* dropped, const int32_t* cu_drop,
+                               const int32_t* cu_ctx, int32_t n_seqs, int32_t n_kv_heads,
+                               int32_t max_ctx, int32_t* keep_idx, int32_t* cu_keep, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* VERICACHE_H */

@@ -1,0 +1,326 @@
+"""Plain fp64 CPU oracle of the VeriCache hot path (TEST INFRASTRUCTURE, not a product path).
+
+What it computes, step by step, in IEEE double precision (paper section 4.1, core loop):
+
+  draft   (step 1) - one query token attends, with exact softmax attention, to whatever the
+                     compressed cache holds for its sequence: retained bf16 rows picked by a
+                     kept-index list (compressor interface, section 6: positions dropped per
+                     (layer, head), bit scheme 16), group-quantised int4 / int2 block records
+                     (bit scheme 4 / 2, keys per channel, values per token), and a bf16 tail of
+                     recent tokens.
+  verify  (step 2) - every drafted position i attends to the full KV plus drafted positions 0..i.
+  accept  (step 3) - greedy: first position whose draft id differs from the arg-max of the
+                     verify logits; the correction (or bonus) token follows.
+  keep    (section 6, CompressedKV.dropped_indices) - complement of the dropped positions.
+
+Every input is taken in the byte layout that the C header of the library describes in prose
+(bf16 / fp16 bit patterns, packed codes); the unpacking below is written from that prose and
+shares no code with the GPU library.  bf16, fp16 and the small integer codes convert to double
+exactly, so the only rounding in here is double-precision arithmetic itself.
+
+Pins (tests, "-m 'not gpu'"): softmax rows sum to one and are shift invariant; identical keys
+give the mean of the values; a dominant key returns its value row; brute force with Python loops
+on tiny shapes; split/merge invariance; zero dropping equals full attention; lossless quantisation
+grids equal bf16 attention; hand-packed records (written element by element from the layout
+prose) unpack to the planted codes; causal rows do not see later rows; planted arg-max logits,
+planted ties, brute-force set difference.  No function here is "parity unpinned".
+"""
+from __future__ import annotations
+
+import numpy as np
+
+HEAD_DIM = 128
+RECORD_BYTES = 5120
+_K_CODES, _V_CODES, _K_META, _V_META = 0, 2048, 4096, 4608
+
+
+# --------------------------------------------------------------------------------------------
+# exact widening of 16-bit floating point bit patterns
+# --------------------------------------------------------------------------------------------
+def bf16_to_f64(bits: np.ndarray) -> np.ndarray:
+    """bf16 bit patterns (uint16) -> float64, exact (bf16 is the top half of an IEEE float32)."""
+    b = np.ascontiguousarray(bits, dtype=np.uint16)
+    return (b.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
+
+
+def f16_to_f64(bits: np.ndarray) -> np.ndarray:
+    """IEEE fp16 bit patterns (uint16) -> float64, exact."""
+    return np.ascontiguousarray(bits, dtype=np.uint16).view(np.float16).astype(np.float64)
+
+
+def tokens_per_block(bits: int) -> int:
+    """Quantisation group: 32 tokens / 32 channels for 4 bit, 64 / 64 for 2 bit."""
+    if bits == 4:
+        return 32
+    if bits == 2:
+        return 64
+    raise ValueError("bits must be 4 or 2")
+
+
+# --------------------------------------------------------------------------------------------
+# block records -> dequantised K, V   (KIVI-style axes: keys per channel, values per token)
+# --------------------------------------------------------------------------------------------
+def unpack_records(records: np.ndarray, bits: int):
+    """Dequantise block records.
+
+    records: uint8 [n_heads, n_blocks, 5120].  One record holds TB = 32 (int4) or 64 (int2)
+    consecutive tokens of one KV head:
+      bytes    0..2047  key codes, token-major: token t, channel d lives in byte
+                        t*(128*bits/8) + d*bits/8 at bit offset bits*(d mod 8/bits)
+      bytes 2048..4095  value codes in 128 slots of 16 bytes; slot L = 64*c + 16*j + n
+                        (c<2, j<4, n<16) holds four little-endian 32-bit words q<4; word q
+                        belongs to channel d = 64*c + 16*q + n and holds tokens
+                        (32/bits)*j + i at bit offset bits*i
+      bytes 4096..4607  key scale[128] then key zero[128], fp16, one pair per channel
+      bytes 4608..5119  value scale[g][t] then value zero[g][t], fp16, g = channel group
+                        (d // TB), t = token in block
+    x_hat = scale * code + zero, evaluated in double (no intermediate rounding).
+
+    Returns (K_hat, V_hat) float64 [n_heads, n_blocks*TB, 128].
+    """
+    tb = tokens_per_block(bits)
+    rec = np.ascontiguousarray(records, dtype=np.uint8)
+    if rec.ndim != 3 or rec.shape[2] != RECORD_BYTES:
+        raise ValueError("records must be [heads, blocks, 5120] uint8")
+    nh, nb, _ = rec.shape
+    per_byte = 8 // bits
+    cmask = (1 << bits) - 1
+
+    kc = rec[:, :, _K_CODES:_K_CODES + 2048]
+    k_code = np.empty((nh, nb, tb, HEAD_DIM), dtype=np.float64)
+    row_bytes = HEAD_DIM * bits // 8
+    for t in range(tb):
+        for d in range(HEAD_DIM):
+            byte = kc[:, :, t * row_bytes + d // per_byte]
+            k_code[:, :, t, d] = (byte >> np.uint8(bits * (d % per_byte))) & np.uint8(cmask)
+
+    vwords = rec[:, :, _V_CODES:_V_CODES + 2048].copy().view("<u4")  # [nh, nb, 512]
+    v_code = np.empty((nh, nb, tb, HEAD_DIM), dtype=np.float64)
+    per_word = 32 // bits
+    for c in range(2):
+        for j in range(4):
+            for n in range(16):
+                slot = 64 * c + 16 * j + n
+                for q in range(4):
+                    d = 64 * c + 16 * q + n
+                    word = vwords[:, :, 4 * slot + q]
+                    for i in range(per_word):
+                        t = per_word * j + i
+                        v_code[:, :, t, d] = (word >> np.uint32(bits * i)) & np.uint32(cmask)
+
+    kmeta = rec[:, :, _K_META:_K_META + 512].copy().view("<u2")       # [nh, nb, 256]
+    k_scale = f16_to_f64(kmeta[:, :, 0:128])
+    k_zero = f16_to_f64(kmeta[:, :, 128:256])
+    k_hat = k_scale[:, :, None, :] * k_code + k_zero[:, :, None, :]
+
+    ngrp = HEAD_DIM // tb
+    vmeta = rec[:, :, _V_META:_V_META + 512].copy().view("<u2")
+    v_scale = f16_to_f64(vmeta[:, :, 0:128]).reshape(nh, nb, ngrp, tb)
+    v_zero = f16_to_f64(vmeta[:, :, 128:256]).reshape(nh, nb, ngrp, tb)
+    v_hat = np.empty_like(v_code)
+    for d in range(HEAD_DIM):
+        g = d // tb
+        v_hat[:, :, :, d] = v_scale[:, :, g, :] * v_code[:, :, :, d] + v_zero[:, :, g, :]
+
+    return k_hat.reshape(nh, nb * tb, HEAD_DIM), v_hat.reshape(nh, nb * tb, HEAD_DIM)
+
+
+# --------------------------------------------------------------------------------------------
+# the attention definition
+# --------------------------------------------------------------------------------------------
+def attend(q: np.ndarray, k: np.ndarray, v: np.ndarray, scale: float):
+    """Softmax attention of one query vector over n keys, textbook definition in double.
+
+    q [128], k [n,128], v [n,128] float64.  s_j = scale * <q, k_j>;  p = softmax(s);
+    o = sum_j p_j v_j;  lse = log sum_j exp(s_j).  Returns (o, lse, p).
+    An empty key set gives o = 0, lse = -inf.
+    """
+    q = np.asarray(q, dtype=np.float64)
+    k = np.asarray(k, dtype=np.float64).reshape(-1, q.shape[0])
+    v = np.asarray(v, dtype=np.float64).reshape(-1, q.shape[0])
+    if k.shape[0] == 0:
+        return np.zeros_like(q), -np.inf, np.zeros(0)
+    s = float(scale) * (k @ q)
+    m = s.max()
+    e = np.exp(s - m)
+    l = e.sum()
+    p = e / l
+    return p @ v, m + np.log(l), p
+
+
+def _rows(a, lo, hi, head):
+    """bf16 pool [T, Hkv, 128] (uint16 bits) -> float64 rows lo..hi of one head."""
+    return bf16_to_f64(np.asarray(a)[lo:hi, head, :])
+
+
+def draft_keys(b: int, kvh: int, *, n_kv_heads: int,
+               pool_k=None, pool_v=None, cu_ctx=None, keep_idx=None, cu_keep=None,
+               blocks=None, cu_blk=None, bits: int = 16,
+               tail_k=None, tail_v=None, cu_tail=None):
+    """Key/value rows sequence b's drafted token sees on KV head kvh (paper section 4.1 step 1).
+
+    Three sources, each optional, concatenated (order does not matter to the result):
+      bf16 pool  [T, Hkv, 128] bf16 bits; sequence b owns rows cu_ctx[b]..cu_ctx[b+1]; with
+                 keep_idx the retained rows are cu_ctx[b] + keep_idx[(cu_keep[b]*Hkv +
+                 kvh*nk) + i], i < nk = cu_keep[b+1]-cu_keep[b] (same count for every head,
+                 section 6 scope (i)); without keep_idx every row of the sequence
+      blocks     uint8 [*, 5120] block records; sequence b, head kvh owns records
+                 cu_blk[b]*Hkv + kvh*nb + i, i < nb = cu_blk[b+1]-cu_blk[b]
+      tail       bf16 [Ttail, Hkv, 128] recent tokens, rows cu_tail[b]..cu_tail[b+1]
+    """
+    ks, vs = [], []
+    if pool_k is not None:
+        base = int(cu_ctx[b])
+        if keep_idx is not None:
+            nk = int(cu_keep[b + 1]) - int(cu_keep[b])
+            start = int(cu_keep[b]) * n_kv_heads + kvh * nk
+            idx = base + np.asarray(keep_idx[start:start + nk], dtype=np.int64)
+        else:
+            idx = np.arange(base, int(cu_ctx[b + 1]), dtype=np.int64)
+        ks.append(bf16_to_f64(np.asarray(pool_k)[idx, kvh, :]))
+        vs.append(bf16_to_f64(np.asarray(pool_v)[idx, kvh, :]))
+    if blocks is not None:
+        nb = int(cu_blk[b + 1]) - int(cu_blk[b])
+        start = int(cu_blk[b]) * n_kv_heads + kvh * nb
+        rec = np.asarray(blocks).reshape(-1, RECORD_BYTES)[start:start + nb]
+        if nb > 0:
+            kh, vh = unpack_records(rec[None], bits)
+            ks.append(kh[0])
+            vs.append(vh[0])
+    if tail_k is not None:
+        lo, hi = int(cu_tail[b]), int(cu_tail[b + 1])
+        ks.append(_rows(tail_k, lo, hi, kvh))
+        vs.append(_rows(tail_v, lo, hi, kvh))
+    if not ks:
+        return np.zeros((0, HEAD_DIM)), np.zeros((0, HEAD_DIM))
+    return np.concatenate(ks, axis=0), np.concatenate(vs, axis=0)
+
+
+def draft_attn_one(q_bits, b: int, h: int, scale: float, *, n_q_heads: int, n_kv_heads: int, **kv):
+    """Draft attention output (o [128], lse) of sequence b, query head h (GQA: KV head h // g)."""
+    g = n_q_heads // n_kv_heads
+    k, v = draft_keys(b, h // g, n_kv_heads=n_kv_heads, **kv)
+    q = bf16_to_f64(np.asarray(q_bits)[b, h, :])
+    o, lse, _ = attend(q, k, v, scale)
+    return o, lse
+
+
+def draft_attn(q_bits, scale: float, *, n_q_heads: int, n_kv_heads: int, **kv):
+    """All sequences and heads: q bf16 bits [B, Hq, 128] -> (out [B,Hq,128], lse [B,Hq]) float64."""
+    q_bits = np.asarray(q_bits)
+    nseq = q_bits.shape[0]
+    out = np.zeros((nseq, n_q_heads, HEAD_DIM))
+    lse = np.zeros((nseq, n_q_heads))
+    g = n_q_heads // n_kv_heads
+    for b in range(nseq):
+        for kvh in range(n_kv_heads):
+            k, v = draft_keys(b, kvh, n_kv_heads=n_kv_heads, **kv)
+            for h in range(kvh * g, (kvh + 1) * g):
+                o, s, _ = attend(bf16_to_f64(q_bits[b, h, :]), k, v, scale)
+                out[b, h] = o
+                lse[b, h] = s
+    return out, lse
+
+
+# --------------------------------------------------------------------------------------------
+# verify: causal window over the full KV  (paper section 4.1 step 2)
+# --------------------------------------------------------------------------------------------
+def verify_attn_one(q_win, k_full, v_full, k_win, v_win, cu_ctx, cu_win,
+                    b: int, i: int, h: int, scale: float, *, n_q_heads: int, n_kv_heads: int):
+    """Window row i of sequence b, query head h: keys are the sequence's full-KV rows followed by
+    window rows 0..i (its own position included).  All arrays are bf16 bit patterns:
+    q_win [W, Hq, 128], k_full/v_full [T, Hkv, 128], k_win/v_win [W, Hkv, 128]."""
+    g = n_q_heads // n_kv_heads
+    kvh = h // g
+    lo, hi = int(cu_ctx[b]), int(cu_ctx[b + 1])
+    w0 = int(cu_win[b])
+    if not 0 <= i < int(cu_win[b + 1]) - w0:
+        raise IndexError("window row out of range")
+    k = np.concatenate([_rows(k_full, lo, hi, kvh), _rows(k_win, w0, w0 + i + 1, kvh)], axis=0)
+    v = np.concatenate([_rows(v_full, lo, hi, kvh), _rows(v_win, w0, w0 + i + 1, kvh)], axis=0)
+    q = bf16_to_f64(np.asarray(q_win)[w0 + i, h, :])
+    o, lse, _ = attend(q, k, v, scale)
+    return o, lse
+
+
+def verify_attn(q_win, k_full, v_full, k_win, v_win, cu_ctx, cu_win, scale: float,
+                *, n_q_heads: int, n_kv_heads: int):
+    """All window rows: returns (out [W, Hq, 128], lse [W, Hq]) float64."""
+    q_win = np.asarray(q_win)
+    nseq = len(cu_win) - 1
+    out = np.zeros((q_win.shape[0], n_q_heads, HEAD_DIM))
+    lse = np.zeros((q_win.shape[0], n_q_heads))
+    for b in range(nseq):
+        for i in range(int(cu_win[b + 1]) - int(cu_win[b])):
+            for h in range(n_q_heads):
+                o, s = verify_attn_one(q_win, k_full, v_full, k_win, v_win, cu_ctx, cu_win,
+                                       b, i, h, scale, n_q_heads=n_q_heads, n_kv_heads=n_kv_heads)
+                out[int(cu_win[b]) + i, h] = o
+                lse[int(cu_win[b]) + i, h] = s
+    return out, lse
+
+
+# --------------------------------------------------------------------------------------------
+# accept: greedy first mismatch  (paper section 4.1 step 3)
+# --------------------------------------------------------------------------------------------
+def argmax_row(row: np.ndarray) -> int:
+    """Index of the largest logit; the lowest index wins a tie.  Logits are finite or -inf."""
+    row = np.asarray(row)
+    best = row.max()
+    return int(np.flatnonzero(row == best)[0])
+
+
+def accept(logits, cu_rows, draft_ids, cu_win):
+    """Greedy acceptance.
+
+    logits fp32 [R, V]; sequence b owns logits rows cu_rows[b]..cu_rows[b+1] (w_b rows, or
+    w_b + 1 when the bonus row is supplied) and draft ids cu_win[b]..cu_win[b+1] (w_b ids).
+    Row j is the full-KV prediction for drafted position j.
+      a_b    = first j < w_b with draft[j] != argmax(row j), else w_b
+      next_b = argmax(row a_b) if that row exists, else -1
+    Returns (accept_len [B] int32, next_token [B] int32, argmax_ids [R] int32).
+    """
+    logits = np.asarray(logits, dtype=np.float32)
+    nseq = len(cu_rows) - 1
+    amax = np.array([argmax_row(logits[r]) for r in range(logits.shape[0])], dtype=np.int32)
+    acc = np.zeros(nseq, dtype=np.int32)
+    nxt = np.zeros(nseq, dtype=np.int32)
+    for b in range(nseq):
+        r0, r1 = int(cu_rows[b]), int(cu_rows[b + 1])
+        w0, w1 = int(cu_win[b]), int(cu_win[b + 1])
+        w = w1 - w0
+        a = w
+        for j in range(w):
+            if int(draft_ids[w0 + j]) != int(amax[r0 + j]):
+                a = j
+                break
+        acc[b] = a
+        nxt[b] = amax[r0 + a] if r0 + a < r1 else -1
+    return acc, nxt, amax
+
+
+# --------------------------------------------------------------------------------------------
+# kept-index lists from dropped-index lists  (section 6, CompressedKV.dropped_indices)
+# --------------------------------------------------------------------------------------------
+def keep_from_dropped(dropped, cu_drop, ctx_len, n_kv_heads: int):
+    """Complement of the dropped positions, ascending.
+
+    dropped int32: list (b, h) is dropped[(cu_drop[b]*Hkv + h*nd) + i], i < nd = cu_drop[b+1] -
+    cu_drop[b], positions in [0, ctx_len[b]).  The kept lists use the same scheme with
+    nk = ctx_len[b] - nd and cu_keep[b] = sum_{b' < b} nk.  Returns (keep_idx, cu_keep) int32.
+    """
+    dropped = np.asarray(dropped, dtype=np.int64)
+    nseq = len(ctx_len)
+    cu_keep = np.zeros(nseq + 1, dtype=np.int32)
+    pieces = []
+    for b in range(nseq):
+        nd = int(cu_drop[b + 1]) - int(cu_drop[b])
+        n = int(ctx_len[b])
+        cu_keep[b + 1] = cu_keep[b] + (n - nd)
+        for h in range(n_kv_heads):
+            start = int(cu_drop[b]) * n_kv_heads + h * nd
+            gone = np.zeros(n, dtype=bool)
+            gone[dropped[start:start + nd]] = True
+            pieces.append(np.flatnonzero(~gone).astype(np.int32))
+    keep = np.concatenate(pieces) if pieces else np.zeros(0, dtype=np.int32)
+    return keep, cu_keep

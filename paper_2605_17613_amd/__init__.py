@@ -1,0 +1,10 @@
+"""MI355X-native hot path of VeriCache (draft / verify / accept / swap-in) - Python binding.
+
+The compute lives in the HIP library built from csrc/; this package only marshals arguments.
+"""
+from .binding import (  # noqa: F401
+    VcError, Context, load, library_path,
+    vc_draft_attn, vc_draft_workspace_bytes, vc_verify_attn, vc_verify_workspace_bytes,
+    vc_accept_len, vc_swap_in, vc_swap_wait, vc_swap_query, vc_swap_sync, vc_keep_from_dropped,
+    vc_version,
+)

@@ -1,0 +1,249 @@
+"""ctypes binding over libvericache.so: argument marshalling only.
+
+Every function takes torch tensors (device memory and streams are torch's), checks dtype / device
+/ contiguity, and passes raw pointers and sizes through the C ABI declared in
+include/vericache.h.  There is no fallback: if the library is not built the first call raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB = None
+
+VC_OK, VC_ERR_INVALID_ARG, VC_ERR_UNSUPPORTED, VC_ERR_WORKSPACE, VC_ERR_HIP, VC_ERR_NOT_READY = range(6)
+
+
+class VcError(RuntimeError):
+    def __init__(self, status: int, msg: str):
+        super().__init__(f"vericache status {status}: {msg}")
+        self.status = status
+
+
+class vc_comp_kv(C.Structure):
+    _fields_ = [("n_seqs", C.c_int32), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32),
+                ("head_dim", C.c_int32), ("bits", C.c_int32), ("max_keep", C.c_int32),
+                ("max_blk", C.c_int32), ("max_tail", C.c_int32),
+                ("pool_k", C.c_void_p), ("pool_v", C.c_void_p), ("cu_ctx", C.c_void_p),
+                ("keep_idx", C.c_void_p), ("cu_keep", C.c_void_p), ("blocks", C.c_void_p),
+                ("cu_blk", C.c_void_p), ("tail_k", C.c_void_p), ("tail_v", C.c_void_p),
+                ("cu_tail", C.c_void_p)]
+
+
+class vc_full_kv(C.Structure):
+    _fields_ = [("n_seqs", C.c_int32), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32),
+                ("head_dim", C.c_int32), ("max_ctx", C.c_int32), ("max_win", C.c_int32),
+                ("k", C.c_void_p), ("v", C.c_void_p), ("cu_ctx", C.c_void_p)]
+
+
+class vc_chunk(C.Structure):
+    _fields_ = [("src_off", C.c_size_t), ("dst_off", C.c_size_t), ("bytes", C.c_size_t)]
+
+
+EXPORTS = ["vc_create", "vc_destroy", "vc_last_error", "vc_version",
+           "vc_draft_workspace_bytes", "vc_draft_attn", "vc_verify_workspace_bytes", "vc_verify_attn",
+           "vc_accept_len", "vc_swap_in", "vc_swap_wait", "vc_swap_query", "vc_swap_sync",
+           "vc_keep_from_dropped"]
+
+
+def library_path() -> str:
+    return os.path.join(_HERE, "libvericache.so")
+
+
+def load():
+    """Load the built library (once).  Raises if it is missing: there is no other code path."""
+    global _LIB
+    if _LIB is not None:
+        return _LIB
+    path = library_path()
+    if not os.path.exists(path):
+        raise ImportError(f"{path} is not built; run `python -c 'import __graft_entry__ as g; g.build()'`")
+    lib = C.CDLL(path)
+    lib.vc_last_error.restype = C.c_char_p
+    lib.vc_version.restype = C.c_char_p
+    lib.vc_create.argtypes = [C.c_int, C.POINTER(C.c_void_p)]
+    lib.vc_destroy.argtypes = [C.c_void_p]
+    lib.vc_draft_workspace_bytes.argtypes = [C.POINTER(vc_comp_kv), C.POINTER(C.c_size_t)]
+    lib.vc_draft_attn.argtypes = [C.c_void_p, C.POINTER(vc_comp_kv), C.c_void_p, C.c_float, C.c_void_p,
+                                  C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.vc_verify_workspace_bytes.argtypes = [C.POINTER(vc_full_kv), C.c_int32, C.POINTER(C.c_size_t)]
+    lib.vc_verify_attn.argtypes = [C.c_void_p, C.POINTER(vc_full_kv), C.c_void_p, C.c_void_p, C.c_void_p,
+                                   C.c_void_p, C.c_int32, C.c_float, C.c_void_p, C.c_void_p, C.c_void_p,
+                                   C.c_size_t, C.c_void_p]
+    lib.vc_accept_len.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p,
+                                  C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+    lib.vc_swap_in.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(vc_chunk), C.c_int32,
+                               C.POINTER(C.c_int64)]
+    lib.vc_swap_wait.argtypes = [C.c_void_p, C.c_int64, C.c_void_p]
+    lib.vc_swap_query.argtypes = [C.c_void_p, C.c_int64]
+    lib.vc_swap_sync.argtypes = [C.c_void_p]
+    lib.vc_keep_from_dropped.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32,
+                                         C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
+    _LIB = lib
+    return lib
+
+
+def _check(status: int):
+    if status != VC_OK:
+        raise VcError(status, load().vc_last_error().decode())
+
+
+def _ptr(t, dtype=None, name="tensor"):
+    if t is None:
+        return None
+    if not isinstance(t, torch.Tensor):
+        raise TypeError(f"{name}: expected a torch tensor")
+    if dtype is not None and t.dtype != dtype:
+        raise TypeError(f"{name}: expected {dtype}, got {t.dtype}")
+    if not t.is_contiguous():
+        raise ValueError(f"{name}: must be contiguous")
+    return C.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return C.c_void_p(stream.cuda_stream)
+
+
+def vc_version() -> str:
+    return load().vc_version().decode()
+
+
+class Context:
+    """vc_ctx: owns the copy stream and chunk events of one device."""
+
+    def __init__(self, device: int = 0):
+        self._h = C.c_void_p()
+        _check(load().vc_create(int(device), C.byref(self._h)))
+        self.device = int(device)
+
+    def close(self):
+        if self._h:
+            load().vc_destroy(self._h)
+            self._h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    @property
+    def handle(self):
+        return self._h
+
+
+def _comp_desc(n_q_heads, n_kv_heads, n_seqs, *, pool_k=None, pool_v=None, cu_ctx=None, keep_idx=None,
+               cu_keep=None, max_keep=0, blocks=None, cu_blk=None, max_blk=0, bits=4,
+               tail_k=None, tail_v=None, cu_tail=None, max_tail=0, head_dim=128):
+    d = vc_comp_kv()
+    d.n_seqs, d.n_q_heads, d.n_kv_heads, d.head_dim = n_seqs, n_q_heads, n_kv_heads, head_dim
+    d.bits, d.max_keep, d.max_blk, d.max_tail = bits, max_keep, max_blk, max_tail
+    d.pool_k = _ptr(pool_k, torch.bfloat16, "pool_k"); d.pool_v = _ptr(pool_v, torch.bfloat16, "pool_v")
+    d.cu_ctx = _ptr(cu_ctx, torch.int32, "cu_ctx")
+    d.keep_idx = _ptr(keep_idx, torch.int32, "keep_idx"); d.cu_keep = _ptr(cu_keep, torch.int32, "cu_keep")
+    d.blocks = _ptr(blocks, torch.uint8, "blocks"); d.cu_blk = _ptr(cu_blk, torch.int32, "cu_blk")
+    d.tail_k = _ptr(tail_k, torch.bfloat16, "tail_k"); d.tail_v = _ptr(tail_v, torch.bfloat16, "tail_v")
+    d.cu_tail = _ptr(cu_tail, torch.int32, "cu_tail")
+    return d
+
+
+def vc_draft_workspace_bytes(n_q_heads, n_kv_heads, n_seqs, **kv) -> int:
+    d = _comp_desc(n_q_heads, n_kv_heads, n_seqs, **kv)
+    n = C.c_size_t()
+    _check(load().vc_draft_workspace_bytes(C.byref(d), C.byref(n)))
+    return n.value
+
+
+def vc_draft_attn(ctx: Context, q, softmax_scale, out, *, n_kv_heads, lse=None, workspace=None, stream=None, **kv):
+    """q, out: bf16 [n_seqs, n_q_heads, 128] device tensors; kv: the vc_comp_kv fields by name."""
+    n_seqs, n_q_heads = q.shape[0], q.shape[1]
+    d = _comp_desc(n_q_heads, n_kv_heads, n_seqs, head_dim=q.shape[2], **kv)
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    _check(load().vc_draft_attn(ctx.handle, C.byref(d), _ptr(q, torch.bfloat16, "q"), float(softmax_scale),
+                                _ptr(out, torch.bfloat16, "out"), _ptr(lse, torch.float32, "lse"),
+                                _ptr(workspace, None, "workspace"), ws_bytes, _stream(stream)))
+    return out
+
+
+def _full_desc(n_q_heads, n_kv_heads, n_seqs, k, v, cu_ctx, max_ctx, max_win, head_dim=128):
+    d = vc_full_kv()
+    d.n_seqs, d.n_q_heads, d.n_kv_heads, d.head_dim = n_seqs, n_q_heads, n_kv_heads, head_dim
+    d.max_ctx, d.max_win = max_ctx, max_win
+    d.k = _ptr(k, torch.bfloat16, "k"); d.v = _ptr(v, torch.bfloat16, "v")
+    d.cu_ctx = _ptr(cu_ctx, torch.int32, "cu_ctx")
+    return d
+
+
+def vc_verify_workspace_bytes(n_q_heads, n_kv_heads, n_seqs, *, k, v, cu_ctx, max_ctx, max_win, total_win) -> int:
+    d = _full_desc(n_q_heads, n_kv_heads, n_seqs, k, v, cu_ctx, max_ctx, max_win)
+    n = C.c_size_t()
+    _check(load().vc_verify_workspace_bytes(C.byref(d), int(total_win), C.byref(n)))
+    return n.value
+
+
+def vc_verify_attn(ctx: Context, q_win, k_win, v_win, cu_win, softmax_scale, out, *, k, v, cu_ctx, max_ctx,
+                   max_win, n_seqs, lse=None, workspace=None, stream=None):
+    total_win, n_q_heads = q_win.shape[0], q_win.shape[1]
+    n_kv_heads = k_win.shape[1]
+    d = _full_desc(n_q_heads, n_kv_heads, n_seqs, k, v, cu_ctx, max_ctx, max_win, head_dim=q_win.shape[2])
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    _check(load().vc_verify_attn(ctx.handle, C.byref(d), _ptr(q_win, torch.bfloat16, "q_win"),
+                                 _ptr(k_win, torch.bfloat16, "k_win"), _ptr(v_win, torch.bfloat16, "v_win"),
+                                 _ptr(cu_win, torch.int32, "cu_win"), int(total_win), float(softmax_scale),
+                                 _ptr(out, torch.bfloat16, "out"), _ptr(lse, torch.float32, "lse"),
+                                 _ptr(workspace, None, "workspace"), ws_bytes, _stream(stream)))
+    return out
+
+
+def vc_accept_len(ctx: Context, logits, cu_rows, draft_ids, cu_win, accept_len, next_token, argmax_ids, stream=None):
+    total_rows, vocab = logits.shape
+    n_seqs = cu_rows.numel() - 1
+    _check(load().vc_accept_len(ctx.handle, _ptr(logits, torch.float32, "logits"), int(vocab),
+                                _ptr(cu_rows, torch.int32, "cu_rows"), int(total_rows),
+                                _ptr(draft_ids, torch.int32, "draft_ids"), _ptr(cu_win, torch.int32, "cu_win"),
+                                int(n_seqs), _ptr(accept_len, torch.int32, "accept_len"),
+                                _ptr(next_token, torch.int32, "next_token"),
+                                _ptr(argmax_ids, torch.int32, "argmax_ids"), _stream(stream)))
+    return accept_len, next_token
+
+
+def vc_swap_in(ctx: Context, host_src, dev_dst, chunks) -> int:
+    """chunks: list of (src_off, dst_off, bytes).  Returns the first ticket."""
+    arr = (vc_chunk * max(1, len(chunks)))()
+    for i, (s, d, n) in enumerate(chunks):
+        arr[i].src_off, arr[i].dst_off, arr[i].bytes = int(s), int(d), int(n)
+    first = C.c_int64()
+    _check(load().vc_swap_in(ctx.handle, C.c_void_p(host_src.data_ptr()), C.c_void_p(dev_dst.data_ptr()),
+                             arr, len(chunks), C.byref(first)))
+    return first.value
+
+
+def vc_swap_wait(ctx: Context, ticket: int, stream=None):
+    _check(load().vc_swap_wait(ctx.handle, int(ticket), _stream(stream)))
+
+
+def vc_swap_query(ctx: Context, ticket: int) -> bool:
+    st = load().vc_swap_query(ctx.handle, int(ticket))
+    if st == VC_ERR_NOT_READY:
+        return False
+    _check(st)
+    return True
+
+
+def vc_swap_sync(ctx: Context):
+    _check(load().vc_swap_sync(ctx.handle))
+
+
+def vc_keep_from_dropped(ctx: Context, dropped, cu_drop, cu_ctx, n_kv_heads, max_ctx, keep_idx, cu_keep, stream=None):
+    n_seqs = cu_ctx.numel() - 1
+    _check(load().vc_keep_from_dropped(ctx.handle, _ptr(dropped, torch.int32, "dropped"),
+                                       _ptr(cu_drop, torch.int32, "cu_drop"), _ptr(cu_ctx, torch.int32, "cu_ctx"),
+                                       int(n_seqs), int(n_kv_heads), int(max_ctx),
+                                       _ptr(keep_idx, torch.int32, "keep_idx"), _ptr(cu_keep, torch.int32, "cu_keep"),
+                                       _stream(stream)))
+    return keep_idx, cu_keep
