@@ -70,12 +70,14 @@ const char* vc_version(void);
  *        blocks          device, 5120-byte records.  (b, h) owns records cu_blk[b]*n_kv_heads +
  *                        h*nb + i, i < nb = cu_blk[b+1]-cu_blk[b]; record i holds tokens
  *                        i*TB .. i*TB+TB-1 of whatever token list was compressed.
- *      Record layout (all multi-byte fields little endian):
- *        bytes    0..2047  key codes, token-major: (token t, channel d) is the `bits`-wide field
- *                          at bit  bits*(d mod (8/bits))  of byte  t*(16*bits) + d*bits/8
+ *      Record layout (all multi-byte fields little endian).  Codes are packed into 32-bit words
+ *      of E = 32/bits elements; element e of a word is the `bits`-wide field at bit
+ *      16*(e mod 2) + bits*(e / 2)  (even elements fill the low half-word, odd ones the high):
+ *        bytes    0..2047  key codes, token-major: token t owns words 4*bits*t .. 4*bits*t +
+ *                          4*bits-1; word wi of a token holds channels E*wi .. E*wi+E-1
  *        bytes 2048..4095  value codes, 128 slots of 16 bytes; slot 64*c + 16*j + n (c<2, j<4,
- *                          n<16) holds 32-bit words q<4; word q is channel d = 64*c + 16*q + n
- *                          and carries tokens (32/bits)*j + i in the field at bit bits*i
+ *                          n<16) holds words q<4; word q is channel d = 64*c + 16*q + n and holds
+ *                          tokens E*j .. E*j+E-1 of the block
  *        bytes 4096..4607  key scale[128] then key zero[128] (fp16, per channel)
  *        bytes 4608..5119  value scale[g][t] then value zero[g][t] (fp16; g = d / TB < 128/TB,
  *                          t < TB), 128 + 128 values
@@ -144,10 +146,12 @@ vc_status vc_verify_attn(vc_ctx* ctx, const vc_full_kv* kv, const void* q_win, c
  *   accept_len  device int32 [n_seqs]: first j with draft_ids[j] != argmax(row j), else w_b
  *   next_token  device int32 [n_seqs]: argmax(row accept_len) - the correction, or the bonus
  *               token when everything matched and the bonus row exists; -1 if that row is absent */
+vc_status vc_accept_workspace_bytes(int32_t total_rows, int32_t vocab, size_t* bytes);
 vc_status vc_accept_len(vc_ctx* ctx, const float* logits, int32_t vocab, const int32_t* cu_rows,
                         int32_t total_rows, const int32_t* draft_ids, const int32_t* cu_win,
                         int32_t n_seqs, int32_t* accept_len, int32_t* next_token,
-                        int32_t* argmax_ids, void* stream);
+                        int32_t* argmax_ids, void* workspace, size_t workspace_bytes,
+                        void* stream);
 
 /* Full-KV reload (paper section 4.2.1 and section 5.2 step (i): the full KV lives in CPU memory
  * and is reloaded asynchronously, overlapped with draft forward passes).
@@ -156,7 +160,8 @@ vc_status vc_accept_len(vc_ctx* ctx, const float* logits, int32_t vocab, const i
  *   dev_dst   device memory
  *   chunks    host array of n_chunks {src_off, dst_off, bytes} (byte offsets from the bases)
  *   first_ticket  receives the ticket of chunks[0]; chunk i has ticket first_ticket + i.
- * Tickets complete in issue order.  At most 65536 tickets may be outstanding. */
+ * Tickets complete in issue order.  At most 4096 tickets may be outstanding (issued and
+ * not yet landed); a call that would exceed that returns VC_ERR_INVALID_ARG and enqueues nothing. */
 typedef struct { size_t src_off, dst_off, bytes; } vc_chunk;
 vc_status vc_swap_in(vc_ctx* ctx, const void* host_src, void* dev_dst, const vc_chunk* chunks,
                      int32_t n_chunks, int64_t* first_ticket);

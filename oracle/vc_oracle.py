@@ -64,13 +64,13 @@ def unpack_records(records: np.ndarray, bits: int):
     """Dequantise block records.
 
     records: uint8 [n_heads, n_blocks, 5120].  One record holds TB = 32 (int4) or 64 (int2)
-    consecutive tokens of one KV head:
-      bytes    0..2047  key codes, token-major: token t, channel d lives in byte
-                        t*(128*bits/8) + d*bits/8 at bit offset bits*(d mod 8/bits)
+    consecutive tokens of one KV head.  Codes sit in little-endian 32-bit words of E = 32/bits
+    elements; element e of a word is the field at bit 16*(e mod 2) + bits*(e // 2):
+      bytes    0..2047  key codes, token-major: token t owns words 4*bits*t ...; word wi of a
+                        token holds channels E*wi .. E*wi+E-1
       bytes 2048..4095  value codes in 128 slots of 16 bytes; slot L = 64*c + 16*j + n
-                        (c<2, j<4, n<16) holds four little-endian 32-bit words q<4; word q
-                        belongs to channel d = 64*c + 16*q + n and holds tokens
-                        (32/bits)*j + i at bit offset bits*i
+                        (c<2, j<4, n<16) holds words q<4; word q belongs to channel
+                        d = 64*c + 16*q + n and holds tokens E*j .. E*j+E-1
       bytes 4096..4607  key scale[128] then key zero[128], fp16, one pair per channel
       bytes 4608..5119  value scale[g][t] then value zero[g][t], fp16, g = channel group
                         (d // TB), t = token in block
@@ -83,20 +83,22 @@ def unpack_records(records: np.ndarray, bits: int):
     if rec.ndim != 3 or rec.shape[2] != RECORD_BYTES:
         raise ValueError("records must be [heads, blocks, 5120] uint8")
     nh, nb, _ = rec.shape
-    per_byte = 8 // bits
     cmask = (1 << bits) - 1
+    per_word = 32 // bits
+    words_per_token = HEAD_DIM // per_word
 
-    kc = rec[:, :, _K_CODES:_K_CODES + 2048]
+    def field(word, e):
+        return (word >> np.uint32(16 * (e % 2) + bits * (e // 2))) & np.uint32(cmask)
+
+    kwords = rec[:, :, _K_CODES:_K_CODES + 2048].copy().view("<u4")  # [nh, nb, 512]
     k_code = np.empty((nh, nb, tb, HEAD_DIM), dtype=np.float64)
-    row_bytes = HEAD_DIM * bits // 8
     for t in range(tb):
         for d in range(HEAD_DIM):
-            byte = kc[:, :, t * row_bytes + d // per_byte]
-            k_code[:, :, t, d] = (byte >> np.uint8(bits * (d % per_byte))) & np.uint8(cmask)
+            word = kwords[:, :, words_per_token * t + d // per_word]
+            k_code[:, :, t, d] = field(word, d % per_word)
 
     vwords = rec[:, :, _V_CODES:_V_CODES + 2048].copy().view("<u4")  # [nh, nb, 512]
     v_code = np.empty((nh, nb, tb, HEAD_DIM), dtype=np.float64)
-    per_word = 32 // bits
     for c in range(2):
         for j in range(4):
             for n in range(16):
@@ -104,9 +106,8 @@ def unpack_records(records: np.ndarray, bits: int):
                 for q in range(4):
                     d = 64 * c + 16 * q + n
                     word = vwords[:, :, 4 * slot + q]
-                    for i in range(per_word):
-                        t = per_word * j + i
-                        v_code[:, :, t, d] = (word >> np.uint32(bits * i)) & np.uint32(cmask)
+                    for e in range(per_word):
+                        v_code[:, :, per_word * j + e, d] = field(word, e)
 
     kmeta = rec[:, :, _K_META:_K_META + 512].copy().view("<u2")       # [nh, nb, 256]
     k_scale = f16_to_f64(kmeta[:, :, 0:128])
@@ -248,15 +249,23 @@ def verify_attn(q_win, k_full, v_full, k_win, v_win, cu_ctx, cu_win, scale: floa
     """All window rows: returns (out [W, Hq, 128], lse [W, Hq]) float64."""
     q_win = np.asarray(q_win)
     nseq = len(cu_win) - 1
+    g = n_q_heads // n_kv_heads
     out = np.zeros((q_win.shape[0], n_q_heads, HEAD_DIM))
     lse = np.zeros((q_win.shape[0], n_q_heads))
     for b in range(nseq):
-        for i in range(int(cu_win[b + 1]) - int(cu_win[b])):
-            for h in range(n_q_heads):
-                o, s = verify_attn_one(q_win, k_full, v_full, k_win, v_win, cu_ctx, cu_win,
-                                       b, i, h, scale, n_q_heads=n_q_heads, n_kv_heads=n_kv_heads)
-                out[int(cu_win[b]) + i, h] = o
-                lse[int(cu_win[b]) + i, h] = s
+        lo, hi = int(cu_ctx[b]), int(cu_ctx[b + 1])
+        w0, w1 = int(cu_win[b]), int(cu_win[b + 1])
+        for kvh in range(n_kv_heads):
+            # same key order as verify_attn_one: full-KV rows, then the window rows
+            k = np.concatenate([_rows(k_full, lo, hi, kvh), _rows(k_win, w0, w1, kvh)], axis=0)
+            v = np.concatenate([_rows(v_full, lo, hi, kvh), _rows(v_win, w0, w1, kvh)], axis=0)
+            n = hi - lo
+            for i in range(w1 - w0):
+                for h in range(kvh * g, (kvh + 1) * g):
+                    q = bf16_to_f64(q_win[w0 + i, h, :])
+                    o, s, _ = attend(q, k[:n + i + 1], v[:n + i + 1], scale)
+                    out[w0 + i, h] = o
+                    lse[w0 + i, h] = s
     return out, lse
 
 

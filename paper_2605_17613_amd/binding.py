@@ -45,7 +45,7 @@ class vc_chunk(C.Structure):
 
 EXPORTS = ["vc_create", "vc_destroy", "vc_last_error", "vc_version",
            "vc_draft_workspace_bytes", "vc_draft_attn", "vc_verify_workspace_bytes", "vc_verify_attn",
-           "vc_accept_len", "vc_swap_in", "vc_swap_wait", "vc_swap_query", "vc_swap_sync",
+           "vc_accept_workspace_bytes", "vc_accept_len", "vc_swap_in", "vc_swap_wait", "vc_swap_query", "vc_swap_sync",
            "vc_keep_from_dropped"]
 
 
@@ -73,8 +73,10 @@ def load():
     lib.vc_verify_attn.argtypes = [C.c_void_p, C.POINTER(vc_full_kv), C.c_void_p, C.c_void_p, C.c_void_p,
                                    C.c_void_p, C.c_int32, C.c_float, C.c_void_p, C.c_void_p, C.c_void_p,
                                    C.c_size_t, C.c_void_p]
+    lib.vc_accept_workspace_bytes.argtypes = [C.c_int32, C.c_int32, C.POINTER(C.c_size_t)]
     lib.vc_accept_len.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p,
-                                  C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+                                  C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                  C.c_size_t, C.c_void_p]
     lib.vc_swap_in.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(vc_chunk), C.c_int32,
                                C.POINTER(C.c_int64)]
     lib.vc_swap_wait.argtypes = [C.c_void_p, C.c_int64, C.c_void_p]
@@ -200,15 +202,24 @@ def vc_verify_attn(ctx: Context, q_win, k_win, v_win, cu_win, softmax_scale, out
     return out
 
 
-def vc_accept_len(ctx: Context, logits, cu_rows, draft_ids, cu_win, accept_len, next_token, argmax_ids, stream=None):
+def vc_accept_workspace_bytes(total_rows: int, vocab: int) -> int:
+    n = C.c_size_t()
+    _check(load().vc_accept_workspace_bytes(int(total_rows), int(vocab), C.byref(n)))
+    return n.value
+
+
+def vc_accept_len(ctx: Context, logits, cu_rows, draft_ids, cu_win, accept_len, next_token, argmax_ids,
+                  workspace=None, stream=None):
     total_rows, vocab = logits.shape
     n_seqs = cu_rows.numel() - 1
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
     _check(load().vc_accept_len(ctx.handle, _ptr(logits, torch.float32, "logits"), int(vocab),
                                 _ptr(cu_rows, torch.int32, "cu_rows"), int(total_rows),
                                 _ptr(draft_ids, torch.int32, "draft_ids"), _ptr(cu_win, torch.int32, "cu_win"),
                                 int(n_seqs), _ptr(accept_len, torch.int32, "accept_len"),
                                 _ptr(next_token, torch.int32, "next_token"),
-                                _ptr(argmax_ids, torch.int32, "argmax_ids"), _stream(stream)))
+                                _ptr(argmax_ids, torch.int32, "argmax_ids"),
+                                _ptr(workspace, None, "workspace"), ws_bytes, _stream(stream)))
     return accept_len, next_token
 
 

@@ -1,0 +1,179 @@
+// Greedy acceptance (paper section 4.1 step 3) and kept-index lists from dropped-index lists
+// (section 6, CompressedKV.dropped_indices).  Integer / compare work only: results are exact.
+//
+// Arg-max is a streaming scan of the fp32 logits (HBM bound).  A row is cut into segments so that
+// few rows still fill the chip; every workgroup reduces its segment to one 64-bit key
+//   key = (order-preserving image of the float) << 32 | ~index
+// and merges it into the row's key with a 64-bit atomic max, so the largest value wins and, among
+// equal values, the lowest index.
+#include "common.h"
+
+namespace vc {
+
+constexpr int kAcceptThreads = 256;
+constexpr int kSegElems = 8192;  // logits per workgroup
+
+__device__ __forceinline__ uint32_t float_order(float f) {
+  uint32_t u = __float_as_uint(f);
+  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+__device__ __forceinline__ unsigned long long make_key(float v, int idx) {
+  return (static_cast<unsigned long long>(float_order(v)) << 32) | static_cast<uint32_t>(~static_cast<uint32_t>(idx));
+}
+
+__global__ void accept_init_kernel(unsigned long long* keys, int total_rows) {
+  int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < total_rows) keys[i] = 0ull;  // below every real key (real keys have a non-zero high word)
+}
+
+__global__ __launch_bounds__(kAcceptThreads) void argmax_segment_kernel(const float* __restrict__ logits, int vocab,
+                                                                       unsigned long long* __restrict__ keys) {
+  const int row = blockIdx.y;
+  const int seg0 = blockIdx.x * kSegElems;
+  const int seg1 = min(vocab, seg0 + kSegElems);
+  const float* base = logits + static_cast<size_t>(row) * vocab;
+  float best = -INFINITY;
+  int bidx = 0x7fffffff;
+  const bool vec_ok = ((reinterpret_cast<uintptr_t>(base + seg0) & 15u) == 0);
+  if (vec_ok) {
+    const int nvec = (seg1 - seg0) >> 2;
+    const float4* b4 = reinterpret_cast<const float4*>(base + seg0);
+    for (int i = threadIdx.x; i < nvec; i += kAcceptThreads) {
+      float4 x = b4[i];
+      int e = seg0 + 4 * i;
+      // ascending index order inside a thread, strict '>' keeps the first of equal values
+      if (x.x > best || bidx == 0x7fffffff) { best = x.x; bidx = e; }
+      if (x.y > best) { best = x.y; bidx = e + 1; }
+      if (x.z > best) { best = x.z; bidx = e + 2; }
+      if (x.w > best) { best = x.w; bidx = e + 3; }
+    }
+    for (int e = seg0 + 4 * nvec + threadIdx.x; e < seg1; e += kAcceptThreads) {
+      float x = base[e];
+      if (x > best || bidx == 0x7fffffff) { best = x; bidx = e; }
+    }
+  } else {
+    for (int e = seg0 + threadIdx.x; e < seg1; e += kAcceptThreads) {
+      float x = base[e];
+      if (x > best || bidx == 0x7fffffff) { best = x; bidx = e; }
+    }
+  }
+  unsigned long long key = (bidx == 0x7fffffff) ? 0ull : make_key(best, bidx);
+  for (int off = 32; off > 0; off >>= 1) {
+    unsigned long long o = __shfl_xor(key, off, 64);
+    key = o > key ? o : key;
+  }
+  __shared__ unsigned long long wk[kAcceptThreads / 64];
+  if ((threadIdx.x & 63) == 0) wk[threadIdx.x >> 6] = key;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    for (int w = 1; w < kAcceptThreads / 64; ++w) key = wk[w] > key ? wk[w] : key;
+    if (key) atomicMax(&keys[row], key);
+  }
+}
+
+__device__ __forceinline__ int key_index(unsigned long long key) { return static_cast<int>(~static_cast<uint32_t>(key)); }
+
+__global__ void accept_finish_kernel(const unsigned long long* __restrict__ keys, int total_rows,
+                                     const int* __restrict__ cu_rows, const int* __restrict__ draft_ids,
+                                     const int* __restrict__ cu_win, int n_seqs, int* __restrict__ accept_len,
+                                     int* __restrict__ next_token, int* __restrict__ argmax_ids) {
+  int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < total_rows) argmax_ids[i] = key_index(keys[i]);
+  if (i < n_seqs) {
+    const int r0 = cu_rows[i], r1 = cu_rows[i + 1];
+    const int w0 = cu_win[i], w = cu_win[i + 1] - w0;
+    int a = w;
+    for (int j = 0; j < w; ++j) {
+      if (draft_ids[w0 + j] != key_index(keys[r0 + j])) { a = j; break; }
+    }
+    accept_len[i] = a;
+    next_token[i] = (r0 + a < r1) ? key_index(keys[r0 + a]) : -1;
+  }
+}
+
+// keep = [0, len) minus dropped: position p is kept iff it is not in the (ascending) dropped list;
+// its rank among the kept ones is p minus the number of dropped positions below it.
+__global__ __launch_bounds__(256) void keep_from_dropped_kernel(const int* __restrict__ dropped,
+                                                                const int* __restrict__ cu_drop,
+                                                                const int* __restrict__ cu_ctx, int n_kv_heads,
+                                                                int* __restrict__ keep_idx, int* __restrict__ cu_keep) {
+  const int b = blockIdx.z, h = blockIdx.y;
+  const int len = cu_ctx[b + 1] - cu_ctx[b];
+  const int nd = cu_drop[b + 1] - cu_drop[b];
+  const int keep_base = (cu_ctx[b] - cu_ctx[0]) - (cu_drop[b] - cu_drop[0]);  // = cu_keep[b]
+  if (blockIdx.x == 0 && h == 0 && threadIdx.x == 0) {
+    cu_keep[b] = keep_base;
+    if (b == gridDim.z - 1) cu_keep[b + 1] = keep_base + len - nd;
+  }
+  const int p = blockIdx.x * 256 + threadIdx.x;
+  if (p >= len) return;
+  const int nk = len - nd;
+  const int* dl = dropped + (static_cast<size_t>(cu_drop[b]) * n_kv_heads + static_cast<size_t>(h) * nd);
+  int lo = 0, hi = nd;  // lower bound: first entry >= p
+  while (lo < hi) {
+    int mid = (lo + hi) >> 1;
+    if (dl[mid] < p) lo = mid + 1; else hi = mid;
+  }
+  if (lo < nd && dl[lo] == p) return;  // dropped
+  keep_idx[static_cast<size_t>(keep_base) * n_kv_heads + static_cast<size_t>(h) * nk + (p - lo)] = p;
+}
+
+}  // namespace vc
+
+using namespace vc;
+
+extern "C" vc_status vc_accept_workspace_bytes(int32_t total_rows, int32_t vocab, size_t* bytes) {
+  VC_REQUIRE(bytes != nullptr, VC_ERR_INVALID_ARG, "vc_accept_workspace_bytes: bytes is NULL");
+  VC_REQUIRE(total_rows >= 0 && vocab > 0, VC_ERR_INVALID_ARG, "vc_accept_workspace_bytes: rows %d vocab %d",
+             total_rows, vocab);
+  *bytes = static_cast<size_t>(total_rows > 0 ? total_rows : 1) * sizeof(unsigned long long);
+  return VC_OK;
+}
+
+extern "C" vc_status vc_accept_len(vc_ctx* ctx, const float* logits, int32_t vocab, const int32_t* cu_rows,
+                                   int32_t total_rows, const int32_t* draft_ids, const int32_t* cu_win, int32_t n_seqs,
+                                   int32_t* accept_len, int32_t* next_token, int32_t* argmax_ids, void* workspace,
+                                   size_t workspace_bytes, void* stream) {
+  VC_REQUIRE(ctx != nullptr, VC_ERR_INVALID_ARG, "vc_accept_len: ctx is NULL");
+  VC_REQUIRE(n_seqs >= 0 && total_rows >= 0 && vocab > 0, VC_ERR_INVALID_ARG, "vc_accept_len: n_seqs %d rows %d vocab %d",
+             n_seqs, total_rows, vocab);
+  if (n_seqs == 0) return VC_OK;
+  VC_REQUIRE(cu_rows && cu_win && accept_len && next_token, VC_ERR_INVALID_ARG, "vc_accept_len: NULL pointer");
+  VC_REQUIRE(total_rows == 0 || (logits && argmax_ids), VC_ERR_INVALID_ARG, "vc_accept_len: logits/argmax_ids NULL");
+  VC_REQUIRE((reinterpret_cast<uintptr_t>(logits) & 3u) == 0, VC_ERR_INVALID_ARG, "vc_accept_len: logits misaligned");
+  size_t need = 0;
+  vc_accept_workspace_bytes(total_rows, vocab, &need);
+  VC_REQUIRE(workspace != nullptr && workspace_bytes >= need, VC_ERR_WORKSPACE,
+             "vc_accept_len: workspace %zu bytes, need %zu", workspace_bytes, need);
+  VC_REQUIRE((reinterpret_cast<uintptr_t>(workspace) & 7u) == 0, VC_ERR_INVALID_ARG, "vc_accept_len: workspace misaligned");
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  unsigned long long* keys = static_cast<unsigned long long*>(workspace);
+  if (total_rows > 0) {
+    hipLaunchKernelGGL(accept_init_kernel, dim3(ceil_div(total_rows, 256)), dim3(256), 0, st, keys, total_rows);
+    dim3 grid(ceil_div(vocab, kSegElems), total_rows);
+    hipLaunchKernelGGL(argmax_segment_kernel, grid, dim3(kAcceptThreads), 0, st, logits, vocab, keys);
+  }
+  int nmax = total_rows > n_seqs ? total_rows : n_seqs;
+  hipLaunchKernelGGL(accept_finish_kernel, dim3(ceil_div(nmax, 256)), dim3(256), 0, st, keys, total_rows, cu_rows,
+                     draft_ids, cu_win, n_seqs, accept_len, next_token, argmax_ids);
+  VC_HIP(hipGetLastError());
+  return VC_OK;
+}
+
+extern "C" vc_status vc_keep_from_dropped(vc_ctx* ctx, const int32_t* dropped, const int32_t* cu_drop,
+                                          const int32_t* cu_ctx, int32_t n_seqs, int32_t n_kv_heads, int32_t max_ctx,
+                                          int32_t* keep_idx, int32_t* cu_keep, void* stream) {
+  VC_REQUIRE(ctx != nullptr, VC_ERR_INVALID_ARG, "vc_keep_from_dropped: ctx is NULL");
+  VC_REQUIRE(n_seqs >= 0 && n_kv_heads > 0 && max_ctx >= 0, VC_ERR_INVALID_ARG,
+             "vc_keep_from_dropped: n_seqs %d n_kv_heads %d max_ctx %d", n_seqs, n_kv_heads, max_ctx);
+  if (n_seqs == 0) return VC_OK;
+  VC_REQUIRE(cu_drop && cu_ctx && cu_keep, VC_ERR_INVALID_ARG, "vc_keep_from_dropped: NULL cu array");
+  VC_REQUIRE(max_ctx == 0 || keep_idx, VC_ERR_INVALID_ARG, "vc_keep_from_dropped: keep_idx is NULL");
+  VC_REQUIRE(n_seqs <= 65535 && n_kv_heads <= 65535, VC_ERR_UNSUPPORTED, "vc_keep_from_dropped: grid too large");
+  dim3 grid(max_ctx > 0 ? ceil_div(max_ctx, 256) : 1, n_kv_heads, n_seqs);
+  hipLaunchKernelGGL(keep_from_dropped_kernel, grid, dim3(256), 0, static_cast<hipStream_t>(stream), dropped, cu_drop,
+                     cu_ctx, n_kv_heads, keep_idx, cu_keep);
+  VC_HIP(hipGetLastError());
+  return VC_OK;
+}

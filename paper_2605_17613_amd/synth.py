@@ -81,21 +81,23 @@ def quantize_records(k: torch.Tensor, v: torch.Tensor, bits: int) -> torch.Tenso
     kf = k.float().view(nb, tb, hkv, d).permute(2, 0, 1, 3)
     vf = v.float().view(nb, tb, hkv, d).permute(2, 0, 1, 3)
 
+    per_word = 32 // bits
+    # element e of a 32-bit word sits at bit 16*(e % 2) + bits*(e // 2)
+    e = torch.arange(per_word, device=dev)
+    sh = 16 * (e % 2) + bits * (e // 2)
+
     kc, ks, kz = _minmax_codes(kf, 2, levels)                       # scale/zero [H, nb, 1, 128]
-    per_byte = 8 // bits
-    kc = kc.reshape(hkv, nb, tb, d // per_byte, per_byte)
-    sh = (torch.arange(per_byte, device=dev) * bits).view(1, 1, 1, 1, per_byte)
-    k_bytes = (kc << sh).sum(-1).to(torch.uint8).reshape(hkv, nb, tb * d // per_byte)
+    kc = kc.reshape(hkv, nb, tb, d // per_word, per_word)
+    k_words = (kc << sh.view(1, 1, 1, 1, per_word)).sum(-1).reshape(hkv, nb, tb * d // per_word)
+    k_bytes = _bytes_of_words(k_words)
 
     ngrp = d // tb
     vg = vf.reshape(hkv, nb, tb, ngrp, tb)
     vc, vs, vz = _minmax_codes(vg, 4, levels)                       # scale/zero [H, nb, tb, ngrp, 1]
     vc = vc.reshape(hkv, nb, tb, d)
-    per_word = 32 // bits
-    # token t = per_word*j + i ; channel d = 64*c + 16*q + n  ->  word order [c][j][n][q]
-    vc = vc.view(hkv, nb, 4, per_word, 2, 4, 16).permute(0, 1, 4, 2, 6, 5, 3)   # H nb c j n q i
-    sh = (torch.arange(per_word, device=dev) * bits).view(1, 1, 1, 1, 1, 1, per_word)
-    words = (vc << sh).sum(-1).reshape(hkv, nb, 512)
+    # token t = per_word*j + e ; channel d = 64*c + 16*q + n  ->  word order [c][j][n][q]
+    vc = vc.view(hkv, nb, 4, per_word, 2, 4, 16).permute(0, 1, 4, 2, 6, 5, 3)   # H nb c j n q e
+    words = (vc << sh.view(1, 1, 1, 1, 1, 1, per_word)).sum(-1).reshape(hkv, nb, 512)
     v_bytes = _bytes_of_words(words)
 
     k_meta = torch.cat([_bytes_of_halves(ks.reshape(hkv, nb, d)),

@@ -1,0 +1,208 @@
+"""GPU parity: every entry point of the C ABI against the fp64 oracle on the same seeded inputs.
+Attention outputs: max|gpu - oracle| / max|oracle| <= 1e-2 (bf16 outputs).  accept_len, next_token,
+arg-max ids and kept-index lists: bit-exact."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import vc_oracle as O
+from paper_2605_17613_amd import synth
+from tests import helpers as H
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+@pytest.fixture(scope="module")
+def ctx(lib):
+    c = lib.Context(0)
+    yield c
+    c.close()
+
+
+def check_draft(lib, ctx, lay, tag, **sel):
+    kw = H.draft_kwargs(lay, **sel)
+    print(f"[draft] {tag} {sel}", flush=True)
+    out, lse = H.gpu_draft(lib, ctx, lay, **kw)
+    ref, ref_lse = H.oracle_draft(lay, kw)
+    err = H.rel_err(out, ref)
+    assert err <= H.TOL, f"{tag}: rel err {err}"
+    fin = np.isfinite(ref_lse)
+    assert np.abs(lse.cpu().numpy()[fin] - ref_lse[fin]).max() <= H.LSE_TOL
+    assert np.array_equal(np.isneginf(lse.cpu().numpy()), np.isneginf(ref_lse))
+    return out
+
+
+# ------------------------------------------------------------------ draft, bf16 rows
+@pytest.mark.parametrize("hq,hkv", [(8, 2), (4, 4), (8, 4), (16, 2), (16, 1)])
+def test_draft_bf16_contiguous_gqa(lib, ctx, hq, hkv):
+    lay = synth.make_layer(11, DEV, ctx_len=[700, 1, 333], n_q_heads=hq, n_kv_heads=hkv)
+    check_draft(lib, ctx, lay, f"bf16 g={hq // hkv}", use_pool=True)
+
+
+def test_draft_bf16_gather_ragged_with_tail_and_empty(lib, ctx):
+    lay = synth.make_layer(12, DEV, ctx_len=[900, 70, 2000, 64], n_q_heads=8, n_kv_heads=2,
+                           keep=[257, 70, 0, 5], keep_first=[4, 2, 0, 1], keep_last=[9, 3, 0, 2],
+                           tail_len=[3, 0, 17, 0])
+    check_draft(lib, ctx, lay, "gather+tail", use_pool=True, use_keep=True, use_tail=True)
+    check_draft(lib, ctx, lay, "gather", use_pool=True, use_keep=True)
+    # sequence 2 keeps nothing and has no tail in the second call: out = 0, lse = -inf there
+
+
+def test_draft_bf16_many_splits(lib, ctx):
+    lay = synth.make_layer(13, DEV, ctx_len=[5000], n_q_heads=8, n_kv_heads=2, keep=[3001], keep_first=64, keep_last=256)
+    check_draft(lib, ctx, lay, "gather splits", use_pool=True, use_keep=True)
+
+
+# ------------------------------------------------------------------ draft, block records
+@pytest.mark.parametrize("bits", [4, 2])
+@pytest.mark.parametrize("hq,hkv", [(8, 2), (2, 2), (16, 2), (6, 2)])
+def test_draft_quant(lib, ctx, bits, hq, hkv):
+    tb = synth.tokens_per_block(bits)
+    lay = synth.make_layer(20 + bits, DEV, ctx_len=[tb * 37, tb, tb * 8 + 5], n_q_heads=hq, n_kv_heads=hkv,
+                           quant_bits=(bits,), outlier_channels=3)
+    check_draft(lib, ctx, lay, f"int{bits} g={hq // hkv}", bits=bits, use_tail=True)
+
+
+@pytest.mark.parametrize("bits", [4, 2])
+def test_draft_quant_long_with_tail(lib, ctx, bits):
+    lay = synth.make_layer(30 + bits, DEV, ctx_len=[20000 + 13, 4096], n_q_heads=8, n_kv_heads=2, quant_bits=(bits,),
+                           tail_len=[63, 1])
+    check_draft(lib, ctx, lay, f"int{bits} long", bits=bits, use_tail=True)
+
+
+@pytest.mark.parametrize("bits", [4, 2])
+def test_draft_lossless_grid_equals_bf16_path(lib, ctx, bits):
+    """Cross-kernel: records built from exact grid values dequantise to the bf16 values, so the
+    record kernel and the bf16 kernel must agree (both are also checked against the oracle)."""
+    tb = synth.tokens_per_block(bits)
+    g = synth.gen(77, DEV)
+    lv = 1 << bits
+    n_tok = 6 * tb
+    codes = torch.randint(0, lv, (n_tok, 2, 128), generator=g, device=DEV)
+    codes[0::tb] = 0
+    codes[1::tb] = lv - 1
+    codes[:, :, 0::tb] = 0
+    codes[:, :, 1::tb] = lv - 1
+    k = (codes.float() / 8.0 - 1.0).to(torch.bfloat16)
+    codes2 = codes.flip(0)
+    v = (codes2.float() / 8.0 + 0.5).to(torch.bfloat16)
+    lay = synth.make_layer(5, DEV, ctx_len=[n_tok], n_q_heads=8, n_kv_heads=2)
+    lay.k_full, lay.v_full = k.contiguous(), v.contiguous()
+    lay.blocks[bits] = synth.quantize_records(lay.k_full, lay.v_full, bits).reshape(-1, 5120).contiguous()
+    lay.cu_blk[bits] = torch.tensor([0, 6], dtype=torch.int32, device=DEV)
+    lay.max_blk[bits] = 6
+    a = check_draft(lib, ctx, lay, "grid bf16", use_pool=True)
+    b = check_draft(lib, ctx, lay, "grid quant", bits=bits)
+    assert (a.float() - b.float()).abs().max().item() <= 2e-2 * a.float().abs().max().item()
+
+
+# ------------------------------------------------------------------ verify
+@pytest.mark.parametrize("win", [[1], [3, 8], [16, 5, 1], [33], [64, 2]])
+@pytest.mark.parametrize("hq,hkv", [(8, 2), (4, 4), (16, 2)])
+def test_verify_windows(lib, ctx, win, hq, hkv):
+    ctx_len = [1000 + 37 * i for i in range(len(win))]
+    lay = synth.make_layer(40 + len(win), DEV, ctx_len=ctx_len, n_q_heads=hq, n_kv_heads=hkv, win=win)
+    print(f"[verify] win={win} hq={hq} hkv={hkv}", flush=True)
+    out, lse = H.gpu_verify(lib, ctx, lay)
+    ref, ref_lse = H.oracle_verify(lay)
+    assert H.rel_err(out, ref) <= H.TOL
+    assert np.abs(lse.cpu().numpy() - ref_lse).max() <= H.LSE_TOL
+
+
+def test_verify_short_context_and_zero_window(lib, ctx):
+    lay = synth.make_layer(45, DEV, ctx_len=[5, 31, 32, 0 + 1], n_q_heads=8, n_kv_heads=2, win=[4, 0, 7, 2])
+    out, lse = H.gpu_verify(lib, ctx, lay)
+    ref, ref_lse = H.oracle_verify(lay)
+    assert H.rel_err(out, ref) <= H.TOL
+
+
+def test_verify_window_of_one_equals_draft(lib, ctx):
+    lay = synth.make_layer(46, DEV, ctx_len=[777, 100], n_q_heads=8, n_kv_heads=2, win=[1, 1])
+    out, _ = H.gpu_verify(lib, ctx, lay)
+    lay.q = lay.q_win
+    kw = dict(pool_k=lay.k_full, pool_v=lay.v_full, cu_ctx=lay.cu_ctx, max_keep=777,
+              tail_k=lay.k_win, tail_v=lay.v_win, cu_tail=lay.cu_win, max_tail=1)
+    d_out, _ = H.gpu_draft(lib, ctx, lay, **kw)
+    assert (out.float() - d_out.float()).abs().max().item() <= 2e-2 * out.float().abs().max().item()
+
+
+# ------------------------------------------------------------------ accept / keep
+def test_accept_planted_ties_bonus(lib, ctx):
+    lay = synth.make_layer(50, DEV, ctx_len=[8] * 6, n_q_heads=4, n_kv_heads=2, win=[5, 5, 3, 1, 64, 7], vocab=32000,
+                           bonus_row=True, prefix_len=[0, 5, 2, 1, 64, 3])
+    lay.logits[3, 100] = 10.0; lay.logits[3, 31999] = 10.0       # ties: lowest index must win
+    lay.logits[7, :] = float("-inf"); lay.logits[7, 17] = -5.0
+    lay.logits[9, :] = 0.25
+    a, n, am = H.gpu_accept(lib, ctx, lay)
+    ra, rn, ram = H.oracle_accept(lay)
+    assert np.array_equal(am, ram) and np.array_equal(a, ra) and np.array_equal(n, rn)
+
+
+@pytest.mark.parametrize("vocab", [128256, 32000, 1001, 7])
+def test_accept_vocab_sizes(lib, ctx, vocab):
+    lay = synth.make_layer(51, DEV, ctx_len=[8] * 5, n_q_heads=4, n_kv_heads=2, win=[4, 9, 1, 0, 33], vocab=vocab)
+    a, n, am = H.gpu_accept(lib, ctx, lay)
+    ra, rn, ram = H.oracle_accept(lay)
+    assert np.array_equal(am, ram) and np.array_equal(a, ra) and np.array_equal(n, rn)
+    assert a.tolist() == lay.prefix_len or vocab == 7
+
+
+def test_keep_from_dropped(lib, ctx):
+    lay = synth.make_layer(60, DEV, ctx_len=[5000, 33, 20, 777], n_q_heads=8, n_kv_heads=4, keep=[500, 33, 0, 78],
+                           keep_first=[64, 2, 0, 8], keep_last=[256, 3, 0, 16])
+    ref_keep, ref_cu = O.keep_from_dropped(H.npi(lay.dropped_idx), H.npi(lay.cu_drop), lay.ctx_len, 4)
+    keep = torch.full((len(ref_keep),), -1, dtype=torch.int32, device=DEV)
+    cu = torch.full((5,), -1, dtype=torch.int32, device=DEV)
+    lib.vc_keep_from_dropped(ctx, lay.dropped_idx, lay.cu_drop, lay.cu_ctx, 4, max(lay.ctx_len), keep, cu)
+    torch.cuda.synchronize()
+    assert np.array_equal(cu.cpu().numpy(), ref_cu)
+    assert np.array_equal(keep.cpu().numpy(), ref_keep)
+
+
+# ------------------------------------------------------------------ swap-in
+def test_swap_in_bytes_tickets_and_wait(lib, ctx):
+    n = 8 << 20
+    src = torch.randint(0, 255, (n,), dtype=torch.uint8).pin_memory()
+    dst = torch.zeros(n, dtype=torch.uint8, device=DEV)
+    chunk = 1 << 20
+    chunks = [(i * chunk, i * chunk, chunk) for i in range(8)]
+    first = lib.vc_swap_in(ctx, src, dst, chunks)
+    lib.vc_swap_wait(ctx, first + 7)                          # current stream waits on the last chunk
+    total = dst.to(torch.int64).sum()
+    torch.cuda.synchronize()
+    assert lib.vc_swap_query(ctx, first + 7) and lib.vc_swap_query(ctx, first)
+    assert int(total) == int(src.to(torch.int64).sum())
+    assert torch.equal(dst.cpu(), src)
+    first2 = lib.vc_swap_in(ctx, src, dst, [(0, chunk, 16)])
+    assert first2 == first + 8
+    lib.vc_swap_sync(ctx)
+    assert torch.equal(dst[chunk:chunk + 16].cpu(), src[:16])
+
+
+def test_swap_in_rejects_pageable_and_bad_ticket(lib, ctx):
+    src = torch.zeros(1024, dtype=torch.uint8)
+    dst = torch.zeros(1024, dtype=torch.uint8, device=DEV)
+    with pytest.raises(lib.VcError) as e:
+        lib.vc_swap_in(ctx, src, dst, [(0, 0, 1024)])
+    assert e.value.status == 1
+    with pytest.raises(lib.VcError):
+        lib.vc_swap_wait(ctx, 1 << 40)
+    # the context still works afterwards
+    pin = src.pin_memory()
+    t = lib.vc_swap_in(ctx, pin, dst, [(0, 0, 1024)])
+    lib.vc_swap_sync(ctx)
+    assert lib.vc_swap_query(ctx, t)
+
+
+# ------------------------------------------------------------------ error paths that need a context
+def test_workspace_too_small_and_null(lib, ctx):
+    lay = synth.make_layer(70, DEV, ctx_len=[128], n_q_heads=8, n_kv_heads=2)
+    out = torch.empty_like(lay.q)
+    kw = H.draft_kwargs(lay, use_pool=True)
+    with pytest.raises(lib.VcError) as e:
+        lib.vc_draft_attn(ctx, lay.q, lay.scale, out, n_kv_heads=2, workspace=torch.empty(16, dtype=torch.uint8, device=DEV), **kw)
+    assert e.value.status == 3
+    with pytest.raises(lib.VcError) as e:
+        lib.vc_draft_attn(ctx, lay.q, lay.scale, out, n_kv_heads=2, workspace=None, **kw)
+    assert e.value.status == 3

@@ -1,0 +1,92 @@
+"""CPU-only checks of the built library: it loads, exports every symbol the header declares, and
+its host-side argument validation and split planning behave (no kernel is launched here)."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+import paper_2605_17613_amd as vc
+from paper_2605_17613_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def header_functions():
+    text = open(os.path.join(ROOT, "include", "vericache.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(vc_[a-z_]+)\s*\(", text)))
+
+
+def test_library_loads_and_exports_every_declared_symbol():
+    lib = vc.load()
+    names = header_functions()
+    assert len(names) >= 14
+    for name in names:
+        assert hasattr(lib, name), f"{name} declared in the header but not exported"
+    assert sorted(B.EXPORTS) == names
+    assert vc.vc_version() == "0.1"
+
+
+def desc(**kw):
+    d = B.vc_comp_kv()
+    d.n_seqs, d.n_q_heads, d.n_kv_heads, d.head_dim, d.bits = 2, 8, 2, 128, 4
+    for k, v in kw.items():
+        setattr(d, k, v)
+    return d
+
+
+def ws_bytes(d):
+    n = C.c_size_t()
+    st = vc.load().vc_draft_workspace_bytes(C.byref(d), C.byref(n))
+    return st, n.value
+
+
+def test_draft_descriptor_validation():
+    assert ws_bytes(desc())[0] == B.VC_OK
+    assert ws_bytes(desc(head_dim=64))[0] == B.VC_ERR_UNSUPPORTED
+    assert ws_bytes(desc(n_q_heads=7))[0] == B.VC_ERR_INVALID_ARG
+    assert ws_bytes(desc(n_q_heads=68, n_kv_heads=2))[0] == B.VC_ERR_UNSUPPORTED
+    assert ws_bytes(desc(max_blk=-1))[0] == B.VC_ERR_INVALID_ARG
+    assert ws_bytes(desc(pool_k=0x1000))[0] == B.VC_ERR_INVALID_ARG            # pool_v / cu_ctx missing
+    assert ws_bytes(desc(pool_k=0x1008, pool_v=0x1000, cu_ctx=0x2000))[0] == B.VC_ERR_INVALID_ARG  # misaligned
+    assert ws_bytes(desc(blocks=0x1000, cu_blk=0x2000, bits=3))[0] == B.VC_ERR_UNSUPPORTED
+    assert b"bits 3" in vc.load().vc_last_error()
+    st = vc.load().vc_draft_workspace_bytes(None, None)
+    assert st == B.VC_ERR_INVALID_ARG
+
+
+def test_draft_workspace_grows_with_work_and_covers_every_split():
+    small = ws_bytes(desc(blocks=0x1000, cu_blk=0x2000, max_blk=64))[1]
+    big = ws_bytes(desc(blocks=0x1000, cu_blk=0x2000, max_blk=1 << 16))[1]
+    both = ws_bytes(desc(blocks=0x1000, cu_blk=0x2000, max_blk=64, tail_k=0x3000, tail_v=0x4000, cu_tail=0x5000,
+                         max_tail=63))[1]
+    assert small >= 2 * 8 * 130 * 4 and big > small and both == small + 2 * 8 * 130 * 4
+    assert small % (130 * 4) == 0
+
+
+def test_verify_and_accept_host_validation():
+    lib = vc.load()
+    d = B.vc_full_kv()
+    d.n_seqs, d.n_q_heads, d.n_kv_heads, d.head_dim, d.max_ctx, d.max_win = 2, 8, 2, 128, 1000, 65
+    d.k, d.v, d.cu_ctx = 0x1000, 0x2000, 0x3000
+    n = C.c_size_t()
+    assert lib.vc_verify_workspace_bytes(C.byref(d), 10, C.byref(n)) == B.VC_ERR_UNSUPPORTED   # window above 64
+    d.max_win = 64
+    assert lib.vc_verify_workspace_bytes(C.byref(d), 10, C.byref(n)) == B.VC_OK and n.value >= 10 * 8 * 130 * 4
+    d.cu_ctx = None
+    assert lib.vc_verify_workspace_bytes(C.byref(d), 10, C.byref(n)) == B.VC_ERR_INVALID_ARG
+    assert lib.vc_accept_workspace_bytes(64, 128256, C.byref(n)) == B.VC_OK and n.value == 64 * 8
+    assert lib.vc_accept_workspace_bytes(64, 0, C.byref(n)) == B.VC_ERR_INVALID_ARG
+    # calls that need a context reject a NULL one without touching the device
+    assert lib.vc_swap_sync(None) == B.VC_ERR_INVALID_ARG
+    assert lib.vc_swap_query(None, 0) == B.VC_ERR_INVALID_ARG
+    assert lib.vc_destroy(None) == B.VC_OK
+
+
+def test_binding_rejects_wrong_dtypes_before_calling_the_library():
+    import torch
+    with pytest.raises(TypeError):
+        B._ptr(torch.zeros(4, dtype=torch.float32), torch.bfloat16, "q")
+    with pytest.raises(ValueError):
+        B._ptr(torch.zeros(4, 4, dtype=torch.bfloat16).t(), torch.bfloat16, "q")

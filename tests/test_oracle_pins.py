@@ -252,21 +252,23 @@ def hand_pack_record(bits, kcode, vcode, kscale, kzero, vscale, vzero):
     generator's vectorised packer and the oracle's unpacker).  kcode/vcode [TB][128] ints."""
     tb = 32 if bits == 4 else 64
     rec = bytearray(5120)
-    per_byte = 8 // bits
+    per_word = 32 // bits
+    mask = (1 << bits) - 1
+
+    def put(word_byte_offset, e, code):
+        bit = 16 * (e % 2) + bits * (e // 2)               # even elements low half-word, odd high
+        rec[word_byte_offset + bit // 8] |= (code & mask) << (bit % 8)
+
     for t in range(tb):
         for d in range(128):
-            byte = t * (16 * bits) + (d * bits) // 8
-            rec[byte] |= (kcode[t][d] & ((1 << bits) - 1)) << (bits * (d % per_byte))
-    per_word = 32 // bits
+            put(4 * ((128 // per_word) * t + d // per_word), d % per_word, kcode[t][d])
     for t in range(tb):
         for d in range(128):
             c, rem = divmod(d, 64)
             q, n = divmod(rem, 16)
-            j, i = divmod(t, per_word)
+            j, e = divmod(t, per_word)
             slot = 64 * c + 16 * j + n
-            bit = bits * i
-            off = 2048 + 16 * slot + 4 * q + bit // 8
-            rec[off] |= (vcode[t][d] & ((1 << bits) - 1)) << (bit % 8)
+            put(2048 + 16 * slot + 4 * q, e, vcode[t][d])
     f16 = lambda x: int(np.array([x], dtype=np.float16).view(np.uint16)[0])
     for d in range(128):
         s, z = f16(kscale[d]), f16(kzero[d])
