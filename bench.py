@@ -1,0 +1,314 @@
+#!/usr/bin/env python3
+"""Benchmark of the VeriCache hot path on one MI355X.
+
+Workload: BASELINE config 2 (Llama-3-8B attention layer shape, 32 q / 8 KV heads, head_dim 128,
+batch 16, context 65536; int4 g32 and int2 g64 block records of the same bf16 KV; verify window 32;
+greedy accept over planted fp32 logits).  All inputs are seeded, synthetic and resident in HBM
+before the timed region starts.
+
+One step = one speculation round per compressor variant of that batch:
+    A0  kept-index lists from the dropped-index lists (token-drop variant, 10 % budget)
+    for s in 0..31 (the draft horizon; the bf16 tail holds the s tokens drafted so far):
+        D1  draft attention over the retained bf16 rows (gather) + tail
+        D2  draft attention over the int4 records + tail
+        D3  draft attention over the int2 records + tail
+    V1  verify attention of the 32 drafted positions over the full bf16 KV
+    G1  greedy accept
+`value` is the aggregate draft-attention bandwidth: algorithmic bytes of all D1+D2+D3 calls
+divided by their summed HIP-event durations.  The swap-in leg (full KV from pinned host memory on
+the copy stream, overlapped with int4 drafting) is measured outside the timed steps and reported
+under "swap"; it never enters `value`.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--batch", type=int, default=16, help="sequences (config 2: 16)")
+    ap.add_argument("--ctx", type=int, default=65536, help="context tokens (config 2: 65536)")
+    ap.add_argument("--window", type=int, default=32)
+    ap.add_argument("--vocab", type=int, default=128256)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-swap", action="store_true")
+    ap.add_argument("--only", default="", help="comma list of legs to run per step: keep,d1,d2,d3,verify,accept")
+    return ap.parse_args()
+
+
+def draft_bytes(n_seqs, hq, hkv, *, blocks=0, kept=0, tail=0):
+    """Algorithmic bytes of one draft call: records + retained rows + index + tail + q + out."""
+    per_head = blocks * 5120 + kept * (512 + 4) + tail * 512
+    return n_seqs * (hkv * per_head + 2 * hq * 128 * 2)
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives or sharding between GPUs); "
+              "use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+
+    import paper_2605_17613_amd as vc
+    from paper_2605_17613_amd import synth
+
+    vc.load()
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    ctx = vc.Context(0)
+    B, N, W, HQ, HKV = args.batch, args.ctx, args.window, 32, 8
+    legs = set(args.only.split(",")) if args.only else {"keep", "d1", "d2", "d3", "verify", "accept"}
+
+    t_setup = time.time()
+    keep_n = -(-N // 10)
+    lay = synth.make_layer(synth.SEED_BASE + 2, dev, ctx_len=[N] * B, n_q_heads=HQ, n_kv_heads=HKV,
+                           keep=[keep_n] * B, keep_first=64, keep_last=256, quant_bits=(4, 2),
+                           win=[W] * B, vocab=args.vocab)
+    torch.cuda.synchronize()
+    print(f"[bench] inputs built in {time.time() - t_setup:.1f}s", file=sys.stderr, flush=True)
+
+    # per-draft-step tails: step s sees the first s window tokens of every sequence (their K/V are
+    # the drafted tokens' own), gathered once into per-step pools
+    tails = []
+    for s in range(W):
+        if s == 0:
+            tails.append(None)
+            continue
+        sel = torch.cat([torch.arange(int(lay.cu_win[b]), int(lay.cu_win[b]) + s, device=dev) for b in range(B)])
+        tails.append((lay.k_win[sel].contiguous(), lay.v_win[sel].contiguous(),
+                      torch.arange(0, (B + 1) * s, s, dtype=torch.int32, device=dev), s))
+
+    out = torch.empty_like(lay.q)
+    keep_out = torch.empty_like(lay.keep_idx)
+    cu_keep_out = torch.empty_like(lay.cu_keep)
+
+    def draft_kw(kind, s):
+        kw = {}
+        if kind == "d1":
+            kw.update(pool_k=lay.k_full, pool_v=lay.v_full, cu_ctx=lay.cu_ctx, keep_idx=keep_out,
+                      cu_keep=cu_keep_out, max_keep=keep_n)
+        else:
+            bits = 4 if kind == "d2" else 2
+            kw.update(blocks=lay.blocks[bits], cu_blk=lay.cu_blk[bits], max_blk=lay.max_blk[bits], bits=bits)
+        if tails[s] is not None:
+            tk, tv, cu, n = tails[s]
+            kw.update(tail_k=tk, tail_v=tv, cu_tail=cu, max_tail=n)
+        return kw
+
+    ws_need = max(vc.vc_draft_workspace_bytes(HQ, HKV, B, **draft_kw(k, W - 1)) for k in ("d1", "d2", "d3"))
+    vargs = dict(k=lay.k_full, v=lay.v_full, cu_ctx=lay.cu_ctx, max_ctx=N, max_win=W)
+    ws_need = max(ws_need, vc.vc_verify_workspace_bytes(HQ, HKV, B, total_win=B * W, **vargs))
+    ws = torch.empty(ws_need, dtype=torch.uint8, device=dev)
+    vout = torch.empty_like(lay.q_win)
+    rows = lay.logits.shape[0]
+    acc = torch.empty(B, dtype=torch.int32, device=dev)
+    nxt = torch.empty(B, dtype=torch.int32, device=dev)
+    amax = torch.empty(rows, dtype=torch.int32, device=dev)
+    aws = torch.empty(vc.vc_accept_workspace_bytes(rows, args.vocab), dtype=torch.uint8, device=dev)
+
+    def ev():
+        return torch.cuda.Event(enable_timing=True)
+
+    def step(record):
+        """One pass of the hot path; `record` collects (leg, start_event, end_event)."""
+        def timed(name, fn):
+            e0, e1 = ev(), ev()
+            e0.record()
+            fn()
+            e1.record()
+            record.append((name, e0, e1))
+        if "keep" in legs:
+            timed("keep", lambda: vc.vc_keep_from_dropped(ctx, lay.dropped_idx, lay.cu_drop, lay.cu_ctx, HKV, N,
+                                                          keep_out, cu_keep_out))
+        for s in range(W):
+            for kind in ("d1", "d2", "d3"):
+                if kind in legs:
+                    kw = draft_kw(kind, s)
+                    timed(kind, lambda kw=kw: vc.vc_draft_attn(ctx, lay.q, lay.scale, out, n_kv_heads=HKV,
+                                                               workspace=ws, **kw))
+        if "verify" in legs:
+            timed("verify", lambda: vc.vc_verify_attn(ctx, lay.q_win, lay.k_win, lay.v_win, lay.cu_win, lay.scale,
+                                                      vout, n_seqs=B, workspace=ws, **vargs))
+        if "accept" in legs:
+            timed("accept", lambda: vc.vc_accept_len(ctx, lay.logits, lay.cu_rows, lay.draft_ids, lay.cu_win,
+                                                     acc, nxt, amax, workspace=aws))
+
+    if "keep" not in legs:   # d1 still needs kept lists
+        vc.vc_keep_from_dropped(ctx, lay.dropped_idx, lay.cu_drop, lay.cu_ctx, HKV, N, keep_out, cu_keep_out)
+    for _ in range(args.warmup):
+        step([])
+    torch.cuda.synchronize()
+    rec = []
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(rec)
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    ms_per_step = wall_ms / args.steps
+
+    dur = {}
+    for name, e0, e1 in rec:
+        dur.setdefault(name, []).append(e0.elapsed_time(e1))
+    mean_ms = {k: sum(v) / len(v) for k, v in dur.items()}
+
+    # algorithmic bytes / flops per call
+    tail_avg = (W - 1) / 2.0
+    by = {
+        "d1": draft_bytes(B, HQ, HKV, kept=keep_n, tail=tail_avg),
+        "d2": draft_bytes(B, HQ, HKV, blocks=N // 32, tail=tail_avg),
+        "d3": draft_bytes(B, HQ, HKV, blocks=N // 64, tail=tail_avg),
+    }
+    verify_flops = B * 4 * HQ * 128 * (W * N + W * (W + 1) / 2)
+    verify_bytes = B * (2 * HKV * N * 256 + 2 * HKV * W * 256 + 2 * W * HQ * 256)
+    accept_bytes = rows * args.vocab * 4
+    res = {}
+    tot_b, tot_t = 0.0, 0.0
+    for k in ("d1", "d2", "d3"):
+        if k in mean_ms:
+            res[k] = {"us": mean_ms[k] * 1e3, "GBps": by[k] / (mean_ms[k] * 1e-3) / 1e9,
+                      "frac_hbm": by[k] / (mean_ms[k] * 1e-3) / 1e9 / HBM_PEAK_GBPS}
+            tot_b += by[k] * len(dur[k])
+            tot_t += sum(dur[k]) * 1e-3
+    value = tot_b / tot_t / 1e9 if tot_t > 0 else 0.0
+    if "verify" in mean_ms:
+        tf = verify_flops / (mean_ms["verify"] * 1e-3) / 1e12
+        ai = verify_flops / verify_bytes
+        attainable = min(MFMA_BF16_PEAK_TFLOPS, ai * HBM_PEAK_GBPS / 1e3)
+        res["verify"] = {"us": mean_ms["verify"] * 1e3, "TFLOPs": tf, "frac_mfma": tf / MFMA_BF16_PEAK_TFLOPS,
+                         "frac_attainable": tf / attainable, "GBps": verify_bytes / (mean_ms["verify"] * 1e-3) / 1e9}
+    if "accept" in mean_ms:
+        res["accept"] = {"us": mean_ms["accept"] * 1e3, "GBps": accept_bytes / (mean_ms["accept"] * 1e-3) / 1e9}
+    if "keep" in mean_ms:
+        res["keep"] = {"us": mean_ms["keep"] * 1e3}
+
+    # roofline of the dominant kernel of a round: the int4 record draft kernel (32 launches per
+    # step against one verify); duration = HIP events around the call (record kernel + tail kernel
+    # + merge kernel), so it is an upper bound of the kernel's own time
+    roofline = None
+    if "d2" in mean_ms:
+        a = by["d2"] / (mean_ms["d2"] * 1e-3) / 1e9
+        roofline = {"bound": "hbm", "kernel": "draft_quant_kernel<4>", "achieved": a, "peak": HBM_PEAK_GBPS,
+                    "unit": "GB/s", "frac": a / HBM_PEAK_GBPS, "traffic": None,
+                    "bytes_per_launch": by["d2"], "avg_us": mean_ms["d2"] * 1e3}
+
+    swap = None
+    if not args.no_swap and "d2" in legs:
+        swap = measure_swap(vc, ctx, lay, torch, draft_kw, out, ws, HKV, N, B, W)
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = cpu_baseline(lay, torch, np, HQ, HKV, N)
+
+    line = {
+        "metric": "draft_attn_hbm_GBps", "value": value, "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16/int4/int2 inputs, fp16+bf16 MFMA, fp32 accumulate", "data": "synthetic",
+        "config": {"workload": f"config2: batch {B}, ctx {N}, 32q/8kv heads, d128, int4 g32 + int2 g64 + 10% token drop, "
+                               f"window {W}, vocab {args.vocab}",
+                   "step": f"keep-index + {W} draft steps x (bf16 gather, int4, int2) + verify + accept"},
+        "legs": res,
+        "verify_TFLOPs": res.get("verify", {}).get("TFLOPs"),
+        "roofline": roofline, "swap": swap, "cpu_baseline": cpu,
+    }
+    print(json.dumps(line))
+    ctx.close()
+
+
+def measure_swap(vc, ctx, lay, torch, draft_kw, out, ws, HKV, N, B, W):
+    """Full-KV reload of every sequence in 8192-token chunks on the copy stream, alone and
+    overlapped with int4 drafting; overlap = (T_draft + T_swap - T_both) / min(T_draft, T_swap)."""
+    dev = lay.k_full.device
+    row_bytes = HKV * 128 * 2
+    host_k = torch.empty(lay.k_full.shape, dtype=torch.bfloat16, pin_memory=True)
+    host_v = torch.empty(lay.v_full.shape, dtype=torch.bfloat16, pin_memory=True)
+    host_k.copy_(lay.k_full)
+    host_v.copy_(lay.v_full)
+    dst_k = torch.empty_like(lay.k_full)
+    dst_v = torch.empty_like(lay.v_full)
+    chunk_tok = 8192
+    chunks = [(t * row_bytes, t * row_bytes, min(chunk_tok, B * N - t) * row_bytes) for t in range(0, B * N, chunk_tok)]
+    total = 2 * B * N * row_bytes
+
+    def swap_all():
+        vc.vc_swap_in(ctx, host_k, dst_k, chunks)
+        return vc.vc_swap_in(ctx, host_v, dst_v, chunks) + len(chunks) - 1
+
+    def drafts(n):
+        for i in range(n):
+            vc.vc_draft_attn(ctx, lay.q, lay.scale, out, n_kv_heads=HKV, workspace=ws, **draft_kw("d2", i % W))
+
+    torch.cuda.synchronize()
+    t0 = time.perf_counter(); swap_all(); vc.vc_swap_sync(ctx); t_swap = time.perf_counter() - t0
+    ok = bool(torch.equal(dst_k[-4096:], lay.k_full[-4096:]) and torch.equal(dst_v[:4096], lay.v_full[:4096]))
+    # enough draft steps to cover the copy
+    drafts(4); torch.cuda.synchronize()
+    t0 = time.perf_counter(); drafts(32); torch.cuda.synchronize(); t32 = time.perf_counter() - t0
+    n_steps = max(32, int(math.ceil(t_swap / (t32 / 32))))
+    t0 = time.perf_counter(); drafts(n_steps); torch.cuda.synchronize(); t_draft = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    last = swap_all()
+    drafts(n_steps)
+    vc.vc_swap_wait(ctx, last)
+    torch.cuda.synchronize()
+    vc.vc_swap_sync(ctx)
+    t_both = time.perf_counter() - t0
+    return {"bytes": total, "chunks": 2 * len(chunks), "swap_alone_ms": t_swap * 1e3, "swap_GBps": total / t_swap / 1e9,
+            "draft_steps": n_steps, "draft_alone_ms": t_draft * 1e3, "both_ms": t_both * 1e3,
+            "overlap": (t_draft + t_swap - t_both) / min(t_draft, t_swap), "bytes_ok": ok,
+            "model_max_ms": max(t_draft, t_swap) * 1e3}
+
+
+def cpu_baseline(lay, torch, np, HQ, HKV, N):
+    """The fp64 oracle, as it stands, on a bounded sample of the same workload: int4 draft
+    attention of a few (sequence, KV head) pairs at full context; single thread."""
+    from oracle import vc_oracle as O
+    try:
+        from threadpoolctl import threadpool_limits
+    except Exception:  # pragma: no cover
+        threadpool_limits = None
+    blocks = lay.blocks[4]
+    nb = N // 32
+    cu = np.array([0, nb], dtype=np.int32)
+    g = HQ // HKV
+    pairs = [(0, 0), (3, 5), (7, 2), (15, 7)]
+    t_total, nbytes = 0.0, 0
+    import contextlib
+    limiter = threadpool_limits(limits=1) if threadpool_limits else contextlib.nullcontext()
+    with limiter:
+        for (b, kvh) in pairs:
+            start = (int(lay.cu_blk[4][b]) * HKV + kvh * nb)
+            rec = blocks[start:start + nb].cpu().numpy()
+            qb = lay.q[b, kvh * g:(kvh + 1) * g].contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+            t0 = time.perf_counter()
+            k, v = O.draft_keys(0, 0, n_kv_heads=1, blocks=rec, cu_blk=cu, bits=4)
+            for h in range(g):
+                O.attend(O.bf16_to_f64(qb[h]), k, v, lay.scale)
+            t_total += time.perf_counter() - t0
+            nbytes += nb * 5120
+    return {"value": nbytes / t_total / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
+            "sample": f"int4 draft attention of {len(pairs)} (sequence, KV head) pairs at ctx {N} "
+                      f"({nbytes / 1e6:.1f} MB of records, {t_total:.1f} s)"}
+
+
+if __name__ == "__main__":
+    main()
