@@ -90,6 +90,8 @@ typedef struct {
   int32_t n_seqs, n_q_heads, n_kv_heads, head_dim;
   int32_t bits;            /* bit scheme of `blocks`: 4 or 2 (ignored when blocks is NULL) */
   int32_t max_keep, max_blk, max_tail;
+  int32_t sum_keep, sum_blk;  /* host hints: sum over sequences of nk / nb (0 = unknown, n_seqs*max is
+                                 assumed); they only steer the load balance, never the result */
   const void* pool_k;      /* (1) */
   const void* pool_v;
   const int32_t* cu_ctx;

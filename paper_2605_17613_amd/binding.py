@@ -26,7 +26,7 @@ class VcError(RuntimeError):
 class vc_comp_kv(C.Structure):
     _fields_ = [("n_seqs", C.c_int32), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32),
                 ("head_dim", C.c_int32), ("bits", C.c_int32), ("max_keep", C.c_int32),
-                ("max_blk", C.c_int32), ("max_tail", C.c_int32),
+                ("max_blk", C.c_int32), ("max_tail", C.c_int32), ("sum_keep", C.c_int32), ("sum_blk", C.c_int32),
                 ("pool_k", C.c_void_p), ("pool_v", C.c_void_p), ("cu_ctx", C.c_void_p),
                 ("keep_idx", C.c_void_p), ("cu_keep", C.c_void_p), ("blocks", C.c_void_p),
                 ("cu_blk", C.c_void_p), ("tail_k", C.c_void_p), ("tail_v", C.c_void_p),
@@ -141,10 +141,12 @@ class Context:
 
 def _comp_desc(n_q_heads, n_kv_heads, n_seqs, *, pool_k=None, pool_v=None, cu_ctx=None, keep_idx=None,
                cu_keep=None, max_keep=0, blocks=None, cu_blk=None, max_blk=0, bits=4,
-               tail_k=None, tail_v=None, cu_tail=None, max_tail=0, head_dim=128):
+               tail_k=None, tail_v=None, cu_tail=None, max_tail=0, sum_keep=0, sum_blk=0,
+               head_dim=128):
     d = vc_comp_kv()
     d.n_seqs, d.n_q_heads, d.n_kv_heads, d.head_dim = n_seqs, n_q_heads, n_kv_heads, head_dim
     d.bits, d.max_keep, d.max_blk, d.max_tail = bits, max_keep, max_blk, max_tail
+    d.sum_keep, d.sum_blk = sum_keep, sum_blk
     d.pool_k = _ptr(pool_k, torch.bfloat16, "pool_k"); d.pool_v = _ptr(pool_v, torch.bfloat16, "pool_v")
     d.cu_ctx = _ptr(cu_ctx, torch.int32, "cu_ctx")
     d.keep_idx = _ptr(keep_idx, torch.int32, "keep_idx"); d.cu_keep = _ptr(cu_keep, torch.int32, "cu_keep")

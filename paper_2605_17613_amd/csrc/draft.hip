@@ -183,14 +183,24 @@ __global__ __launch_bounds__(256) void draft_bf16_kernel(DraftBf16Params p) {
 // --------------------------------------------------------------------------------------------
 // int4 / int2 block records, dequantisation fused into fp16 MFMA tiles
 // --------------------------------------------------------------------------------------------
-// Scores:   s[h][t] = sum_d (q[h][d]*sK[d]) * code[t][d]  +  sum_d q[h][d]*zK[d]
-//           the key scale is folded into the query once per block (a packed fp16 multiply per two
-//           channels), the key zero becomes one extra MFMA per block, and the codes reach the
-//           matrix core as exact small integers in fp16.
-// Output:   o[h][d] = sum_t (p[h][t]*sV[t][G]) * code[t][d]  +  sum_t p[h][t]*zV[t][G]
-//           likewise with the value scale folded into the probabilities per channel group G.
-// MFMA 16x16x32 f16: the 16 rows of the query operand are 4 token tiles x 4 query heads, so a
-// 64-token iteration produces its 256 scores with lane = token, register = head.
+// Everything is laid out so that the matrix core's own register layouts do the data movement and
+// the loop needs neither LDS nor cross-lane shuffles (MFMA 16x16x32 f16, D = A*B + C):
+//
+//   S^T[token][col] = K[token][:] . Q'[col][:]     A = key codes of 16 tokens (exact small integers
+//                                                  in fp16), B = the query with the block's key
+//                                                  scale folded in; col = (slot, query head)
+//   the D layout gives every lane 4 tokens of one column, which is exactly the B layout of
+//   O^T[d][col]    += V^T[d][token] * P'[token][col]   A = value codes, B = probabilities times the
+//                                                  value scale of channel group `slot`
+//   The four column slots carry the four (two for int2) value channel groups, so one pass of the
+//   probabilities serves all groups and each output tile picks the slot of its own group.
+//   The zero points never touch the codes: the key zero is one extra product with an all-ones A
+//   operand (sum_d q[d]*zK[d], the same for every token of the block), the value zero likewise
+//   (sum_t p[t]*zV[t]).
+//   Codes reach the matrix core as fp16 1024 + f*code, built with one and-or per two codes
+//   (0x6400 is fp16 1024; f is 1, 4, 16 or 64 depending on where the field sits in its byte).
+//   1/f is folded into the operand on the other side of the product once, outside the loop, and
+//   the 1024 offset is cancelled by a product with a constant -1024 A operand.
 struct DraftQuantParams {
   const uint16_t* q;
   const uint8_t* blocks;
@@ -208,38 +218,37 @@ __device__ __forceinline__ half8v as_half8(const uint32_t (&u)[4]) {
 }
 __device__ __forceinline__ half2v as_half2(uint32_t u) { return __builtin_bit_cast(half2v, u); }
 __device__ __forceinline__ uint32_t as_u32(half2v h) { return __builtin_bit_cast(uint32_t, h); }
-
-// One 32-bit word of eight 4-bit codes (element e at bit 16*(e&1) + 4*(e>>1)) -> eight exact fp16
-// integers in element order.  0x6400 is fp16 1024: or-ing a code into its mantissa gives 1024+code
-// (or 1024+16*code for the upper nibble of a byte).
-__device__ __forceinline__ void unpack_i4(uint32_t x, uint32_t (&out)[4]) {
-  const uint32_t magic = 0x64006400u;
-  const uint32_t y = x >> 8;
-  const half2v k1024 = {(_Float16)1024.f, (_Float16)1024.f};
-  const half2v k16th = {(_Float16)0.0625f, (_Float16)0.0625f};
-  const half2v k64 = {(_Float16)64.f, (_Float16)64.f};
-  out[0] = as_u32(as_half2((x & 0x000F000Fu) | magic) - k1024);
-  out[1] = as_u32(as_half2((x & 0x00F000F0u) | magic) * k16th - k64);
-  out[2] = as_u32(as_half2((y & 0x000F000Fu) | magic) - k1024);
-  out[3] = as_u32(as_half2((y & 0x00F000F0u) | magic) * k16th - k64);
+__device__ __forceinline__ uint32_t pack_half2(float a, float b) {
+  half2v h;
+  h[0] = (_Float16)a;
+  h[1] = (_Float16)b;
+  return as_u32(h);
 }
 
-// One word of sixteen 2-bit codes (element e at bit 16*(e&1) + 2*(e>>1)) -> sixteen fp16 integers.
-__device__ __forceinline__ void unpack_i2(uint32_t x, uint32_t (&out)[8]) {
-  const uint32_t magic = 0x64006400u;
+// (x & mask) | magic in one VALU op; magic lives in a VGPR so that only one literal is needed
+__device__ __forceinline__ uint32_t and_or(uint32_t x, uint32_t mask, uint32_t magic) { return (x & mask) | magic; }
+
+// Eight 4-bit codes of one word (element e at bit 16*(e&1) + 4*(e>>1)) -> four fp16 pairs in element
+// order holding 1024 + code (pairs 0, 2) or 1024 + 16*code (pairs 1, 3).
+__device__ __forceinline__ void unpack_i4(uint32_t x, uint32_t magic, uint32_t (&out)[4]) {
   const uint32_t y = x >> 8;
-  const half2v s0 = {(_Float16)1.f, (_Float16)1.f}, b0 = {(_Float16)1024.f, (_Float16)1024.f};
-  const half2v s1 = {(_Float16)0.25f, (_Float16)0.25f}, b1 = {(_Float16)256.f, (_Float16)256.f};
-  const half2v s2 = {(_Float16)0.0625f, (_Float16)0.0625f}, b2 = {(_Float16)64.f, (_Float16)64.f};
-  const half2v s3 = {(_Float16)0.015625f, (_Float16)0.015625f}, b3 = {(_Float16)16.f, (_Float16)16.f};
-  out[0] = as_u32(as_half2((x & 0x00030003u) | magic) * s0 - b0);
-  out[1] = as_u32(as_half2((x & 0x000C000Cu) | magic) * s1 - b1);
-  out[2] = as_u32(as_half2((x & 0x00300030u) | magic) * s2 - b2);
-  out[3] = as_u32(as_half2((x & 0x00C000C0u) | magic) * s3 - b3);
-  out[4] = as_u32(as_half2((y & 0x00030003u) | magic) * s0 - b0);
-  out[5] = as_u32(as_half2((y & 0x000C000Cu) | magic) * s1 - b1);
-  out[6] = as_u32(as_half2((y & 0x00300030u) | magic) * s2 - b2);
-  out[7] = as_u32(as_half2((y & 0x00C000C0u) | magic) * s3 - b3);
+  out[0] = and_or(x, 0x000F000Fu, magic);
+  out[1] = and_or(x, 0x00F000F0u, magic);
+  out[2] = and_or(y, 0x000F000Fu, magic);
+  out[3] = and_or(y, 0x00F000F0u, magic);
+}
+// Sixteen 2-bit codes (element e at bit 16*(e&1) + 2*(e>>1)) -> eight fp16 pairs holding
+// 1024 + 4^(r&3) * code for pair r.
+__device__ __forceinline__ void unpack_i2(uint32_t x, uint32_t magic, uint32_t (&out)[8]) {
+  const uint32_t y = x >> 8;
+  out[0] = and_or(x, 0x00030003u, magic);
+  out[1] = and_or(x, 0x000C000Cu, magic);
+  out[2] = and_or(x, 0x00300030u, magic);
+  out[3] = and_or(x, 0x00C000C0u, magic);
+  out[4] = and_or(y, 0x00030003u, magic);
+  out[5] = and_or(y, 0x000C000Cu, magic);
+  out[6] = and_or(y, 0x00300030u, magic);
+  out[7] = and_or(y, 0x00C000C0u, magic);
 }
 
 __device__ __forceinline__ float4v mfma16(const uint32_t (&a)[4], const uint32_t (&b)[4], float4v c) {
@@ -250,11 +259,13 @@ __device__ __forceinline__ void u4_to_arr(const uint4& v, uint32_t (&a)[4]) {
   a[0] = v.x; a[1] = v.y; a[2] = v.z; a[3] = v.w;
 }
 
+constexpr float kLazyMargin = 4.f;  // the running maximum may lag the true one by this much (log2 units)
+
 template <int BITS>
 __global__ __launch_bounds__(256, 2) void draft_quant_kernel(DraftQuantParams p) {
   constexpr int TB = (BITS == 4) ? 32 : 64;   // tokens per block record
-  constexpr int BPI = 64 / TB;                // records per 64-token iteration
-  constexpr int NG = kHeadDim / TB;           // value channel groups
+  constexpr int NT = TB / 16;                 // 16-token score tiles per record
+  constexpr int NKS = TB / 32;                // 32-token k-steps of the output product per record
   const int b = blockIdx.z, sp = blockIdx.x;
   const int kvh = blockIdx.y / p.nquad, quad = blockIdx.y % p.nquad;
   const int nb = p.cu_blk[b + 1] - p.cu_blk[b];
@@ -264,12 +275,17 @@ __global__ __launch_bounds__(256, 2) void draft_quant_kernel(DraftQuantParams p)
   const uint8_t* rec_base =
       p.blocks + (static_cast<size_t>(p.cu_blk[b]) * p.n_kv_heads + static_cast<size_t>(kvh) * nb) * kRecordBytes;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int n = lane & 15, j = lane >> 4;
-  const int tsel = (lane >> 2) & 3, hq = lane & 3;
-  const int hloc = quad * 4 + hq;             // query head inside the GQA group
+  const int n = lane & 15, j = lane >> 4;     // n: column / operand row, j: k-block and D row block
+  const int slot = n >> 2, hq = n & 3;
+  const int G = (BITS == 4) ? slot : (slot & 1);   // value channel group this column carries
+  const int hloc = quad * 4 + hq;
   const bool head_ok = hloc < p.g;
 
-  // query operand rows: row (tsel, hq) = query head hq, channels 32j .. 32j+31 as natural fp16 pairs
+  uint32_t magic = 0x64006400u;
+  asm volatile("" : "+v"(magic));             // keep it in a VGPR (see and_or)
+
+  // query as B operand of the score product: channels 32j .. 32j+31 in natural fp16 pairs, with the
+  // softmax scale, log2(e) and the 1/f of the code field each channel meets folded in
   uint32_t qn[16];
   {
     const uint16_t* qp = p.q + (static_cast<size_t>(b) * p.n_q_heads + kvh * p.g + (head_ok ? hloc : 0)) * kHeadDim + 32 * j;
@@ -279,205 +295,214 @@ __global__ __launch_bounds__(256, 2) void draft_quant_kernel(DraftQuantParams p)
       const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
 #pragma unroll
       for (int k = 0; k < 4; ++k) {
-        half2v h;
-        h[0] = (_Float16)(head_ok ? bf16_lo(w[k]) * p.scale_log2e : 0.f);
-        h[1] = (_Float16)(head_ok ? bf16_hi(w[k]) * p.scale_log2e : 0.f);
-        qn[4 * i + k] = as_u32(h);
+        // pair index 4i+k: int4 words hold 8 channels (pairs k = 0..3 of word i: f = 1,16,1,16);
+        // int2 words hold 16 channels (pairs r = 0..7 of word i/2: f = 4^(r&3), r = 4*(i&1) + k)
+        const float f = (BITS == 4) ? ((k & 1) ? 0.0625f : 1.f) : (k == 0 ? 1.f : k == 1 ? 0.25f : k == 2 ? 0.0625f : 0.015625f);
+        const float sc = head_ok ? p.scale_log2e * f : 0.f;
+        qn[4 * i + k] = pack_half2(bf16_lo(w[k]) * sc, bf16_hi(w[k]) * sc);
       }
     }
   }
-
-  __shared__ _Float16 p_lds[4][4][72];        // per wave: probabilities [head][token], fp16
-  __shared__ float st[4][4][kPartialFloats];  // per wave end state for the cross-wave merge
-
-  float m_run[4], l_part[4];
-  float4v oacc[8], zacc;
+  // per-pair un-scaling constants for operands that must stay un-scaled (the key-zero product)
+  uint32_t finv[4];
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    m_run[i] = -INFINITY;
-    l_part[i] = 0.f;
+  for (int k = 0; k < 4; ++k) {
+    const float f = (BITS == 4) ? ((k & 1) ? 16.f : 1.f) : (k == 0 ? 1.f : k == 1 ? 4.f : k == 2 ? 16.f : 64.f);
+    finv[k] = pack_half2(f, f);
   }
-#pragma unroll
-  for (int ct = 0; ct < 8; ++ct) oacc[ct] = float4v{0.f, 0.f, 0.f, 0.f};
-  zacc = float4v{0.f, 0.f, 0.f, 0.f};
+  const uint32_t ones[4] = {0x3C003C00u, 0x3C003C00u, 0x3C003C00u, 0x3C003C00u};      // fp16 1.0
+  const uint32_t m1024[4] = {0xE400E400u, 0xE400E400u, 0xE400E400u, 0xE400E400u};     // fp16 -1024.0
 
-  for (int it = blk0 + wave * BPI; it < blk1; it += 4 * BPI) {
-    const int nvalid = min(BPI, blk1 - it);   // records present in this iteration (1 or 2)
-    // ---------------- scores ----------------
-    // fold the key scale of this row's block into the query
-    const int gsel = (BITS == 4) ? (tsel >> 1) : 0;
-    const uint8_t* rec_mine = rec_base + static_cast<size_t>(it + min(gsel, nvalid - 1)) * kRecordBytes;
-    uint32_t qf[16];
+  // log2 of the field factor f of each probability register (token position inside its word)
+  // int4: token e of a word -> pair e/2 -> f = 16 if (e/2) odd;  int2: pair r = e/2, f = 4^(r&3)
+  // register index i of score tile T is token 4*T' + i of the word, see below
+  float m_run = -INFINITY;                    // running maximum of this column's head (log2 domain)
+  float l_part = 0.f;                         // this lane's share of sum 2^(s - m_run)
+  float4v oacc[8], ozero;
+#pragma unroll
+  for (int dt = 0; dt < 8; ++dt) oacc[dt] = float4v{0.f, 0.f, 0.f, 0.f};
+  ozero = float4v{0.f, 0.f, 0.f, 0.f};
+
+  for (int blk = blk0 + wave; blk < blk1; blk += 4) {
+    const uint8_t* rec = rec_base + static_cast<size_t>(blk) * kRecordBytes;
+    // ---------------- loads of the whole record share of this lane ----------------
+    uint32_t kw[NT][BITS == 4 ? 4 : 2];
+#pragma unroll
+    for (int T = 0; T < NT; ++T) {
+      // tile row m = n is token (TB/4)*(m>>2) + 4*T + (m&3) of the block
+      const int tok = (TB / 4) * (n >> 2) + 4 * T + (n & 3);
+      if constexpr (BITS == 4) {
+        const uint4 v = *reinterpret_cast<const uint4*>(rec + tok * 64 + 16 * j);
+        kw[T][0] = v.x; kw[T][1] = v.y; kw[T][2] = v.z; kw[T][3] = v.w;
+      } else {
+        const uint2 v = *reinterpret_cast<const uint2*>(rec + tok * 32 + 8 * j);
+        kw[T][0] = v.x; kw[T][1] = v.y;
+      }
+    }
+    uint32_t ksc[16], kzr[16];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const uint4 sc = *reinterpret_cast<const uint4*>(rec_mine + 4096 + 64 * j + 16 * i);
-      const uint32_t w[4] = {sc.x, sc.y, sc.z, sc.w};
-#pragma unroll
-      for (int k = 0; k < 4; ++k) qf[4 * i + k] = as_u32(as_half2(qn[4 * i + k]) * as_half2(w[k]));
+      const uint4 s4 = *reinterpret_cast<const uint4*>(rec + 4096 + 64 * j + 16 * i);
+      const uint4 z4 = *reinterpret_cast<const uint4*>(rec + 4096 + 256 + 64 * j + 16 * i);
+      ksc[4 * i] = s4.x; ksc[4 * i + 1] = s4.y; ksc[4 * i + 2] = s4.z; ksc[4 * i + 3] = s4.w;
+      kzr[4 * i] = z4.x; kzr[4 * i + 1] = z4.y; kzr[4 * i + 2] = z4.z; kzr[4 * i + 3] = z4.w;
     }
-    // key zero term: q . zK, the same for every token of a block
-    float4v bias[BPI];
+    uint32_t vsl[2][4];
 #pragma unroll
-    for (int gi = 0; gi < BPI; ++gi) {
-      const uint8_t* rec = rec_base + static_cast<size_t>(it + min(gi, nvalid - 1)) * kRecordBytes;
-      float4v acc = {0.f, 0.f, 0.f, 0.f};
+    for (int c = 0; c < 2; ++c) u4_to_arr(*reinterpret_cast<const uint4*>(rec + 2048 + (64 * c + lane) * 16), vsl[c]);
+    uint32_t vsc[NKS][4], vzr[NKS][4];
 #pragma unroll
-      for (int s = 0; s < 4; ++s) {
-        const uint4 z = *reinterpret_cast<const uint4*>(rec + 4096 + 256 + 64 * j + 16 * s);
-        uint32_t zb[4];
-        u4_to_arr(z, zb);
-        const uint32_t a[4] = {qn[4 * s], qn[4 * s + 1], qn[4 * s + 2], qn[4 * s + 3]};
-        acc = mfma16(a, zb, acc);
-      }
-      bias[gi] = acc;
+    for (int a = 0; a < NKS; ++a) {
+      // value scale / zero of channel group G for the 8 tokens (TB/4)*j + 8a .. +7
+      const int off = 2 * (G * TB + (TB / 4) * j + 8 * a);
+      u4_to_arr(*reinterpret_cast<const uint4*>(rec + 4608 + off), vsc[a]);
+      u4_to_arr(*reinterpret_cast<const uint4*>(rec + 4608 + 256 + off), vzr[a]);
     }
-    float4v sacc[4];
+
+    // ---------------- scores ----------------
+    uint32_t qf[16], qz[16];
 #pragma unroll
-    for (int t = 0; t < 4; ++t) {
-      const int gi = (BITS == 4) ? (t >> 1) : 0;
-      const uint8_t* rec = rec_base + static_cast<size_t>(it + min(gi, nvalid - 1)) * kRecordBytes;
-      float4v acc = bias[gi];
+    for (int i = 0; i < 16; ++i) {
+      qf[i] = as_u32(as_half2(qn[i]) * as_half2(ksc[i]));                            // q * sK / f
+      qz[i] = as_u32(as_half2(qn[i]) * as_half2(finv[i & 3]) * as_half2(kzr[i]));    // q * zK
+    }
+    float4v init = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      const uint32_t bz[4] = {qz[4 * s], qz[4 * s + 1], qz[4 * s + 2], qz[4 * s + 3]};
+      const uint32_t bf[4] = {qf[4 * s], qf[4 * s + 1], qf[4 * s + 2], qf[4 * s + 3]};
+      init = mfma16(ones, bz, init);       // + sum_d q[d] zK[d]
+      init = mfma16(m1024, bf, init);      // - 1024 * sum_d q'[d]: cancels the code offset
+    }
+    float4v sacc[NT];
+#pragma unroll
+    for (int T = 0; T < NT; ++T) {
+      float4v acc = init;
       if constexpr (BITS == 4) {
-        const int tt = 16 * (t & 1) + n;
-        const uint4 kw = *reinterpret_cast<const uint4*>(rec + tt * 64 + 16 * j);
-        const uint32_t w[4] = {kw.x, kw.y, kw.z, kw.w};
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
-          uint32_t kb[4];
-          unpack_i4(w[s], kb);
-          const uint32_t a[4] = {qf[4 * s], qf[4 * s + 1], qf[4 * s + 2], qf[4 * s + 3]};
-          acc = mfma16(a, kb, acc);
+          uint32_t ka[4];
+          unpack_i4(kw[T][s], magic, ka);
+          const uint32_t bf[4] = {qf[4 * s], qf[4 * s + 1], qf[4 * s + 2], qf[4 * s + 3]};
+          acc = mfma16(ka, bf, acc);
         }
       } else {
-        const int tt = 16 * t + n;
-        const uint2 kw = *reinterpret_cast<const uint2*>(rec + tt * 32 + 8 * j);
-        const uint32_t w[2] = {kw.x, kw.y};
 #pragma unroll
         for (int h2 = 0; h2 < 2; ++h2) {
-          uint32_t kb8[8];
-          unpack_i2(w[h2], kb8);
+          uint32_t k8[8];
+          unpack_i2(kw[T][h2], magic, k8);
 #pragma unroll
           for (int a2 = 0; a2 < 2; ++a2) {
             const int s = 2 * h2 + a2;
-            const uint32_t kb[4] = {kb8[4 * a2], kb8[4 * a2 + 1], kb8[4 * a2 + 2], kb8[4 * a2 + 3]};
-            const uint32_t a[4] = {qf[4 * s], qf[4 * s + 1], qf[4 * s + 2], qf[4 * s + 3]};
-            acc = mfma16(a, kb, acc);
+            const uint32_t ka[4] = {k8[4 * a2], k8[4 * a2 + 1], k8[4 * a2 + 2], k8[4 * a2 + 3]};
+            const uint32_t bf[4] = {qf[4 * s], qf[4 * s + 1], qf[4 * s + 2], qf[4 * s + 3]};
+            acc = mfma16(ka, bf, acc);
           }
         }
       }
-      sacc[t] = acc;
+      sacc[T] = acc;
     }
-    // row (tsel = t, head i) of tile t sits in lanes 16t..16t+15, register i: lane = token
-    float sv[4];
+    // lane (n, j) now holds, for column n, register i of tile T = token (TB/4)*j + 4T + i
+
+    // ---------------- softmax with a lazily updated maximum ----------------
+    float smax = sacc[0][0];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      float x = (j == 0) ? sacc[0][i] : (j == 1) ? sacc[1][i] : (j == 2) ? sacc[2][i] : sacc[3][i];
-      sv[i] = (lane < nvalid * TB) ? x : -INFINITY;
+    for (int T = 0; T < NT; ++T)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) smax = fmaxf(smax, sacc[T][i]);
+    if (__any(smax > m_run + kLazyMargin)) {
+      // agree on the new maximum among the 16 lanes of this head (all slots, all row blocks)
+      float mx = smax;
+      mx = fmaxf(mx, __shfl_xor(mx, 4, 64));
+      mx = fmaxf(mx, __shfl_xor(mx, 8, 64));
+      mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      const float mn = fmaxf(m_run, mx);
+      const float alpha = exp2_diff(m_run, mn);
+      l_part *= alpha;
+#pragma unroll
+      for (int dt = 0; dt < 8; ++dt) oacc[dt] *= alpha;
+      ozero *= alpha;
+      m_run = mn;
     }
-    // ---------------- online softmax (log2 domain) ----------------
-    float pr[4];
+    // probabilities, pre-divided by the field factor of the value code they will meet:
+    // token e of a value word (e = 4*(T&1) + i for int4, 4*(T&3) + i for int2) sits in pair e/2
+    uint32_t pb[NKS][4];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const float mt = wave_max(sv[i]);
-      const float mn = fmaxf(m_run[i], mt);
-      const float alpha = exp2_diff(m_run[i], mn);
-      pr[i] = exp2_diff(sv[i], mn);
-      l_part[i] = l_part[i] * alpha + pr[i];
-      m_run[i] = mn;
+    for (int a = 0; a < NKS; ++a) {
+      float pe[8];
 #pragma unroll
-      for (int ct = 0; ct < 8; ++ct) oacc[ct][i] *= alpha;
-      zacc[i] *= alpha;
-      p_lds[wave][i][lane] = (_Float16)pr[i];
+      for (int e = 0; e < 8; ++e) {
+        const int T = 2 * a + (e >> 2), i = e & 3;
+        const int r = (BITS == 4) ? (e >> 1) : ((8 * a + e) >> 1);
+        const float lf = (BITS == 4) ? ((r & 1) ? 4.f : 0.f) : 2.f * (r & 3);     // log2 f
+        const float f = (BITS == 4) ? ((r & 1) ? 16.f : 1.f) : ((r & 3) == 0 ? 1.f : (r & 3) == 1 ? 4.f : (r & 3) == 2 ? 16.f : 64.f);
+        pe[e] = __builtin_amdgcn_exp2f(sacc[T][i] - (m_run + lf));
+        l_part = fmaf(pe[e], f, l_part);
+      }
+#pragma unroll
+      for (int k = 0; k < 4; ++k) pb[a][k] = pack_half2(pe[2 * k], pe[2 * k + 1]);
     }
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+
     // ---------------- output ----------------
+    uint32_t pg[NKS][4];
 #pragma unroll
-    for (int bi = 0; bi < BPI; ++bi) {
-      if (bi >= nvalid) break;
-      const uint8_t* rec = rec_base + static_cast<size_t>(it + bi) * kRecordBytes;
-      if constexpr (BITS == 4) {
-        uint32_t pa[4];
-        u4_to_arr(*reinterpret_cast<const uint4*>(&p_lds[wave][n & 3][32 * bi + 8 * j]), pa);
-        uint32_t pg[NG][4];
+    for (int a = 0; a < NKS; ++a) {
+      uint32_t pz[4];
 #pragma unroll
-        for (int G = 0; G < NG; ++G) {
-          const uint4 sc = *reinterpret_cast<const uint4*>(rec + 4608 + 64 * G + 16 * j);
-          const uint32_t w[4] = {sc.x, sc.y, sc.z, sc.w};
+      for (int k = 0; k < 4; ++k) {
+        pg[a][k] = as_u32(as_half2(pb[a][k]) * as_half2(vsc[a][k]));                            // p * sV / f
+        const int r = (BITS == 4) ? k : (4 * a + k);
+        pz[k] = as_u32(as_half2(pb[a][k]) * as_half2(finv[(BITS == 4) ? (r & 1) : (r & 3)]) * as_half2(vzr[a][k]));   // p * zV
+      }
+      ozero = mfma16(ones, pz, ozero);        // + sum_t p[t] zV[t][G]
+      ozero = mfma16(m1024, pg[a], ozero);    // - 1024 * sum_t p'[t]: cancels the code offset
+    }
 #pragma unroll
-          for (int k = 0; k < 4; ++k) pg[G][k] = as_u32(as_half2(pa[k]) * as_half2(w[k]));
-        }
-        uint32_t zb[4];
-        u4_to_arr(*reinterpret_cast<const uint4*>(rec + 4608 + 256 + 64 * (n & 3) + 16 * j), zb);
-        zacc = mfma16(pa, zb, zacc);
+    for (int c = 0; c < 2; ++c) {
 #pragma unroll
-        for (int c = 0; c < 2; ++c) {
-          const uint4 slot = *reinterpret_cast<const uint4*>(rec + 2048 + (64 * c + lane) * 16);
-          const uint32_t w[4] = {slot.x, slot.y, slot.z, slot.w};
+      for (int qq = 0; qq < 4; ++qq) {
+        const int dt = 4 * c + qq;
+        if constexpr (BITS == 4) {
+          uint32_t va[4];
+          unpack_i4(vsl[c][qq], magic, va);
+          oacc[dt] = mfma16(va, pg[0], oacc[dt]);
+        } else {
+          uint32_t v8[8];
+          unpack_i2(vsl[c][qq], magic, v8);
 #pragma unroll
-          for (int qq = 0; qq < 4; ++qq) {
-            const int ct = 4 * c + qq;
-            uint32_t vb[4];
-            unpack_i4(w[qq], vb);
-            oacc[ct] = mfma16(pg[ct >> 1], vb, oacc[ct]);
-          }
-        }
-      } else {
-        uint32_t pa[2][4], pg[NG][2][4];
-#pragma unroll
-        for (int a2 = 0; a2 < 2; ++a2) {
-          u4_to_arr(*reinterpret_cast<const uint4*>(&p_lds[wave][n & 3][16 * j + 8 * a2]), pa[a2]);
-#pragma unroll
-          for (int G = 0; G < NG; ++G) {
-            const uint4 sc = *reinterpret_cast<const uint4*>(rec + 4608 + 128 * G + 32 * j + 16 * a2);
-            const uint32_t w[4] = {sc.x, sc.y, sc.z, sc.w};
-#pragma unroll
-            for (int k = 0; k < 4; ++k) pg[G][a2][k] = as_u32(as_half2(pa[a2][k]) * as_half2(w[k]));
-          }
-          uint32_t zb[4];
-          u4_to_arr(*reinterpret_cast<const uint4*>(rec + 4608 + 256 + 128 * (n & 1) + 32 * j + 16 * a2), zb);
-          zacc = mfma16(pa[a2], zb, zacc);
-        }
-#pragma unroll
-        for (int c = 0; c < 2; ++c) {
-          const uint4 slot = *reinterpret_cast<const uint4*>(rec + 2048 + (64 * c + lane) * 16);
-          const uint32_t w[4] = {slot.x, slot.y, slot.z, slot.w};
-#pragma unroll
-          for (int qq = 0; qq < 4; ++qq) {
-            const int ct = 4 * c + qq;
-            uint32_t vb8[8];
-            unpack_i2(w[qq], vb8);
-#pragma unroll
-            for (int a2 = 0; a2 < 2; ++a2) {
-              const uint32_t vb[4] = {vb8[4 * a2], vb8[4 * a2 + 1], vb8[4 * a2 + 2], vb8[4 * a2 + 3]};
-              oacc[ct] = mfma16(pg[ct >> 2][a2], vb, oacc[ct]);
-            }
+          for (int a = 0; a < NKS; ++a) {
+            const uint32_t va[4] = {v8[4 * a], v8[4 * a + 1], v8[4 * a + 2], v8[4 * a + 3]};
+            oacc[dt] = mfma16(va, pg[a], oacc[dt]);
           }
         }
       }
     }
-    __builtin_amdgcn_wave_barrier();
   }
 
   // ---------------- end of split: wave state -> LDS -> merged partial ----------------
-#pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    const float lsum = wave_sum(l_part[i]);
-    if (lane == 0) {
-      st[wave][i][0] = m_run[i];
-      st[wave][i][1] = lsum;
+  __shared__ float st[4][4][kPartialFloats];
+  {
+    // the 16 lanes of a head agree on m_run; sum l over the row blocks j (slots are replicas)
+    float lsum = l_part;
+    lsum += __shfl_xor(lsum, 16, 64);
+    lsum += __shfl_xor(lsum, 32, 64);
+    if (j == 0 && slot == 0) {
+      st[wave][hq][0] = m_run;
+      st[wave][hq][1] = lsum;
     }
+    // output tile dt (channels 16dt..16dt+15) is valid in the columns whose slot carries its group
 #pragma unroll
-    for (int ct = 0; ct < 8; ++ct) {
-      // zero term of (head i, channel group of tile ct) sits in lane G (column G), register i
-      const int G = (BITS == 4) ? (ct >> 1) : (ct >> 2);
-      const float z = __shfl(zacc[i], G, 64);
-      if (j == 0) st[wave][i][2 + 16 * ct + n] = oacc[ct][i] + z;
+    for (int dt = 0; dt < 8; ++dt) {
+      const int Gd = (BITS == 4) ? (dt >> 1) : (dt >> 2);
+      if (slot == Gd) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) st[wave][hq][2 + 16 * dt + 4 * j + i] = oacc[dt][i] + ozero[i];
+      }
     }
   }
   __syncthreads();
-  const int slot = p.slot0 + sp;
+  const int oslot = p.slot0 + sp;
   for (int idx = threadIdx.x; idx < 4 * kHeadDim; idx += 256) {
     const int i = idx >> 7, d = idx & 127;
     const int hl = quad * 4 + i;
@@ -490,7 +515,7 @@ __global__ __launch_bounds__(256, 2) void draft_quant_kernel(DraftQuantParams p)
       acc = fmaf(a, st[w][i][2 + d], acc);
       lsum = fmaf(a, st[w][i][1], lsum);
     }
-    float* dst = p.ws + ((static_cast<size_t>(b) * p.n_q_heads + kvh * p.g + hl) * p.ns + slot) * kPartialFloats;
+    float* dst = p.ws + ((static_cast<size_t>(b) * p.n_q_heads + kvh * p.g + hl) * p.ns + oslot) * kPartialFloats;
     dst[2 + d] = acc;
     if (d == 0) {
       dst[0] = mm;
@@ -500,38 +525,93 @@ __global__ __launch_bounds__(256, 2) void draft_quant_kernel(DraftQuantParams p)
 }
 
 // --------------------------------------------------------------------------------------------
-// merge of the split partials of all sources -> bf16 output (+ natural-log LSE)
+// merge of the split partials, fused with the attention over the bf16 tail -> bf16 output (+ LSE)
 // --------------------------------------------------------------------------------------------
 struct DraftMergeParams {
   const float* ws;
+  const uint16_t* q;
   uint16_t* out;
   float* lse;
   const int* cu_a;      // bf16 source: cu_keep (gather) or cu_ctx (contiguous), or NULL
   const int* cu_blk;    // or NULL
-  const int* cu_tail;   // or NULL
-  int n_q_heads, ns;
-  int split_a, s1, bps, s2, split_t;
+  const uint16_t* tail_k;  // or NULL
+  const uint16_t* tail_v;
+  const int* cu_tail;
+  int n_q_heads, n_kv_heads, g, ns;
+  int split_a, s1, bps;
+  float scale_log2e;
 };
 
+// One workgroup of 128 threads per (sequence, query head).  The tail holds at most a few tens of
+// tokens (this horizon's drafts plus a partial block), so it is attended to here instead of in a
+// launch of its own: thread t scores token t, thread d accumulates channel d.
 __global__ __launch_bounds__(128) void draft_merge_kernel(DraftMergeParams p) {
   const int b = blockIdx.y, h = blockIdx.x, d = threadIdx.x;
   const int n1 = p.cu_a ? ceil_div_dev(p.cu_a[b + 1] - p.cu_a[b], p.split_a) : 0;
   const int n2 = p.cu_blk ? ceil_div_dev(p.cu_blk[b + 1] - p.cu_blk[b], p.bps) : 0;
-  const int n3 = p.cu_tail ? ceil_div_dev(p.cu_tail[b + 1] - p.cu_tail[b], p.split_t) : 0;
   const float* base = p.ws + (static_cast<size_t>(b) * p.n_q_heads + h) * p.ns * kPartialFloats;
   float mm = -INFINITY;
   for (int s = 0; s < n1; ++s) mm = fmaxf(mm, base[static_cast<size_t>(s) * kPartialFloats]);
   for (int s = 0; s < n2; ++s) mm = fmaxf(mm, base[static_cast<size_t>(p.s1 + s) * kPartialFloats]);
-  for (int s = 0; s < n3; ++s) mm = fmaxf(mm, base[static_cast<size_t>(p.s1 + p.s2 + s) * kPartialFloats]);
   float acc = 0.f, lsum = 0.f;
-  for (int src = 0; src < 3; ++src) {
-    const int cnt = src == 0 ? n1 : src == 1 ? n2 : n3;
-    const int off = src == 0 ? 0 : src == 1 ? p.s1 : p.s1 + p.s2;
+  for (int src = 0; src < 2; ++src) {
+    const int cnt = src == 0 ? n1 : n2;
+    const int off = src == 0 ? 0 : p.s1;
+#pragma unroll 4
     for (int s = 0; s < cnt; ++s) {
       const float* pp = base + static_cast<size_t>(off + s) * kPartialFloats;
       const float a = exp2_diff(pp[0], mm);
       acc = fmaf(a, pp[2 + d], acc);
       lsum = fmaf(a, pp[1], lsum);
+    }
+  }
+  if (p.tail_k) {
+    const int t0 = p.cu_tail[b], nt = p.cu_tail[b + 1] - t0;
+    if (nt > 0) {
+      __shared__ float qs[kHeadDim];
+      __shared__ float ps[128];
+      __shared__ float red[2];
+      const int kvh = h / p.g;
+      qs[d] = bf16_bits_to_float(p.q[(static_cast<size_t>(b) * p.n_q_heads + h) * kHeadDim + d]) * p.scale_log2e;
+      __syncthreads();
+      const size_t row_stride = static_cast<size_t>(p.n_kv_heads) * kHeadDim;
+      for (int c0 = 0; c0 < nt; c0 += 128) {
+        const int t = c0 + d;
+        float s = -INFINITY;
+        if (t < nt) {
+          const uint16_t* kr = p.tail_k + static_cast<size_t>(t0 + t) * row_stride + static_cast<size_t>(kvh) * kHeadDim;
+          float a = 0.f;
+#pragma unroll
+          for (int i = 0; i < 16; ++i) {
+            const uint4 raw = *reinterpret_cast<const uint4*>(kr + 8 * i);
+            const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+              a = fmaf(qs[8 * i + 2 * k], bf16_lo(w[k]), a);
+              a = fmaf(qs[8 * i + 2 * k + 1], bf16_hi(w[k]), a);
+            }
+          }
+          s = a;
+        }
+        const float wm = wave_max(s);
+        if ((d & 63) == 0) red[d >> 6] = wm;
+        __syncthreads();
+        const float mn = fmaxf(mm, fmaxf(red[0], red[1]));
+        const float alpha = exp2_diff(mm, mn);
+        ps[d] = exp2_diff(s, mn);
+        __syncthreads();
+        acc *= alpha;
+        lsum *= alpha;
+        const int cn = min(128, nt - c0);
+        const uint16_t* vr = p.tail_v + static_cast<size_t>(t0 + c0) * row_stride + static_cast<size_t>(kvh) * kHeadDim + d;
+        for (int t2 = 0; t2 < cn; ++t2) {
+          const float pv = ps[t2];
+          acc = fmaf(pv, bf16_bits_to_float(vr[static_cast<size_t>(t2) * row_stride]), acc);
+          lsum += pv;
+        }
+        mm = mn;
+        __syncthreads();
+      }
     }
   }
   const float o = lsum > 0.f ? acc / lsum : 0.f;
@@ -543,37 +623,39 @@ __global__ __launch_bounds__(128) void draft_merge_kernel(DraftMergeParams p) {
 // host side
 // --------------------------------------------------------------------------------------------
 struct DraftPlan {
-  int split_a, s1;   // bf16 pool source
-  int bps, s2;       // block records
-  int split_t, s3;   // tail
+  int split_a, s1;   // bf16 pool source: tokens per split, splits of the longest sequence
+  int bps, s2;       // block records: records per split, splits of the longest sequence
   int ns;
 };
 
-static int pick_split(int max_count, int pairs, int unit, int min_per_split) {
-  if (max_count <= 0) return unit;
-  const int target_wgs = env_int("VC_DRAFT_TARGET_WGS", 4096, 1, 1 << 20);
-  int splits = ceil_div(target_wgs, pairs > 0 ? pairs : 1);
-  if (splits < 1) splits = 1;
-  int per = ceil_div(max_count, splits);
-  if (per < min_per_split) per = min_per_split;
-  per = ceil_div(per, unit) * unit;
-  return per;
+// Work is cut into equal chunks so that the whole launch is about one resident round of
+// workgroups (`target`), never smaller than `min_per` units per chunk.
+static int pick_chunk(int64_t sum_units, int max_units, int lists, int unit, int min_per, int target) {
+  if (max_units <= 0) return unit;
+  if (sum_units <= 0) sum_units = static_cast<int64_t>(max_units) * lists;
+  int64_t per = ceil_div64(sum_units, target > 0 ? target : 1);
+  if (per < min_per) per = min_per;
+  if (per > max_units) per = max_units;
+  per = ceil_div64(per, unit) * unit;
+  return static_cast<int>(per);
 }
 
 static DraftPlan make_plan(const vc_comp_kv* kv) {
   DraftPlan pl{};
-  const int pairs = kv->n_seqs * kv->n_kv_heads;
+  const int g = kv->n_q_heads / kv->n_kv_heads;
+  const int lists = kv->n_seqs * kv->n_kv_heads;
   const bool has_a = kv->pool_k != nullptr && kv->max_keep > 0;
   const bool has_b = kv->blocks != nullptr && kv->max_blk > 0;
-  const bool has_t = kv->tail_k != nullptr && kv->max_tail > 0;
-  pl.split_a = pick_split(kv->max_keep, pairs, 64, env_int("VC_DRAFT_MIN_TOK", 256, 64, 1 << 20));
+  const int target_a = env_int("VC_DRAFT_BF16_WGS", 2048, 1, 1 << 20);
+  const int target_b = env_int("VC_DRAFT_QUANT_WGS", 768, 1, 1 << 20);
+  pl.split_a = pick_chunk(static_cast<int64_t>(kv->sum_keep) * kv->n_kv_heads, kv->max_keep, lists, 64,
+                          env_int("VC_DRAFT_MIN_TOK", 256, 64, 1 << 20), target_a);
   pl.s1 = has_a ? ceil_div(kv->max_keep, pl.split_a) : 0;
-  const int unit = kv->bits == 2 ? 4 : 8;  // one 64-token iteration per wave
-  pl.bps = pick_split(kv->max_blk, pairs, unit, env_int("VC_DRAFT_MIN_BLK", 32, 4, 1 << 20));
+  const int nquad = ceil_div(g, 4);
+  pl.bps = pick_chunk(static_cast<int64_t>(kv->sum_blk) * kv->n_kv_heads * nquad, kv->max_blk, lists * nquad, 4,
+                      env_int("VC_DRAFT_MIN_BLK", 16, 4, 1 << 20), target_b);
   pl.s2 = has_b ? ceil_div(kv->max_blk, pl.bps) : 0;
-  pl.split_t = pick_split(kv->max_tail, pairs, 64, 256);
-  pl.s3 = has_t ? ceil_div(kv->max_tail, pl.split_t) : 0;
-  pl.ns = pl.s1 + pl.s2 + pl.s3;
+  pl.ns = pl.s1 + pl.s2;
   if (pl.ns == 0) pl.ns = 1;
   return pl;
 }
@@ -585,8 +667,10 @@ static vc_status check_comp(const vc_comp_kv* kv, const char* who) {
   VC_REQUIRE(kv->n_q_heads % kv->n_kv_heads == 0, VC_ERR_INVALID_ARG, "%s: n_q_heads %d not a multiple of n_kv_heads %d",
              who, kv->n_q_heads, kv->n_kv_heads);
   VC_REQUIRE(kv->n_q_heads / kv->n_kv_heads <= 16, VC_ERR_UNSUPPORTED, "%s: GQA ratio above 16", who);
-  VC_REQUIRE(kv->n_seqs <= 65535 && kv->n_kv_heads * 4 <= 65535, VC_ERR_UNSUPPORTED, "%s: batch too large for one launch", who);
-  VC_REQUIRE(kv->max_keep >= 0 && kv->max_blk >= 0 && kv->max_tail >= 0, VC_ERR_INVALID_ARG, "%s: negative max", who);
+  VC_REQUIRE(kv->n_seqs <= 65535 && kv->n_kv_heads * 4 <= 65535 && kv->n_q_heads <= 65535, VC_ERR_UNSUPPORTED,
+             "%s: batch too large for one launch", who);
+  VC_REQUIRE(kv->max_keep >= 0 && kv->max_blk >= 0 && kv->max_tail >= 0 && kv->sum_keep >= 0 && kv->sum_blk >= 0,
+             VC_ERR_INVALID_ARG, "%s: negative count", who);
   if (kv->pool_k || kv->pool_v) {
     VC_REQUIRE(kv->pool_k && kv->pool_v && kv->cu_ctx, VC_ERR_INVALID_ARG, "%s: pool needs pool_k, pool_v, cu_ctx", who);
     VC_REQUIRE(aligned16(kv->pool_k) && aligned16(kv->pool_v), VC_ERR_INVALID_ARG, "%s: pool not 16-byte aligned", who);
@@ -680,28 +764,20 @@ extern "C" vc_status vc_draft_attn(vc_ctx* ctx, const vc_comp_kv* kv, const void
     if (kv->bits == 4) hipLaunchKernelGGL(draft_quant_kernel<4>, grid, dim3(256), 0, st, qp);
     else hipLaunchKernelGGL(draft_quant_kernel<2>, grid, dim3(256), 0, st, qp);
   }
-  if (pl.s3 > 0) {
-    DraftBf16Params bp{};
-    bp.q = static_cast<const uint16_t*>(q);
-    bp.pk = static_cast<const uint16_t*>(kv->tail_k);
-    bp.pv = static_cast<const uint16_t*>(kv->tail_v);
-    bp.cu_rows = kv->cu_tail;
-    bp.ws = ws;
-    bp.n_q_heads = kv->n_q_heads; bp.n_kv_heads = kv->n_kv_heads; bp.g = g;
-    bp.split_tok = pl.split_t; bp.slot0 = pl.s1 + pl.s2; bp.ns = pl.ns;
-    bp.scale_log2e = sl2;
-    dim3 grid(pl.s3, kv->n_kv_heads, kv->n_seqs);
-    launch_bf16<false>(gp, grid, st, bp);
-  }
   DraftMergeParams mp{};
   mp.ws = ws;
+  mp.q = static_cast<const uint16_t*>(q);
   mp.out = static_cast<uint16_t*>(out);
   mp.lse = lse;
   mp.cu_a = pl.s1 > 0 ? (kv->keep_idx ? kv->cu_keep : kv->cu_ctx) : nullptr;
   mp.cu_blk = pl.s2 > 0 ? kv->cu_blk : nullptr;
-  mp.cu_tail = pl.s3 > 0 ? kv->cu_tail : nullptr;
-  mp.n_q_heads = kv->n_q_heads; mp.ns = pl.ns;
-  mp.split_a = pl.split_a; mp.s1 = pl.s1; mp.bps = pl.bps; mp.s2 = pl.s2; mp.split_t = pl.split_t;
+  const bool has_t = kv->tail_k != nullptr && kv->max_tail > 0;
+  mp.tail_k = has_t ? static_cast<const uint16_t*>(kv->tail_k) : nullptr;
+  mp.tail_v = has_t ? static_cast<const uint16_t*>(kv->tail_v) : nullptr;
+  mp.cu_tail = kv->cu_tail;
+  mp.n_q_heads = kv->n_q_heads; mp.n_kv_heads = kv->n_kv_heads; mp.g = g; mp.ns = pl.ns;
+  mp.split_a = pl.split_a; mp.s1 = pl.s1; mp.bps = pl.bps;
+  mp.scale_log2e = sl2;
   hipLaunchKernelGGL(draft_merge_kernel, dim3(kv->n_q_heads, kv->n_seqs), dim3(128), 0, st, mp);
   VC_HIP(hipGetLastError());
   return VC_OK;

@@ -59,10 +59,17 @@ def test_draft_descriptor_validation():
 def test_draft_workspace_grows_with_work_and_covers_every_split():
     small = ws_bytes(desc(blocks=0x1000, cu_blk=0x2000, max_blk=64))[1]
     big = ws_bytes(desc(blocks=0x1000, cu_blk=0x2000, max_blk=1 << 16))[1]
-    both = ws_bytes(desc(blocks=0x1000, cu_blk=0x2000, max_blk=64, tail_k=0x3000, tail_v=0x4000, cu_tail=0x5000,
-                         max_tail=63))[1]
-    assert small >= 2 * 8 * 130 * 4 and big > small and both == small + 2 * 8 * 130 * 4
+    both = ws_bytes(desc(blocks=0x1000, cu_blk=0x2000, max_blk=64, pool_k=0x3000, pool_v=0x4000, cu_ctx=0x5000,
+                         max_keep=1000))[1]
+    assert small >= 2 * 8 * 130 * 4 and big > small and both > small
     assert small % (130 * 4) == 0
+    # the tail is attended to inside the merge kernel: it needs no partial slots
+    tail = ws_bytes(desc(blocks=0x1000, cu_blk=0x2000, max_blk=64, tail_k=0x3000, tail_v=0x4000, cu_tail=0x5000,
+                         max_tail=63))[1]
+    assert tail == small
+    # the sum hint changes the chunking (load balance), never below one slot per list
+    hinted = ws_bytes(desc(blocks=0x1000, cu_blk=0x2000, max_blk=1 << 16, sum_blk=1 << 16))[1]
+    assert hinted >= big
 
 
 def test_verify_and_accept_host_validation():
