@@ -35,7 +35,7 @@ extern "C" {
 typedef enum {
   VC_OK = 0,
   VC_ERR_INVALID_ARG = 1,  /* null / misaligned pointer, negative size, bad geometry          */
-  VC_ERR_UNSUPPORTED = 2,  /* head_dim != 128, GQA ratio > 16, window > 64, bits not 16/4/2   */
+  VC_ERR_UNSUPPORTED = 2,  /* head_dim != 128, GQA ratio > 16, window too long, bits not 4/2     */
   VC_ERR_WORKSPACE = 3,    /* workspace missing or smaller than the query says                */
   VC_ERR_HIP = 4,          /* a HIP runtime call failed (message holds hipGetErrorString)     */
   VC_ERR_NOT_READY = 5     /* vc_swap_query: the ticket's copy has not finished yet           */
@@ -120,13 +120,14 @@ vc_status vc_draft_attn(vc_ctx* ctx, const vc_comp_kv* kv, const void* q, float 
 typedef struct {
   int32_t n_seqs, n_q_heads, n_kv_heads, head_dim;
   int32_t max_ctx, max_win;
+  int32_t sum_ctx;         /* host hint: sum of context lengths (0 = unknown); load balance only */
   const void* k;           /* device bf16 pools; sequence b owns rows cu_ctx[b] .. cu_ctx[b+1]-1 */
   const void* v;
   const int32_t* cu_ctx;
 } vc_full_kv;
 
 /* Verify attention (paper section 4.1 step 2).  Sequence b brings w_b = cu_win[b+1]-cu_win[b]
- * drafted positions (1 <= w_b <= 64 or 0).  Window row i of head h attends to the sequence's
+ * drafted positions (w_b * n_q_heads / n_kv_heads <= 256, i.e. w_b <= 64 at a GQA ratio of 4; 0 allowed).  Window row i of head h attends to the sequence's
  * full KV and to window rows 0..i (its own position included):
  *   q_win         device bf16 [sum w, n_q_heads, 128]
  *   k_win, v_win  device bf16 pools [sum w, n_kv_heads, 128]

@@ -35,7 +35,7 @@ class vc_comp_kv(C.Structure):
 
 class vc_full_kv(C.Structure):
     _fields_ = [("n_seqs", C.c_int32), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32),
-                ("head_dim", C.c_int32), ("max_ctx", C.c_int32), ("max_win", C.c_int32),
+                ("head_dim", C.c_int32), ("max_ctx", C.c_int32), ("max_win", C.c_int32), ("sum_ctx", C.c_int32),
                 ("k", C.c_void_p), ("v", C.c_void_p), ("cu_ctx", C.c_void_p)]
 
 
@@ -174,27 +174,29 @@ def vc_draft_attn(ctx: Context, q, softmax_scale, out, *, n_kv_heads, lse=None, 
     return out
 
 
-def _full_desc(n_q_heads, n_kv_heads, n_seqs, k, v, cu_ctx, max_ctx, max_win, head_dim=128):
+def _full_desc(n_q_heads, n_kv_heads, n_seqs, k, v, cu_ctx, max_ctx, max_win, head_dim=128, sum_ctx=0):
     d = vc_full_kv()
     d.n_seqs, d.n_q_heads, d.n_kv_heads, d.head_dim = n_seqs, n_q_heads, n_kv_heads, head_dim
-    d.max_ctx, d.max_win = max_ctx, max_win
+    d.max_ctx, d.max_win, d.sum_ctx = max_ctx, max_win, sum_ctx
     d.k = _ptr(k, torch.bfloat16, "k"); d.v = _ptr(v, torch.bfloat16, "v")
     d.cu_ctx = _ptr(cu_ctx, torch.int32, "cu_ctx")
     return d
 
 
-def vc_verify_workspace_bytes(n_q_heads, n_kv_heads, n_seqs, *, k, v, cu_ctx, max_ctx, max_win, total_win) -> int:
-    d = _full_desc(n_q_heads, n_kv_heads, n_seqs, k, v, cu_ctx, max_ctx, max_win)
+def vc_verify_workspace_bytes(n_q_heads, n_kv_heads, n_seqs, *, k, v, cu_ctx, max_ctx, max_win, total_win,
+                              sum_ctx=0) -> int:
+    d = _full_desc(n_q_heads, n_kv_heads, n_seqs, k, v, cu_ctx, max_ctx, max_win, sum_ctx=sum_ctx)
     n = C.c_size_t()
     _check(load().vc_verify_workspace_bytes(C.byref(d), int(total_win), C.byref(n)))
     return n.value
 
 
 def vc_verify_attn(ctx: Context, q_win, k_win, v_win, cu_win, softmax_scale, out, *, k, v, cu_ctx, max_ctx,
-                   max_win, n_seqs, lse=None, workspace=None, stream=None):
+                   max_win, n_seqs, lse=None, workspace=None, stream=None, sum_ctx=0):
     total_win, n_q_heads = q_win.shape[0], q_win.shape[1]
     n_kv_heads = k_win.shape[1]
-    d = _full_desc(n_q_heads, n_kv_heads, n_seqs, k, v, cu_ctx, max_ctx, max_win, head_dim=q_win.shape[2])
+    d = _full_desc(n_q_heads, n_kv_heads, n_seqs, k, v, cu_ctx, max_ctx, max_win, head_dim=q_win.shape[2],
+                   sum_ctx=sum_ctx)
     ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
     _check(load().vc_verify_attn(ctx.handle, C.byref(d), _ptr(q_win, torch.bfloat16, "q_win"),
                                  _ptr(k_win, torch.bfloat16, "k_win"), _ptr(v_win, torch.bfloat16, "v_win"),

@@ -104,6 +104,11 @@ def test_verify_windows(lib, ctx, win, hq, hkv):
     ctx_len = [1000 + 37 * i for i in range(len(win))]
     lay = synth.make_layer(40 + len(win), DEV, ctx_len=ctx_len, n_q_heads=hq, n_kv_heads=hkv, win=win)
     print(f"[verify] win={win} hq={hq} hkv={hkv}", flush=True)
+    if max(win) * (hq // hkv) > 256:          # more than 256 (window x query head) rows per KV head
+        with pytest.raises(lib.VcError) as e:
+            H.gpu_verify(lib, ctx, lay)
+        assert e.value.status == 2
+        return
     out, lse = H.gpu_verify(lib, ctx, lay)
     ref, ref_lse = H.oracle_verify(lay)
     assert H.rel_err(out, ref) <= H.TOL
