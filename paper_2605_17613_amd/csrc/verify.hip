@@ -12,11 +12,9 @@
 //
 // A workgroup (8 waves, two per SIMD so one wave's softmax overlaps the other's MFMAs) owns one
 // chunk of tokens of one (sequence, KV head).  Rows are cut into groups of 32 (one per wave); with
-// R <= 64 rows the waves split each 128-token tile four ways, with R <= 128 two ways, above that
-// every wave takes its own 32 rows of a 32-token tile.  Tiles are double buffered in LDS: the next
-// tile is fetched into registers while the current one is used.
-#include <type_traits>
-
+// R <= 128 rows the waves split each 64-token tile two ways, above that every wave takes its own
+// 32 rows of a 32-token tile.  K/V tiles stream from HBM straight into a ring of LDS stages
+// (direct-to-LDS loads, xor-swizzled 16-byte chunks), several tiles ahead of their use.
 #include "attn_common.h"
 #include "common.h"
 
@@ -36,13 +34,9 @@ struct VerifyParams {
   float scale_log2e;
 };
 
-constexpr int kLdsStride = 136;                 // bf16 per LDS row: 128 + 8 pad (272 bytes)
-constexpr int kTileBytes = 128 * kLdsStride * 2;  // one 128-token K or V tile
-constexpr int kVerifyLds = 4 * kTileBytes;      // K and V, double buffered
+constexpr int kVerifyLds = 128 * 1024;          // ring of K/V tiles in LDS
 constexpr float kVerifyMargin = 4.f;
 constexpr float kMinusBig = -1.0e30f;    // "no key seen yet": finite, so 2^(s - m) needs no special cases
-
-typedef short short4v __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ float16v mfma32(bf16x8v a, bf16x8v b, float16v c) {
   return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
@@ -55,44 +49,65 @@ __device__ __forceinline__ bf16x8v load_bf16x8(const uint16_t* p) {
   return r;
 }
 
-// 16-byte LDS accesses through explicit LDS pointers (ds_read_b128 / ds_write_b128)
+// LDS accesses by raw LDS byte address
 typedef uint32_t u32x4v __attribute__((ext_vector_type(4)));
+typedef short short4v __attribute__((ext_vector_type(4)));
+typedef short short8v __attribute__((ext_vector_type(8)));
 typedef __attribute__((address_space(3))) u32x4v lds_u32x4v;
-__device__ __forceinline__ bf16x8v lds_load_bf16x8(const uint16_t* p) {
-  const u32x4v raw = *(const lds_u32x4v*)(p);
+typedef __attribute__((address_space(3))) short4v lds_short4v;
+__device__ __forceinline__ bf16x8v lds_load_bf16x8(uint32_t addr) {   // ds_read_b128
+  const u32x4v raw = *reinterpret_cast<const lds_u32x4v*>(static_cast<size_t>(addr));
   return __builtin_bit_cast(bf16x8v, raw);
 }
-__device__ __forceinline__ void lds_store16(uint16_t* p, const uint4& v) {
-  const u32x4v raw = {v.x, v.y, v.z, v.w};
-  *(lds_u32x4v*)(p) = raw;
+// Transposing LDS read: the 16 lanes of a block fetch a 4 x 16 patch of 16-bit values (lane 4k+c:
+// row k, columns 4c..4c+3) and lane i of the block receives column i of the patch (4 rows).
+__device__ __forceinline__ short4v lds_read_tr(uint32_t addr) {
+  return __builtin_amdgcn_ds_read_tr16_b64_v4i16(reinterpret_cast<lds_short4v*>(static_cast<size_t>(addr)));
 }
 
-// Transposing LDS read: the 16 lanes of a block fetch a 4 x 16 patch (lane 4k+c: row k, columns
-// 4c..4c+3) and lane i of the block receives column i of the patch (4 rows).
-__device__ __forceinline__ short4v lds_read_tr(const uint16_t* p) {
-  return __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) short4v*)(p));
+// 16-byte chunk c of tile row `row` is stored at chunk position c ^ (row & 15): rows are 256 bytes
+// with no padding (direct-to-LDS loads write 1 KB per wave contiguously), the xor spreads a
+// column of chunks over all banks.
+__device__ __forceinline__ int swz(int row, int chunk) { return row * 256 + ((chunk ^ (row & 15)) << 4); }
+
+// Direct HBM -> LDS load of 16 bytes per lane: lane i's data lands at lds_addr + 16*i (lds_addr is
+// wave-uniform and travels in M0).  Issued as inline assembly so that the compiler's own wait-count
+// bookkeeping does not force every later LDS read to wait for all tiles in flight; the ring below
+// waits for exactly the tile it is about to read.
+__device__ __forceinline__ void load_to_lds(const uint16_t* gsrc, uint32_t lds_addr) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(lds_addr), "v"(gsrc) : "memory");
+}
+
+template <int N_OUTSTANDING>
+__device__ __forceinline__ void wait_vm() {
+  // s_waitcnt with only the vector-memory counter constrained (gfx9 encoding: vmcnt in bits 3:0
+  // and 15:14, expcnt 6:4 and lgkmcnt 11:8 left at "don't wait")
+  __builtin_amdgcn_s_waitcnt((N_OUTSTANDING & 15) | ((N_OUTSTANDING >> 4) << 14) | 0x0F70);
 }
 
 // One wave owns 32 rows (one MFMA row tile) and, of every LDS tile, one 32-token slice.
 // NTG = token slices per tile; the 8 waves of a workgroup form NRG = 8/NTG row groups.
+// Tiles travel HBM -> LDS directly (no registers) through a ring of NSTAGE stages, NSTAGE-1 tiles
+// in flight, one barrier per tile.
 template <int NTG>
-__device__ __forceinline__ void verify_body(const VerifyParams& p, uint16_t* smem, int kvh, int chunk, int w0, int w,
+__device__ __forceinline__ void verify_body(const VerifyParams& p, char* smem, int kvh, int chunk, int w0, int w,
                                             int c0, int N) {
   constexpr int NRG = 8 / NTG;
-  constexpr int TT = 32 * NTG;          // tokens per LDS tile
-  constexpr int NLD = NTG;              // 16-byte loads per thread per matrix per tile (512 threads)
+  constexpr int U = 1;                         // 32-token slices per wave per tile (2 was measured slower: fewer tiles in flight)
+  constexpr int TT = 32 * NTG * U;             // tokens per tile
+  constexpr int STAGE_BYTES = TT * 512;        // K tile then V tile, 256 bytes per row
+  constexpr int NSTAGE = kVerifyLds / STAGE_BYTES;
+  constexpr int LPT = NTG * U;                 // 1 KB wave-loads per matrix per wave per tile: TT*256/1024/8
+  static_assert(NSTAGE >= 2 && NSTAGE <= 8, "ring depth");
   const int R = w * p.g;
   const int total = N + w;
   const int t_begin = chunk * p.chunk_tok;
   const int t_end = min(total, t_begin + p.chunk_tok);
+  const int ntiles = (t_end - t_begin + TT - 1) / TT;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int rg = wave % NRG, tg = wave / NRG;
   const int n = lane & 31, hh = lane >> 5;
   const bool wave_rows = rg * 32 < R;
-
-  // smem in 2-byte elements: buffer 0 = [K tile | V tile], buffer 1 = [K tile | V tile]
-  uint16_t* Ks[2] = {smem, smem + kTileBytes};
-  uint16_t* Vs[2] = {smem + kTileBytes / 2, smem + kTileBytes + kTileBytes / 2};
 
   const int r = rg * 32 + n;
   const bool row_ok = r < R;
@@ -103,6 +118,10 @@ __device__ __forceinline__ void verify_body(const VerifyParams& p, uint16_t* sme
     const uint16_t* qp = p.qw + (static_cast<size_t>(w0 + iw) * p.n_q_heads + kvh * p.g + hq) * kHeadDim + 8 * hh;
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) qb[ks] = load_bf16x8(qp + 16 * ks);
+    // pin the query registers here: their loads must be waited for before the ring starts, or the
+    // wait would sit inside the loop and also drain the tiles in flight
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) asm volatile("" : "+v"(qb[ks]));
   }
 
   float m = kMinusBig, l = 0.f;
@@ -115,138 +134,174 @@ __device__ __forceinline__ void verify_body(const VerifyParams& p, uint16_t* sme
   const size_t row_stride = static_cast<size_t>(p.n_kv_heads) * kHeadDim;
   const size_t head_off = static_cast<size_t>(kvh) * kHeadDim;
 
-  // Two register sets of in-flight tiles: a tile is requested two iterations before it is used,
-  // so two compute phases (not one) cover the HBM latency.
-  uint4 kx[2][NLD], vx[2][NLD];
-  const size_t thr_off = static_cast<size_t>(tid >> 4) * row_stride + head_off + 8 * (tid & 15);
-  const uint16_t* kfast = p.kf + static_cast<size_t>(c0) * row_stride + thr_off;
-  const uint16_t* vfast = p.vf + static_cast<size_t>(c0) * row_stride + thr_off;
-  auto fetch = [&](auto SET, int t) {
-    constexpr int S = decltype(SET)::value;
-    if (t + TT <= N) {                      // whole tile inside the full KV: plain strided loads
-      const size_t toff = static_cast<size_t>(t) * row_stride;
+  // ---- tile loads: wave-load c of this wave covers tile rows 4*(wave + 8c) .. +3 ----
+  const uint32_t lds_base = static_cast<uint32_t>(reinterpret_cast<size_t>((__attribute__((address_space(3))) char*)smem));
+  // fast path (tile entirely inside the full KV): per-lane pointers that advance by one tile
+  const uint16_t* kfast[LPT];
+  const uint16_t* vfast[LPT];
 #pragma unroll
-      for (int c = 0; c < NLD; ++c) {
-        kx[S][c] = *reinterpret_cast<const uint4*>(kfast + toff + static_cast<size_t>(32 * c) * row_stride);
-        vx[S][c] = *reinterpret_cast<const uint4*>(vfast + toff + static_cast<size_t>(32 * c) * row_stride);
+  for (int c = 0; c < LPT; ++c) {
+    const int row = 4 * (wave + 8 * c) + (lane >> 4);
+    const size_t off = static_cast<size_t>(c0 + t_begin + row) * row_stride + head_off + 8 * ((lane & 15) ^ (row & 15));
+    kfast[c] = p.kf + off;
+    vfast[c] = p.vf + off;
+  }
+  const size_t tile_step = static_cast<size_t>(TT) * row_stride;
+  auto issue = [&](int j) {                    // request tile j into stage j % NSTAGE
+    const int t = t_begin + j * TT;
+    const uint32_t stage = lds_base + (j % NSTAGE) * STAGE_BYTES;
+    if (t + TT <= N) {
+#pragma unroll
+      for (int c = 0; c < LPT; ++c) {
+        const int grp = wave + 8 * c;
+        load_to_lds(kfast[c] + static_cast<size_t>(j) * tile_step, __builtin_amdgcn_readfirstlane(stage + grp * 1024));
+        load_to_lds(vfast[c] + static_cast<size_t>(j) * tile_step, __builtin_amdgcn_readfirstlane(stage + TT * 256 + grp * 1024));
       }
     } else {
 #pragma unroll
-      for (int c = 0; c < NLD; ++c) {
-        const int tok = t + 32 * c + (tid >> 4), part = tid & 15;
-        kx[S][c] = uint4{0u, 0u, 0u, 0u};
-        vx[S][c] = uint4{0u, 0u, 0u, 0u};
-        if (tok < N) {
-          const size_t off = static_cast<size_t>(c0 + tok) * row_stride + head_off + 8 * part;
-          kx[S][c] = *reinterpret_cast<const uint4*>(p.kf + off);
-          vx[S][c] = *reinterpret_cast<const uint4*>(p.vf + off);
-        } else if (tok < total) {
-          const size_t off = static_cast<size_t>(w0 + tok - N) * row_stride + head_off + 8 * part;
-          kx[S][c] = *reinterpret_cast<const uint4*>(p.kw + off);
-          vx[S][c] = *reinterpret_cast<const uint4*>(p.vw + off);
-        }
+      for (int c = 0; c < LPT; ++c) {
+        const int grp = wave + 8 * c;
+        const int row = 4 * grp + (lane >> 4);
+        const int chunkpos = (lane & 15) ^ (row & 15);
+        int tok = t + row;
+        tok = tok < total ? tok : total - 1;   // rows past the end re-read the last row; their scores are masked
+        const bool in_full = tok < N;
+        const size_t grow = in_full ? static_cast<size_t>(c0 + tok) : static_cast<size_t>(w0 + tok - N);
+        const size_t off = grow * row_stride + head_off + 8 * chunkpos;
+        load_to_lds((in_full ? p.kf : p.kw) + off, __builtin_amdgcn_readfirstlane(stage + grp * 1024));
+        load_to_lds((in_full ? p.vf : p.vw) + off, __builtin_amdgcn_readfirstlane(stage + TT * 256 + grp * 1024));
       }
     }
   };
-  auto stash = [&](auto SET, int buf) {
-    constexpr int S = decltype(SET)::value;
-#pragma unroll
-    for (int c = 0; c < NLD; ++c) {
-      const int tt = 32 * c + (tid >> 4), part = tid & 15;
-      lds_store16(&Ks[buf][tt * kLdsStride + 8 * part], kx[S][c]);
-      lds_store16(&Vs[buf][tt * kLdsStride + 8 * part], vx[S][c]);
-    }
-  };
-  using Set0 = std::integral_constant<int, 0>;
-  using Set1 = std::integral_constant<int, 1>;
 
-  // transposing-read coordinates of this lane inside a (token, channel) patch
+  // ---- LDS read addresses of this lane, relative to the stage base; slice u of this wave is
+  //      tile rows 32*(tg + NTG*u) .. +31 ----
+  uint32_t kaddr[U][8];
+#pragma unroll
+  for (int u = 0; u < U; ++u)
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) kaddr[u][ks] = swz(32 * (tg + NTG * u) + n, 2 * ks + hh);
+  // transposing read: lane -> (token row, 8-byte half of a 16-byte chunk) inside a 4 x 16 patch
   const int blk16 = lane >> 4;
   const int tr_row = 4 * (blk16 >> 1) + ((lane & 15) >> 2);
-  const int tr_col = 16 * (blk16 & 1) + 4 * (lane & 3);
+  const int tr_chunk = 2 * (blk16 & 1) + ((lane & 3) >> 1);
+  const int tr_sub = 8 * (lane & 1);
+  // V addresses: only the row part depends on (u, kk, half); the chunk xor is the same for rows
+  // that differ by a multiple of 16, so one table for u = 0 plus a constant row offset serves all
+  uint32_t vaddr[4][2][2];
+#pragma unroll
+  for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+    for (int kk = 0; kk < 2; ++kk)
+#pragma unroll
+      for (int h2 = 0; h2 < 2; ++h2)
+        vaddr[dt][kk][h2] = TT * 256 + swz(32 * tg + 16 * kk + 8 * h2 + tr_row, 4 * dt + tr_chunk) + tr_sub;
+  constexpr int kSliceStride = 32 * NTG * 256;  // bytes between slice u and u+1 (a multiple of 16 rows)
 
-  auto compute = [&](int buf, int t) {
-    const int ts = t + 32 * tg;             // first token of this wave's slice
-    if (wave_rows && ts < t_end) {
-      const uint16_t* Kt = Ks[buf] + (32 * tg) * kLdsStride;
-      const uint16_t* Vt = Vs[buf] + (32 * tg) * kLdsStride;
-      // ---- S^T = K Q^T ----
-      float16v sacc;
+  float16v zero16;
 #pragma unroll
-      for (int i = 0; i < 16; ++i) sacc[i] = 0.f;
+  for (int i = 0; i < 16; ++i) zero16[i] = 0.f;
+  asm volatile("" : "+v"(zero16));             // keep one zero accumulator in registers
+
+  auto compute = [&](int j) {
+    const int t = t_begin + j * TT;
+    if (!wave_rows) return;
+    const uint32_t sbase = lds_base + (j % NSTAGE) * STAGE_BYTES;
+    int ts[U];
+    bool live[U];
 #pragma unroll
-      for (int ks = 0; ks < 8; ++ks) {
-        const bf16x8v a = lds_load_bf16x8(&Kt[n * kLdsStride + 16 * ks + 8 * hh]);
-        sacc = mfma32(a, qb[ks], sacc);
-      }
-      // register i of this lane is token row 8*(i/4) + 4*hh + i%4 of the slice, for row n
-      float s[16];
+    for (int u = 0; u < U; ++u) {
+      ts[u] = t + 32 * (tg + NTG * u);          // first token of slice u
+      live[u] = ts[u] < t_end;
+    }
+    if (!live[0]) return;
+    // ---- S^T = K Q^T, the slices' accumulator chains interleaved ----
+    float16v sacc[U];
 #pragma unroll
-      for (int i = 0; i < 16; ++i) s[i] = sacc[i] * p.scale_log2e;
-      if (ts + 32 > min(N, t_end)) {        // slice touches the window or the end of the chunk
+    for (int u = 0; u < U; ++u) sacc[u] = zero16;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) {
+#pragma unroll
+      for (int u = 0; u < U; ++u)
+        if (live[u]) sacc[u] = mfma32(lds_load_bf16x8(sbase + kaddr[u][ks]), qb[ks], sacc[u]);
+    }
+    // register i of this lane is token row 8*(i/4) + 4*hh + i%4 of the slice, for row n
+    float mt = -INFINITY;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      if (!live[u]) continue;
+      if (ts[u] + 32 > min(N, t_end)) {        // slice touches the window or the end of the chunk
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
-          const int tok = ts + 8 * (i >> 2) + 4 * hh + (i & 3);
+          const int tok = ts[u] + 8 * (i >> 2) + 4 * hh + (i & 3);
           const bool ok = tok < t_end && (tok < N || tok - N <= iw);
-          s[i] = ok ? s[i] : -INFINITY;
+          sacc[u][i] = ok ? sacc[u][i] : -INFINITY;
         }
       }
-      float mt = s[0];
 #pragma unroll
-      for (int i = 1; i < 16; ++i) mt = fmaxf(mt, s[i]);
-      if (__any(mt > m + kVerifyMargin)) {
-        const float mx = fmaxf(mt, __shfl_xor(mt, 32, 64));
-        const float mn = fmaxf(m, mx);
-        const float alpha = __builtin_amdgcn_exp2f(m - mn);
-        l *= alpha;
+      for (int i = 0; i < 16; ++i) mt = fmaxf(mt, sacc[u][i]);
+    }
+    mt *= p.scale_log2e;                       // the scale is positive: max commutes with it
+    if (__any(mt > m + kVerifyMargin)) {
+      const float mx = fmaxf(mt, __shfl_xor(mt, 32, 64));
+      const float mn = fmaxf(m, mx);
+      const float alpha = __builtin_amdgcn_exp2f(m - mn);
+      l *= alpha;
 #pragma unroll
-        for (int dt = 0; dt < 4; ++dt)
+      for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
-          for (int i = 0; i < 16; ++i) oacc[dt][i] *= alpha;
-        m = mn;
+        for (int i = 0; i < 16; ++i) oacc[dt][i] *= alpha;
+      m = mn;
+    }
+    bf16x8v pb[U][2];
+    float ps0 = 0.f, ps1 = 0.f;
+    const float negm = -m;
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      if (!live[u]) continue;
+#pragma unroll
+      for (int i = 0; i < 16; i += 2) {
+        const float p0 = __builtin_amdgcn_exp2f(fmaf(sacc[u][i], p.scale_log2e, negm));
+        const float p1 = __builtin_amdgcn_exp2f(fmaf(sacc[u][i + 1], p.scale_log2e, negm));
+        ps0 += p0;
+        ps1 += p1;
+        pb[u][i >> 3][i & 7] = (__bf16)p0;
+        pb[u][i >> 3][(i & 7) + 1] = (__bf16)p1;
       }
-      bf16x8v pb[2];
-      float ps = 0.f;
+    }
+    l += ps0 + ps1;
+    // ---- O^T += V^T P^T ; A element e of k-step kk is token row 16kk + 8(e/4) + 4hh + e%4 ----
 #pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const float pr = __builtin_amdgcn_exp2f(s[i] - m);
-        ps += pr;
-        pb[i >> 3][i & 7] = (__bf16)pr;
-      }
-      l += ps;
-      // ---- O^T += V^T P^T ; A element e of k-step kk is token row 16kk + 8(e/4) + 4hh + e%4 ----
+    for (int u = 0; u < U; ++u) {
+      if (!live[u]) continue;
 #pragma unroll
-      for (int dt = 0; dt < 4; ++dt) {
+      for (int kk = 0; kk < 2; ++kk) {
 #pragma unroll
-        for (int kk = 0; kk < 2; ++kk) {
-          const uint16_t* base = Vt + (16 * kk + tr_row) * kLdsStride + 32 * dt + tr_col;
-          const short4v lo = lds_read_tr(base);
-          const short4v hi = lds_read_tr(base + 8 * kLdsStride);
-          bf16x8v av;
-          const short sv8[8] = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-          __builtin_memcpy(&av, sv8, 16);
-          oacc[dt] = mfma32(av, pb[kk], oacc[dt]);
+        for (int dt = 0; dt < 4; ++dt) {
+          const short4v lo = lds_read_tr(sbase + u * kSliceStride + vaddr[dt][kk][0]);
+          const short4v hi = lds_read_tr(sbase + u * kSliceStride + vaddr[dt][kk][1]);
+          const short8v both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+          oacc[dt] = mfma32(__builtin_bit_cast(bf16x8v, both), pb[u][kk], oacc[dt]);
         }
       }
     }
   };
 
-  // tile j lives in register set j%2 and LDS buffer j%2
-  fetch(Set0{}, t_begin);
-  stash(Set0{}, 0);
-  if (t_begin + TT < t_end) fetch(Set1{}, t_begin + TT);
-  if (t_begin + 2 * TT < t_end) fetch(Set0{}, t_begin + 2 * TT);
-  __syncthreads();
-  for (int t = t_begin; t < t_end; t += 2 * TT) {
-    compute(0, t);
-    if (t + TT < t_end) stash(Set1{}, 1);
-    if (t + 3 * TT < t_end) fetch(Set1{}, t + 3 * TT);
-    __syncthreads();
-    if (t + TT >= t_end) break;
-    compute(1, t + TT);
-    if (t + 2 * TT < t_end) stash(Set0{}, 0);
-    if (t + 4 * TT < t_end) fetch(Set0{}, t + 4 * TT);
-    __syncthreads();
+  // ---- ring: tile j is requested NSTAGE-1 iterations before it is used ----
+#pragma unroll
+  for (int j = 0; j < NSTAGE - 1; ++j)
+    if (j < ntiles) issue(j);
+  for (int j = 0; j < ntiles; ++j) {
+    // this wave's loads of tile j have landed once at most the loads of the younger tiles are
+    // outstanding; near the end fewer tiles are in flight, so the count shrinks
+    const int younger = min(NSTAGE - 2, ntiles - 1 - j);
+    if (younger <= 0) wait_vm<0>();
+    else if (younger == 1) wait_vm<(NSTAGE > 2 ? 1 : 0) * 2 * LPT>();
+    else if (younger == 2) wait_vm<(NSTAGE > 3 ? 2 : 0) * 2 * LPT>();
+    else wait_vm<(NSTAGE > 4 ? 3 : 0) * 2 * LPT>();
+    __syncthreads();                            // every wave's share of tile j is in LDS; tile j-1 is no longer read
+    if (j + NSTAGE - 1 < ntiles) issue(j + NSTAGE - 1);   // into the stage tile j-1 just left
+    compute(j);
   }
 
   if (!wave_rows) return;
@@ -264,18 +319,16 @@ __device__ __forceinline__ void verify_body(const VerifyParams& p, uint16_t* sme
     for (int i = 0; i < 16; ++i) dst[2 + 32 * dt + 8 * (i >> 2) + 4 * hh + (i & 3)] = oacc[dt][i];
 }
 
-__device__ __forceinline__ int tokens_split(int rows) { return rows <= 64 ? 4 : rows <= 128 ? 2 : 1; }
+__device__ __forceinline__ int tokens_split(int rows) { return rows <= 128 ? 2 : 1; }
 
 __global__ __launch_bounds__(512) void verify_kernel(VerifyParams p) {
-  extern __shared__ __attribute__((aligned(16))) uint16_t smem[];
+  extern __shared__ __attribute__((aligned(1024))) char smem[];
   const int b = blockIdx.z, kvh = blockIdx.y, chunk = blockIdx.x;
   const int w0 = p.cu_win[b], w = p.cu_win[b + 1] - w0;
   if (w == 0) return;
   const int c0 = p.cu_ctx[b], N = p.cu_ctx[b + 1] - c0;
   if (chunk * p.chunk_tok >= N + w) return;
-  const int ntg = tokens_split(w * p.g);
-  if (ntg == 4) verify_body<4>(p, smem, kvh, chunk, w0, w, c0, N);
-  else if (ntg == 2) verify_body<2>(p, smem, kvh, chunk, w0, w, c0, N);
+  if (tokens_split(w * p.g) == 2) verify_body<2>(p, smem, kvh, chunk, w0, w, c0, N);
   else verify_body<1>(p, smem, kvh, chunk, w0, w, c0, N);
 }
 
