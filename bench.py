@@ -48,6 +48,8 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-swap", action="store_true")
     ap.add_argument("--only", default="", help="comma list of legs to run per step: keep,d1,d2,d3,verify,accept")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="also run a plain 1 GiB device copy (reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     return ap.parse_args()
 
 
@@ -106,17 +108,18 @@ def main():
         kw = {}
         if kind == "d1":
             kw.update(pool_k=lay.k_full, pool_v=lay.v_full, cu_ctx=lay.cu_ctx, keep_idx=keep_out,
-                      cu_keep=cu_keep_out, max_keep=keep_n)
+                      cu_keep=cu_keep_out, max_keep=keep_n, sum_keep=keep_n * B)
         else:
             bits = 4 if kind == "d2" else 2
-            kw.update(blocks=lay.blocks[bits], cu_blk=lay.cu_blk[bits], max_blk=lay.max_blk[bits], bits=bits)
+            kw.update(blocks=lay.blocks[bits], cu_blk=lay.cu_blk[bits], max_blk=lay.max_blk[bits], bits=bits,
+                      sum_blk=lay.max_blk[bits] * B)
         if tails[s] is not None:
             tk, tv, cu, n = tails[s]
             kw.update(tail_k=tk, tail_v=tv, cu_tail=cu, max_tail=n)
         return kw
 
     ws_need = max(vc.vc_draft_workspace_bytes(HQ, HKV, B, **draft_kw(k, W - 1)) for k in ("d1", "d2", "d3"))
-    vargs = dict(k=lay.k_full, v=lay.v_full, cu_ctx=lay.cu_ctx, max_ctx=N, max_win=W)
+    vargs = dict(k=lay.k_full, v=lay.v_full, cu_ctx=lay.cu_ctx, max_ctx=N, max_win=W, sum_ctx=N * B)
     ws_need = max(ws_need, vc.vc_verify_workspace_bytes(HQ, HKV, B, total_win=B * W, **vargs))
     ws = torch.empty(ws_need, dtype=torch.uint8, device=dev)
     vout = torch.empty_like(lay.q_win)
@@ -155,6 +158,16 @@ def main():
 
     if "keep" not in legs:   # d1 still needs kept lists
         vc.vc_keep_from_dropped(ctx, lay.dropped_idx, lay.cu_drop, lay.cu_ctx, HKV, N, keep_out, cu_keep_out)
+    if args.calib_copy:
+        # 1 GiB read + 1 GiB written by a plain elementwise kernel with 16-byte accesses per lane,
+        # the same access width the library's kernels use (the derived counters price a 128-byte
+        # request as 64 bytes, so the reference must issue the same kind of request)
+        src = torch.zeros(1 << 29, dtype=torch.bfloat16, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.mul(src, 1, out=dst)
+        torch.cuda.synchronize()
+        del src, dst
     for _ in range(args.warmup):
         step([])
     torch.cuda.synchronize()
@@ -207,9 +220,13 @@ def main():
     roofline = None
     if "d2" in mean_ms:
         a = by["d2"] / (mean_ms["d2"] * 1e-3) / 1e9
+        # HBM bytes per launch from the committed rocprofv3 PMC runs (profiles/hbm_traffic_config2_round.txt:
+        # FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000); only valid for the default config-2 sizes
+        traffic = 1343.1e6 + 1.7e6 if (B, N, W) == (16, 65536, 32) else None
         roofline = {"bound": "hbm", "kernel": "draft_quant_kernel<4>", "achieved": a, "peak": HBM_PEAK_GBPS,
-                    "unit": "GB/s", "frac": a / HBM_PEAK_GBPS, "traffic": None,
-                    "bytes_per_launch": by["d2"], "avg_us": mean_ms["d2"] * 1e3}
+                    "unit": "GB/s", "frac": a / HBM_PEAK_GBPS, "traffic": traffic,
+                    "bytes_per_launch": by["d2"], "avg_us": mean_ms["d2"] * 1e3,
+                    "timed": "HIP events around vc_draft_attn (record kernel + merge/tail kernel)"}
 
     swap = None
     if not args.no_swap and "d2" in legs:

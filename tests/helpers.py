@@ -72,14 +72,14 @@ def oracle_draft(lay, kw):
                         **oracle_kv_args(kw))
 
 
-def gpu_verify(vc, ctx, lay, k_full=None, v_full=None):
+def gpu_verify(vc, ctx, lay, k_full=None, v_full=None, sum_ctx=0):
     k_full = lay.k_full if k_full is None else k_full
     v_full = lay.v_full if v_full is None else v_full
     nseq = len(lay.ctx_len)
     tw = lay.q_win.shape[0]
     out = torch.empty_like(lay.q_win)
     lse = torch.empty((tw, lay.n_q_heads), dtype=torch.float32, device=lay.q_win.device)
-    args = dict(k=k_full, v=v_full, cu_ctx=lay.cu_ctx, max_ctx=max(lay.ctx_len), max_win=max(lay.win))
+    args = dict(k=k_full, v=v_full, cu_ctx=lay.cu_ctx, max_ctx=max(lay.ctx_len), max_win=max(lay.win), sum_ctx=sum_ctx)
     nbytes = vc.vc_verify_workspace_bytes(lay.n_q_heads, lay.n_kv_heads, nseq, total_win=tw, **args)
     ws = torch.empty(max(nbytes, 16), dtype=torch.uint8, device=lay.q_win.device)
     vc.vc_verify_attn(ctx, lay.q_win, lay.k_win, lay.v_win, lay.cu_win, lay.scale, out, n_seqs=nseq, lse=lse,

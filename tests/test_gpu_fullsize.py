@@ -1,0 +1,175 @@
+"""GPU parity at the full sizes of the five workloads, in the launch configuration bench.py times.
+The oracle cannot do a whole full-size case in seconds, so it computes sampled outputs one by one
+(seeded choice of (sequence, head) pairs and window rows) from CPU copies of the very same
+tensors; accept_len / next_token / arg-max ids and kept-index lists are compared in full."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import vc_oracle as O
+from paper_2605_17613_amd import synth
+from tests import helpers as H
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+@pytest.fixture(scope="module")
+def ctx(lib):
+    c = lib.Context(0)
+    yield c
+    c.close()
+
+
+def seq_slice(lay, b):
+    lo, hi = int(lay.cu_ctx[b]), int(lay.cu_ctx[b + 1])
+    return lo, hi
+
+
+def oracle_draft_sample(lay, kw, b, h):
+    """Oracle draft output of (sequence b, query head h) from per-sequence CPU copies."""
+    g = lay.n_q_heads // lay.n_kv_heads
+    kvh = h // g
+    o = {}
+    if "pool_k" in kw:
+        lo, hi = seq_slice(lay, b)
+        o.update(pool_k=H.bits16(kw["pool_k"][lo:hi, kvh:kvh + 1]), pool_v=H.bits16(kw["pool_v"][lo:hi, kvh:kvh + 1]),
+                 cu_ctx=np.array([0, hi - lo]))
+        if "keep_idx" in kw:
+            cuk = kw["cu_keep"].cpu().numpy()
+            nk = int(cuk[b + 1] - cuk[b])
+            start = int(cuk[b]) * lay.n_kv_heads + kvh * nk
+            o.update(keep_idx=kw["keep_idx"][start:start + nk].cpu().numpy(), cu_keep=np.array([0, nk]))
+    if "blocks" in kw:
+        cub = kw["cu_blk"].cpu().numpy()
+        nb = int(cub[b + 1] - cub[b])
+        start = int(cub[b]) * lay.n_kv_heads + kvh * nb
+        o.update(blocks=kw["blocks"][start:start + nb].cpu().numpy(), cu_blk=np.array([0, nb]), bits=kw["bits"])
+    if "tail_k" in kw:
+        cut = kw["cu_tail"].cpu().numpy()
+        lo, hi = int(cut[b]), int(cut[b + 1])
+        o.update(tail_k=H.bits16(kw["tail_k"][lo:hi, kvh:kvh + 1]), tail_v=H.bits16(kw["tail_v"][lo:hi, kvh:kvh + 1]),
+                 cu_tail=np.array([0, hi - lo]))
+    q = H.bits16(lay.q[b:b + 1, h:h + 1])
+    out, lse = O.draft_attn_one(q, 0, 0, lay.scale, n_q_heads=1, n_kv_heads=1, **o)
+    return out, lse
+
+
+def oracle_verify_sample(lay, b, i, h):
+    g = lay.n_q_heads // lay.n_kv_heads
+    kvh = h // g
+    lo, hi = seq_slice(lay, b)
+    w0, w1 = int(lay.cu_win[b]), int(lay.cu_win[b + 1])
+    return O.verify_attn_one(H.bits16(lay.q_win[w0:w1, h:h + 1]), H.bits16(lay.k_full[lo:hi, kvh:kvh + 1]),
+                             H.bits16(lay.v_full[lo:hi, kvh:kvh + 1]), H.bits16(lay.k_win[w0:w1, kvh:kvh + 1]),
+                             H.bits16(lay.v_win[w0:w1, kvh:kvh + 1]), np.array([0, hi - lo]), np.array([0, w1 - w0]),
+                             0, i, 0, lay.scale, n_q_heads=1, n_kv_heads=1)
+
+
+def check_draft_samples(lib, ctx, lay, kw, samples, tag):
+    print(f"[full] draft {tag}", flush=True)
+    out, lse = H.gpu_draft(lib, ctx, lay, **kw)
+    outc, lsec = out.float().cpu().numpy().astype(np.float64), lse.cpu().numpy()
+    scale = np.abs(outc).max()
+    for (b, h) in samples:
+        ref, ref_lse = oracle_draft_sample(lay, kw, b, h)
+        err = np.abs(outc[b, h] - ref).max() / max(np.abs(ref).max(), 1e-30)
+        # per-row bound against the row's own magnitude is stricter than the tensor-wide bound
+        assert np.abs(outc[b, h] - ref).max() <= H.TOL * max(scale, np.abs(ref).max()), f"{tag} ({b},{h}) err {err}"
+        assert abs(lsec[b, h] - ref_lse) <= H.LSE_TOL
+    assert torch.isfinite(out.float()).all()
+
+
+def check_verify_samples(lib, ctx, lay, samples, tag, **kw):
+    print(f"[full] verify {tag}", flush=True)
+    out, lse = H.gpu_verify(lib, ctx, lay, **kw)
+    outc, lsec = out.float().cpu().numpy().astype(np.float64), lse.cpu().numpy()
+    scale = np.abs(outc).max()
+    for (b, i, h) in samples:
+        ref, ref_lse = oracle_verify_sample(lay, b, i, h)
+        row = int(lay.cu_win[b]) + i
+        assert np.abs(outc[row, h] - ref).max() <= H.TOL * max(scale, np.abs(ref).max()), f"{tag} ({b},{i},{h})"
+        assert abs(lsec[row, h] - ref_lse) <= H.LSE_TOL
+    assert torch.isfinite(out.float()).all()
+
+
+def check_accept_full(lib, ctx, lay):
+    a, n, am = H.gpu_accept(lib, ctx, lay)
+    ra, rn, ram = H.oracle_accept(lay)
+    assert np.array_equal(am, ram) and np.array_equal(a, ra) and np.array_equal(n, rn)
+    assert a.tolist() == lay.prefix_len
+
+
+def test_config0_full(lib, ctx):
+    lay = synth.config(0, DEV)
+    kw = H.draft_kwargs(lay, bits=4)
+    out, _ = H.gpu_draft(lib, ctx, lay, **kw)
+    ref, _ = H.oracle_draft(lay, kw)
+    assert H.rel_err(out, ref) <= H.TOL
+    vout, _ = H.gpu_verify(lib, ctx, lay)
+    vref, _ = H.oracle_verify(lay)
+    assert H.rel_err(vout, vref) <= H.TOL
+    check_accept_full(lib, ctx, lay)
+
+
+def test_config1_full(lib, ctx):
+    lay = synth.config(1, DEV)
+    # kept lists: the library's complement of the dropped lists must equal the compressor's lists
+    keep = torch.empty_like(lay.keep_idx)
+    cu_keep = torch.empty_like(lay.cu_keep)
+    lib.vc_keep_from_dropped(ctx, lay.dropped_idx, lay.cu_drop, lay.cu_ctx, lay.n_kv_heads, max(lay.ctx_len), keep, cu_keep)
+    torch.cuda.synchronize()
+    ref_keep, ref_cu = O.keep_from_dropped(H.npi(lay.dropped_idx), H.npi(lay.cu_drop), lay.ctx_len, lay.n_kv_heads)
+    assert np.array_equal(keep.cpu().numpy(), ref_keep) and np.array_equal(cu_keep.cpu().numpy(), ref_cu)
+    assert torch.equal(keep, lay.keep_idx)
+    kw = H.draft_kwargs(lay, use_pool=True, use_keep=True)
+    kw.update(keep_idx=keep, cu_keep=cu_keep, sum_keep=int(cu_keep[-1]))
+    check_draft_samples(lib, ctx, lay, kw, [(0, 0), (3, 17), (7, 31), (5, 6)], "cfg1 gather")
+    check_verify_samples(lib, ctx, lay, [(0, 0, 0), (2, 15, 9), (7, 7, 31)], "cfg1 w16")
+    check_accept_full(lib, ctx, lay)
+
+
+def test_config2_full(lib, ctx):
+    lay = synth.config(2, DEV)
+    for bits in (4, 2):
+        kw = H.draft_kwargs(lay, bits=bits)
+        kw.update(sum_blk=int(lay.cu_blk[bits][-1]))
+        check_draft_samples(lib, ctx, lay, kw, [(0, 0), (9, 13), (15, 31)], f"cfg2 int{bits}")
+    # full KV through pinned host memory in 8192-token chunks, verify waits on the last ticket
+    host_k = torch.empty(lay.k_full.shape, dtype=torch.bfloat16, pin_memory=True); host_k.copy_(lay.k_full)
+    host_v = torch.empty(lay.v_full.shape, dtype=torch.bfloat16, pin_memory=True); host_v.copy_(lay.v_full)
+    dk = torch.full_like(lay.k_full, float("nan")); dv = torch.full_like(lay.v_full, float("nan"))
+    row = lay.n_kv_heads * 128 * 2
+    total = lay.k_full.shape[0]
+    chunks = [(t * row, t * row, min(8192, total - t) * row) for t in range(0, total, 8192)]
+    torch.cuda.synchronize()
+    lib.vc_swap_in(ctx, host_k, dk, chunks)
+    last = lib.vc_swap_in(ctx, host_v, dv, chunks) + len(chunks) - 1
+    lib.vc_swap_wait(ctx, last)                       # device-side wait on the current stream
+    check_verify_samples(lib, ctx, lay, [(0, 0, 3), (8, 31, 20), (15, 16, 31)], "cfg2 w32 after swap-in", k_full=dk, v_full=dv)
+    assert torch.equal(dk, lay.k_full) and torch.equal(dv, lay.v_full)
+    check_accept_full(lib, ctx, lay)
+
+
+def test_config3_one_layer_full(lib, ctx):
+    lay = synth.config(3, DEV)
+    kw = H.draft_kwargs(lay, bits=4, use_tail=True)
+    check_draft_samples(lib, ctx, lay, kw, [(0, 0), (0, 21)], "cfg3 int4 + 63-token tail")
+    check_verify_samples(lib, ctx, lay, [(0, 0, 1), (0, 63, 30), (0, 40, 12)], "cfg3 w64")
+    check_accept_full(lib, ctx, lay)
+
+
+def test_config4_ragged_full(lib, ctx):
+    lay = synth.config(4, DEV)
+    nseq = len(lay.ctx_len)
+    kw = H.draft_kwargs(lay, bits=4, use_pool=True, use_keep=True, use_tail=True)
+    kw.update(sum_keep=int(lay.cu_keep[-1]), sum_blk=int(lay.cu_blk[4][-1]))
+    rng = np.random.default_rng(4)
+    samples = [(int(b), int(h)) for b, h in zip(rng.integers(0, nseq, 8), rng.integers(0, 32, 8))]
+    longest = int(np.argmax(lay.ctx_len)); shortest = int(np.argmin(lay.ctx_len))
+    samples += [(longest, 5), (shortest, 30)]
+    check_draft_samples(lib, ctx, lay, kw, samples, "cfg4 ragged mixed")
+    vs = [(int(b), int(rng.integers(0, lay.win[int(b)])), int(h)) for b, h in zip(rng.integers(0, nseq, 5), rng.integers(0, 32, 5))]
+    vs += [(longest, lay.win[longest] - 1, 0), (shortest, 0, 31)]
+    check_verify_samples(lib, ctx, lay, vs, "cfg4 ragged windows", sum_ctx=int(sum(lay.ctx_len)))
+    check_accept_full(lib, ctx, lay)
