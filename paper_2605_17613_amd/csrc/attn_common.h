@@ -20,6 +20,9 @@ typedef float float16v __attribute__((ext_vector_type(16)));
 
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
+// running maximum before any key was seen: finite, so 2^(s - m) and 2^(m_old - m_new) need no
+// special cases (2^(-1e30 - x) is 0, and -inf - (-1e30) is -inf)
+constexpr float kNoKeyYet = -1.0e30f;
 
 __device__ __forceinline__ float bf16_bits_to_float(uint32_t bits16) { return __uint_as_float(bits16 << 16); }
 __device__ __forceinline__ float bf16_lo(uint32_t pair) { return __uint_as_float(pair << 16); }

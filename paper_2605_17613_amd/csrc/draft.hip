@@ -29,6 +29,35 @@ struct DraftBf16Params {
 
 // Lane layout: 16 lanes share one token row (lane c holds channels 8c..8c+7), so one wave load
 // instruction fetches four 256-byte rows; a wave step covers 16 tokens (4 per 16-lane slot).
+// Arithmetic stays in packed bf16 pairs: scores are v_dot2 over (q, k) pairs reduced across the 16
+// lanes with DPP adds; the output is v_dot2 over token pairs (values of two tokens interleaved with
+// one byte-permute per pair, probabilities rounded to bf16).  Indices are fetched two steps ahead
+// and rows one step ahead of their use.
+typedef __bf16 bf16x2v __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ float dot2_bf16(uint32_t a, uint32_t b, float c) {
+  return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2v, a), __builtin_bit_cast(bf16x2v, b), c, false);
+}
+template <int CTRL>
+__device__ __forceinline__ float dpp_add(float v) {
+  const int moved = __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xF, 0xF, true);
+  return v + __builtin_bit_cast(float, moved);
+}
+// sum over the 16 lanes of a DPP row, result in every lane
+__device__ __forceinline__ float row_sum16(float v) {
+  v = dpp_add<0xB1>(v);    // quad_perm [1,0,3,2]
+  v = dpp_add<0x4E>(v);    // quad_perm [2,3,0,1]
+  v = dpp_add<0x124>(v);   // row_ror 4
+  v = dpp_add<0x128>(v);   // row_ror 8
+  return v;
+}
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+  bf16x2v r;
+  r[0] = (__bf16)lo;
+  r[1] = (__bf16)hi;
+  return __builtin_bit_cast(uint32_t, r);
+}
+
 template <int GP, bool GATHER>
 __global__ __launch_bounds__(256) void draft_bf16_kernel(DraftBf16Params p) {
   const int b = blockIdx.z, kvh = blockIdx.y, sp = blockIdx.x;
@@ -42,28 +71,19 @@ __global__ __launch_bounds__(256) void draft_bf16_kernel(DraftBf16Params p) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int c = lane & 15, ts = lane >> 4;
 
-  float qf[GP][8];
+  uint32_t qpk[GP][4];                        // query, channels 8c..8c+7 as bf16 pairs (unscaled, exact)
 #pragma unroll
   for (int hq = 0; hq < GP; ++hq) {
-    if (hq < p.g) {
-      const uint4 raw = *reinterpret_cast<const uint4*>(
-          p.q + (static_cast<size_t>(b) * p.n_q_heads + kvh * p.g + hq) * kHeadDim + 8 * c);
-      const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        qf[hq][2 * i] = bf16_lo(w[i]) * p.scale_log2e;
-        qf[hq][2 * i + 1] = bf16_hi(w[i]) * p.scale_log2e;
-      }
-    } else {
-#pragma unroll
-      for (int e = 0; e < 8; ++e) qf[hq][e] = 0.f;
-    }
+    uint4 raw = {0u, 0u, 0u, 0u};
+    if (hq < p.g)
+      raw = *reinterpret_cast<const uint4*>(p.q + (static_cast<size_t>(b) * p.n_q_heads + kvh * p.g + hq) * kHeadDim + 8 * c);
+    qpk[hq][0] = raw.x; qpk[hq][1] = raw.y; qpk[hq][2] = raw.z; qpk[hq][3] = raw.w;
   }
 
   float m[GP], l[GP], o[GP][8];
 #pragma unroll
   for (int hq = 0; hq < GP; ++hq) {
-    m[hq] = -INFINITY;
+    m[hq] = kNoKeyYet;
     l[hq] = 0.f;
 #pragma unroll
     for (int e = 0; e < 8; ++e) o[hq][e] = 0.f;
@@ -71,68 +91,97 @@ __global__ __launch_bounds__(256) void draft_bf16_kernel(DraftBf16Params p) {
 
   const size_t head_off = static_cast<size_t>(kvh) * kHeadDim + 8 * c;
   const size_t row_stride = static_cast<size_t>(p.n_kv_heads) * kHeadDim;
+  const uint16_t* kbase = p.pk + static_cast<size_t>(row0) * row_stride + head_off;
+  const uint16_t* vbase = p.pv + static_cast<size_t>(row0) * row_stride + head_off;
 
-  for (int t0 = start + wave * 16; t0 < end; t0 += 64) {
-    uint4 kk[4], vv[4];
-    bool valid[4];
+  // token of (step t0, sub-step u) for this lane's slot, clamped into the split
+  auto token_of = [&](int t0, int u) { return min(t0 + u * 4 + ts, end - 1); };
+  auto load_idx = [&](int t0, int (&r)[4]) {
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
-      const int tok = t0 + u * 4 + ts;
-      valid[u] = tok < end;
-      const int tokc = valid[u] ? tok : end - 1;
-      const int r = GATHER ? idx[tokc] : tokc;
-      const size_t off = static_cast<size_t>(row0 + r) * row_stride + head_off;
-      kk[u] = *reinterpret_cast<const uint4*>(p.pk + off);
-      vv[u] = *reinterpret_cast<const uint4*>(p.pv + off);
+      const int tok = token_of(t0, u);
+      r[u] = GATHER ? idx[tok] : tok;
     }
+  };
+  auto load_rows = [&](const int (&r)[4], uint4 (&kk)[4], uint4 (&vv)[4]) {
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const size_t off = static_cast<size_t>(r[u]) * row_stride;
+      kk[u] = *reinterpret_cast<const uint4*>(kbase + off);
+      vv[u] = *reinterpret_cast<const uint4*>(vbase + off);
+    }
+  };
+
+  const int first = start + wave * 16;
+  int rcur[4], rnext[4];
+  uint4 kk[4], vv[4];
+  if (first < end) {
+    load_idx(first, rcur);
+    load_idx(min(first + 64, end - 1), rnext);
+    load_rows(rcur, kk, vv);
+  }
+  for (int t0 = first; t0 < end; t0 += 64) {
+    // rows of the next step (their indices arrived during the previous step), indices of the one after
+    uint4 kn[4], vn[4];
+    const bool has_next = t0 + 64 < end;
+    if (has_next) {
+      load_rows(rnext, kn, vn);
+      load_idx(min(t0 + 128, end - 1), rnext);
+    }
+    // ---- scores of the 4 tokens of this slot ----
     float s[4][GP];
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
       const uint32_t w[4] = {kk[u].x, kk[u].y, kk[u].z, kk[u].w};
-      float kf[8];
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        kf[2 * i] = bf16_lo(w[i]);
-        kf[2 * i + 1] = bf16_hi(w[i]);
-      }
+      const bool valid = t0 + u * 4 + ts < end;
 #pragma unroll
       for (int hq = 0; hq < GP; ++hq) {
         float a = 0.f;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) a = fmaf(qf[hq][e], kf[e], a);
-        a += __shfl_xor(a, 1, 64);
-        a += __shfl_xor(a, 2, 64);
-        a += __shfl_xor(a, 4, 64);
-        a += __shfl_xor(a, 8, 64);
-        s[u][hq] = valid[u] ? a : -INFINITY;
+        for (int i = 0; i < 4; ++i) a = dot2_bf16(qpk[hq][i], w[i], a);
+        a = row_sum16(a);
+        s[u][hq] = valid ? a * p.scale_log2e : -INFINITY;
       }
     }
-    float vf[4][8];
+    // ---- online softmax per slot, output by token pairs ----
+    uint32_t ve[2][4], vo[2][4];              // values of token pairs (0,1), (2,3): even / odd channels interleaved
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      const uint32_t w[4] = {vv[u].x, vv[u].y, vv[u].z, vv[u].w};
+    for (int pr = 0; pr < 2; ++pr) {
+      const uint32_t wa[4] = {vv[2 * pr].x, vv[2 * pr].y, vv[2 * pr].z, vv[2 * pr].w};
+      const uint32_t wb[4] = {vv[2 * pr + 1].x, vv[2 * pr + 1].y, vv[2 * pr + 1].z, vv[2 * pr + 1].w};
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        vf[u][2 * i] = bf16_lo(w[i]);
-        vf[u][2 * i + 1] = bf16_hi(w[i]);
+        ve[pr][i] = __builtin_amdgcn_perm(wb[i], wa[i], 0x05040100u);   // (a.lo, b.lo): channel 2i of both tokens
+        vo[pr][i] = __builtin_amdgcn_perm(wb[i], wa[i], 0x07060302u);   // (a.hi, b.hi): channel 2i+1
       }
     }
 #pragma unroll
     for (int hq = 0; hq < GP; ++hq) {
       const float mn = fmaxf(fmaxf(m[hq], fmaxf(s[0][hq], s[1][hq])), fmaxf(s[2][hq], s[3][hq]));
-      const float alpha = exp2_diff(m[hq], mn);
+      const float alpha = __builtin_amdgcn_exp2f(m[hq] - mn);
       float pu[4];
 #pragma unroll
-      for (int u = 0; u < 4; ++u) pu[u] = exp2_diff(s[u][hq], mn);
+      for (int u = 0; u < 4; ++u) pu[u] = __builtin_amdgcn_exp2f(s[u][hq] - mn);
       l[hq] = l[hq] * alpha + (pu[0] + pu[1]) + (pu[2] + pu[3]);
+      const uint32_t p01 = pack_bf16x2(pu[0], pu[1]), p23 = pack_bf16x2(pu[2], pu[3]);
 #pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        float acc = o[hq][e] * alpha;
-#pragma unroll
-        for (int u = 0; u < 4; ++u) acc = fmaf(pu[u], vf[u][e], acc);
-        o[hq][e] = acc;
+      for (int i = 0; i < 4; ++i) {
+        float e0 = o[hq][2 * i] * alpha, e1 = o[hq][2 * i + 1] * alpha;
+        e0 = dot2_bf16(ve[0][i], p01, e0);
+        e1 = dot2_bf16(vo[0][i], p01, e1);
+        e0 = dot2_bf16(ve[1][i], p23, e0);
+        e1 = dot2_bf16(vo[1][i], p23, e1);
+        o[hq][2 * i] = e0;
+        o[hq][2 * i + 1] = e1;
       }
       m[hq] = mn;
+    }
+    if (has_next) {
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        kk[u] = kn[u];
+        vv[u] = vn[u];
+      }
     }
   }
 
@@ -142,7 +191,7 @@ __global__ __launch_bounds__(256) void draft_bf16_kernel(DraftBf16Params p) {
   for (int hq = 0; hq < GP; ++hq) {
     float mw = fmaxf(m[hq], __shfl_xor(m[hq], 16, 64));
     mw = fmaxf(mw, __shfl_xor(mw, 32, 64));
-    const float a = exp2_diff(m[hq], mw);
+    const float a = __builtin_amdgcn_exp2f(m[hq] - mw);
     float lw = l[hq] * a;
     lw += __shfl_xor(lw, 16, 64);
     lw += __shfl_xor(lw, 32, 64);
@@ -167,7 +216,7 @@ __global__ __launch_bounds__(256) void draft_bf16_kernel(DraftBf16Params p) {
     float acc = 0.f, lsum = 0.f;
 #pragma unroll
     for (int w = 0; w < 4; ++w) {
-      const float a = exp2_diff(st[w][hq][0], mm);
+      const float a = __builtin_amdgcn_exp2f(st[w][hq][0] - mm);
       acc = fmaf(a, st[w][hq][2 + d], acc);
       lsum = fmaf(a, st[w][hq][1], lsum);
     }
@@ -262,7 +311,7 @@ __device__ __forceinline__ void u4_to_arr(const uint4& v, uint32_t (&a)[4]) {
 constexpr float kLazyMargin = 4.f;  // the running maximum may lag the true one by this much (log2 units)
 
 template <int BITS>
-__global__ __launch_bounds__(256, 2) void draft_quant_kernel(DraftQuantParams p) {
+__global__ __launch_bounds__(256, 3) void draft_quant_kernel(DraftQuantParams p) {
   constexpr int TB = (BITS == 4) ? 32 : 64;   // tokens per block record
   constexpr int NT = TB / 16;                 // 16-token score tiles per record
   constexpr int NKS = TB / 32;                // 32-token k-steps of the output product per record
@@ -646,7 +695,7 @@ static DraftPlan make_plan(const vc_comp_kv* kv) {
   const int lists = kv->n_seqs * kv->n_kv_heads;
   const bool has_a = kv->pool_k != nullptr && kv->max_keep > 0;
   const bool has_b = kv->blocks != nullptr && kv->max_blk > 0;
-  const int target_a = env_int("VC_DRAFT_BF16_WGS", 2048, 1, 1 << 20);
+  const int target_a = env_int("VC_DRAFT_BF16_WGS", 512, 1, 1 << 20);
   const int target_b = env_int("VC_DRAFT_QUANT_WGS", 768, 1, 1 << 20);
   pl.split_a = pick_chunk(static_cast<int64_t>(kv->sum_keep) * kv->n_kv_heads, kv->max_keep, lists, 64,
                           env_int("VC_DRAFT_MIN_TOK", 256, 64, 1 << 20), target_a);
