@@ -372,6 +372,11 @@ __global__ __launch_bounds__(256, 3) void draft_quant_kernel(DraftQuantParams p)
   for (int dt = 0; dt < 8; ++dt) oacc[dt] = float4v{0.f, 0.f, 0.f, 0.f};
   ozero = float4v{0.f, 0.f, 0.f, 0.f};
 
+  // query with the field factor undone again, for the key-zero product
+  uint32_t qnf[16];
+#pragma unroll
+  for (int i = 0; i < 16; ++i) qnf[i] = as_u32(as_half2(qn[i]) * as_half2(finv[i & 3]));
+
   for (int blk = blk0 + wave; blk < blk1; blk += 4) {
     const uint8_t* rec = rec_base + static_cast<size_t>(blk) * kRecordBytes;
     // ---------------- loads of the whole record share of this lane ----------------
@@ -413,7 +418,7 @@ __global__ __launch_bounds__(256, 3) void draft_quant_kernel(DraftQuantParams p)
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
       qf[i] = as_u32(as_half2(qn[i]) * as_half2(ksc[i]));                            // q * sK / f
-      qz[i] = as_u32(as_half2(qn[i]) * as_half2(finv[i & 3]) * as_half2(kzr[i]));    // q * zK
+      qz[i] = as_u32(as_half2(qnf[i]) * as_half2(kzr[i]));                           // q * zK
     }
     float4v init = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
