@@ -65,10 +65,13 @@ __device__ __forceinline__ short4v lds_read_tr(uint32_t addr) {
   return __builtin_amdgcn_ds_read_tr16_b64_v4i16(reinterpret_cast<lds_short4v*>(static_cast<size_t>(addr)));
 }
 
-// 16-byte chunk c of tile row `row` is stored at chunk position c ^ (row & 15): rows are 256 bytes
-// with no padding (direct-to-LDS loads write 1 KB per wave contiguously), the xor spreads a
-// column of chunks over all banks.
-__device__ __forceinline__ int swz(int row, int chunk) { return row * 256 + ((chunk ^ (row & 15)) << 4); }
+// 16-byte chunk c of tile row `row` is stored at chunk position c ^ rot(row), rot = the low four
+// row bits rotated left by one.  Rows are 256 bytes with no padding (direct-to-LDS loads write 1 KB
+// per wave contiguously); the xor spreads a column of chunks over all banks (K operand reads), and
+// because the two lowest row bits land on chunk bits 1 and 2, the four rows of a transposing-read
+// patch put their two adjacent chunks on eight different positions (V operand reads).
+__device__ __forceinline__ int rot_row(int row) { return ((row << 1) & 14) | ((row >> 3) & 1); }
+__device__ __forceinline__ int swz(int row, int chunk) { return row * 256 + ((chunk ^ rot_row(row)) << 4); }
 
 // Direct HBM -> LDS load of 16 bytes per lane: lane i's data lands at lds_addr + 16*i (lds_addr is
 // wave-uniform and travels in M0).  Issued as inline assembly so that the compiler's own wait-count
@@ -85,20 +88,22 @@ __device__ __forceinline__ void wait_vm() {
   __builtin_amdgcn_s_waitcnt((N_OUTSTANDING & 15) | ((N_OUTSTANDING >> 4) << 14) | 0x0F70);
 }
 
-// One wave owns 32 rows (one MFMA row tile) and, of every LDS tile, one 32-token slice.
-// NTG = token slices per tile; the 8 waves of a workgroup form NRG = 8/NTG row groups.
-// Tiles travel HBM -> LDS directly (no registers) through a ring of NSTAGE stages, NSTAGE-1 tiles
-// in flight, one barrier per tile.
-template <int NTG>
+// One wave owns RT row tiles of 32 rows and, of every LDS tile, one 32-token slice.  With RT = 2
+// every K and V^T operand read from LDS feeds two matrix instructions, which halves the LDS
+// traffic per flop: at RT = 1 the matrix cores could at best be fed at the full LDS bandwidth.
+// NW = 8/RT waves per workgroup; NTG = token slices per tile; NRG = NW/NTG row groups.
+// Tiles travel HBM -> LDS directly (no registers) through a ring of NSTAGE stages, one barrier per tile.
+template <int NTG, int RT>
 __device__ __forceinline__ void verify_body(const VerifyParams& p, char* smem, int kvh, int chunk, int w0, int w,
                                             int c0, int N) {
-  constexpr int NRG = 8 / NTG;
-  constexpr int U = 1;                         // 32-token slices per wave per tile (2 was measured slower: fewer tiles in flight)
-  constexpr int TT = 32 * NTG * U;             // tokens per tile
+  constexpr int NW = 8 / RT;
+  constexpr int NRG = NW / NTG;
+  constexpr int TT = 32 * NTG;                 // tokens per tile
   constexpr int STAGE_BYTES = TT * 512;        // K tile then V tile, 256 bytes per row
-  constexpr int NSTAGE = kVerifyLds / STAGE_BYTES;
-  constexpr int LPT = NTG * U;                 // 1 KB wave-loads per matrix per wave per tile: TT*256/1024/8
-  static_assert(NSTAGE >= 2 && NSTAGE <= 8, "ring depth");
+  constexpr int NSTAGE = (kVerifyLds / STAGE_BYTES) > 8 ? 8 : (kVerifyLds / STAGE_BYTES);
+  constexpr int LPT = TT / (4 * NW);           // 1 KB wave-loads per matrix per wave per tile
+  constexpr int DEPTH = NSTAGE - 1;            // tiles in flight
+  static_assert(NSTAGE >= 3 && NSTAGE <= 8 && LPT >= 1, "ring geometry");
   const int R = w * p.g;
   const int total = N + w;
   const int t_begin = chunk * p.chunk_tok;
@@ -107,42 +112,53 @@ __device__ __forceinline__ void verify_body(const VerifyParams& p, char* smem, i
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int rg = wave % NRG, tg = wave / NRG;
   const int n = lane & 31, hh = lane >> 5;
-  const bool wave_rows = rg * 32 < R;
+  const bool wave_rows = rg * 32 * RT < R;
 
-  const int r = rg * 32 + n;
-  const bool row_ok = r < R;
-  const int rc = row_ok ? r : R - 1;
-  const int iw = rc / p.g, hq = rc % p.g;
-  bf16x8v qb[8];
-  {
-    const uint16_t* qp = p.qw + (static_cast<size_t>(w0 + iw) * p.n_q_heads + kvh * p.g + hq) * kHeadDim + 8 * hh;
+  int iw[RT], hq[RT];
+  bool row_ok[RT];
+  bf16x8v qb[RT][8];
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks) qb[ks] = load_bf16x8(qp + 16 * ks);
-    // pin the query registers here: their loads must be waited for before the ring starts, or the
-    // wait would sit inside the loop and also drain the tiles in flight
+  for (int rt = 0; rt < RT; ++rt) {
+    const int r = (rg * RT + rt) * 32 + n;
+    row_ok[rt] = r < R;
+    const int rc = row_ok[rt] ? r : R - 1;
+    iw[rt] = rc / p.g;
+    hq[rt] = rc % p.g;
+    const uint16_t* qp = p.qw + (static_cast<size_t>(w0 + iw[rt]) * p.n_q_heads + kvh * p.g + hq[rt]) * kHeadDim + 8 * hh;
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks) asm volatile("" : "+v"(qb[ks]));
+    for (int ks = 0; ks < 8; ++ks) qb[rt][ks] = load_bf16x8(qp + 16 * ks);
   }
+  // pin the query registers here: their loads must be waited for before the ring starts, or the
+  // wait would sit inside the loop and also drain the tiles in flight
+#pragma unroll
+  for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) asm volatile("" : "+v"(qb[rt][ks]));
 
-  float m = kMinusBig, l = 0.f;
-  float16v oacc[4];
+  float m[RT], l[RT];
+  float16v oacc[RT][4];
 #pragma unroll
-  for (int dt = 0; dt < 4; ++dt)
+  for (int rt = 0; rt < RT; ++rt) {
+    m[rt] = kMinusBig;
+    l[rt] = 0.f;
 #pragma unroll
-    for (int i = 0; i < 16; ++i) oacc[dt][i] = 0.f;
+    for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) oacc[rt][dt][i] = 0.f;
+  }
 
   const size_t row_stride = static_cast<size_t>(p.n_kv_heads) * kHeadDim;
   const size_t head_off = static_cast<size_t>(kvh) * kHeadDim;
 
-  // ---- tile loads: wave-load c of this wave covers tile rows 4*(wave + 8c) .. +3 ----
+  // ---- tile loads: wave-load c of this wave covers tile rows 4*(wave + NW*c) .. +3 ----
   const uint32_t lds_base = static_cast<uint32_t>(reinterpret_cast<size_t>((__attribute__((address_space(3))) char*)smem));
   // fast path (tile entirely inside the full KV): per-lane pointers that advance by one tile
   const uint16_t* kfast[LPT];
   const uint16_t* vfast[LPT];
 #pragma unroll
   for (int c = 0; c < LPT; ++c) {
-    const int row = 4 * (wave + 8 * c) + (lane >> 4);
-    const size_t off = static_cast<size_t>(c0 + t_begin + row) * row_stride + head_off + 8 * ((lane & 15) ^ (row & 15));
+    const int row = 4 * (wave + NW * c) + (lane >> 4);
+    const size_t off = static_cast<size_t>(c0 + t_begin + row) * row_stride + head_off + 8 * ((lane & 15) ^ rot_row(row));
     kfast[c] = p.kf + off;
     vfast[c] = p.vf + off;
   }
@@ -153,16 +169,16 @@ __device__ __forceinline__ void verify_body(const VerifyParams& p, char* smem, i
     if (t + TT <= N) {
 #pragma unroll
       for (int c = 0; c < LPT; ++c) {
-        const int grp = wave + 8 * c;
+        const int grp = wave + NW * c;
         load_to_lds(kfast[c] + static_cast<size_t>(j) * tile_step, __builtin_amdgcn_readfirstlane(stage + grp * 1024));
         load_to_lds(vfast[c] + static_cast<size_t>(j) * tile_step, __builtin_amdgcn_readfirstlane(stage + TT * 256 + grp * 1024));
       }
     } else {
 #pragma unroll
       for (int c = 0; c < LPT; ++c) {
-        const int grp = wave + 8 * c;
+        const int grp = wave + NW * c;
         const int row = 4 * grp + (lane >> 4);
-        const int chunkpos = (lane & 15) ^ (row & 15);
+        const int chunkpos = (lane & 15) ^ rot_row(row);
         int tok = t + row;
         tok = tok < total ? tok : total - 1;   // rows past the end re-read the last row; their scores are masked
         const bool in_full = tok < N;
@@ -174,20 +190,15 @@ __device__ __forceinline__ void verify_body(const VerifyParams& p, char* smem, i
     }
   };
 
-  // ---- LDS read addresses of this lane, relative to the stage base; slice u of this wave is
-  //      tile rows 32*(tg + NTG*u) .. +31 ----
-  uint32_t kaddr[U][8];
+  // ---- LDS read addresses of this lane, relative to the stage base ----
+  uint32_t kaddr[8];
 #pragma unroll
-  for (int u = 0; u < U; ++u)
-#pragma unroll
-    for (int ks = 0; ks < 8; ++ks) kaddr[u][ks] = swz(32 * (tg + NTG * u) + n, 2 * ks + hh);
+  for (int ks = 0; ks < 8; ++ks) kaddr[ks] = swz(32 * tg + n, 2 * ks + hh);
   // transposing read: lane -> (token row, 8-byte half of a 16-byte chunk) inside a 4 x 16 patch
   const int blk16 = lane >> 4;
   const int tr_row = 4 * (blk16 >> 1) + ((lane & 15) >> 2);
   const int tr_chunk = 2 * (blk16 & 1) + ((lane & 3) >> 1);
   const int tr_sub = 8 * (lane & 1);
-  // V addresses: only the row part depends on (u, kk, half); the chunk xor is the same for rows
-  // that differ by a multiple of 16, so one table for u = 0 plus a constant row offset serves all
   uint32_t vaddr[4][2][2];
 #pragma unroll
   for (int dt = 0; dt < 4; ++dt)
@@ -196,131 +207,123 @@ __device__ __forceinline__ void verify_body(const VerifyParams& p, char* smem, i
 #pragma unroll
       for (int h2 = 0; h2 < 2; ++h2)
         vaddr[dt][kk][h2] = TT * 256 + swz(32 * tg + 16 * kk + 8 * h2 + tr_row, 4 * dt + tr_chunk) + tr_sub;
-  constexpr int kSliceStride = 32 * NTG * 256;  // bytes between slice u and u+1 (a multiple of 16 rows)
-
-  float16v zero16;
-#pragma unroll
-  for (int i = 0; i < 16; ++i) zero16[i] = 0.f;
-  asm volatile("" : "+v"(zero16));             // keep one zero accumulator in registers
 
   auto compute = [&](int j) {
-    const int t = t_begin + j * TT;
-    if (!wave_rows) return;
+    const int ts = t_begin + j * TT + 32 * tg;  // first token of this wave's slice
+    if (!(wave_rows && ts < t_end)) return;
     const uint32_t sbase = lds_base + (j % NSTAGE) * STAGE_BYTES;
-    int ts[U];
-    bool live[U];
+    // ---- S^T = K Q^T : one K operand read feeds RT products ----
+    float16v sacc[RT];
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-      ts[u] = t + 32 * (tg + NTG * u);          // first token of slice u
-      live[u] = ts[u] < t_end;
-    }
-    if (!live[0]) return;
-    // ---- S^T = K Q^T, the slices' accumulator chains interleaved ----
-    float16v sacc[U];
+    for (int rt = 0; rt < RT; ++rt)
 #pragma unroll
-    for (int u = 0; u < U; ++u) sacc[u] = zero16;
+      for (int i = 0; i < 16; ++i) sacc[rt][i] = 0.f;
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) {
+      const bf16x8v a = lds_load_bf16x8(sbase + kaddr[ks]);
 #pragma unroll
-      for (int u = 0; u < U; ++u)
-        if (live[u]) sacc[u] = mfma32(lds_load_bf16x8(sbase + kaddr[u][ks]), qb[ks], sacc[u]);
+      for (int rt = 0; rt < RT; ++rt) sacc[rt] = mfma32(a, qb[rt][ks], sacc[rt]);
     }
     // register i of this lane is token row 8*(i/4) + 4*hh + i%4 of the slice, for row n
-    float mt = -INFINITY;
+    bf16x8v pb[RT][2];
+    const bool edge = ts + 32 > min(N, t_end);  // slice touches the window or the end of the chunk
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-      if (!live[u]) continue;
-      if (ts[u] + 32 > min(N, t_end)) {        // slice touches the window or the end of the chunk
+    for (int rt = 0; rt < RT; ++rt) {
+      if (edge) {
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
-          const int tok = ts[u] + 8 * (i >> 2) + 4 * hh + (i & 3);
-          const bool ok = tok < t_end && (tok < N || tok - N <= iw);
-          sacc[u][i] = ok ? sacc[u][i] : -INFINITY;
+          const int tok = ts + 8 * (i >> 2) + 4 * hh + (i & 3);
+          const bool ok = tok < t_end && (tok < N || tok - N <= iw[rt]);
+          sacc[rt][i] = ok ? sacc[rt][i] : -INFINITY;
         }
       }
+      float mt = fmaxf(sacc[rt][0], sacc[rt][1]);
 #pragma unroll
-      for (int i = 0; i < 16; ++i) mt = fmaxf(mt, sacc[u][i]);
-    }
-    mt *= p.scale_log2e;                       // the scale is positive: max commutes with it
-    if (__any(mt > m + kVerifyMargin)) {
-      const float mx = fmaxf(mt, __shfl_xor(mt, 32, 64));
-      const float mn = fmaxf(m, mx);
-      const float alpha = __builtin_amdgcn_exp2f(m - mn);
-      l *= alpha;
+      for (int i = 2; i < 16; ++i) mt = fmaxf(mt, sacc[rt][i]);
+      mt *= p.scale_log2e;                     // the scale is positive: max commutes with it
+      if (__any(mt > m[rt] + kVerifyMargin)) {
+        const float mx = fmaxf(mt, __shfl_xor(mt, 32, 64));
+        const float mn = fmaxf(m[rt], mx);
+        const float alpha = __builtin_amdgcn_exp2f(m[rt] - mn);
+        l[rt] *= alpha;
 #pragma unroll
-      for (int dt = 0; dt < 4; ++dt)
+        for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
-        for (int i = 0; i < 16; ++i) oacc[dt][i] *= alpha;
-      m = mn;
-    }
-    bf16x8v pb[U][2];
-    float ps0 = 0.f, ps1 = 0.f;
-    const float negm = -m;
-#pragma unroll
-    for (int u = 0; u < U; ++u) {
-      if (!live[u]) continue;
+          for (int i = 0; i < 16; ++i) oacc[rt][dt][i] *= alpha;
+        m[rt] = mn;
+      }
+      float ps0 = 0.f, ps1 = 0.f;
+      const float negm = -m[rt];
 #pragma unroll
       for (int i = 0; i < 16; i += 2) {
-        const float p0 = __builtin_amdgcn_exp2f(fmaf(sacc[u][i], p.scale_log2e, negm));
-        const float p1 = __builtin_amdgcn_exp2f(fmaf(sacc[u][i + 1], p.scale_log2e, negm));
+        const float p0 = __builtin_amdgcn_exp2f(fmaf(sacc[rt][i], p.scale_log2e, negm));
+        const float p1 = __builtin_amdgcn_exp2f(fmaf(sacc[rt][i + 1], p.scale_log2e, negm));
         ps0 += p0;
         ps1 += p1;
-        pb[u][i >> 3][i & 7] = (__bf16)p0;
-        pb[u][i >> 3][(i & 7) + 1] = (__bf16)p1;
+        pb[rt][i >> 3][i & 7] = (__bf16)p0;
+        pb[rt][i >> 3][(i & 7) + 1] = (__bf16)p1;
       }
+      l[rt] += ps0 + ps1;
     }
-    l += ps0 + ps1;
     // ---- O^T += V^T P^T ; A element e of k-step kk is token row 16kk + 8(e/4) + 4hh + e%4 ----
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-      if (!live[u]) continue;
+    for (int kk = 0; kk < 2; ++kk) {
 #pragma unroll
-      for (int kk = 0; kk < 2; ++kk) {
+      for (int dt = 0; dt < 4; ++dt) {
+        const short4v lo = lds_read_tr(sbase + vaddr[dt][kk][0]);
+        const short4v hi = lds_read_tr(sbase + vaddr[dt][kk][1]);
+        const bf16x8v av = __builtin_bit_cast(bf16x8v, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
 #pragma unroll
-        for (int dt = 0; dt < 4; ++dt) {
-          const short4v lo = lds_read_tr(sbase + u * kSliceStride + vaddr[dt][kk][0]);
-          const short4v hi = lds_read_tr(sbase + u * kSliceStride + vaddr[dt][kk][1]);
-          const short8v both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-          oacc[dt] = mfma32(__builtin_bit_cast(bf16x8v, both), pb[u][kk], oacc[dt]);
-        }
+        for (int rt = 0; rt < RT; ++rt) oacc[rt][dt] = mfma32(av, pb[rt][kk], oacc[rt][dt]);
       }
     }
   };
 
-  // ---- ring: tile j is requested NSTAGE-1 iterations before it is used ----
+  // ---- ring: tile j is requested DEPTH iterations before it is used ----
 #pragma unroll
-  for (int j = 0; j < NSTAGE - 1; ++j)
+  for (int j = 0; j < DEPTH; ++j)
     if (j < ntiles) issue(j);
   for (int j = 0; j < ntiles; ++j) {
     // this wave's loads of tile j have landed once at most the loads of the younger tiles are
     // outstanding; near the end fewer tiles are in flight, so the count shrinks
-    const int younger = min(NSTAGE - 2, ntiles - 1 - j);
+    const int younger = min(DEPTH - 1, ntiles - 1 - j);
     if (younger <= 0) wait_vm<0>();
-    else if (younger == 1) wait_vm<(NSTAGE > 2 ? 1 : 0) * 2 * LPT>();
-    else if (younger == 2) wait_vm<(NSTAGE > 3 ? 2 : 0) * 2 * LPT>();
-    else wait_vm<(NSTAGE > 4 ? 3 : 0) * 2 * LPT>();
+    else if (younger == 1) wait_vm<(DEPTH > 1 ? 1 : 0) * 2 * LPT>();
+    else if (younger == 2) wait_vm<(DEPTH > 2 ? 2 : 0) * 2 * LPT>();
+    else if (younger == 3) wait_vm<(DEPTH > 3 ? 3 : 0) * 2 * LPT>();
+    else if (younger == 4) wait_vm<(DEPTH > 4 ? 4 : 0) * 2 * LPT>();
+    else if (younger == 5) wait_vm<(DEPTH > 5 ? 5 : 0) * 2 * LPT>();
+    else wait_vm<(DEPTH > 6 ? 6 : 0) * 2 * LPT>();
     __syncthreads();                            // every wave's share of tile j is in LDS; tile j-1 is no longer read
-    if (j + NSTAGE - 1 < ntiles) issue(j + NSTAGE - 1);   // into the stage tile j-1 just left
+    if (j + DEPTH < ntiles) issue(j + DEPTH);   // into the stage tile j-1 just left
     compute(j);
   }
 
   if (!wave_rows) return;
-  const float lt = l + __shfl_xor(l, 32, 64);
-  if (!row_ok) return;
-  const size_t grow = static_cast<size_t>(w0 + iw) * p.n_q_heads + kvh * p.g + hq;
-  float* dst = p.ws + (grow * p.ns + chunk * 4 + tg) * kPartialFloats;
-  if (hh == 0) {
-    dst[0] = m;
-    dst[1] = lt;
+#pragma unroll
+  for (int rt = 0; rt < RT; ++rt) {
+    const float lt = l[rt] + __shfl_xor(l[rt], 32, 64);
+    if (!row_ok[rt]) continue;
+    const size_t grow = static_cast<size_t>(w0 + iw[rt]) * p.n_q_heads + kvh * p.g + hq[rt];
+    float* dst = p.ws + (grow * p.ns + chunk * 4 + tg) * kPartialFloats;
+    if (hh == 0) {
+      dst[0] = m[rt];
+      dst[1] = lt;
+    }
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) dst[2 + 32 * dt + 8 * (i >> 2) + 4 * hh + (i & 3)] = oacc[rt][dt][i];
   }
-#pragma unroll
-  for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-    for (int i = 0; i < 16; ++i) dst[2 + 32 * dt + 8 * (i >> 2) + 4 * hh + (i & 3)] = oacc[dt][i];
 }
 
-__device__ __forceinline__ int tokens_split(int rows) { return rows <= 128 ? 2 : 1; }
+// token slices per tile for a given row count; `wide` = the 4-wave kernel with 64 rows per wave
+__device__ __forceinline__ int tokens_split(int rows, bool wide) {
+  (void)wide;                                  // both kernels: two slices up to 128 rows, one above
+  return rows <= 128 ? 2 : 1;
+}
 
+// 8 waves x 32 rows: windows with up to 128 rows per KV head (HBM bound)
 __global__ __launch_bounds__(512) void verify_kernel(VerifyParams p) {
   extern __shared__ __attribute__((aligned(1024))) char smem[];
   const int b = blockIdx.z, kvh = blockIdx.y, chunk = blockIdx.x;
@@ -328,8 +331,20 @@ __global__ __launch_bounds__(512) void verify_kernel(VerifyParams p) {
   if (w == 0) return;
   const int c0 = p.cu_ctx[b], N = p.cu_ctx[b + 1] - c0;
   if (chunk * p.chunk_tok >= N + w) return;
-  if (tokens_split(w * p.g) == 2) verify_body<2>(p, smem, kvh, chunk, w0, w, c0, N);
-  else verify_body<1>(p, smem, kvh, chunk, w0, w, c0, N);
+  if (tokens_split(w * p.g, false) == 2) verify_body<2, 1>(p, smem, kvh, chunk, w0, w, c0, N);
+  else verify_body<1, 1>(p, smem, kvh, chunk, w0, w, c0, N);
+}
+
+// 4 waves x 64 rows: used when some window has more than 128 rows (matrix-core / LDS bound)
+__global__ __launch_bounds__(256) void verify_wide_kernel(VerifyParams p) {
+  extern __shared__ __attribute__((aligned(1024))) char smem[];
+  const int b = blockIdx.z, kvh = blockIdx.y, chunk = blockIdx.x;
+  const int w0 = p.cu_win[b], w = p.cu_win[b + 1] - w0;
+  if (w == 0) return;
+  const int c0 = p.cu_ctx[b], N = p.cu_ctx[b + 1] - c0;
+  if (chunk * p.chunk_tok >= N + w) return;
+  if (tokens_split(w * p.g, true) == 2) verify_body<2, 2>(p, smem, kvh, chunk, w0, w, c0, N);
+  else verify_body<1, 2>(p, smem, kvh, chunk, w0, w, c0, N);
 }
 
 struct VerifyMergeParams {
@@ -338,7 +353,7 @@ struct VerifyMergeParams {
   float* lse;
   const int* cu_ctx;
   const int* cu_win;
-  int n_seqs, n_q_heads, g, ns, chunk_tok;
+  int n_seqs, n_q_heads, g, ns, chunk_tok, wide;
 };
 
 __global__ __launch_bounds__(128) void verify_merge_kernel(VerifyMergeParams p) {
@@ -348,7 +363,7 @@ __global__ __launch_bounds__(128) void verify_merge_kernel(VerifyMergeParams p) 
   const int w = p.cu_win[b + 1] - p.cu_win[b];
   const int total = (p.cu_ctx[b + 1] - p.cu_ctx[b]) + w;
   const int nchunk = ceil_div_dev(total, p.chunk_tok);
-  const int ntg = tokens_split(w * p.g);
+  const int ntg = tokens_split(w * p.g, p.wide != 0);
   const float* base = p.ws + (static_cast<size_t>(row) * p.n_q_heads + h) * p.ns * kPartialFloats;
   float mm = -INFINITY;
   for (int c = 0; c < nchunk; ++c)
@@ -442,6 +457,8 @@ extern "C" vc_status vc_verify_attn(vc_ctx* ctx, const vc_full_kv* kv, const voi
   if (!lds_attr_set) {
     VC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(verify_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
                                kVerifyLds));
+    VC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(verify_wide_kernel),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, kVerifyLds));
     lds_attr_set = true;
   }
   const VerifyPlan pl = make_verify_plan(kv);
@@ -459,7 +476,11 @@ extern "C" vc_status vc_verify_attn(vc_ctx* ctx, const vc_full_kv* kv, const voi
   vp.chunk_tok = pl.chunk_tok; vp.ns = pl.ns;
   vp.scale_log2e = softmax_scale * kLog2e;
   dim3 grid(pl.nchunk, kv->n_kv_heads, kv->n_seqs);
-  hipLaunchKernelGGL(verify_kernel, grid, dim3(512), kVerifyLds, st, vp);
+  // The 64-rows-per-wave variant halves the LDS traffic per flop but leaves one wave per SIMD;
+  // measured slower at every window (1781 vs 1409 us at w = 64, config-2 shape), so it is opt-in.
+  const bool wide = env_int("VC_VERIFY_WIDE", 0, 0, 1) != 0;
+  if (wide) hipLaunchKernelGGL(verify_wide_kernel, grid, dim3(256), kVerifyLds, st, vp);
+  else hipLaunchKernelGGL(verify_kernel, grid, dim3(512), kVerifyLds, st, vp);
   VerifyMergeParams mp{};
   mp.ws = vp.ws;
   mp.out = static_cast<uint16_t*>(out);
@@ -467,6 +488,7 @@ extern "C" vc_status vc_verify_attn(vc_ctx* ctx, const vc_full_kv* kv, const voi
   mp.cu_ctx = kv->cu_ctx;
   mp.cu_win = cu_win;
   mp.n_seqs = kv->n_seqs; mp.n_q_heads = kv->n_q_heads; mp.g = vp.g; mp.ns = pl.ns; mp.chunk_tok = pl.chunk_tok;
+  mp.wide = wide ? 1 : 0;
   hipLaunchKernelGGL(verify_merge_kernel, dim3(kv->n_q_heads, total_win), dim3(128), 0, st, mp);
   VC_HIP(hipGetLastError());
   return VC_OK;
