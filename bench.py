@@ -289,10 +289,41 @@ def measure_swap(vc, ctx, lay, torch, draft_kw, out, ws, HKV, N, B, W):
     torch.cuda.synchronize()
     vc.vc_swap_sync(ctx)
     t_both = time.perf_counter() - t0
+
+    # chunk-streamed verify: every 8192-token chunk is attended to as soon as its ticket has landed,
+    # so only the last chunk's share of the verify is exposed after the transfer
+    streamed = None
+    if N % chunk_tok == 0 and lay.q_win is not None:
+        vkw = dict(k=dst_k, v=dst_v, cu_ctx=lay.cu_ctx, max_ctx=N, max_win=W, n_seqs=B, chunk_tokens=chunk_tok)
+        vws = torch.empty(vc.vc_verify_workspace_bytes(lay.n_q_heads, HKV, B, total_win=B * W, k=dst_k, v=dst_v,
+                                                       cu_ctx=lay.cu_ctx, max_ctx=N, max_win=W, chunk_tokens=chunk_tok),
+                          dtype=torch.uint8, device=dev)
+        vout = torch.empty_like(lay.q_win)
+        per_seq = N // chunk_tok
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        vc.vc_verify_attn(ctx, lay.q_win, lay.k_win, lay.v_win, lay.cu_win, lay.scale, vout, workspace=vws, **vkw)
+        torch.cuda.synchronize()
+        t_verify = time.perf_counter() - t0
+        ref = vout.clone()
+        t0 = time.perf_counter()
+        for i, ch in enumerate(chunks):
+            vc.vc_swap_in(ctx, host_k, dst_k, [ch])
+            ticket = vc.vc_swap_in(ctx, host_v, dst_v, [ch])
+            vc.vc_swap_wait(ctx, ticket)
+            b, c = divmod(i, per_seq)
+            vc.vc_verify_attn_range(ctx, lay.q_win, lay.k_win, lay.v_win, lay.cu_win, lay.scale, b, b + 1, c * chunk_tok,
+                                    (1 << 30) if c == per_seq - 1 else (c + 1) * chunk_tok, workspace=vws, **vkw)
+        vc.vc_verify_finish(ctx, lay.cu_win, vout, n_q_heads=lay.n_q_heads, n_kv_heads=HKV, workspace=vws, **vkw)
+        torch.cuda.synchronize()
+        t_stream = time.perf_counter() - t0
+        streamed = {"verify_alone_ms": t_verify * 1e3, "swap_then_verify_ms": (t_swap + t_verify) * 1e3,
+                    "streamed_ms": t_stream * 1e3, "exposed_after_swap_ms": (t_stream - t_swap) * 1e3,
+                    "same_bits": bool(torch.equal(ref.view(torch.int16), vout.view(torch.int16)))}
     return {"bytes": total, "chunks": 2 * len(chunks), "swap_alone_ms": t_swap * 1e3, "swap_GBps": total / t_swap / 1e9,
             "draft_steps": n_steps, "draft_alone_ms": t_draft * 1e3, "both_ms": t_both * 1e3,
             "overlap": (t_draft + t_swap - t_both) / min(t_draft, t_swap), "bytes_ok": ok,
-            "model_max_ms": max(t_draft, t_swap) * 1e3}
+            "model_max_ms": max(t_draft, t_swap) * 1e3, "streamed_verify": streamed}
 
 
 def cpu_baseline(lay, torch, np, HQ, HKV, N):

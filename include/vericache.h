@@ -121,6 +121,8 @@ typedef struct {
   int32_t n_seqs, n_q_heads, n_kv_heads, head_dim;
   int32_t max_ctx, max_win;
   int32_t sum_ctx;         /* host hint: sum of context lengths (0 = unknown); load balance only */
+  int32_t chunk_tokens;    /* tokens per workgroup chunk (a multiple of 128), 0 = the library picks;
+                              set it to the swap-in chunk length to verify chunk by chunk */
   const void* k;           /* device bf16 pools; sequence b owns rows cu_ctx[b] .. cu_ctx[b+1]-1 */
   const void* v;
   const int32_t* cu_ctx;
@@ -138,6 +140,26 @@ vc_status vc_verify_attn(vc_ctx* ctx, const vc_full_kv* kv, const void* q_win, c
                          const void* v_win, const int32_t* cu_win, int32_t total_win,
                          float softmax_scale, void* out, float* lse, void* workspace,
                          size_t workspace_bytes, void* stream);
+
+/* Chunk-streamed verify (paper section 5.2 step (i) and the HBM ring of section 5.1: the reload is
+ * in flight while the GPU works).  The key stream of sequence b is its full-KV tokens followed by
+ * its window tokens.  vc_verify_attn_range attends, for sequences seq_begin .. seq_end-1, to stream
+ * positions [tok_begin, tok_end) and leaves split partials in `workspace`; it can be issued as soon
+ * as the swap-in ticket of those tokens has been waited for on `stream`.  tok_begin must be a
+ * multiple of the chunk length that vc_verify_plan reports, tok_end a multiple of it or past the end
+ * of every sequence (the window tokens belong to the last range).  vc_verify_finish merges the
+ * partials once every position of every sequence has been covered exactly once; the same workspace
+ * (sized by vc_verify_workspace_bytes) must be passed to all calls.  vc_verify_attn is the two calls
+ * back to back over the whole stream. */
+vc_status vc_verify_plan(const vc_full_kv* kv, int32_t* chunk_tokens, int32_t* n_chunks);
+vc_status vc_verify_attn_range(vc_ctx* ctx, const vc_full_kv* kv, const void* q_win, const void* k_win,
+                               const void* v_win, const int32_t* cu_win, int32_t total_win,
+                               float softmax_scale, int32_t seq_begin, int32_t seq_end,
+                               int32_t tok_begin, int32_t tok_end, void* workspace,
+                               size_t workspace_bytes, void* stream);
+vc_status vc_verify_finish(vc_ctx* ctx, const vc_full_kv* kv, const int32_t* cu_win, int32_t total_win,
+                           void* out, float* lse, void* workspace, size_t workspace_bytes,
+                           void* stream);
 
 /* Greedy acceptance (paper section 4.1 step 3).
  *   logits      device fp32 [total_rows, vocab]; sequence b owns rows cu_rows[b]..cu_rows[b+1]-1:

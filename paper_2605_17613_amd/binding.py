@@ -36,6 +36,7 @@ class vc_comp_kv(C.Structure):
 class vc_full_kv(C.Structure):
     _fields_ = [("n_seqs", C.c_int32), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32),
                 ("head_dim", C.c_int32), ("max_ctx", C.c_int32), ("max_win", C.c_int32), ("sum_ctx", C.c_int32),
+                ("chunk_tokens", C.c_int32),
                 ("k", C.c_void_p), ("v", C.c_void_p), ("cu_ctx", C.c_void_p)]
 
 
@@ -45,6 +46,7 @@ class vc_chunk(C.Structure):
 
 EXPORTS = ["vc_create", "vc_destroy", "vc_last_error", "vc_version",
            "vc_draft_workspace_bytes", "vc_draft_attn", "vc_verify_workspace_bytes", "vc_verify_attn",
+           "vc_verify_plan", "vc_verify_attn_range", "vc_verify_finish",
            "vc_accept_workspace_bytes", "vc_accept_len", "vc_swap_in", "vc_swap_wait", "vc_swap_query", "vc_swap_sync",
            "vc_keep_from_dropped"]
 
@@ -73,6 +75,12 @@ def load():
     lib.vc_verify_attn.argtypes = [C.c_void_p, C.POINTER(vc_full_kv), C.c_void_p, C.c_void_p, C.c_void_p,
                                    C.c_void_p, C.c_int32, C.c_float, C.c_void_p, C.c_void_p, C.c_void_p,
                                    C.c_size_t, C.c_void_p]
+    lib.vc_verify_plan.argtypes = [C.POINTER(vc_full_kv), C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
+    lib.vc_verify_attn_range.argtypes = [C.c_void_p, C.POINTER(vc_full_kv), C.c_void_p, C.c_void_p, C.c_void_p,
+                                         C.c_void_p, C.c_int32, C.c_float, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
+                                         C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.vc_verify_finish.argtypes = [C.c_void_p, C.POINTER(vc_full_kv), C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p,
+                                     C.c_void_p, C.c_size_t, C.c_void_p]
     lib.vc_accept_workspace_bytes.argtypes = [C.c_int32, C.c_int32, C.POINTER(C.c_size_t)]
     lib.vc_accept_len.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p,
                                   C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
@@ -174,35 +182,71 @@ def vc_draft_attn(ctx: Context, q, softmax_scale, out, *, n_kv_heads, lse=None, 
     return out
 
 
-def _full_desc(n_q_heads, n_kv_heads, n_seqs, k, v, cu_ctx, max_ctx, max_win, head_dim=128, sum_ctx=0):
+def _full_desc(n_q_heads, n_kv_heads, n_seqs, k, v, cu_ctx, max_ctx, max_win, head_dim=128, sum_ctx=0,
+               chunk_tokens=0):
     d = vc_full_kv()
     d.n_seqs, d.n_q_heads, d.n_kv_heads, d.head_dim = n_seqs, n_q_heads, n_kv_heads, head_dim
-    d.max_ctx, d.max_win, d.sum_ctx = max_ctx, max_win, sum_ctx
+    d.max_ctx, d.max_win, d.sum_ctx, d.chunk_tokens = max_ctx, max_win, sum_ctx, chunk_tokens
     d.k = _ptr(k, torch.bfloat16, "k"); d.v = _ptr(v, torch.bfloat16, "v")
     d.cu_ctx = _ptr(cu_ctx, torch.int32, "cu_ctx")
     return d
 
 
 def vc_verify_workspace_bytes(n_q_heads, n_kv_heads, n_seqs, *, k, v, cu_ctx, max_ctx, max_win, total_win,
-                              sum_ctx=0) -> int:
-    d = _full_desc(n_q_heads, n_kv_heads, n_seqs, k, v, cu_ctx, max_ctx, max_win, sum_ctx=sum_ctx)
+                              sum_ctx=0, chunk_tokens=0) -> int:
+    d = _full_desc(n_q_heads, n_kv_heads, n_seqs, k, v, cu_ctx, max_ctx, max_win, sum_ctx=sum_ctx,
+                   chunk_tokens=chunk_tokens)
     n = C.c_size_t()
     _check(load().vc_verify_workspace_bytes(C.byref(d), int(total_win), C.byref(n)))
     return n.value
 
 
 def vc_verify_attn(ctx: Context, q_win, k_win, v_win, cu_win, softmax_scale, out, *, k, v, cu_ctx, max_ctx,
-                   max_win, n_seqs, lse=None, workspace=None, stream=None, sum_ctx=0):
+                   max_win, n_seqs, lse=None, workspace=None, stream=None, sum_ctx=0, chunk_tokens=0):
     total_win, n_q_heads = q_win.shape[0], q_win.shape[1]
     n_kv_heads = k_win.shape[1]
     d = _full_desc(n_q_heads, n_kv_heads, n_seqs, k, v, cu_ctx, max_ctx, max_win, head_dim=q_win.shape[2],
-                   sum_ctx=sum_ctx)
+                   sum_ctx=sum_ctx, chunk_tokens=chunk_tokens)
     ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
     _check(load().vc_verify_attn(ctx.handle, C.byref(d), _ptr(q_win, torch.bfloat16, "q_win"),
                                  _ptr(k_win, torch.bfloat16, "k_win"), _ptr(v_win, torch.bfloat16, "v_win"),
                                  _ptr(cu_win, torch.int32, "cu_win"), int(total_win), float(softmax_scale),
                                  _ptr(out, torch.bfloat16, "out"), _ptr(lse, torch.float32, "lse"),
                                  _ptr(workspace, None, "workspace"), ws_bytes, _stream(stream)))
+    return out
+
+
+def vc_verify_plan(n_q_heads, n_kv_heads, n_seqs, *, k, v, cu_ctx, max_ctx, max_win, sum_ctx=0, chunk_tokens=0):
+    """Returns (chunk_tokens, n_chunks) of the verify launch plan."""
+    d = _full_desc(n_q_heads, n_kv_heads, n_seqs, k, v, cu_ctx, max_ctx, max_win, sum_ctx=sum_ctx,
+                   chunk_tokens=chunk_tokens)
+    ct, nc = C.c_int32(), C.c_int32()
+    _check(load().vc_verify_plan(C.byref(d), C.byref(ct), C.byref(nc)))
+    return ct.value, nc.value
+
+
+def vc_verify_attn_range(ctx: Context, q_win, k_win, v_win, cu_win, softmax_scale, seq_begin, seq_end, tok_begin,
+                         tok_end, *, k, v, cu_ctx, max_ctx, max_win, n_seqs, workspace, stream=None, sum_ctx=0,
+                         chunk_tokens=0):
+    total_win, n_q_heads = q_win.shape[0], q_win.shape[1]
+    d = _full_desc(n_q_heads, k_win.shape[1], n_seqs, k, v, cu_ctx, max_ctx, max_win, head_dim=q_win.shape[2],
+                   sum_ctx=sum_ctx, chunk_tokens=chunk_tokens)
+    _check(load().vc_verify_attn_range(ctx.handle, C.byref(d), _ptr(q_win, torch.bfloat16, "q_win"),
+                                       _ptr(k_win, torch.bfloat16, "k_win"), _ptr(v_win, torch.bfloat16, "v_win"),
+                                       _ptr(cu_win, torch.int32, "cu_win"), int(total_win), float(softmax_scale),
+                                       int(seq_begin), int(seq_end), int(tok_begin), int(tok_end),
+                                       _ptr(workspace, None, "workspace"), workspace.numel() * workspace.element_size(),
+                                       _stream(stream)))
+
+
+def vc_verify_finish(ctx: Context, cu_win, out, *, n_q_heads, n_kv_heads, k, v, cu_ctx, max_ctx, max_win, n_seqs,
+                     workspace, lse=None, stream=None, sum_ctx=0, chunk_tokens=0):
+    d = _full_desc(n_q_heads, n_kv_heads, n_seqs, k, v, cu_ctx, max_ctx, max_win, sum_ctx=sum_ctx,
+                   chunk_tokens=chunk_tokens)
+    _check(load().vc_verify_finish(ctx.handle, C.byref(d), _ptr(cu_win, torch.int32, "cu_win"), int(out.shape[0]),
+                                   _ptr(out, torch.bfloat16, "out"), _ptr(lse, torch.float32, "lse"),
+                                   _ptr(workspace, None, "workspace"), workspace.numel() * workspace.element_size(),
+                                   _stream(stream)))
     return out
 
 

@@ -31,6 +31,7 @@ struct VerifyParams {
   float* ws;
   int n_q_heads, n_kv_heads, g;
   int chunk_tok, ns;   // ns = 4 * chunks of the longest sequence
+  int seq0, chunk0, tok_hi;   // this launch: first sequence, first chunk, end of the token range
   float scale_log2e;
 };
 
@@ -107,7 +108,7 @@ __device__ __forceinline__ void verify_body(const VerifyParams& p, char* smem, i
   const int R = w * p.g;
   const int total = N + w;
   const int t_begin = chunk * p.chunk_tok;
-  const int t_end = min(total, t_begin + p.chunk_tok);
+  const int t_end = min(min(total, p.tok_hi), t_begin + p.chunk_tok);
   const int ntiles = (t_end - t_begin + TT - 1) / TT;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int rg = wave % NRG, tg = wave / NRG;
@@ -326,11 +327,11 @@ __device__ __forceinline__ int tokens_split(int rows, bool wide) {
 // 8 waves x 32 rows: windows with up to 128 rows per KV head (HBM bound)
 __global__ __launch_bounds__(512) void verify_kernel(VerifyParams p) {
   extern __shared__ __attribute__((aligned(1024))) char smem[];
-  const int b = blockIdx.z, kvh = blockIdx.y, chunk = blockIdx.x;
+  const int b = p.seq0 + blockIdx.z, kvh = blockIdx.y, chunk = p.chunk0 + blockIdx.x;
   const int w0 = p.cu_win[b], w = p.cu_win[b + 1] - w0;
   if (w == 0) return;
   const int c0 = p.cu_ctx[b], N = p.cu_ctx[b + 1] - c0;
-  if (chunk * p.chunk_tok >= N + w) return;
+  if (chunk * p.chunk_tok >= min(N + w, p.tok_hi)) return;
   if (tokens_split(w * p.g, false) == 2) verify_body<2, 1>(p, smem, kvh, chunk, w0, w, c0, N);
   else verify_body<1, 1>(p, smem, kvh, chunk, w0, w, c0, N);
 }
@@ -338,11 +339,11 @@ __global__ __launch_bounds__(512) void verify_kernel(VerifyParams p) {
 // 4 waves x 64 rows: used when some window has more than 128 rows (matrix-core / LDS bound)
 __global__ __launch_bounds__(256) void verify_wide_kernel(VerifyParams p) {
   extern __shared__ __attribute__((aligned(1024))) char smem[];
-  const int b = blockIdx.z, kvh = blockIdx.y, chunk = blockIdx.x;
+  const int b = p.seq0 + blockIdx.z, kvh = blockIdx.y, chunk = p.chunk0 + blockIdx.x;
   const int w0 = p.cu_win[b], w = p.cu_win[b + 1] - w0;
   if (w == 0) return;
   const int c0 = p.cu_ctx[b], N = p.cu_ctx[b + 1] - c0;
-  if (chunk * p.chunk_tok >= N + w) return;
+  if (chunk * p.chunk_tok >= min(N + w, p.tok_hi)) return;
   if (tokens_split(w * p.g, true) == 2) verify_body<2, 2>(p, smem, kvh, chunk, w0, w, c0, N);
   else verify_body<1, 2>(p, smem, kvh, chunk, w0, w, c0, N);
 }
@@ -398,6 +399,7 @@ static VerifyPlan make_verify_plan(const vc_full_kv* kv) {
   if (per < min_tok) per = min_tok;
   if (per > total_max) per = total_max > 0 ? total_max : 1;
   per = ceil_div64(per, 128) * 128;
+  if (kv->chunk_tokens > 0) per = kv->chunk_tokens;
   pl.chunk_tok = static_cast<int>(per);
   pl.nchunk = ceil_div(total_max > 0 ? total_max : 1, pl.chunk_tok);
   pl.ns = 4 * pl.nchunk;
@@ -412,6 +414,8 @@ static vc_status check_full(const vc_full_kv* kv, const char* who) {
   VC_REQUIRE(kv->n_q_heads % kv->n_kv_heads == 0, VC_ERR_INVALID_ARG, "%s: n_q_heads %d not a multiple of n_kv_heads %d",
              who, kv->n_q_heads, kv->n_kv_heads);
   VC_REQUIRE(kv->max_ctx >= 0 && kv->max_win >= 0 && kv->sum_ctx >= 0, VC_ERR_INVALID_ARG, "%s: negative count", who);
+  VC_REQUIRE(kv->chunk_tokens >= 0 && kv->chunk_tokens % 128 == 0, VC_ERR_INVALID_ARG,
+             "%s: chunk_tokens %d is not a multiple of 128", who, kv->chunk_tokens);
   VC_REQUIRE(kv->max_win * (kv->n_q_heads / kv->n_kv_heads) <= 256, VC_ERR_UNSUPPORTED,
              "%s: window %d x GQA ratio %d exceeds 256 rows", who, kv->max_win, kv->n_q_heads / kv->n_kv_heads);
   VC_REQUIRE(kv->n_seqs <= 65535 && kv->n_kv_heads <= 65535 && kv->n_q_heads <= 65535, VC_ERR_UNSUPPORTED,
@@ -435,23 +439,51 @@ extern "C" vc_status vc_verify_workspace_bytes(const vc_full_kv* kv, int32_t tot
   return VC_OK;
 }
 
-extern "C" vc_status vc_verify_attn(vc_ctx* ctx, const vc_full_kv* kv, const void* q_win, const void* k_win,
-                                    const void* v_win, const int32_t* cu_win, int32_t total_win, float softmax_scale,
-                                    void* out, float* lse, void* workspace, size_t workspace_bytes, void* stream) {
-  VC_REQUIRE(ctx != nullptr, VC_ERR_INVALID_ARG, "vc_verify_attn: ctx is NULL");
-  vc_status stt = check_full(kv, "vc_verify_attn");
+extern "C" vc_status vc_verify_plan(const vc_full_kv* kv, int32_t* chunk_tokens, int32_t* n_chunks) {
+  vc_status st = check_full(kv, "vc_verify_plan");
+  if (st != VC_OK) return st;
+  const VerifyPlan pl = make_verify_plan(kv);
+  if (chunk_tokens) *chunk_tokens = pl.chunk_tok;
+  if (n_chunks) *n_chunks = pl.nchunk;
+  return VC_OK;
+}
+
+static vc_status check_verify_call(vc_ctx* ctx, const vc_full_kv* kv, int32_t total_win, const void* workspace,
+                                   size_t workspace_bytes, const char* who) {
+  VC_REQUIRE(ctx != nullptr, VC_ERR_INVALID_ARG, "%s: ctx is NULL", who);
+  vc_status stt = check_full(kv, who);
   if (stt != VC_OK) return stt;
-  VC_REQUIRE(total_win >= 0, VC_ERR_INVALID_ARG, "vc_verify_attn: total_win %d", total_win);
-  if (kv->n_seqs == 0 || total_win == 0 || kv->max_win == 0) return VC_OK;
-  VC_REQUIRE(q_win && k_win && v_win && cu_win && out, VC_ERR_INVALID_ARG, "vc_verify_attn: NULL pointer");
-  VC_REQUIRE(aligned16(q_win) && aligned16(k_win) && aligned16(v_win) && aligned16(out), VC_ERR_INVALID_ARG,
-             "vc_verify_attn: window tensors not 16-byte aligned");
-  VC_REQUIRE(total_win <= 65535, VC_ERR_UNSUPPORTED, "vc_verify_attn: more than 65535 window rows");
+  VC_REQUIRE(total_win >= 0 && total_win <= 65535, total_win < 0 ? VC_ERR_INVALID_ARG : VC_ERR_UNSUPPORTED,
+             "%s: total_win %d", who, total_win);
   size_t need = 0;
   vc_verify_workspace_bytes(kv, total_win, &need);
-  VC_REQUIRE(workspace != nullptr && workspace_bytes >= need, VC_ERR_WORKSPACE, "vc_verify_attn: workspace %zu bytes, need %zu",
+  VC_REQUIRE(workspace != nullptr && workspace_bytes >= need, VC_ERR_WORKSPACE, "%s: workspace %zu bytes, need %zu", who,
              workspace_bytes, need);
-  VC_REQUIRE(aligned16(workspace), VC_ERR_INVALID_ARG, "vc_verify_attn: workspace not 16-byte aligned");
+  VC_REQUIRE(aligned16(workspace), VC_ERR_INVALID_ARG, "%s: workspace not 16-byte aligned", who);
+  return VC_OK;
+}
+
+extern "C" vc_status vc_verify_attn_range(vc_ctx* ctx, const vc_full_kv* kv, const void* q_win, const void* k_win,
+                                          const void* v_win, const int32_t* cu_win, int32_t total_win,
+                                          float softmax_scale, int32_t seq_begin, int32_t seq_end, int32_t tok_begin,
+                                          int32_t tok_end, void* workspace, size_t workspace_bytes, void* stream) {
+  vc_status stt = check_verify_call(ctx, kv, total_win, workspace, workspace_bytes, "vc_verify_attn_range");
+  if (stt != VC_OK) return stt;
+  VC_REQUIRE(seq_begin >= 0 && seq_begin <= seq_end && seq_end <= kv->n_seqs, VC_ERR_INVALID_ARG,
+             "vc_verify_attn_range: sequences [%d, %d) of %d", seq_begin, seq_end, kv->n_seqs);
+  VC_REQUIRE(tok_begin >= 0 && tok_begin <= tok_end, VC_ERR_INVALID_ARG, "vc_verify_attn_range: tokens [%d, %d)", tok_begin, tok_end);
+  if (seq_begin == seq_end || tok_begin == tok_end || total_win == 0 || kv->max_win == 0) return VC_OK;
+  VC_REQUIRE(q_win && k_win && v_win && cu_win, VC_ERR_INVALID_ARG, "vc_verify_attn_range: NULL pointer");
+  VC_REQUIRE(aligned16(q_win) && aligned16(k_win) && aligned16(v_win), VC_ERR_INVALID_ARG,
+             "vc_verify_attn_range: window tensors not 16-byte aligned");
+  const VerifyPlan pl = make_verify_plan(kv);
+  const int total_max = kv->max_ctx + kv->max_win;
+  VC_REQUIRE(tok_begin % pl.chunk_tok == 0, VC_ERR_INVALID_ARG, "vc_verify_attn_range: tok_begin %d is not a multiple of the chunk length %d",
+             tok_begin, pl.chunk_tok);
+  VC_REQUIRE(tok_end % pl.chunk_tok == 0 || tok_end >= total_max, VC_ERR_INVALID_ARG,
+             "vc_verify_attn_range: tok_end %d is neither a multiple of the chunk length %d nor past the end (%d)", tok_end,
+             pl.chunk_tok, total_max);
+  if (tok_begin >= total_max) return VC_OK;
 
   static bool lds_attr_set = false;
   if (!lds_attr_set) {
@@ -461,7 +493,6 @@ extern "C" vc_status vc_verify_attn(vc_ctx* ctx, const vc_full_kv* kv, const voi
                                hipFuncAttributeMaxDynamicSharedMemorySize, kVerifyLds));
     lds_attr_set = true;
   }
-  const VerifyPlan pl = make_verify_plan(kv);
   hipStream_t st = static_cast<hipStream_t>(stream);
   VerifyParams vp{};
   vp.qw = static_cast<const uint16_t*>(q_win);
@@ -474,22 +505,53 @@ extern "C" vc_status vc_verify_attn(vc_ctx* ctx, const vc_full_kv* kv, const voi
   vp.ws = static_cast<float*>(workspace);
   vp.n_q_heads = kv->n_q_heads; vp.n_kv_heads = kv->n_kv_heads; vp.g = kv->n_q_heads / kv->n_kv_heads;
   vp.chunk_tok = pl.chunk_tok; vp.ns = pl.ns;
+  vp.seq0 = seq_begin;
+  vp.chunk0 = tok_begin / pl.chunk_tok;
+  vp.tok_hi = tok_end;
   vp.scale_log2e = softmax_scale * kLog2e;
-  dim3 grid(pl.nchunk, kv->n_kv_heads, kv->n_seqs);
+  const int hi = tok_end < total_max ? tok_end : total_max;
+  const int nchunk = ceil_div(hi, pl.chunk_tok) - vp.chunk0;
+  dim3 grid(nchunk, kv->n_kv_heads, seq_end - seq_begin);
   // The 64-rows-per-wave variant halves the LDS traffic per flop but leaves one wave per SIMD;
   // measured slower at every window (1781 vs 1409 us at w = 64, config-2 shape), so it is opt-in.
   const bool wide = env_int("VC_VERIFY_WIDE", 0, 0, 1) != 0;
   if (wide) hipLaunchKernelGGL(verify_wide_kernel, grid, dim3(256), kVerifyLds, st, vp);
   else hipLaunchKernelGGL(verify_kernel, grid, dim3(512), kVerifyLds, st, vp);
+  VC_HIP(hipGetLastError());
+  return VC_OK;
+}
+
+extern "C" vc_status vc_verify_finish(vc_ctx* ctx, const vc_full_kv* kv, const int32_t* cu_win, int32_t total_win,
+                                      void* out, float* lse, void* workspace, size_t workspace_bytes, void* stream) {
+  vc_status stt = check_verify_call(ctx, kv, total_win, workspace, workspace_bytes, "vc_verify_finish");
+  if (stt != VC_OK) return stt;
+  if (kv->n_seqs == 0 || total_win == 0 || kv->max_win == 0) return VC_OK;
+  VC_REQUIRE(cu_win && out, VC_ERR_INVALID_ARG, "vc_verify_finish: NULL pointer");
+  VC_REQUIRE(aligned16(out), VC_ERR_INVALID_ARG, "vc_verify_finish: out not 16-byte aligned");
+  const VerifyPlan pl = make_verify_plan(kv);
   VerifyMergeParams mp{};
-  mp.ws = vp.ws;
+  mp.ws = static_cast<const float*>(workspace);
   mp.out = static_cast<uint16_t*>(out);
   mp.lse = lse;
   mp.cu_ctx = kv->cu_ctx;
   mp.cu_win = cu_win;
-  mp.n_seqs = kv->n_seqs; mp.n_q_heads = kv->n_q_heads; mp.g = vp.g; mp.ns = pl.ns; mp.chunk_tok = pl.chunk_tok;
-  mp.wide = wide ? 1 : 0;
-  hipLaunchKernelGGL(verify_merge_kernel, dim3(kv->n_q_heads, total_win), dim3(128), 0, st, mp);
+  mp.n_seqs = kv->n_seqs; mp.n_q_heads = kv->n_q_heads; mp.g = kv->n_q_heads / kv->n_kv_heads; mp.ns = pl.ns;
+  mp.chunk_tok = pl.chunk_tok;
+  mp.wide = env_int("VC_VERIFY_WIDE", 0, 0, 1);
+  hipLaunchKernelGGL(verify_merge_kernel, dim3(kv->n_q_heads, total_win), dim3(128), 0, static_cast<hipStream_t>(stream), mp);
   VC_HIP(hipGetLastError());
   return VC_OK;
+}
+
+extern "C" vc_status vc_verify_attn(vc_ctx* ctx, const vc_full_kv* kv, const void* q_win, const void* k_win,
+                                    const void* v_win, const int32_t* cu_win, int32_t total_win, float softmax_scale,
+                                    void* out, float* lse, void* workspace, size_t workspace_bytes, void* stream) {
+  vc_status stt = check_verify_call(ctx, kv, total_win, workspace, workspace_bytes, "vc_verify_attn");
+  if (stt != VC_OK) return stt;
+  if (kv->n_seqs == 0 || total_win == 0 || kv->max_win == 0) return VC_OK;
+  VC_REQUIRE(out != nullptr, VC_ERR_INVALID_ARG, "vc_verify_attn: out is NULL");
+  stt = vc_verify_attn_range(ctx, kv, q_win, k_win, v_win, cu_win, total_win, softmax_scale, 0, kv->n_seqs, 0,
+                             kv->max_ctx + kv->max_win, workspace, workspace_bytes, stream);
+  if (stt != VC_OK) return stt;
+  return vc_verify_finish(ctx, kv, cu_win, total_win, out, lse, workspace, workspace_bytes, stream);
 }
