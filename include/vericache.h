@@ -50,6 +50,12 @@ vc_status vc_destroy(vc_ctx* ctx);
 const char* vc_last_error(void);
 /* Library version, "major.minor". */
 const char* vc_version(void);
+/* Measurement aid.  Arms two caller-owned hipEvent_t (passed as void*, created with timing
+ * enabled): the next vc_draft_attn or vc_verify_attn[_range] call on this context records
+ * `begin_event` on its stream just before its main attention kernel(s) and `end_event` just after
+ * them, i.e. without the merge kernel that follows, then disarms.  Pass two NULLs to disarm.
+ * The events must stay alive until that call has been made. */
+vc_status vc_time_main_kernel(vc_ctx* ctx, void* begin_event, void* end_event);
 
 /* ------------------------------------------------------------------------------------------
  * Compressed KV of one attention layer for a ragged batch (paper section 6: a compressed cache

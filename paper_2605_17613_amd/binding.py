@@ -44,7 +44,7 @@ class vc_chunk(C.Structure):
     _fields_ = [("src_off", C.c_size_t), ("dst_off", C.c_size_t), ("bytes", C.c_size_t)]
 
 
-EXPORTS = ["vc_create", "vc_destroy", "vc_last_error", "vc_version",
+EXPORTS = ["vc_create", "vc_destroy", "vc_last_error", "vc_version", "vc_time_main_kernel",
            "vc_draft_workspace_bytes", "vc_draft_attn", "vc_verify_workspace_bytes", "vc_verify_attn",
            "vc_verify_plan", "vc_verify_attn_range", "vc_verify_finish",
            "vc_accept_workspace_bytes", "vc_accept_len", "vc_swap_in", "vc_swap_wait", "vc_swap_query", "vc_swap_sync",
@@ -68,6 +68,7 @@ def load():
     lib.vc_version.restype = C.c_char_p
     lib.vc_create.argtypes = [C.c_int, C.POINTER(C.c_void_p)]
     lib.vc_destroy.argtypes = [C.c_void_p]
+    lib.vc_time_main_kernel.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
     lib.vc_draft_workspace_bytes.argtypes = [C.POINTER(vc_comp_kv), C.POINTER(C.c_size_t)]
     lib.vc_draft_attn.argtypes = [C.c_void_p, C.POINTER(vc_comp_kv), C.c_void_p, C.c_float, C.c_void_p,
                                   C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
@@ -292,6 +293,14 @@ def vc_swap_query(ctx: Context, ticket: int) -> bool:
         return False
     _check(st)
     return True
+
+
+def vc_time_main_kernel(ctx: Context, begin_event=None, end_event=None):
+    """Arm two torch.cuda.Event(enable_timing=True) objects (already recorded once, so that their
+    handles exist) around the main kernel(s) of the next attention call; None, None disarms."""
+    b = None if begin_event is None else C.c_void_p(begin_event.cuda_event)
+    e = None if end_event is None else C.c_void_p(end_event.cuda_event)
+    _check(load().vc_time_main_kernel(ctx.handle, b, e))
 
 
 def vc_swap_sync(ctx: Context):

@@ -45,4 +45,16 @@ struct vc_ctx {
   static constexpr int kRing = 4096;
   hipEvent_t* events;  // created on first use
   int64_t issued;  // next ticket
+  // armed by vc_time_main_kernel: events recorded around the main kernel(s) of the next attention call
+  hipEvent_t time_begin, time_end;
 };
+
+namespace vc {
+// Record the armed timing events (if any) on `st`; the end mark disarms.
+inline void mark_begin(vc_ctx* c, hipStream_t st) { if (c->time_begin) (void)hipEventRecord(c->time_begin, st); }
+inline void mark_end(vc_ctx* c, hipStream_t st) {
+  if (c->time_end) (void)hipEventRecord(c->time_end, st);
+  c->time_begin = nullptr; c->time_end = nullptr;
+}
+}  // namespace vc
+

@@ -66,6 +66,15 @@ extern "C" vc_status vc_create(int device, vc_ctx** out) {
   return VC_OK;
 }
 
+extern "C" vc_status vc_time_main_kernel(vc_ctx* c, void* begin_event, void* end_event) {
+  VC_REQUIRE(c != nullptr, VC_ERR_INVALID_ARG, "vc_time_main_kernel: ctx is NULL");
+  VC_REQUIRE((begin_event == nullptr) == (end_event == nullptr), VC_ERR_INVALID_ARG,
+             "vc_time_main_kernel: pass both events or neither");
+  c->time_begin = static_cast<hipEvent_t>(begin_event);
+  c->time_end = static_cast<hipEvent_t>(end_event);
+  return VC_OK;
+}
+
 extern "C" vc_status vc_destroy(vc_ctx* c) {
   if (!c) return VC_OK;
   (void)hipStreamSynchronize(c->copy_stream);

@@ -598,74 +598,118 @@ struct DraftMergeParams {
 
 // One workgroup of 128 threads per (sequence, query head).  The tail holds at most a few tens of
 // tokens (this horizon's drafts plus a partial block), so it is attended to here instead of in a
-// launch of its own: thread t scores token t, thread d accumulates channel d.
+// launch of its own: thread t scores token t, thread d accumulates channel d.  Everything the
+// kernel needs (partials, q, the thread's key row, the first value rows) is requested up front so
+// that the launch costs one memory round trip, not one per stage.
+constexpr int kTailPrefetch = 32;
+
 __global__ __launch_bounds__(128) void draft_merge_kernel(DraftMergeParams p) {
   const int b = blockIdx.y, h = blockIdx.x, d = threadIdx.x;
   const int n1 = p.cu_a ? ceil_div_dev(p.cu_a[b + 1] - p.cu_a[b], p.split_a) : 0;
   const int n2 = p.cu_blk ? ceil_div_dev(p.cu_blk[b + 1] - p.cu_blk[b], p.bps) : 0;
-  const float* base = p.ws + (static_cast<size_t>(b) * p.n_q_heads + h) * p.ns * kPartialFloats;
-  float mm = -INFINITY;
-  for (int s = 0; s < n1; ++s) mm = fmaxf(mm, base[static_cast<size_t>(s) * kPartialFloats]);
-  for (int s = 0; s < n2; ++s) mm = fmaxf(mm, base[static_cast<size_t>(p.s1 + s) * kPartialFloats]);
-  float acc = 0.f, lsum = 0.f;
-  for (int src = 0; src < 2; ++src) {
-    const int cnt = src == 0 ? n1 : n2;
-    const int off = src == 0 ? 0 : p.s1;
-#pragma unroll 4
-    for (int s = 0; s < cnt; ++s) {
-      const float* pp = base + static_cast<size_t>(off + s) * kPartialFloats;
-      const float a = exp2_diff(pp[0], mm);
-      acc = fmaf(a, pp[2 + d], acc);
-      lsum = fmaf(a, pp[1], lsum);
-    }
-  }
+  const int nsl = n1 + n2;
+  int t0 = 0, nt = 0;
   if (p.tail_k) {
-    const int t0 = p.cu_tail[b], nt = p.cu_tail[b + 1] - t0;
-    if (nt > 0) {
-      __shared__ float qs[kHeadDim];
-      __shared__ float ps[128];
-      __shared__ float red[2];
-      const int kvh = h / p.g;
-      qs[d] = bf16_bits_to_float(p.q[(static_cast<size_t>(b) * p.n_q_heads + h) * kHeadDim + d]) * p.scale_log2e;
-      __syncthreads();
-      const size_t row_stride = static_cast<size_t>(p.n_kv_heads) * kHeadDim;
-      for (int c0 = 0; c0 < nt; c0 += 128) {
-        const int t = c0 + d;
-        float s = -INFINITY;
-        if (t < nt) {
-          const uint16_t* kr = p.tail_k + static_cast<size_t>(t0 + t) * row_stride + static_cast<size_t>(kvh) * kHeadDim;
-          float a = 0.f;
+    t0 = p.cu_tail[b];
+    nt = p.cu_tail[b + 1] - t0;
+  }
+  const int kvh = h / p.g;
+  const size_t row_stride = static_cast<size_t>(p.n_kv_heads) * kHeadDim;
+  // requests for the tail first (they are consumed last)
+  uint4 kraw[16];
+  uint16_t vpre[kTailPrefetch];
+  float qd = 0.f;
+  if (nt > 0) {
+    qd = bf16_bits_to_float(p.q[(static_cast<size_t>(b) * p.n_q_heads + h) * kHeadDim + d]) * p.scale_log2e;
+    const int tk = min(d, nt - 1);
+    const uint16_t* kr = p.tail_k + static_cast<size_t>(t0 + tk) * row_stride + static_cast<size_t>(kvh) * kHeadDim;
 #pragma unroll
-          for (int i = 0; i < 16; ++i) {
-            const uint4 raw = *reinterpret_cast<const uint4*>(kr + 8 * i);
-            const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+    for (int i = 0; i < 16; ++i) kraw[i] = *reinterpret_cast<const uint4*>(kr + 8 * i);
+    const uint16_t* vr = p.tail_v + static_cast<size_t>(t0) * row_stride + static_cast<size_t>(kvh) * kHeadDim + d;
 #pragma unroll
-            for (int k = 0; k < 4; ++k) {
-              a = fmaf(qs[8 * i + 2 * k], bf16_lo(w[k]), a);
-              a = fmaf(qs[8 * i + 2 * k + 1], bf16_hi(w[k]), a);
-            }
+    for (int t = 0; t < kTailPrefetch; ++t) vpre[t] = vr[static_cast<size_t>(min(t, nt - 1)) * row_stride];
+  }
+  const float* base = p.ws + (static_cast<size_t>(b) * p.n_q_heads + h) * p.ns * kPartialFloats;
+  float mm = -INFINITY, acc = 0.f, lsum = 0.f;
+  for (int s0 = 0; s0 < nsl; s0 += 8) {
+    float m8[8], l8[8], o8[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int s = min(s0 + i, nsl - 1);
+      const float* pp = base + static_cast<size_t>(s < n1 ? s : p.s1 + (s - n1)) * kPartialFloats;
+      m8[i] = s0 + i < nsl ? pp[0] : -INFINITY;
+      l8[i] = pp[1];
+      o8[i] = pp[2 + d];
+    }
+    float mn = mm;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) mn = fmaxf(mn, m8[i]);
+    const float alpha = exp2_diff(mm, mn);
+    acc *= alpha;
+    lsum *= alpha;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const float a = exp2_diff(m8[i], mn);
+      acc = fmaf(a, o8[i], acc);
+      lsum = fmaf(a, l8[i], lsum);
+    }
+    mm = mn;
+  }
+  if (nt > 0) {
+    __shared__ float qs[kHeadDim];
+    __shared__ float ps[128];
+    __shared__ float red[2];
+    qs[d] = qd;
+    __syncthreads();
+    for (int c0 = 0; c0 < nt; c0 += 128) {
+      const int t = c0 + d;
+      float s = -INFINITY;
+      if (c0 > 0 && t < nt) {
+        const uint16_t* kr = p.tail_k + static_cast<size_t>(t0 + t) * row_stride + static_cast<size_t>(kvh) * kHeadDim;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) kraw[i] = *reinterpret_cast<const uint4*>(kr + 8 * i);
+      }
+      if (t < nt) {
+        float a = 0.f;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+          const uint32_t w[4] = {kraw[i].x, kraw[i].y, kraw[i].z, kraw[i].w};
+#pragma unroll
+          for (int k = 0; k < 4; ++k) {
+            a = fmaf(qs[8 * i + 2 * k], bf16_lo(w[k]), a);
+            a = fmaf(qs[8 * i + 2 * k + 1], bf16_hi(w[k]), a);
           }
-          s = a;
         }
-        const float wm = wave_max(s);
-        if ((d & 63) == 0) red[d >> 6] = wm;
-        __syncthreads();
-        const float mn = fmaxf(mm, fmaxf(red[0], red[1]));
-        const float alpha = exp2_diff(mm, mn);
-        ps[d] = exp2_diff(s, mn);
-        __syncthreads();
-        acc *= alpha;
-        lsum *= alpha;
-        const int cn = min(128, nt - c0);
-        const uint16_t* vr = p.tail_v + static_cast<size_t>(t0 + c0) * row_stride + static_cast<size_t>(kvh) * kHeadDim + d;
-        for (int t2 = 0; t2 < cn; ++t2) {
-          const float pv = ps[t2];
-          acc = fmaf(pv, bf16_bits_to_float(vr[static_cast<size_t>(t2) * row_stride]), acc);
+        s = a;
+      }
+      const float wm = wave_max(s);
+      if ((d & 63) == 0) red[d >> 6] = wm;
+      __syncthreads();
+      const float mn = fmaxf(mm, fmaxf(red[0], red[1]));
+      const float alpha = exp2_diff(mm, mn);
+      ps[d] = exp2_diff(s, mn);
+      __syncthreads();
+      acc *= alpha;
+      lsum *= alpha;
+      const int cn = min(128, nt - c0);
+      int t2 = 0;
+      if (c0 == 0) {
+#pragma unroll
+        for (int u = 0; u < kTailPrefetch; ++u) {
+          const float pv = u < cn ? ps[u] : 0.f;
+          acc = fmaf(pv, bf16_bits_to_float(vpre[u]), acc);
           lsum += pv;
         }
-        mm = mn;
-        __syncthreads();
+        t2 = min(cn, kTailPrefetch);
       }
+      const uint16_t* vr = p.tail_v + static_cast<size_t>(t0 + c0) * row_stride + static_cast<size_t>(kvh) * kHeadDim + d;
+      for (; t2 < cn; ++t2) {
+        const float pv = ps[t2];
+        acc = fmaf(pv, bf16_bits_to_float(vr[static_cast<size_t>(t2) * row_stride]), acc);
+        lsum += pv;
+      }
+      mm = mn;
+      __syncthreads();
     }
   }
   const float o = lsum > 0.f ? acc / lsum : 0.f;
@@ -789,6 +833,7 @@ extern "C" vc_status vc_draft_attn(vc_ctx* ctx, const vc_comp_kv* kv, const void
   const float sl2 = softmax_scale * kLog2e;
   float* ws = static_cast<float*>(workspace);
 
+  mark_begin(ctx, st);
   if (pl.s1 > 0) {
     DraftBf16Params bp{};
     bp.q = static_cast<const uint16_t*>(q);
@@ -818,6 +863,7 @@ extern "C" vc_status vc_draft_attn(vc_ctx* ctx, const vc_comp_kv* kv, const void
     if (kv->bits == 4) hipLaunchKernelGGL(draft_quant_kernel<4>, grid, dim3(256), 0, st, qp);
     else hipLaunchKernelGGL(draft_quant_kernel<2>, grid, dim3(256), 0, st, qp);
   }
+  mark_end(ctx, st);
   DraftMergeParams mp{};
   mp.ws = ws;
   mp.q = static_cast<const uint16_t*>(q);

@@ -357,6 +357,8 @@ struct VerifyMergeParams {
   int n_seqs, n_q_heads, g, ns, chunk_tok, wide;
 };
 
+// One workgroup of 128 threads per (window row, query head); slots are fetched eight at a time so
+// that a launch costs about one memory round trip.
 __global__ __launch_bounds__(128) void verify_merge_kernel(VerifyMergeParams p) {
   const int row = blockIdx.y, h = blockIdx.x, d = threadIdx.x;
   int b = 0;
@@ -365,18 +367,33 @@ __global__ __launch_bounds__(128) void verify_merge_kernel(VerifyMergeParams p) 
   const int total = (p.cu_ctx[b + 1] - p.cu_ctx[b]) + w;
   const int nchunk = ceil_div_dev(total, p.chunk_tok);
   const int ntg = tokens_split(w * p.g, p.wide != 0);
+  const int nsl = nchunk * ntg;
   const float* base = p.ws + (static_cast<size_t>(row) * p.n_q_heads + h) * p.ns * kPartialFloats;
-  float mm = -INFINITY;
-  for (int c = 0; c < nchunk; ++c)
-    for (int t = 0; t < ntg; ++t) mm = fmaxf(mm, base[static_cast<size_t>(4 * c + t) * kPartialFloats]);
-  float acc = 0.f, lsum = 0.f;
-  for (int c = 0; c < nchunk; ++c) {
-    for (int t = 0; t < ntg; ++t) {
-      const float* pp = base + static_cast<size_t>(4 * c + t) * kPartialFloats;
-      const float a = exp2_diff(pp[0], mm);
-      acc = fmaf(a, pp[2 + d], acc);
-      lsum = fmaf(a, pp[1], lsum);
+  float mm = -INFINITY, acc = 0.f, lsum = 0.f;
+  for (int s0 = 0; s0 < nsl; s0 += 8) {
+    float m8[8], l8[8], o8[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int s = min(s0 + i, nsl - 1);
+      const int slot = ntg == 2 ? 4 * (s >> 1) + (s & 1) : 4 * s;
+      const float* pp = base + static_cast<size_t>(slot) * kPartialFloats;
+      m8[i] = s0 + i < nsl ? pp[0] : -INFINITY;
+      l8[i] = pp[1];
+      o8[i] = pp[2 + d];
     }
+    float mn = mm;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) mn = fmaxf(mn, m8[i]);
+    const float alpha = exp2_diff(mm, mn);
+    acc *= alpha;
+    lsum *= alpha;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const float a = exp2_diff(m8[i], mn);
+      acc = fmaf(a, o8[i], acc);
+      lsum = fmaf(a, l8[i], lsum);
+    }
+    mm = mn;
   }
   const float o = lsum > 0.f ? acc / lsum : 0.f;
   p.out[(static_cast<size_t>(row) * p.n_q_heads + h) * kHeadDim + d] = static_cast<uint16_t>(float_to_bf16_bits(o));
@@ -515,8 +532,10 @@ extern "C" vc_status vc_verify_attn_range(vc_ctx* ctx, const vc_full_kv* kv, con
   // The 64-rows-per-wave variant halves the LDS traffic per flop but leaves one wave per SIMD;
   // measured slower at every window (1781 vs 1409 us at w = 64, config-2 shape), so it is opt-in.
   const bool wide = env_int("VC_VERIFY_WIDE", 0, 0, 1) != 0;
+  mark_begin(ctx, st);
   if (wide) hipLaunchKernelGGL(verify_wide_kernel, grid, dim3(256), kVerifyLds, st, vp);
   else hipLaunchKernelGGL(verify_kernel, grid, dim3(512), kVerifyLds, st, vp);
+  mark_end(ctx, st);
   VC_HIP(hipGetLastError());
   return VC_OK;
 }

@@ -211,3 +211,27 @@ def test_workspace_too_small_and_null(lib, ctx):
     with pytest.raises(lib.VcError) as e:
         lib.vc_draft_attn(ctx, lay.q, lay.scale, out, n_kv_heads=2, workspace=None, **kw)
     assert e.value.status == 3
+
+
+def test_main_kernel_timing_events(lib, ctx):
+    """vc_time_main_kernel brackets the main kernel inside the call: 0 < kernel time <= call time,
+    and the hook disarms itself (a second call leaves the events alone)."""
+    lay = synth.config(0, DEV)
+    kw = H.draft_kwargs(lay, bits=4)
+    out = torch.empty_like(lay.q)
+    ws = torch.empty(max(lib.vc_draft_workspace_bytes(lay.n_q_heads, lay.n_kv_heads, 1, **kw), 16), dtype=torch.uint8, device=DEV)
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+    for e in ev:
+        e.record()
+    lib.vc_time_main_kernel(ctx, ev[1], ev[2])
+    ev[0].record()
+    lib.vc_draft_attn(ctx, lay.q, lay.scale, out, n_kv_heads=lay.n_kv_heads, workspace=ws, **kw)
+    ev[3].record()
+    torch.cuda.synchronize()
+    inner, outer = ev[1].elapsed_time(ev[2]), ev[0].elapsed_time(ev[3])
+    assert 0.0 < inner <= outer
+    lib.vc_draft_attn(ctx, lay.q, lay.scale, out, n_kv_heads=lay.n_kv_heads, workspace=ws, **kw)
+    torch.cuda.synchronize()
+    assert ev[1].elapsed_time(ev[2]) == inner
+    with pytest.raises(lib.VcError):
+        lib.vc_time_main_kernel(ctx, ev[0], None)
