@@ -12,6 +12,10 @@ What it computes, step by step, in IEEE double precision (paper section 4.1, cor
   accept  (step 3) - greedy: first position whose draft id differs from the arg-max of the
                      verify logits; the correction (or bonus) token follows.
   keep    (section 6, CompressedKV.dropped_indices) - complement of the dropped positions.
+  compress / decompress (section 6, Compressor interface, quantising methods) - min/max group
+                     quantiser into block records (decisions in float32, spelled out at
+                     quantise_groups) and its inverse, rounded once to bf16.
+  topk_keep (section 6, what update() decides) - kept positions from importance scores.
 
 Every input is taken in the byte layout that the C header of the library describes in prose
 (bf16 / fp16 bit patterns, packed codes); the unpacking below is written from that prose and
@@ -23,7 +27,11 @@ give the mean of the values; a dominant key returns its value row; brute force w
 on tiny shapes; split/merge invariance; zero dropping equals full attention; lossless quantisation
 grids equal bf16 attention; hand-packed records (written element by element from the layout
 prose) unpack to the planted codes; causal rows do not see later rows; planted arg-max logits,
-planted ties, brute-force set difference.  No function here is "parity unpinned".
+planted ties, brute-force set difference; for the compressor side: hand-computed groups and
+rounding ties, closed-form records against a byte-by-byte hand packer, error bound and extreme
+codes per group, key/value group axes, a second vectorised packer, grid data surviving a round
+trip, single rounding to bf16, brute-force top-k with exact ties and forced positions.
+No function here is "parity unpinned".
 """
 from __future__ import annotations
 
@@ -331,5 +339,144 @@ def keep_from_dropped(dropped, cu_drop, ctx_len, n_kv_heads: int):
             gone = np.zeros(n, dtype=bool)
             gone[dropped[start:start + nd]] = True
             pieces.append(np.flatnonzero(~gone).astype(np.int32))
+    keep = np.concatenate(pieces) if pieces else np.zeros(0, dtype=np.int32)
+    return keep, cu_keep
+
+
+# --------------------------------------------------------------------------------------------
+# quantising compressor and its inverse  (section 6: Compressor.compress / decompress for the
+# quantisation methods; section 2: keys per channel, values per token)
+# --------------------------------------------------------------------------------------------
+def quantise_groups(x32: np.ndarray, levels: int):
+    """Asymmetric min/max quantisation of groups along the last axis.
+
+    The decisions are integers taken from floating point, so the precision is part of the
+    definition: everything below is IEEE float32 (one rounding per operation), the stored scale and
+    zero point are fp16 (round to nearest even), and the code is computed from the STORED values:
+        zero  = fp16(min)                       scale = fp16((max - min) / levels)
+        code  = clamp(rne((x - zero) * (1 / scale)), 0, levels)      (scale = 0: code 0)
+    Returns (code int64 [..., G], scale fp16 [...], zero fp16 [...]).
+    """
+    x32 = np.asarray(x32, dtype=np.float32)
+    mn = x32.min(axis=-1)
+    mx = x32.max(axis=-1)
+    zero = mn.astype(np.float16)
+    scale = ((mx - mn) / np.float32(levels)).astype(np.float16)
+    zf = zero.astype(np.float32)[..., None]
+    sf = scale.astype(np.float32)[..., None]
+    pos = sf > 0
+    inv = np.float32(1.0) / np.where(pos, sf, np.float32(1.0))
+    code = np.rint((x32 - zf) * inv)
+    code = np.clip(code, 0, levels)
+    code = np.where(pos, code, 0.0).astype(np.int64)
+    return code, scale, zero
+
+
+def _put_field(words, index, e, bits, code):
+    """OR `code` into element e of words[..., index] (element e sits at bit 16*(e%2)+bits*(e//2))."""
+    words[..., index] |= (code.astype(np.uint32) << np.uint32(16 * (e % 2) + bits * (e // 2)))
+
+
+def quantize_records(k_bits: np.ndarray, v_bits: np.ndarray, bits: int) -> np.ndarray:
+    """bf16 K, V bit patterns [T, n_heads, 128] of one sequence -> block records
+    uint8 [n_heads, T // TB, 5120] over its first (T // TB) * TB tokens (the layout is the one
+    unpack_records documents).  Keys: one group per channel over the TB tokens of a block;
+    values: one group per token over TB consecutive channels."""
+    tb = tokens_per_block(bits)
+    levels = (1 << bits) - 1
+    per_word = 32 // bits
+    words_per_token = HEAD_DIM // per_word
+    ngrp = HEAD_DIM // tb
+    t_all, nh, d = np.asarray(k_bits).shape
+    if d != HEAD_DIM:
+        raise ValueError("head dim must be 128")
+    nb = t_all // tb
+    widen = lambda a: (np.ascontiguousarray(a, dtype=np.uint16).astype(np.uint32) << np.uint32(16)).view(np.float32)
+    k32 = widen(k_bits)[:nb * tb].reshape(nb, tb, nh, HEAD_DIM)
+    v32 = widen(v_bits)[:nb * tb].reshape(nb, tb, nh, HEAD_DIM)
+    rec = np.zeros((nh, nb, RECORD_BYTES), dtype=np.uint8)
+    for h in range(nh):
+        # keys: groups over tokens -> move the token axis last
+        kc, ks, kz = quantise_groups(np.transpose(k32[:, :, h, :], (0, 2, 1)), levels)   # [nb, 128, tb]
+        kwords = np.zeros((nb, 512), dtype=np.uint32)
+        for t in range(tb):
+            for ch in range(HEAD_DIM):
+                _put_field(kwords, words_per_token * t + ch // per_word, ch % per_word, bits, kc[:, ch, t])
+        # values: groups of tb channels of one token
+        vc, vs, vz = quantise_groups(v32[:, :, h, :].reshape(nb, tb, ngrp, tb), levels)   # [nb, tb, ngrp, tb]
+        vc = vc.reshape(nb, tb, HEAD_DIM)
+        vwords = np.zeros((nb, 512), dtype=np.uint32)
+        for c in range(2):
+            for j in range(4):
+                for n in range(16):
+                    slot = 64 * c + 16 * j + n
+                    for q in range(4):
+                        ch = 64 * c + 16 * q + n
+                        for e in range(per_word):
+                            _put_field(vwords, 4 * slot + q, e, bits, vc[:, per_word * j + e, ch])
+        rec[h, :, _K_CODES:_K_CODES + 2048] = kwords.astype("<u4").view(np.uint8).reshape(nb, 2048)
+        rec[h, :, _V_CODES:_V_CODES + 2048] = vwords.astype("<u4").view(np.uint8).reshape(nb, 2048)
+        kmeta = np.concatenate([ks.view(np.uint16), kz.view(np.uint16)], axis=-1)            # [nb, 256]
+        rec[h, :, _K_META:_K_META + 512] = kmeta.astype("<u2").view(np.uint8).reshape(nb, 512)
+        vs_gt = np.transpose(vs, (0, 2, 1)).reshape(nb, HEAD_DIM)                             # [g][t]
+        vz_gt = np.transpose(vz, (0, 2, 1)).reshape(nb, HEAD_DIM)
+        vmeta = np.concatenate([vs_gt.view(np.uint16), vz_gt.view(np.uint16)], axis=-1)
+        rec[h, :, _V_META:_V_META + 512] = vmeta.astype("<u2").view(np.uint8).reshape(nb, 512)
+    return rec
+
+
+def f64_to_bf16_bits(x: np.ndarray) -> np.ndarray:
+    """Round doubles to bf16 (8 significant bits, round to nearest even) in ONE rounding step and
+    return the bit patterns.  For values in bf16's normal range (and zero)."""
+    x = np.asarray(x, dtype=np.float64)
+    m, e = np.frexp(x)                      # x = m * 2^e, 0.5 <= |m| < 1
+    r = np.ldexp(np.rint(np.ldexp(m, 8)), e - 8)   # rint is round-half-to-even; r has <= 8 bits
+    f32 = r.astype(np.float32)              # exact: 8 significant bits fit
+    return (f32.view(np.uint32) >> np.uint32(16)).astype(np.uint16)
+
+
+def dequantize_records(records: np.ndarray, bits: int):
+    """Inverse of the quantising compressor: x_hat = scale * code + zero exactly (the sum is exact
+    in double), then ONE rounding to bf16.  Returns (k_bits, v_bits) uint16 [T, n_heads, 128]."""
+    k_hat, v_hat = unpack_records(records, bits)        # [nh, T, 128] float64
+    return (np.ascontiguousarray(np.transpose(f64_to_bf16_bits(k_hat), (1, 0, 2))),
+            np.ascontiguousarray(np.transpose(f64_to_bf16_bits(v_hat), (1, 0, 2))))
+
+
+# --------------------------------------------------------------------------------------------
+# kept-index lists from importance scores  (section 6: what an online compressor's update()
+# decides per request and head; every head of a layer keeps the same number of positions)
+# --------------------------------------------------------------------------------------------
+def topk_keep(scores, ctx_len, keep_len, n_kv_heads: int, forced_first=None, forced_last=None):
+    """Per (sequence b, head h) list: keep the first F_b and the last L_b positions, fill the
+    remaining keep_len[b] - F_b - L_b slots with the highest-scoring other positions (equal
+    scores: the lower position wins), and return the kept positions in ascending order.
+
+    scores float32: list (b, h) is scores[(cu_ctx[b]*Hkv + h*N_b) + t], t < N_b = ctx_len[b].
+    F_b = min(forced_first[b], keep_len[b]); L_b = min(forced_last[b], keep_len[b] - F_b).
+    Returns (keep_idx int32, cu_keep int32) in the list layout of keep_from_dropped.
+    """
+    scores = np.asarray(scores, dtype=np.float32)
+    nseq = len(ctx_len)
+    cu_keep = np.zeros(nseq + 1, dtype=np.int32)
+    pieces = []
+    off = 0
+    for b in range(nseq):
+        n = int(ctx_len[b])
+        k = min(int(keep_len[b]), n)
+        cu_keep[b + 1] = cu_keep[b] + k
+        f = min(int(forced_first[b]) if forced_first is not None else 0, k)
+        l = min(int(forced_last[b]) if forced_last is not None else 0, k - f)
+        for h in range(n_kv_heads):
+            s = scores[off:off + n]
+            off += n
+            forced = np.zeros(n, dtype=bool)
+            forced[:f] = True
+            forced[n - l:n] = l > 0
+            free = np.flatnonzero(~forced)
+            # stable sort of the negated scores: descending score, ascending position among equals
+            order = free[np.argsort(-s[free].astype(np.float64), kind="stable")]
+            chosen = np.concatenate([np.flatnonzero(forced), order[:k - f - l]])
+            pieces.append(np.sort(chosen).astype(np.int32))
     keep = np.concatenate(pieces) if pieces else np.zeros(0, dtype=np.int32)
     return keep, cu_keep

@@ -42,15 +42,15 @@ def tokens_per_block(bits: int) -> int:
 # ------------------------------------------------------------------------------------------------
 def _minmax_codes(x: torch.Tensor, dim: int, levels: int):
     """x fp32; groups reduce over `dim`.  zero = fp16(min), scale = fp16((max-min)/levels),
-    code = clamp(rne((x - zero)/scale), 0, levels) with the stored fp16 values; a constant group
-    gets scale 0 and code 0."""
+    code = clamp(rne((x - zero) * (1/scale)), 0, levels) with the stored fp16 values, every step
+    one fp32 operation; a constant group gets scale 0 and code 0."""
     mn = x.amin(dim=dim, keepdim=True)
     mx = x.amax(dim=dim, keepdim=True)
     zero = mn.to(torch.float16)
     scale = ((mx - mn) / levels).to(torch.float16)
     zf, sf = zero.float(), scale.float()
     safe = torch.where(sf > 0, sf, torch.ones_like(sf))
-    code = torch.round((x - zf) / safe).clamp_(0, levels)
+    code = torch.round((x - zf) * (1.0 / safe)).clamp_(0, levels)
     code = torch.where(sf > 0, code, torch.zeros_like(code))
     return code.to(torch.int64), scale, zero
 
@@ -115,7 +115,7 @@ def quantize_records(k: torch.Tensor, v: torch.Tensor, bits: int) -> torch.Tenso
 # stand-in token-dropping compressor
 # ------------------------------------------------------------------------------------------------
 def topk_keep(n_ctx: int, n_keep: int, n_first: int, n_last: int, n_lists: int,
-              g: torch.Generator) -> torch.Tensor:
+              g: torch.Generator, return_scores: bool = False):
     """Kept positions for `n_lists` (sequence, KV head) lists over a context of n_ctx tokens:
     always the first n_first and last n_last positions, the remaining slots by the highest
     seeded N(0,1) score (ties to the lower position); ascending int32 [n_lists, n_keep]."""
@@ -123,11 +123,13 @@ def topk_keep(n_ctx: int, n_keep: int, n_first: int, n_last: int, n_lists: int,
     n_first = min(n_first, n_keep)
     n_last = min(n_last, n_keep - n_first)
     score = torch.randn((n_lists, n_ctx), generator=g, device=g.device, dtype=torch.float32)
+    raw = score.clone() if return_scores else None
     score[:, :n_first] = float("inf")
     if n_last:
         score[:, n_ctx - n_last:] = float("inf")
     order = torch.sort(score, dim=1, descending=True, stable=True).indices[:, :n_keep]
-    return torch.sort(order, dim=1).values.to(torch.int32).contiguous()
+    keep = torch.sort(order, dim=1).values.to(torch.int32).contiguous()
+    return (keep, raw) if return_scores else keep
 
 
 def dropped_from_keep(keep: torch.Tensor, n_ctx: int) -> torch.Tensor:
