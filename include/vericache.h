@@ -214,6 +214,54 @@ vc_status vc_keep_from_dropped(vc_ctx* ctx, const int32_t* dropped, const int32_
                                const int32_t* cu_ctx, int32_t n_seqs, int32_t n_kv_heads,
                                int32_t max_ctx, int32_t* keep_idx, int32_t* cu_keep, void* stream);
 
+/* ------------------------------------------------------------------------------------------
+ * Compressor side (paper section 6, Compressor interface: compress / decompress for the
+ * quantisation methods; section 2: keys quantised per channel, values per token).
+ *
+ * vc_compress_quant writes, for every sequence b and KV head h, the block records of the first
+ * nb_b * TB tokens of the sequence (nb_b = cu_blk[b+1] - cu_blk[b]; TB = 32 tokens for bits 4,
+ * 64 for bits 2) in the record layout and list order vc_comp_kv.blocks describes.  The caller
+ * chooses nb_b <= len_b / TB; tokens beyond nb_b * TB stay bf16 (they are what vc_comp_kv's tail
+ * is for).  Quantiser, every step one IEEE float32 operation, metadata rounded to fp16 (nearest
+ * even), codes computed from the STORED metadata:
+ *     zero = fp16(min + 0)         scale = fp16((max - min) / (2^bits - 1))
+ *     code = clamp(rne((x - zero) * (1 / scale)), 0, 2^bits - 1)        (scale 0: code 0)
+ * Key groups: one channel over the TB tokens of a record; value groups: one token over TB
+ * consecutive channels.  A group whose range exceeds fp16 gives an infinite scale (undefined).
+ *   k, v      device bf16 [sum tokens][n_kv_heads][128], 16-byte aligned (the layout of pool_k)
+ *   cu_ctx    device int32 [n_seqs+1] token offsets of the sequences in k, v
+ *   cu_blk    device int32 [n_seqs+1] record offsets (per head) of the sequences
+ *   max_blk   host-side max of nb_b
+ *   blocks    device, written: n_kv_heads * cu_blk[n_seqs] records of 5120 bytes
+ *
+ * vc_decompress_quant is the inverse (the remote-prefix decompress that materialises bf16 KV at
+ * the drafter): token t < nb_b * TB of sequence b gets x_hat = scale * code + zero, evaluated
+ * as one float32 fused multiply-add and rounded to bf16 (nearest even), written to row
+ * cu_ctx[b] + t of k_out / v_out (same layout as k, v above).  Rows beyond nb_b * TB are not
+ * touched.  Both calls enqueue on `stream` and need no workspace. */
+vc_status vc_compress_quant(vc_ctx* ctx, const void* k, const void* v, const int32_t* cu_ctx,
+                            const int32_t* cu_blk, int32_t n_seqs, int32_t n_kv_heads, int32_t bits,
+                            int32_t max_blk, void* blocks, void* stream);
+vc_status vc_decompress_quant(vc_ctx* ctx, const void* blocks, const int32_t* cu_blk,
+                              const int32_t* cu_ctx, int32_t n_seqs, int32_t n_kv_heads, int32_t bits,
+                              int32_t max_blk, void* k_out, void* v_out, void* stream);
+
+/* Kept positions from importance scores (paper section 6: what a token-dropping compressor's
+ * update() decides per request and head; scope (i): every head of a layer keeps the same number
+ * of positions).  List (b, h) keeps nk_b = min(cu_keep[b+1] - cu_keep[b], len_b) positions: the
+ * first F_b = min(forced_first[b], nk_b), the last L_b = min(forced_last[b], nk_b - F_b), and the
+ * nk_b - F_b - L_b highest-scoring of the others; equal scores go to the lower position (-0 equals
+ * +0; NaN scores are a contract violation).  Output ascending, in the layout of
+ * vc_comp_kv.keep_idx.
+ *   scores        device float32: list (b, h) starts at cu_ctx[b] * n_kv_heads + h * len_b
+ *   cu_ctx        device int32 [n_seqs+1]
+ *   cu_keep       device int32 [n_seqs+1], read (the caller fixes the budget per sequence)
+ *   forced_first, forced_last   device int32 [n_seqs], or NULL for 0
+ *   keep_idx      device int32, written */
+vc_status vc_topk_keep(vc_ctx* ctx, const float* scores, const int32_t* cu_ctx, const int32_t* cu_keep,
+                       const int32_t* forced_first, const int32_t* forced_last, int32_t n_seqs,
+                       int32_t n_kv_heads, int32_t* keep_idx, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -353,14 +353,14 @@ def quantise_groups(x32: np.ndarray, levels: int):
     The decisions are integers taken from floating point, so the precision is part of the
     definition: everything below is IEEE float32 (one rounding per operation), the stored scale and
     zero point are fp16 (round to nearest even), and the code is computed from the STORED values:
-        zero  = fp16(min)                       scale = fp16((max - min) / levels)
+        zero  = fp16(min)  (-0 stored as +0)    scale = fp16((max - min) / levels)
         code  = clamp(rne((x - zero) * (1 / scale)), 0, levels)      (scale = 0: code 0)
     Returns (code int64 [..., G], scale fp16 [...], zero fp16 [...]).
     """
     x32 = np.asarray(x32, dtype=np.float32)
     mn = x32.min(axis=-1)
     mx = x32.max(axis=-1)
-    zero = mn.astype(np.float16)
+    zero = (mn + np.float32(0.0)).astype(np.float16)
     scale = ((mx - mn) / np.float32(levels)).astype(np.float16)
     zf = zero.astype(np.float32)[..., None]
     sf = scale.astype(np.float32)[..., None]

@@ -48,7 +48,7 @@ EXPORTS = ["vc_create", "vc_destroy", "vc_last_error", "vc_version", "vc_time_ma
            "vc_draft_workspace_bytes", "vc_draft_attn", "vc_verify_workspace_bytes", "vc_verify_attn",
            "vc_verify_plan", "vc_verify_attn_range", "vc_verify_finish",
            "vc_accept_workspace_bytes", "vc_accept_len", "vc_swap_in", "vc_swap_wait", "vc_swap_query", "vc_swap_sync",
-           "vc_keep_from_dropped"]
+           "vc_keep_from_dropped", "vc_compress_quant", "vc_decompress_quant", "vc_topk_keep"]
 
 
 def library_path() -> str:
@@ -93,6 +93,12 @@ def load():
     lib.vc_swap_sync.argtypes = [C.c_void_p]
     lib.vc_keep_from_dropped.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32,
                                          C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
+    lib.vc_compress_quant.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32,
+                                      C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
+    lib.vc_decompress_quant.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32,
+                                        C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
+    lib.vc_topk_keep.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
+                                 C.c_int32, C.c_void_p, C.c_void_p]
     _LIB = lib
     return lib
 
@@ -315,3 +321,27 @@ def vc_keep_from_dropped(ctx: Context, dropped, cu_drop, cu_ctx, n_kv_heads, max
                                        _ptr(keep_idx, torch.int32, "keep_idx"), _ptr(cu_keep, torch.int32, "cu_keep"),
                                        _stream(stream)))
     return keep_idx, cu_keep
+
+
+def vc_compress_quant(ctx: Context, k, v, cu_ctx, cu_blk, bits, max_blk, blocks, stream=None):
+    n_seqs = cu_ctx.numel() - 1
+    _check(load().vc_compress_quant(ctx.handle, _ptr(k, torch.bfloat16, "k"), _ptr(v, torch.bfloat16, "v"),
+                                    _ptr(cu_ctx, torch.int32, "cu_ctx"), _ptr(cu_blk, torch.int32, "cu_blk"), n_seqs,
+                                    k.shape[1], bits, max_blk, _ptr(blocks, torch.uint8, "blocks"), _stream(stream)))
+
+
+def vc_decompress_quant(ctx: Context, blocks, cu_blk, cu_ctx, bits, max_blk, k_out, v_out, stream=None):
+    n_seqs = cu_ctx.numel() - 1
+    _check(load().vc_decompress_quant(ctx.handle, _ptr(blocks, torch.uint8, "blocks"), _ptr(cu_blk, torch.int32, "cu_blk"),
+                                      _ptr(cu_ctx, torch.int32, "cu_ctx"), n_seqs, k_out.shape[1], bits, max_blk,
+                                      _ptr(k_out, torch.bfloat16, "k_out"), _ptr(v_out, torch.bfloat16, "v_out"),
+                                      _stream(stream)))
+
+
+def vc_topk_keep(ctx: Context, scores, cu_ctx, cu_keep, n_kv_heads, keep_idx, forced_first=None, forced_last=None,
+                 stream=None):
+    n_seqs = cu_ctx.numel() - 1
+    _check(load().vc_topk_keep(ctx.handle, _ptr(scores, torch.float32, "scores"), _ptr(cu_ctx, torch.int32, "cu_ctx"),
+                               _ptr(cu_keep, torch.int32, "cu_keep"), _ptr(forced_first, torch.int32, "forced_first"),
+                               _ptr(forced_last, torch.int32, "forced_last"), n_seqs, n_kv_heads,
+                               _ptr(keep_idx, torch.int32, "keep_idx"), _stream(stream)))

@@ -1,0 +1,467 @@
+// Compressor-side kernels (paper section 6, Compressor interface): the quantising compress()
+// (bf16 K, V -> int4 / int2 block records), its decompress() (records -> bf16 K, V, what a remote
+// drafter materialises), and the kept-position lists an online update() derives from scores.
+//
+// All three are bandwidth work: one wave owns one 5120-byte record (32 or 64 tokens of one KV
+// head); rows are fetched with 16 bytes per lane, four token rows per wave load.
+#include "attn_common.h"
+#include "common.h"
+
+namespace vc {
+
+struct QuantParams {
+  const uint16_t* k;      // bf16 [tokens][Hkv][128]  (compress: in, decompress: out)
+  const uint16_t* v;
+  uint16_t* k_out;
+  uint16_t* v_out;
+  const uint8_t* blocks;  // decompress: in
+  uint8_t* blocks_out;    // compress: out
+  const int* cu_ctx;
+  const int* cu_blk;
+  int n_kv_heads;
+};
+
+template <int BITS>
+struct QuantGeom {
+  static constexpr int TB = BITS == 4 ? 32 : 64;     // tokens per record = channels per value group
+  static constexpr int LEVELS = (1 << BITS) - 1;
+  static constexpr int E = 32 / BITS;                // codes per 32-bit word
+  static constexpr int NL = TB / 4;                  // wave loads per matrix (4 token rows each)
+  static constexpr int STAGE_ROW = TB + 16;          // bytes per channel row of the value staging tile
+};
+
+// bit position of element e of a code word
+template <int BITS>
+__device__ __forceinline__ constexpr int field_shift(int e) { return 16 * (e & 1) + BITS * (e >> 1); }
+
+__device__ __forceinline__ void unpack8(const uint4& r, float (&x)[8]) {
+  x[0] = bf16_lo(r.x); x[1] = bf16_hi(r.x); x[2] = bf16_lo(r.y); x[3] = bf16_hi(r.y);
+  x[4] = bf16_lo(r.z); x[5] = bf16_hi(r.z); x[6] = bf16_lo(r.w); x[7] = bf16_hi(r.w);
+}
+
+// fp16 scale and zero point of a group from its minimum and maximum, and the factor the codes are
+// computed with: all float32, one rounding per step; code = clamp(rne((x - zero) * inv))
+template <int LEVELS>
+__device__ __forceinline__ void group_meta(float mn, float mx, _Float16& sh, _Float16& zh, float& zf, float& inv) {
+  sh = static_cast<_Float16>(__fdiv_rn(mx - mn, static_cast<float>(LEVELS)));
+  zh = static_cast<_Float16>(mn + 0.0f);           // a minimum of -0 is stored as +0
+  const float sf = static_cast<float>(sh);
+  zf = static_cast<float>(zh);
+  inv = sf > 0.f ? __fdiv_rn(1.0f, sf) : 0.f;      // a constant group: every code 0
+}
+
+template <int LEVELS>
+__device__ __forceinline__ uint32_t code_of(float x, float zf, float inv) {
+  const float c = fminf(fmaxf(rintf((x - zf) * inv), 0.f), static_cast<float>(LEVELS));
+  return static_cast<uint32_t>(c);
+}
+
+// ---------------------------------------------------------------------------------------------
+// compress: grid (ceil(max_blk / 4), Hkv, n_seqs), 4 waves, one record per wave
+// ---------------------------------------------------------------------------------------------
+template <int BITS>
+__global__ __launch_bounds__(256) void compress_quant_kernel(QuantParams p) {
+  using G = QuantGeom<BITS>;
+  constexpr int TB = G::TB, LEVELS = G::LEVELS, E = G::E, NL = G::NL, SR = G::STAGE_ROW;
+  __shared__ __attribute__((aligned(16))) uint8_t stage_all[4][kHeadDim * SR];   // value codes, [channel][token]
+  __shared__ __attribute__((aligned(16))) uint16_t vmeta_all[4][256];            // value scale[g][t], zero[g][t]
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, lg = lane >> 4, lc = lane & 15;
+  const int b = blockIdx.z, kvh = blockIdx.y, blk = blockIdx.x * 4 + wave;
+  const int nb = p.cu_blk[b + 1] - p.cu_blk[b];
+  const bool live = blk < nb;                        // the barriers below are reached by every wave
+  uint8_t* stage = stage_all[wave];
+  uint16_t* vmeta = vmeta_all[wave];
+  const size_t rs = static_cast<size_t>(p.n_kv_heads) * kHeadDim;
+  const size_t row0 = (static_cast<size_t>(p.cu_ctx[b]) + static_cast<size_t>(live ? blk : 0) * TB) * rs +
+                      static_cast<size_t>(kvh) * kHeadDim + 8 * lc;
+  uint8_t* rec = p.blocks_out + (static_cast<size_t>(p.cu_blk[b]) * p.n_kv_heads + static_cast<size_t>(kvh) * nb +
+                                 (live ? blk : 0)) * kRecordBytes;
+  uint4 kraw[NL], vraw[NL];
+  if (live) {
+#pragma unroll
+    for (int i = 0; i < NL; ++i) {
+      kraw[i] = *reinterpret_cast<const uint4*>(p.k + row0 + static_cast<size_t>(4 * i + lg) * rs);
+      vraw[i] = *reinterpret_cast<const uint4*>(p.v + row0 + static_cast<size_t>(4 * i + lg) * rs);
+    }
+    // ---- keys: one group per channel over the TB tokens
+    float mn[8], mx[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) { mn[e] = INFINITY; mx[e] = -INFINITY; }
+#pragma unroll
+    for (int i = 0; i < NL; ++i) {
+      float x[8];
+      unpack8(kraw[i], x);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) { mn[e] = fminf(mn[e], x[e]); mx[e] = fmaxf(mx[e], x[e]); }
+    }
+    float zf[8], inv[8];
+    uint32_t sw[4], zw[4];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      mn[e] = fminf(mn[e], __shfl_xor(mn[e], 16, 64)); mx[e] = fmaxf(mx[e], __shfl_xor(mx[e], 16, 64));
+      mn[e] = fminf(mn[e], __shfl_xor(mn[e], 32, 64)); mx[e] = fmaxf(mx[e], __shfl_xor(mx[e], 32, 64));
+      _Float16 sh, zh;
+      group_meta<LEVELS>(mn[e], mx[e], sh, zh, zf[e], inv[e]);
+      const uint32_t sb = __builtin_bit_cast(uint16_t, sh), zb = __builtin_bit_cast(uint16_t, zh);
+      if (e & 1) { sw[e >> 1] |= sb << 16; zw[e >> 1] |= zb << 16; } else { sw[e >> 1] = sb; zw[e >> 1] = zb; }
+    }
+    if (lg == 0) {
+      *reinterpret_cast<uint4*>(rec + 4096 + 16 * lc) = make_uint4(sw[0], sw[1], sw[2], sw[3]);
+      *reinterpret_cast<uint4*>(rec + 4352 + 16 * lc) = make_uint4(zw[0], zw[1], zw[2], zw[3]);
+    }
+#pragma unroll
+    for (int i = 0; i < NL; ++i) {
+      float x[8];
+      unpack8(kraw[i], x);
+      const int tk = 4 * i + lg;
+      uint32_t w = 0;
+      if (BITS == 4) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) w |= code_of<LEVELS>(x[e], zf[e], inv[e]) << field_shift<BITS>(e);
+        *reinterpret_cast<uint32_t*>(rec + tk * 64 + 4 * lc) = w;
+      } else {
+        // 16 channels per word: this lane holds elements 8*(lc & 1) .. +7, its neighbour the rest
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const uint32_t c = code_of<LEVELS>(x[e], zf[e], inv[e]);
+          w |= (lc & 1) ? c << field_shift<BITS>(8 + e) : c << field_shift<BITS>(e);
+        }
+        w |= __shfl_xor(w, 1, 64);
+        if ((lc & 1) == 0) *reinterpret_cast<uint32_t*>(rec + tk * 32 + 4 * (lc >> 1)) = w;
+      }
+    }
+    // ---- values: one group per token over TB consecutive channels (TB / 8 lanes)
+#pragma unroll
+    for (int i = 0; i < NL; ++i) {
+      float x[8];
+      unpack8(vraw[i], x);
+      float lo = x[0], hi = x[0];
+#pragma unroll
+      for (int e = 1; e < 8; ++e) { lo = fminf(lo, x[e]); hi = fmaxf(hi, x[e]); }
+#pragma unroll
+      for (int off = 1; off < TB / 8; off <<= 1) {
+        lo = fminf(lo, __shfl_xor(lo, off, 64));
+        hi = fmaxf(hi, __shfl_xor(hi, off, 64));
+      }
+      _Float16 sh, zh;
+      float zfv, invv;
+      group_meta<LEVELS>(lo, hi, sh, zh, zfv, invv);
+      const int tk = 4 * i + lg;
+      const int grp = (8 * lc) / TB;
+      if ((8 * lc) % TB == 0) {
+        vmeta[grp * TB + tk] = __builtin_bit_cast(uint16_t, sh);
+        vmeta[128 + grp * TB + tk] = __builtin_bit_cast(uint16_t, zh);
+      }
+#pragma unroll
+      for (int e = 0; e < 8; ++e) stage[(8 * lc + e) * SR + tk] = static_cast<uint8_t>(code_of<LEVELS>(x[e], zfv, invv));
+    }
+  }
+  __syncthreads();
+  if (live) {
+    // value code words: word W = 4 * slot + q, slot = 64c + 16j + n, channel 64c + 16q + n,
+    // tokens E*j .. E*j+E-1, which are E consecutive bytes of the staging tile
+#pragma unroll
+    for (int m = 0; m < 8; ++m) {
+      const int W = 64 * m + lane;
+      const int slot = W >> 2, q = W & 3;
+      const int c = slot >> 6, j = (slot >> 4) & 3, n = slot & 15;
+      const uint8_t* src = stage + (64 * c + 16 * q + n) * SR + E * j;
+      uint32_t w = 0;
+      if (BITS == 4) {
+        const uint2 by = *reinterpret_cast<const uint2*>(src);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          w |= ((by.x >> (8 * e)) & 0xFFu) << field_shift<BITS>(e);
+          w |= ((by.y >> (8 * e)) & 0xFFu) << field_shift<BITS>(4 + e);
+        }
+      } else {
+        const uint4 by = *reinterpret_cast<const uint4*>(src);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          w |= ((by.x >> (8 * e)) & 0xFFu) << field_shift<BITS>(e);
+          w |= ((by.y >> (8 * e)) & 0xFFu) << field_shift<BITS>(4 + e);
+          w |= ((by.z >> (8 * e)) & 0xFFu) << field_shift<BITS>(8 + e);
+          w |= ((by.w >> (8 * e)) & 0xFFu) << field_shift<BITS>(12 + e);
+        }
+      }
+      *reinterpret_cast<uint32_t*>(rec + 2048 + 4 * W) = w;
+    }
+    *reinterpret_cast<uint2*>(rec + 4608 + 8 * lane) = *reinterpret_cast<const uint2*>(vmeta + 4 * lane);
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// decompress: same geometry; the record is staged in LDS, rows leave as 16-byte stores
+// x_hat = fma(scale, code, zero) in float32 (exact whenever scale*code and zero are within 2^9 of
+// each other in magnitude, i.e. for any group a min/max quantiser produces), rounded once to bf16
+// ---------------------------------------------------------------------------------------------
+template <int BITS>
+__global__ __launch_bounds__(256) void decompress_quant_kernel(QuantParams p) {
+  using G = QuantGeom<BITS>;
+  constexpr int TB = G::TB, E = G::E, NL = G::NL;
+  constexpr uint32_t MASK = (1u << BITS) - 1u;
+  __shared__ __attribute__((aligned(16))) uint8_t rec_all[4][kRecordBytes];
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, lg = lane >> 4, lc = lane & 15;
+  const int b = blockIdx.z, kvh = blockIdx.y, blk = blockIdx.x * 4 + wave;
+  const int nb = p.cu_blk[b + 1] - p.cu_blk[b];
+  const bool live = blk < nb;
+  uint8_t* rec = rec_all[wave];
+  if (live) {
+    const uint8_t* src = p.blocks + (static_cast<size_t>(p.cu_blk[b]) * p.n_kv_heads + static_cast<size_t>(kvh) * nb + blk) *
+                                        kRecordBytes;
+#pragma unroll
+    for (int m = 0; m < 5; ++m)
+      *reinterpret_cast<uint4*>(rec + 16 * (64 * m + lane)) = *reinterpret_cast<const uint4*>(src + 16 * (64 * m + lane));
+  }
+  __syncthreads();
+  if (!live) return;
+  const size_t rs = static_cast<size_t>(p.n_kv_heads) * kHeadDim;
+  const size_t row0 = (static_cast<size_t>(p.cu_ctx[b]) + static_cast<size_t>(blk) * TB) * rs +
+                      static_cast<size_t>(kvh) * kHeadDim + 8 * lc;
+  const _Float16* meta = reinterpret_cast<const _Float16*>(rec + 4096);
+  float ks[8], kz[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    ks[e] = static_cast<float>(meta[8 * lc + e]);
+    kz[e] = static_cast<float>(meta[128 + 8 * lc + e]);
+  }
+  const int grp = (8 * lc) / TB;
+  // value words of this lane's 8 channels: channel 8*lc + e -> c = lc >> 3, q = (lc >> 1) & 3, n = 8*(lc & 1) + e
+  const int vc = lc >> 3, vq = (lc >> 1) & 3, vn0 = 8 * (lc & 1);
+#pragma unroll
+  for (int i = 0; i < NL; ++i) {
+    const int tk = 4 * i + lg;
+    uint32_t kw;
+    int ebase;
+    if (BITS == 4) { kw = *reinterpret_cast<const uint32_t*>(rec + tk * 64 + 4 * lc); ebase = 0; }
+    else { kw = *reinterpret_cast<const uint32_t*>(rec + tk * 32 + 4 * (lc >> 1)); ebase = 8 * (lc & 1); }
+    uint32_t ko[4], vo[4];
+    const int j = tk / E, ee = tk % E;
+    const float vs = static_cast<float>(meta[256 + grp * TB + tk]);
+    const float vz = static_cast<float>(meta[384 + grp * TB + tk]);
+    const int vshift = 16 * (ee & 1) + BITS * (ee >> 1);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const int el = ebase + e;
+      const uint32_t kcode = (kw >> (16 * (el & 1) + BITS * (el >> 1))) & MASK;
+      const uint32_t kb = float_to_bf16_bits(fmaf(ks[e], static_cast<float>(kcode), kz[e]));
+      const uint32_t vword = *reinterpret_cast<const uint32_t*>(rec + 2048 + 16 * (64 * vc + 16 * j + vn0 + e) + 4 * vq);
+      const uint32_t vcode = (vword >> vshift) & MASK;
+      const uint32_t vb = float_to_bf16_bits(fmaf(vs, static_cast<float>(vcode), vz));
+      if (e & 1) { ko[e >> 1] |= kb << 16; vo[e >> 1] |= vb << 16; } else { ko[e >> 1] = kb; vo[e >> 1] = vb; }
+    }
+    *reinterpret_cast<uint4*>(p.k_out + row0 + static_cast<size_t>(tk) * rs) = make_uint4(ko[0], ko[1], ko[2], ko[3]);
+    *reinterpret_cast<uint4*>(p.v_out + row0 + static_cast<size_t>(tk) * rs) = make_uint4(vo[0], vo[1], vo[2], vo[3]);
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// kept positions from scores: one workgroup of 1024 threads per (sequence, head) list.
+// Radix select (4 passes of 8 bits) finds the score threshold among the free positions; ties at
+// the threshold go to the lowest positions; thread i then owns the contiguous run i of positions
+// so that the output comes out ascending after one workgroup-wide prefix sum.
+// ---------------------------------------------------------------------------------------------
+constexpr int kTopkThreads = 1024;
+
+struct TopkParams {
+  const float* scores;
+  const int* cu_ctx;
+  const int* cu_keep;
+  const int* forced_first;   // or NULL
+  const int* forced_last;    // or NULL
+  int* keep_idx;
+  int n_kv_heads;
+};
+
+// order-preserving key of a float (larger score -> larger key); -0 counts as +0
+__device__ __forceinline__ uint32_t score_key(float s) {
+  const uint32_t u = __float_as_uint(s + 0.0f);
+  return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+// number of set bits of `mask` below this lane
+__device__ __forceinline__ int lanes_below(unsigned long long mask) {
+  return __builtin_amdgcn_mbcnt_hi(static_cast<uint32_t>(mask >> 32), __builtin_amdgcn_mbcnt_lo(static_cast<uint32_t>(mask), 0));
+}
+
+__global__ __launch_bounds__(kTopkThreads) void topk_keep_kernel(TopkParams p) {
+  __shared__ int hist[256];
+  __shared__ uint32_t sh_prefix;
+  __shared__ int sh_remaining;
+  const int b = blockIdx.y, h = blockIdx.x, tid = threadIdx.x;
+  const int n = p.cu_ctx[b + 1] - p.cu_ctx[b];
+  const int k = min(p.cu_keep[b + 1] - p.cu_keep[b], n);
+  if (k <= 0) return;
+  const int f = min(p.forced_first ? p.forced_first[b] : 0, k);
+  const int l = min(p.forced_last ? p.forced_last[b] : 0, k - f);
+  const float* s = p.scores + static_cast<size_t>(p.cu_ctx[b]) * p.n_kv_heads + static_cast<size_t>(h) * n;
+  int* out = p.keep_idx + static_cast<size_t>(p.cu_keep[b]) * p.n_kv_heads + static_cast<size_t>(h) * k;
+  const int free_lo = f, free_hi = n - l;          // free positions: [free_lo, free_hi)
+  const int want = k - f - l;                      // how many of them to keep
+  // ---- threshold: the want-th largest key among the free positions
+  uint32_t prefix = 0, mask = 0;
+  int remaining = want;
+  const bool all_free = want >= free_hi - free_lo;
+  if (want > 0 && !all_free) {
+    for (int shift = 24; shift >= 0; shift -= 8) {
+      if (tid < 256) hist[tid] = 0;
+      __syncthreads();
+      for (int t = free_lo + tid; t < free_hi; t += kTopkThreads) {
+        const uint32_t key = score_key(s[t]);
+        if ((key & mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1);
+      }
+      __syncthreads();
+      // suffix sums over the 256 digits (Hillis-Steele), then the digit that holds the want-th key
+      for (int off = 1; off < 256; off <<= 1) {
+        int add = 0;
+        if (tid < 256 && tid + off < 256) add = hist[tid + off];
+        __syncthreads();
+        if (tid < 256) hist[tid] += add;
+        __syncthreads();
+      }
+      if (tid < 256) {
+        const int here = hist[tid], above = tid < 255 ? hist[tid + 1] : 0;
+        if (here >= remaining && above < remaining) {
+          sh_prefix = prefix | (static_cast<uint32_t>(tid) << shift);
+          sh_remaining = remaining - above;
+        }
+      }
+      __syncthreads();
+      prefix = sh_prefix;
+      remaining = sh_remaining;
+      mask |= 255u << shift;
+      __syncthreads();
+    }
+  }
+  // `prefix` is the threshold key, `remaining` how many positions equal to it are kept
+  const uint32_t thr = prefix;
+  const int need_eq = (want > 0 && !all_free) ? remaining : 0;
+  // ---- ordered compaction: wave w owns the contiguous range [wlo, whi) and walks it 64 positions
+  // at a time (coalesced); ranks inside a step come from ballots, ranks across waves from LDS
+  constexpr int NW = kTopkThreads / 64;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int per_w = ((n + NW - 1) / NW + 63) / 64 * 64;
+  const int wlo = min(wave * per_w, n), whi = min(wlo + per_w, n);
+  const bool pick = want > 0 && !all_free;
+  int cnt_eq = 0, cnt_sure = 0;
+  for (int base = wlo; base < whi; base += 64) {
+    const int t = base + lane;
+    bool sure = false, eq = false;
+    if (t < whi) {
+      if (t < free_lo || t >= free_hi) sure = true;
+      else if (want > 0 && all_free) sure = true;
+      else if (pick) {
+        const uint32_t key = score_key(s[t]);
+        sure = key > thr;
+        eq = key == thr;
+      }
+    }
+    cnt_sure += __popcll(__ballot(sure));
+    cnt_eq += __popcll(__ballot(eq));
+  }
+  __syncthreads();                 // hist is reused below
+  if (lane == 0) { hist[wave] = cnt_eq; hist[NW + wave] = cnt_sure; }
+  __syncthreads();
+  int eq_before = 0, pos = 0;
+  for (int w = 0; w < wave; ++w) {
+    const int e = hist[w];
+    const int take = max(0, min(e, need_eq - eq_before));
+    pos += hist[NW + w] + take;
+    eq_before += e;
+  }
+  const int my_eq = max(0, min(cnt_eq, need_eq - eq_before));
+  int eq_taken = 0;
+  for (int base = wlo; base < whi; base += 64) {
+    const int t = base + lane;
+    bool sure = false, eq = false;
+    if (t < whi) {
+      if (t < free_lo || t >= free_hi) sure = true;
+      else if (want > 0 && all_free) sure = true;
+      else if (pick) {
+        const uint32_t key = score_key(s[t]);
+        sure = key > thr;
+        eq = key == thr;
+      }
+    }
+    const unsigned long long eq_mask = __ballot(eq);
+    const bool keep = sure || (eq && eq_taken + lanes_below(eq_mask) < my_eq);
+    const unsigned long long keep_mask = __ballot(keep);
+    if (keep) out[pos + lanes_below(keep_mask)] = t;
+    pos += __popcll(keep_mask);
+    eq_taken += __popcll(eq_mask);
+  }
+}
+
+static vc_status check_quant_call(vc_ctx* ctx, const int32_t* cu_ctx, const int32_t* cu_blk, int32_t n_seqs,
+                                  int32_t n_kv_heads, int32_t bits, int32_t max_blk, const char* who) {
+  VC_REQUIRE(ctx != nullptr, VC_ERR_INVALID_ARG, "%s: ctx is NULL", who);
+  VC_REQUIRE(n_seqs >= 0 && n_kv_heads > 0 && max_blk >= 0, VC_ERR_INVALID_ARG, "%s: n_seqs %d n_kv_heads %d max_blk %d",
+             who, n_seqs, n_kv_heads, max_blk);
+  VC_REQUIRE(bits == 4 || bits == 2, VC_ERR_UNSUPPORTED, "%s: bits %d (block records are 4 or 2 bit)", who, bits);
+  VC_REQUIRE(n_seqs <= 65535 && n_kv_heads <= 65535, VC_ERR_UNSUPPORTED, "%s: grid too large", who);
+  if (n_seqs > 0) VC_REQUIRE(cu_ctx && cu_blk, VC_ERR_INVALID_ARG, "%s: NULL cu array", who);
+  return VC_OK;
+}
+
+}  // namespace vc
+
+using namespace vc;
+
+extern "C" vc_status vc_compress_quant(vc_ctx* ctx, const void* k, const void* v, const int32_t* cu_ctx,
+                                       const int32_t* cu_blk, int32_t n_seqs, int32_t n_kv_heads, int32_t bits,
+                                       int32_t max_blk, void* blocks, void* stream) {
+  vc_status st = check_quant_call(ctx, cu_ctx, cu_blk, n_seqs, n_kv_heads, bits, max_blk, "vc_compress_quant");
+  if (st != VC_OK) return st;
+  if (n_seqs == 0 || max_blk == 0) return VC_OK;
+  VC_REQUIRE(k && v && blocks, VC_ERR_INVALID_ARG, "vc_compress_quant: NULL pointer");
+  VC_REQUIRE(aligned16(k) && aligned16(v) && aligned16(blocks), VC_ERR_INVALID_ARG,
+             "vc_compress_quant: pointers must be 16-byte aligned");
+  QuantParams p{};
+  p.k = static_cast<const uint16_t*>(k);
+  p.v = static_cast<const uint16_t*>(v);
+  p.blocks_out = static_cast<uint8_t*>(blocks);
+  p.cu_ctx = cu_ctx; p.cu_blk = cu_blk; p.n_kv_heads = n_kv_heads;
+  dim3 grid(ceil_div(max_blk, 4), n_kv_heads, n_seqs);
+  if (bits == 4) hipLaunchKernelGGL(compress_quant_kernel<4>, grid, dim3(256), 0, static_cast<hipStream_t>(stream), p);
+  else hipLaunchKernelGGL(compress_quant_kernel<2>, grid, dim3(256), 0, static_cast<hipStream_t>(stream), p);
+  VC_HIP(hipGetLastError());
+  return VC_OK;
+}
+
+extern "C" vc_status vc_decompress_quant(vc_ctx* ctx, const void* blocks, const int32_t* cu_blk, const int32_t* cu_ctx,
+                                         int32_t n_seqs, int32_t n_kv_heads, int32_t bits, int32_t max_blk, void* k_out,
+                                         void* v_out, void* stream) {
+  vc_status st = check_quant_call(ctx, cu_ctx, cu_blk, n_seqs, n_kv_heads, bits, max_blk, "vc_decompress_quant");
+  if (st != VC_OK) return st;
+  if (n_seqs == 0 || max_blk == 0) return VC_OK;
+  VC_REQUIRE(k_out && v_out && blocks, VC_ERR_INVALID_ARG, "vc_decompress_quant: NULL pointer");
+  VC_REQUIRE(aligned16(k_out) && aligned16(v_out) && aligned16(blocks), VC_ERR_INVALID_ARG,
+             "vc_decompress_quant: pointers must be 16-byte aligned");
+  QuantParams p{};
+  p.blocks = static_cast<const uint8_t*>(blocks);
+  p.k_out = static_cast<uint16_t*>(k_out);
+  p.v_out = static_cast<uint16_t*>(v_out);
+  p.cu_ctx = cu_ctx; p.cu_blk = cu_blk; p.n_kv_heads = n_kv_heads;
+  dim3 grid(ceil_div(max_blk, 4), n_kv_heads, n_seqs);
+  if (bits == 4) hipLaunchKernelGGL(decompress_quant_kernel<4>, grid, dim3(256), 0, static_cast<hipStream_t>(stream), p);
+  else hipLaunchKernelGGL(decompress_quant_kernel<2>, grid, dim3(256), 0, static_cast<hipStream_t>(stream), p);
+  VC_HIP(hipGetLastError());
+  return VC_OK;
+}
+
+extern "C" vc_status vc_topk_keep(vc_ctx* ctx, const float* scores, const int32_t* cu_ctx, const int32_t* cu_keep,
+                                  const int32_t* forced_first, const int32_t* forced_last, int32_t n_seqs,
+                                  int32_t n_kv_heads, int32_t* keep_idx, void* stream) {
+  VC_REQUIRE(ctx != nullptr, VC_ERR_INVALID_ARG, "vc_topk_keep: ctx is NULL");
+  VC_REQUIRE(n_seqs >= 0 && n_kv_heads > 0, VC_ERR_INVALID_ARG, "vc_topk_keep: n_seqs %d n_kv_heads %d", n_seqs, n_kv_heads);
+  if (n_seqs == 0) return VC_OK;
+  VC_REQUIRE(scores && cu_ctx && cu_keep && keep_idx, VC_ERR_INVALID_ARG, "vc_topk_keep: NULL pointer");
+  VC_REQUIRE(n_seqs <= 65535, VC_ERR_UNSUPPORTED, "vc_topk_keep: grid too large");
+  TopkParams p{};
+  p.scores = scores; p.cu_ctx = cu_ctx; p.cu_keep = cu_keep;
+  p.forced_first = forced_first; p.forced_last = forced_last;
+  p.keep_idx = keep_idx; p.n_kv_heads = n_kv_heads;
+  hipLaunchKernelGGL(topk_keep_kernel, dim3(n_kv_heads, n_seqs), dim3(kTopkThreads), 0, static_cast<hipStream_t>(stream), p);
+  VC_HIP(hipGetLastError());
+  return VC_OK;
+}

@@ -46,7 +46,7 @@ def _minmax_codes(x: torch.Tensor, dim: int, levels: int):
     one fp32 operation; a constant group gets scale 0 and code 0."""
     mn = x.amin(dim=dim, keepdim=True)
     mx = x.amax(dim=dim, keepdim=True)
-    zero = mn.to(torch.float16)
+    zero = (mn + 0.0).to(torch.float16)
     scale = ((mx - mn) / levels).to(torch.float16)
     zf, sf = zero.float(), scale.float()
     safe = torch.where(sf > 0, sf, torch.ones_like(sf))
