@@ -47,6 +47,7 @@ def parse():
     ap.add_argument("--vocab", type=int, default=128256)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-swap", action="store_true")
+    ap.add_argument("--no-compressor", action="store_true", help="skip the compress / decompress / top-k legs")
     ap.add_argument("--only", default="", help="comma list of legs to run per step: keep,d1,d2,d3,verify,accept")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
@@ -249,6 +250,10 @@ def main():
     if not args.no_swap and "d2" in legs:
         swap = measure_swap(vc, ctx, lay, torch, draft_kw, out, ws, HKV, N, B, W)
 
+    comp = None
+    if not args.no_compressor and not args.only:
+        comp = measure_compressor(vc, ctx, lay, torch, HKV, N, B)
+
     cpu = None
     if not args.no_cpu_baseline:
         cpu = cpu_baseline(lay, torch, np, HQ, HKV, N)
@@ -262,10 +267,54 @@ def main():
                    "step": f"keep-index + {W} draft steps x (bf16 gather, int4, int2) + verify + accept"},
         "legs": res,
         "verify_TFLOPs": res.get("verify", {}).get("TFLOPs"),
-        "roofline": roofline, "swap": swap, "cpu_baseline": cpu,
+        "roofline": roofline, "swap": swap, "compressor": comp, "cpu_baseline": cpu,
     }
     print(json.dumps(line))
     ctx.close()
+
+
+def measure_compressor(vc, ctx, lay, torch, HKV, N, B, reps=5):
+    """The compressor-side entry points on the same layer (not part of a step): bf16 KV -> int4 /
+    int2 records, int4 records -> bf16 KV, kept lists (10 %) from fp32 scores.  GB/s counts the
+    algorithmic bytes read plus written."""
+    dev = lay.k_full.device
+    res = {}
+
+    def timed(fn):
+        fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    kv_bytes = 2 * B * N * HKV * 256
+    for bits in (4, 2):
+        ref = lay.blocks[bits]
+        blocks = torch.empty_like(ref)
+        nb = lay.max_blk[bits]
+        ms = timed(lambda: vc.vc_compress_quant(ctx, lay.k_full, lay.v_full, lay.cu_ctx, lay.cu_blk[bits], bits, nb, blocks))
+        res[f"compress_int{bits}"] = {"us": ms * 1e3, "GBps": (kv_bytes + blocks.numel()) / (ms * 1e-3) / 1e9,
+                                      "equals_generator_records": bool(torch.equal(blocks, ref))}
+        if bits == 4:
+            ko, vo = torch.empty_like(lay.k_full), torch.empty_like(lay.v_full)
+            ms = timed(lambda: vc.vc_decompress_quant(ctx, blocks, lay.cu_blk[bits], lay.cu_ctx, bits, nb, ko, vo))
+            res["decompress_int4"] = {"us": ms * 1e3, "GBps": (kv_bytes + blocks.numel()) / (ms * 1e-3) / 1e9}
+            del ko, vo
+        del blocks
+    keep_n = N // 10
+    scores = torch.randn(B * HKV * N, device=dev, dtype=torch.float32)
+    cu_keep = torch.arange(0, (B + 1) * keep_n, keep_n, dtype=torch.int32, device=dev)
+    first = torch.full((B,), 64, dtype=torch.int32, device=dev)
+    last = torch.full((B,), 256, dtype=torch.int32, device=dev)
+    keep = torch.empty(B * HKV * keep_n, dtype=torch.int32, device=dev)
+    ms = timed(lambda: vc.vc_topk_keep(ctx, scores, lay.cu_ctx, cu_keep, HKV, keep, forced_first=first, forced_last=last))
+    res["topk_keep"] = {"us": ms * 1e3, "lists": B * HKV, "positions": N, "kept": keep_n,
+                        "GBps": (scores.numel() * 4 + keep.numel() * 4) / (ms * 1e-3) / 1e9}
+    return res
 
 
 def measure_swap(vc, ctx, lay, torch, draft_kw, out, ws, HKV, N, B, W):

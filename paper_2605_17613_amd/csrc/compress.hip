@@ -284,10 +284,82 @@ __device__ __forceinline__ int lanes_below(unsigned long long mask) {
   return __builtin_amdgcn_mbcnt_hi(static_cast<uint32_t>(mask >> 32), __builtin_amdgcn_mbcnt_lo(static_cast<uint32_t>(mask), 0));
 }
 
+constexpr int kTopkBins = 4096;    // first digit: 12 bits (sign, exponent, 3 mantissa bits), then 10 + 10
+constexpr int kTopkCand = 8192;    // keys of the first digit's bucket kept in LDS for the later passes
+
+struct TopkShared {
+  int hist[kTopkBins];
+  uint32_t cand[kTopkCand];
+  int red[kTopkThreads / 64];
+  int digit, remaining, bucket, count;
+};
+
+// hist[0..nbins) holds digit counts; finds the digit d with  #(digits > d) < remaining <= #(digits >= d).
+// Returns d; `remaining` becomes the rank inside that digit's bucket, `bucket` its size.
+__device__ __forceinline__ uint32_t select_digit(TopkShared& sh, int nbins, int& remaining, int& bucket) {
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int per = nbins / kTopkThreads;            // 4 or 1
+  int local[kTopkBins / kTopkThreads];
+  int v = 0;
+#pragma unroll
+  for (int i = 0; i < kTopkBins / kTopkThreads; ++i) {
+    local[i] = i < per ? sh.hist[tid * per + i] : 0;
+    v += local[i];
+  }
+  int inc = v;                                     // inclusive suffix sum inside the wave
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const int o = __shfl_down(inc, off, 64);
+    if (lane + off < 64) inc += o;
+  }
+  if (lane == 0) sh.red[wave] = inc;
+  __syncthreads();
+  int above = inc - v;
+  for (int w = wave + 1; w < kTopkThreads / 64; ++w) above += sh.red[w];
+#pragma unroll
+  for (int i = kTopkBins / kTopkThreads - 1; i >= 0; --i) {
+    if (i < per) {
+      const int here = above + local[i];
+      if (above < remaining && remaining <= here) {
+        sh.digit = tid * per + i;
+        sh.remaining = remaining - above;
+        sh.bucket = local[i];
+      }
+      above = here;
+    }
+  }
+  __syncthreads();
+  const uint32_t d = static_cast<uint32_t>(sh.digit);
+  remaining = sh.remaining;
+  bucket = sh.bucket;
+  __syncthreads();
+  return d;
+}
+
+// Visit positions lo + start, lo + start + stride, ... below hi, eight loads in flight per thread:
+// fn(t, valid, score) runs for every slot of a batch (valid = false past the end), so that code
+// inside may use wave-wide ballots.
+constexpr int kTopkBatch = 8;
+template <class F>
+__device__ __forceinline__ void for_scores(const float* s, int lo, int hi, int start, int stride, F fn) {
+  for (int base = lo; base < hi; base += kTopkBatch * stride) {
+    float v[kTopkBatch];
+#pragma unroll
+    for (int u = 0; u < kTopkBatch; ++u) {
+      const int t = base + start + u * stride;
+      v[u] = t < hi ? s[t] : 0.f;
+    }
+#pragma unroll
+    for (int u = 0; u < kTopkBatch; ++u) {
+      const int t = base + start + u * stride;
+      fn(t, t < hi, v[u]);
+    }
+  }
+}
+
 __global__ __launch_bounds__(kTopkThreads) void topk_keep_kernel(TopkParams p) {
-  __shared__ int hist[256];
-  __shared__ uint32_t sh_prefix;
-  __shared__ int sh_remaining;
+  __shared__ TopkShared sh;
+  int* hist = sh.hist;
   const int b = blockIdx.y, h = blockIdx.x, tid = threadIdx.x;
   const int n = p.cu_ctx[b + 1] - p.cu_ctx[b];
   const int k = min(p.cu_keep[b + 1] - p.cu_keep[b], n);
@@ -298,39 +370,53 @@ __global__ __launch_bounds__(kTopkThreads) void topk_keep_kernel(TopkParams p) {
   int* out = p.keep_idx + static_cast<size_t>(p.cu_keep[b]) * p.n_kv_heads + static_cast<size_t>(h) * k;
   const int free_lo = f, free_hi = n - l;          // free positions: [free_lo, free_hi)
   const int want = k - f - l;                      // how many of them to keep
-  // ---- threshold: the want-th largest key among the free positions
-  uint32_t prefix = 0, mask = 0;
+  // ---- threshold: the want-th largest key among the free positions (radix select, 12 + 10 + 10 bits)
+  uint32_t prefix = 0;
   int remaining = want;
   const bool all_free = want >= free_hi - free_lo;
   if (want > 0 && !all_free) {
-    for (int shift = 24; shift >= 0; shift -= 8) {
-      if (tid < 256) hist[tid] = 0;
+    for (int i = tid; i < kTopkBins; i += kTopkThreads) hist[i] = 0;
+    if (tid == 0) sh.count = 0;
+    __syncthreads();
+    for_scores(s, free_lo, free_hi, tid, kTopkThreads, [&](int, bool valid, float sc) {
+      if (valid) atomicAdd(&hist[score_key(sc) >> 20], 1);
+    });
+    __syncthreads();
+    int bucket;
+    prefix = select_digit(sh, kTopkBins, remaining, bucket) << 20;
+    const bool in_lds = bucket <= kTopkCand;
+    if (in_lds) {
+      // gather the bucket's keys (order does not matter for the threshold)
+      for_scores(s, free_lo, free_hi, tid, kTopkThreads, [&](int, bool valid, float sc) {
+        const uint32_t key = score_key(sc);
+        const bool hit = valid && (key & 0xFFF00000u) == prefix;
+        const unsigned long long m = __ballot(hit);
+        int start = 0;
+        if (m != 0 && (tid & 63) == 0) start = atomicAdd(&sh.count, __popcll(m));
+        start = __shfl(start, 0, 64);
+        if (hit) sh.cand[start + lanes_below(m)] = key;
+      });
       __syncthreads();
-      for (int t = free_lo + tid; t < free_hi; t += kTopkThreads) {
-        const uint32_t key = score_key(s[t]);
-        if ((key & mask) == prefix) atomicAdd(&hist[(key >> shift) & 255u], 1);
-      }
+    }
+    uint32_t mask = 0xFFF00000u;
+    for (int shift = 10; shift >= 0; shift -= 10) {
+      for (int i = tid; i < 1024; i += kTopkThreads) hist[i] = 0;
       __syncthreads();
-      // suffix sums over the 256 digits (Hillis-Steele), then the digit that holds the want-th key
-      for (int off = 1; off < 256; off <<= 1) {
-        int add = 0;
-        if (tid < 256 && tid + off < 256) add = hist[tid + off];
-        __syncthreads();
-        if (tid < 256) hist[tid] += add;
-        __syncthreads();
-      }
-      if (tid < 256) {
-        const int here = hist[tid], above = tid < 255 ? hist[tid + 1] : 0;
-        if (here >= remaining && above < remaining) {
-          sh_prefix = prefix | (static_cast<uint32_t>(tid) << shift);
-          sh_remaining = remaining - above;
+      if (in_lds) {
+        for (int i = tid; i < bucket; i += kTopkThreads) {
+          const uint32_t key = sh.cand[i];
+          if ((key & mask) == prefix) atomicAdd(&hist[(key >> shift) & 1023u], 1);
         }
+      } else {
+        for_scores(s, free_lo, free_hi, tid, kTopkThreads, [&](int, bool valid, float sc) {
+          const uint32_t key = score_key(sc);
+          if (valid && (key & mask) == prefix) atomicAdd(&hist[(key >> shift) & 1023u], 1);
+        });
       }
       __syncthreads();
-      prefix = sh_prefix;
-      remaining = sh_remaining;
-      mask |= 255u << shift;
-      __syncthreads();
+      int dummy;
+      prefix |= select_digit(sh, 1024, remaining, dummy) << shift;
+      mask |= 1023u << shift;
     }
   }
   // `prefix` is the threshold key, `remaining` how many positions equal to it are kept
@@ -344,22 +430,25 @@ __global__ __launch_bounds__(kTopkThreads) void topk_keep_kernel(TopkParams p) {
   const int wlo = min(wave * per_w, n), whi = min(wlo + per_w, n);
   const bool pick = want > 0 && !all_free;
   int cnt_eq = 0, cnt_sure = 0;
-  for (int base = wlo; base < whi; base += 64) {
-    const int t = base + lane;
-    bool sure = false, eq = false;
-    if (t < whi) {
-      if (t < free_lo || t >= free_hi) sure = true;
-      else if (want > 0 && all_free) sure = true;
-      else if (pick) {
-        const uint32_t key = score_key(s[t]);
-        sure = key > thr;
-        eq = key == thr;
-      }
+  // class of position t: kept for sure (forced, above the threshold, or everything is kept), or
+  // equal to the threshold (kept while the quota lasts)
+  auto classify = [&](int t, bool valid, float sc, bool& sure, bool& eq) {
+    sure = false; eq = false;
+    if (!valid) return;
+    if (t < free_lo || t >= free_hi) sure = true;
+    else if (want > 0 && all_free) sure = true;
+    else if (pick) {
+      const uint32_t key = score_key(sc);
+      sure = key > thr;
+      eq = key == thr;
     }
+  };
+  for_scores(s, wlo, whi, lane, 64, [&](int t, bool valid, float sc) {
+    bool sure, eq;
+    classify(t, valid, sc, sure, eq);
     cnt_sure += __popcll(__ballot(sure));
     cnt_eq += __popcll(__ballot(eq));
-  }
-  __syncthreads();                 // hist is reused below
+  });
   if (lane == 0) { hist[wave] = cnt_eq; hist[NW + wave] = cnt_sure; }
   __syncthreads();
   int eq_before = 0, pos = 0;
@@ -371,25 +460,16 @@ __global__ __launch_bounds__(kTopkThreads) void topk_keep_kernel(TopkParams p) {
   }
   const int my_eq = max(0, min(cnt_eq, need_eq - eq_before));
   int eq_taken = 0;
-  for (int base = wlo; base < whi; base += 64) {
-    const int t = base + lane;
-    bool sure = false, eq = false;
-    if (t < whi) {
-      if (t < free_lo || t >= free_hi) sure = true;
-      else if (want > 0 && all_free) sure = true;
-      else if (pick) {
-        const uint32_t key = score_key(s[t]);
-        sure = key > thr;
-        eq = key == thr;
-      }
-    }
+  for_scores(s, wlo, whi, lane, 64, [&](int t, bool valid, float sc) {
+    bool sure, eq;
+    classify(t, valid, sc, sure, eq);
     const unsigned long long eq_mask = __ballot(eq);
     const bool keep = sure || (eq && eq_taken + lanes_below(eq_mask) < my_eq);
     const unsigned long long keep_mask = __ballot(keep);
     if (keep) out[pos + lanes_below(keep_mask)] = t;
     pos += __popcll(keep_mask);
     eq_taken += __popcll(eq_mask);
-  }
+  });
 }
 
 static vc_status check_quant_call(vc_ctx* ctx, const int32_t* cu_ctx, const int32_t* cu_blk, int32_t n_seqs,

@@ -173,3 +173,40 @@ def test_config4_ragged_full(lib, ctx):
     vs += [(longest, lay.win[longest] - 1, 0), (shortest, 0, 31)]
     check_verify_samples(lib, ctx, lay, vs, "cfg4 ragged windows", sum_ctx=int(sum(lay.ctx_len)))
     check_accept_full(lib, ctx, lay)
+
+
+def test_config2_compressor_side_full(lib, ctx):
+    """Config-2 size: the library's quantiser reproduces the generator's records byte for byte (all
+    16 x 8 x 2048 / 1024 records) and the oracle's for sampled (sequence, head) pairs; the inverse
+    matches the oracle on the same samples; kept lists from scores match the oracle."""
+    lay = synth.config(2, DEV)
+    n = lay.ctx_len[0]
+    for bits in (4, 2):
+        print(f"[full] compress int{bits}", flush=True)
+        nb = lay.max_blk[bits]
+        blocks = torch.empty_like(lay.blocks[bits])
+        lib.vc_compress_quant(ctx, lay.k_full, lay.v_full, lay.cu_ctx, lay.cu_blk[bits], bits, nb, blocks)
+        torch.cuda.synchronize()
+        assert torch.equal(blocks, lay.blocks[bits])
+        ko = torch.empty_like(lay.k_full); vo = torch.empty_like(lay.v_full)
+        lib.vc_decompress_quant(ctx, blocks, lay.cu_blk[bits], lay.cu_ctx, bits, nb, ko, vo)
+        torch.cuda.synchronize()
+        recs = blocks.view(len(lay.ctx_len), lay.n_kv_heads, nb, 5120)
+        for (b, h) in [(0, 0), (11, 5)]:
+            lo = b * n
+            ref = O.quantize_records(H.bits16(lay.k_full[lo:lo + n, h:h + 1]), H.bits16(lay.v_full[lo:lo + n, h:h + 1]), bits)
+            assert np.array_equal(recs[b, h].cpu().numpy(), ref[0])
+            rk, rv = O.dequantize_records(ref, bits)
+            assert np.array_equal(H.bits16(ko[lo:lo + n, h]), rk[:, 0]) and np.array_equal(H.bits16(vo[lo:lo + n, h]), rv[:, 0])
+        del ko, vo, blocks
+    print("[full] topk", flush=True)
+    nseq, hkv, keep_n = len(lay.ctx_len), lay.n_kv_heads, n // 10
+    scores = torch.randn(nseq * hkv * n, device=DEV, generator=synth.gen(99, DEV))
+    cu_keep = torch.arange(0, (nseq + 1) * keep_n, keep_n, dtype=torch.int32, device=DEV)
+    first = torch.full((nseq,), 64, dtype=torch.int32, device=DEV)
+    last = torch.full((nseq,), 256, dtype=torch.int32, device=DEV)
+    keep = torch.empty(nseq * hkv * keep_n, dtype=torch.int32, device=DEV)
+    lib.vc_topk_keep(ctx, scores, lay.cu_ctx, cu_keep, hkv, keep, forced_first=first, forced_last=last)
+    torch.cuda.synchronize()
+    ref, _ = O.topk_keep(scores.cpu().numpy(), lay.ctx_len, [keep_n] * nseq, hkv, [64] * nseq, [256] * nseq)
+    assert np.array_equal(keep.cpu().numpy(), ref)
