@@ -386,7 +386,54 @@ def measure_swap(vc, ctx, lay, torch, draft_kw, out, ws, HKV, N, B, W):
         streamed = {"verify_alone_ms": t_verify * 1e3, "swap_then_verify_ms": (t_swap + t_verify) * 1e3,
                     "streamed_ms": t_stream * 1e3, "exposed_after_swap_ms": (t_stream - t_swap) * 1e3,
                     "same_bits": bool(torch.equal(ref.view(torch.int16), vout.view(torch.int16)))}
+    # reload of the dropped rows only (token dropping keeps 10 % resident): the host holds them
+    # packed; per sequence two contiguous copies into a staging buffer and a short placement kernel,
+    # all on the copy stream, alone and under bf16-gather drafting
+    rows = None
+    if lay.dropped_idx is not None:
+        nd = N - lay.max_keep
+        rows_bytes = 2 * B * HKV * nd * 256
+        pk = torch.empty((B * HKV * nd, 128), dtype=torch.bfloat16, device=dev)
+        pv = torch.empty_like(pk)
+        vc.vc_pack_rows(ctx, lay.k_full, lay.v_full, lay.dropped_idx, lay.cu_drop, lay.cu_ctx, HKV, nd, pk, pv)
+        hpk = torch.empty(pk.shape, dtype=torch.bfloat16, pin_memory=True); hpk.copy_(pk)
+        hpv = torch.empty(pv.shape, dtype=torch.bfloat16, pin_memory=True); hpv.copy_(pv)
+        del pk, pv
+        stage_k = torch.empty((HKV * nd, 128), dtype=torch.bfloat16, device=dev)
+        stage_v = torch.empty_like(stage_k)
+        cu_drop_host = lay.cu_drop.cpu()
+        dst_k.fill_(float("nan")); dst_v.fill_(float("nan"))
+        torch.cuda.synchronize()
+
+        def rows_all():
+            return vc.vc_swap_in_rows(ctx, hpk, hpv, stage_k, stage_v, dst_k, dst_v, lay.dropped_idx, lay.cu_drop,
+                                      cu_drop_host, lay.cu_ctx, HKV, 0, B) + B - 1
+
+        t0 = time.perf_counter(); rows_all(); vc.vc_swap_sync(ctx); t_rows = time.perf_counter() - t0
+        # every dropped row arrived, every kept row is still untouched
+        landed = ~torch.isnan(dst_k[:, :, 0].float())
+        rows_ok = bool(int(landed.sum()) == B * HKV * nd and torch.equal(dst_k[landed], lay.k_full[landed]))
+
+        def drafts1(n):
+            for i in range(n):
+                vc.vc_draft_attn(ctx, lay.q, lay.scale, out, n_kv_heads=HKV, workspace=ws, **draft_kw("d1", i % W))
+
+        drafts1(4); torch.cuda.synchronize()
+        t0 = time.perf_counter(); drafts1(64); torch.cuda.synchronize(); t64 = time.perf_counter() - t0
+        n1 = max(64, int(math.ceil(t_rows / (t64 / 64))))
+        t0 = time.perf_counter(); drafts1(n1); torch.cuda.synchronize(); t_d1 = time.perf_counter() - t0
+        t0 = time.perf_counter()
+        last = rows_all()
+        drafts1(n1)
+        vc.vc_swap_wait(ctx, last)
+        torch.cuda.synchronize()
+        vc.vc_swap_sync(ctx)
+        t_both1 = time.perf_counter() - t0
+        rows = {"bytes": rows_bytes, "fraction_of_full": rows_bytes / total, "alone_ms": t_rows * 1e3,
+                "GBps": rows_bytes / t_rows / 1e9, "draft_steps": n1, "draft_alone_ms": t_d1 * 1e3, "both_ms": t_both1 * 1e3,
+                "overlap": (t_d1 + t_rows - t_both1) / min(t_d1, t_rows), "rows_ok": rows_ok}
     return {"bytes": total, "chunks": 2 * len(chunks), "swap_alone_ms": t_swap * 1e3, "swap_GBps": total / t_swap / 1e9,
+            "dropped_rows_reload": rows,
             "draft_steps": n_steps, "draft_alone_ms": t_draft * 1e3, "both_ms": t_both * 1e3,
             "overlap": (t_draft + t_swap - t_both) / min(t_draft, t_swap), "bytes_ok": ok,
             "model_max_ms": max(t_draft, t_swap) * 1e3, "streamed_verify": streamed}

@@ -203,6 +203,38 @@ vc_status vc_swap_query(vc_ctx* ctx, int64_t ticket);
 /* Block the host until every issued chunk has landed. */
 vc_status vc_swap_sync(vc_ctx* ctx);
 
+/* Reload of the dropped rows only (paper appendix B.1, the transfer term of the per-iteration
+ * time: with token dropping a verify needs only the extra (1 - c) * KV_full, because the kept rows
+ * already sit in HBM).  The host keeps the dropped rows of every (sequence, head) list PACKED:
+ * packed row cu_drop[b]*n_kv_heads + h*nd_b + i is the 256-byte row (cu_ctx[b] + t, h) of the full
+ * KV, t = entry i of dropped list (b, h) - vc_pack_rows builds that buffer on the device from a
+ * full pool (at compression time; the caller copies it to pinned memory).
+ *
+ * vc_swap_in_rows, for every sequence b in [seq_begin, seq_end) in turn: copies the sequence's
+ * packed rows host -> staging with the copy engine (two contiguous copies, K and V), places them
+ * into rows (cu_ctx[b] + t, h) of dev_k / dev_v with a short kernel, and records one event, all
+ * on the context's copy stream; sequence b gets ticket first_ticket + (b - seq_begin) for
+ * vc_swap_wait / vc_swap_query.  Rows of the destination that no list names are left alone, so a
+ * pool whose kept rows are valid becomes the full KV of those sequences.
+ *   host_packed_k, host_packed_v   pinned host memory (hipHostMalloc), packed rows as above
+ *   stage_k, stage_v   device staging, each at least stage_rows * 256 bytes; must hold one
+ *                      sequence: stage_rows >= nd_b * n_kv_heads (else VC_ERR_INVALID_ARG).  The
+ *                      in-order copy stream makes reuse across sequences and calls safe.
+ *   dev_k, dev_v       device bf16 pools [sum tokens][n_kv_heads][128]
+ *   dropped, cu_drop, cu_ctx   device int32, as for vc_keep_from_dropped (positions relative to
+ *                      the sequence start, in range: the caller's contract)
+ *   cu_drop_host       host copy of cu_drop (the copy sizes are needed on the host)
+ *
+ * vc_pack_rows: pool rows named by index lists (any lists in the dropped / kept list layout)
+ * -> packed rows, on `stream`; max_idx = host-side max list length. */
+vc_status vc_pack_rows(vc_ctx* ctx, const void* k, const void* v, const int32_t* idx, const int32_t* cu_idx,
+                       const int32_t* cu_ctx, int32_t n_seqs, int32_t n_kv_heads, int32_t max_idx,
+                       void* packed_k, void* packed_v, void* stream);
+vc_status vc_swap_in_rows(vc_ctx* ctx, const void* host_packed_k, const void* host_packed_v, void* stage_k,
+                          void* stage_v, int64_t stage_rows, void* dev_k, void* dev_v, const int32_t* dropped,
+                          const int32_t* cu_drop, const int32_t* cu_drop_host, const int32_t* cu_ctx,
+                          int32_t n_kv_heads, int32_t seq_begin, int32_t seq_end, int64_t* first_ticket);
+
 /* Kept-index lists from the compressor's dropped-index lists (section 6,
  * CompressedKV.dropped_indices): keep = [0, len_b) minus dropped, ascending.
  *   dropped  device int32: list (b, h) is dropped[(cu_drop[b]*n_kv_heads + h*nd) + i], ascending,

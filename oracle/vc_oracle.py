@@ -16,6 +16,8 @@ What it computes, step by step, in IEEE double precision (paper section 4.1, cor
                      quantiser into block records (decisions in float32, spelled out at
                      quantise_groups) and its inverse, rounded once to bf16.
   topk_keep (section 6, what update() decides) - kept positions from importance scores.
+  pack_rows / swap_in_rows (appendix B.1, the (1 - c) * KV_full transfer) - the dropped rows kept
+                     on the host, and their placement back into the pool.
 
 Every input is taken in the byte layout that the C header of the library describes in prose
 (bf16 / fp16 bit patterns, packed codes); the unpacking below is written from that prose and
@@ -480,3 +482,44 @@ def topk_keep(scores, ctx_len, keep_len, n_kv_heads: int, forced_first=None, for
             pieces.append(np.sort(chosen).astype(np.int32))
     keep = np.concatenate(pieces) if pieces else np.zeros(0, dtype=np.int32)
     return keep, cu_keep
+
+
+# --------------------------------------------------------------------------------------------
+# reload of the dropped rows only  (appendix B.1: a verify after token dropping needs only the
+# extra (1 - c) * KV_full, the kept rows are already resident)
+# --------------------------------------------------------------------------------------------
+def pack_rows(k, v, idx, cu_idx, cu_ctx, n_kv_heads: int):
+    """Rows named by the index lists, list after list: packed row (cu_idx[b]*Hkv + h*n_b + i) is
+    row (cu_ctx[b] + idx_list(b, h)[i], h) of the pools [tokens, n_kv_heads, 128] (16-bit patterns).
+    This is what the host keeps of a token-dropped sequence: its dropped rows only."""
+    idx = np.asarray(idx, dtype=np.int64)
+    nseq = len(cu_idx) - 1
+    total = int(cu_idx[-1]) * n_kv_heads
+    pk = np.zeros((total, k.shape[2]), dtype=k.dtype)
+    pv = np.zeros((total, v.shape[2]), dtype=v.dtype)
+    for b in range(nseq):
+        n = int(cu_idx[b + 1]) - int(cu_idx[b])
+        for h in range(n_kv_heads):
+            start = int(cu_idx[b]) * n_kv_heads + h * n
+            for i in range(n):
+                row = int(cu_ctx[b]) + int(idx[start + i])
+                pk[start + i] = k[row, h]
+                pv[start + i] = v[row, h]
+    return pk, pv
+
+
+def swap_in_rows(packed_k, packed_v, dev_k, dev_v, dropped, cu_drop, cu_ctx, n_kv_heads: int, seqs):
+    """The inverse placement for the sequences in `seqs`: packed row (cu_drop[b]*Hkv + h*nd + i)
+    goes to row (cu_ctx[b] + dropped_list(b, h)[i], h) of the device pools.  Returns new
+    (dev_k, dev_v); every other row is untouched."""
+    dk, dv = np.array(dev_k, copy=True), np.array(dev_v, copy=True)
+    dropped = np.asarray(dropped, dtype=np.int64)
+    for b in seqs:
+        nd = int(cu_drop[b + 1]) - int(cu_drop[b])
+        for h in range(n_kv_heads):
+            start = int(cu_drop[b]) * n_kv_heads + h * nd
+            for i in range(nd):
+                row = int(cu_ctx[b]) + int(dropped[start + i])
+                dk[row, h] = packed_k[start + i]
+                dv[row, h] = packed_v[start + i]
+    return dk, dv

@@ -47,7 +47,7 @@ class vc_chunk(C.Structure):
 EXPORTS = ["vc_create", "vc_destroy", "vc_last_error", "vc_version", "vc_time_main_kernel",
            "vc_draft_workspace_bytes", "vc_draft_attn", "vc_verify_workspace_bytes", "vc_verify_attn",
            "vc_verify_plan", "vc_verify_attn_range", "vc_verify_finish",
-           "vc_accept_workspace_bytes", "vc_accept_len", "vc_swap_in", "vc_swap_wait", "vc_swap_query", "vc_swap_sync",
+           "vc_accept_workspace_bytes", "vc_accept_len", "vc_swap_in", "vc_swap_in_rows", "vc_pack_rows", "vc_swap_wait", "vc_swap_query", "vc_swap_sync",
            "vc_keep_from_dropped", "vc_compress_quant", "vc_decompress_quant", "vc_topk_keep"]
 
 
@@ -88,6 +88,11 @@ def load():
                                   C.c_size_t, C.c_void_p]
     lib.vc_swap_in.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(vc_chunk), C.c_int32,
                                C.POINTER(C.c_int64)]
+    lib.vc_swap_in_rows.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p,
+                                    C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32,
+                                    C.c_int32, C.POINTER(C.c_int64)]
+    lib.vc_pack_rows.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
+                                 C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
     lib.vc_swap_wait.argtypes = [C.c_void_p, C.c_int64, C.c_void_p]
     lib.vc_swap_query.argtypes = [C.c_void_p, C.c_int64]
     lib.vc_swap_sync.argtypes = [C.c_void_p]
@@ -287,6 +292,32 @@ def vc_swap_in(ctx: Context, host_src, dev_dst, chunks) -> int:
     _check(load().vc_swap_in(ctx.handle, C.c_void_p(host_src.data_ptr()), C.c_void_p(dev_dst.data_ptr()),
                              arr, len(chunks), C.byref(first)))
     return first.value
+
+
+def vc_swap_in_rows(ctx: Context, host_packed_k, host_packed_v, stage_k, stage_v, dev_k, dev_v, dropped, cu_drop,
+                    cu_drop_host, cu_ctx, n_kv_heads, seq_begin, seq_end) -> int:
+    """Reload only the dropped rows of sequences [seq_begin, seq_end) from packed pinned buffers.
+    cu_drop_host: CPU int32 tensor (a copy of cu_drop).  Returns the first ticket."""
+    if cu_drop_host.device.type != "cpu" or cu_drop_host.dtype != torch.int32:
+        raise TypeError("cu_drop_host: expected a CPU int32 tensor")
+    first = C.c_int64()
+    stage_rows = min(stage_k.numel(), stage_v.numel()) // 128
+    _check(load().vc_swap_in_rows(ctx.handle, C.c_void_p(host_packed_k.data_ptr()), C.c_void_p(host_packed_v.data_ptr()),
+                                  _ptr(stage_k, torch.bfloat16, "stage_k"), _ptr(stage_v, torch.bfloat16, "stage_v"),
+                                  stage_rows, _ptr(dev_k, torch.bfloat16, "dev_k"), _ptr(dev_v, torch.bfloat16, "dev_v"),
+                                  _ptr(dropped, torch.int32, "dropped"), _ptr(cu_drop, torch.int32, "cu_drop"),
+                                  C.c_void_p(cu_drop_host.data_ptr()), _ptr(cu_ctx, torch.int32, "cu_ctx"), n_kv_heads,
+                                  seq_begin, seq_end, C.byref(first)))
+    return first.value
+
+
+def vc_pack_rows(ctx: Context, k, v, idx, cu_idx, cu_ctx, n_kv_heads, max_idx, packed_k, packed_v, stream=None):
+    n_seqs = cu_ctx.numel() - 1
+    _check(load().vc_pack_rows(ctx.handle, _ptr(k, torch.bfloat16, "k"), _ptr(v, torch.bfloat16, "v"),
+                               _ptr(idx, torch.int32, "idx"), _ptr(cu_idx, torch.int32, "cu_idx"),
+                               _ptr(cu_ctx, torch.int32, "cu_ctx"), n_seqs, n_kv_heads, max_idx,
+                               _ptr(packed_k, torch.bfloat16, "packed_k"), _ptr(packed_v, torch.bfloat16, "packed_v"),
+                               _stream(stream)))
 
 
 def vc_swap_wait(ctx: Context, ticket: int, stream=None):

@@ -129,6 +129,171 @@ extern "C" vc_status vc_swap_in(vc_ctx* c, const void* host_src, void* dev_dst, 
   return VC_OK;
 }
 
+namespace vc {
+// Rows named by index lists move between a pool (row (cu_ctx[b] + t, h)) and a packed buffer
+// (row cu_idx[b]*Hkv + h*n_b + i, list after list); every 16 lanes move one 256-byte row of K and
+// of V.  SCATTER: packed -> pool (reload of the dropped rows), else pool -> packed.
+struct MoveRowsParams {
+  uint16_t* pool_k;
+  uint16_t* pool_v;
+  uint16_t* packed_k;
+  uint16_t* packed_v;
+  const int* idx;
+  const int* cu_idx;
+  const int* cu_ctx;
+  int n_kv_heads, seq0;
+  long long packed_row0;   // packed row that sits at packed_k / packed_v (staging holds one sequence)
+};
+
+constexpr int kMoveRowsUnroll = 4;
+
+template <bool SCATTER>
+__global__ __launch_bounds__(256) void move_rows_kernel(MoveRowsParams p) {
+  const int b = p.seq0 + blockIdx.z, h = blockIdx.y;
+  const int n = p.cu_idx[b + 1] - p.cu_idx[b];
+  const size_t list0 = static_cast<size_t>(p.cu_idx[b]) * p.n_kv_heads + static_cast<size_t>(h) * n;
+  const int* list = p.idx + list0;
+  const size_t row0 = static_cast<size_t>(p.cu_ctx[b]);
+  const int sub = threadIdx.x & 15, grp = threadIdx.x >> 4;
+  constexpr int kRowsPerPass = 16 * kMoveRowsUnroll;
+  for (int i0 = blockIdx.x * kRowsPerPass; i0 < n; i0 += gridDim.x * kRowsPerPass) {
+    size_t pool_off[kMoveRowsUnroll], pack_off[kMoveRowsUnroll];
+    bool ok[kMoveRowsUnroll];
+    uint4 kr[kMoveRowsUnroll], vr[kMoveRowsUnroll];
+#pragma unroll
+    for (int u = 0; u < kMoveRowsUnroll; ++u) {
+      const int i = i0 + grp + 16 * u;
+      ok[u] = i < n;
+      const int t = ok[u] ? list[i] : 0;
+      pool_off[u] = ((row0 + t) * p.n_kv_heads + h) * kHeadDim + 8 * sub;
+      pack_off[u] = (list0 + (ok[u] ? i : 0) - static_cast<size_t>(p.packed_row0)) * kHeadDim + 8 * sub;
+    }
+#pragma unroll
+    for (int u = 0; u < kMoveRowsUnroll; ++u) {
+      if (ok[u]) {
+        kr[u] = *reinterpret_cast<const uint4*>((SCATTER ? p.packed_k + pack_off[u] : p.pool_k + pool_off[u]));
+        vr[u] = *reinterpret_cast<const uint4*>((SCATTER ? p.packed_v + pack_off[u] : p.pool_v + pool_off[u]));
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < kMoveRowsUnroll; ++u) {
+      if (ok[u]) {
+        *reinterpret_cast<uint4*>((SCATTER ? p.pool_k + pool_off[u] : p.packed_k + pack_off[u])) = kr[u];
+        *reinterpret_cast<uint4*>((SCATTER ? p.pool_v + pool_off[u] : p.packed_v + pack_off[u])) = vr[u];
+      }
+    }
+  }
+}
+}  // namespace vc
+
+static vc_status require_kind(const void* ptr, hipMemoryType kind, const char* who, const char* what) {
+  hipPointerAttribute_t at;
+  hipError_t e = hipPointerGetAttributes(&at, ptr);
+  if (e != hipSuccess || at.type != kind) {
+    (void)hipGetLastError();
+    return fail(VC_ERR_INVALID_ARG, "%s: %s", who, what);
+  }
+  return VC_OK;
+}
+
+extern "C" vc_status vc_pack_rows(vc_ctx* c, const void* k, const void* v, const int32_t* idx, const int32_t* cu_idx,
+                                  const int32_t* cu_ctx, int32_t n_seqs, int32_t n_kv_heads, int32_t max_idx,
+                                  void* packed_k, void* packed_v, void* stream) {
+  VC_REQUIRE(c != nullptr, VC_ERR_INVALID_ARG, "vc_pack_rows: ctx is NULL");
+  VC_REQUIRE(n_seqs >= 0 && n_seqs <= 65535 && n_kv_heads > 0 && n_kv_heads <= 65535 && max_idx >= 0, VC_ERR_INVALID_ARG,
+             "vc_pack_rows: n_seqs %d n_kv_heads %d max_idx %d", n_seqs, n_kv_heads, max_idx);
+  if (n_seqs == 0 || max_idx == 0) return VC_OK;
+  VC_REQUIRE(k && v && idx && cu_idx && cu_ctx && packed_k && packed_v, VC_ERR_INVALID_ARG, "vc_pack_rows: NULL pointer");
+  VC_REQUIRE(aligned16(k) && aligned16(v) && aligned16(packed_k) && aligned16(packed_v), VC_ERR_INVALID_ARG,
+             "vc_pack_rows: pools must be 16-byte aligned");
+  vc::MoveRowsParams p{};
+  p.pool_k = static_cast<uint16_t*>(const_cast<void*>(k));
+  p.pool_v = static_cast<uint16_t*>(const_cast<void*>(v));
+  p.packed_k = static_cast<uint16_t*>(packed_k);
+  p.packed_v = static_cast<uint16_t*>(packed_v);
+  p.idx = idx; p.cu_idx = cu_idx; p.cu_ctx = cu_ctx; p.n_kv_heads = n_kv_heads; p.seq0 = 0; p.packed_row0 = 0;
+  const int per_list = ceil_div(max_idx, 16 * vc::kMoveRowsUnroll * 8);   // eight passes per workgroup
+  hipLaunchKernelGGL(vc::move_rows_kernel<false>, dim3(per_list, n_kv_heads, n_seqs), dim3(256), 0,
+                     static_cast<hipStream_t>(stream), p);
+  VC_HIP(hipGetLastError());
+  return VC_OK;
+}
+
+extern "C" vc_status vc_swap_in_rows(vc_ctx* c, const void* host_packed_k, const void* host_packed_v, void* stage_k,
+                                     void* stage_v, int64_t stage_rows, void* dev_k, void* dev_v, const int32_t* dropped,
+                                     const int32_t* cu_drop, const int32_t* cu_drop_host, const int32_t* cu_ctx,
+                                     int32_t n_kv_heads, int32_t seq_begin, int32_t seq_end, int64_t* first_ticket) {
+  const char* who = "vc_swap_in_rows";
+  VC_REQUIRE(c && first_ticket, VC_ERR_INVALID_ARG, "%s: ctx or first_ticket is NULL", who);
+  VC_REQUIRE(n_kv_heads > 0 && n_kv_heads <= 65535 && stage_rows >= 0, VC_ERR_INVALID_ARG, "%s: n_kv_heads %d stage_rows %lld",
+             who, n_kv_heads, static_cast<long long>(stage_rows));
+  VC_REQUIRE(seq_begin >= 0 && seq_end >= seq_begin, VC_ERR_INVALID_ARG, "%s: sequences [%d, %d)", who, seq_begin, seq_end);
+  *first_ticket = c->issued;
+  const int nseq = seq_end - seq_begin;
+  if (nseq == 0) return VC_OK;
+  VC_REQUIRE(host_packed_k && host_packed_v && stage_k && stage_v && dev_k && dev_v && dropped && cu_drop && cu_drop_host &&
+                 cu_ctx, VC_ERR_INVALID_ARG, "%s: NULL pointer", who);
+  VC_REQUIRE(aligned16(host_packed_k) && aligned16(host_packed_v) && aligned16(stage_k) && aligned16(stage_v) &&
+                 aligned16(dev_k) && aligned16(dev_v), VC_ERR_INVALID_ARG, "%s: buffers must be 16-byte aligned", who);
+  VC_REQUIRE(nseq <= vc_ctx::kRing, VC_ERR_INVALID_ARG, "%s: more than %d sequences per call", who, vc_ctx::kRing);
+  vc_status st = require_kind(host_packed_k, hipMemoryTypeHost, who, "host_packed_k is not pinned host memory");
+  if (st == VC_OK) st = require_kind(host_packed_v, hipMemoryTypeHost, who, "host_packed_v is not pinned host memory");
+  if (st == VC_OK) st = require_kind(stage_k, hipMemoryTypeDevice, who, "stage_k is not device memory");
+  if (st == VC_OK) st = require_kind(stage_v, hipMemoryTypeDevice, who, "stage_v is not device memory");
+  if (st == VC_OK) st = require_kind(dev_k, hipMemoryTypeDevice, who, "dev_k is not device memory");
+  if (st == VC_OK) st = require_kind(dev_v, hipMemoryTypeDevice, who, "dev_v is not device memory");
+  if (st != VC_OK) return st;
+  int max_nd = 0;
+  for (int b = seq_begin; b < seq_end; ++b) {
+    const int nd = cu_drop_host[b + 1] - cu_drop_host[b];
+    VC_REQUIRE(nd >= 0, VC_ERR_INVALID_ARG, "%s: cu_drop_host is not ascending at %d", who, b);
+    VC_REQUIRE(static_cast<int64_t>(nd) * n_kv_heads <= stage_rows, VC_ERR_INVALID_ARG,
+               "%s: sequence %d needs %lld staging rows, stage_rows is %lld", who, b,
+               static_cast<long long>(nd) * n_kv_heads, static_cast<long long>(stage_rows));
+    max_nd = nd > max_nd ? nd : max_nd;
+  }
+  int64_t oldest_needed = c->issued + nseq - vc_ctx::kRing;
+  if (oldest_needed > 0) {
+    hipEvent_t ev = c->events[(oldest_needed - 1) % vc_ctx::kRing];
+    if (ev && hipEventQuery(ev) != hipSuccess) {
+      (void)hipGetLastError();
+      return fail(VC_ERR_INVALID_ARG, "%s: more than %d tickets outstanding", who, vc_ctx::kRing);
+    }
+  }
+  VC_HIP(hipSetDevice(c->device));
+  vc::MoveRowsParams p{};
+  p.pool_k = static_cast<uint16_t*>(dev_k);
+  p.pool_v = static_cast<uint16_t*>(dev_v);
+  p.packed_k = static_cast<uint16_t*>(stage_k);
+  p.packed_v = static_cast<uint16_t*>(stage_v);
+  p.idx = dropped; p.cu_idx = cu_drop; p.cu_ctx = cu_ctx; p.n_kv_heads = n_kv_heads;
+  const size_t row_bytes = kHeadDim * 2;
+  for (int b = seq_begin; b < seq_end; ++b) {
+    int slot = static_cast<int>(c->issued % vc_ctx::kRing);
+    if (!c->events[slot]) VC_HIP(hipEventCreateWithFlags(&c->events[slot], hipEventDisableTiming));
+    const int nd = cu_drop_host[b + 1] - cu_drop_host[b];
+    if (nd > 0) {
+      // the copy stream is in order: the staging buffer is free again once the previous
+      // sequence's placement kernel has run
+      const size_t first_row = static_cast<size_t>(cu_drop_host[b]) * n_kv_heads;
+      const size_t bytes = static_cast<size_t>(nd) * n_kv_heads * row_bytes;
+      VC_HIP(hipMemcpyAsync(stage_k, static_cast<const char*>(host_packed_k) + first_row * row_bytes, bytes,
+                            hipMemcpyHostToDevice, c->copy_stream));
+      VC_HIP(hipMemcpyAsync(stage_v, static_cast<const char*>(host_packed_v) + first_row * row_bytes, bytes,
+                            hipMemcpyHostToDevice, c->copy_stream));
+      p.seq0 = b;
+      p.packed_row0 = static_cast<long long>(first_row);
+      const int per_list = ceil_div(nd, 16 * vc::kMoveRowsUnroll * 8);
+      hipLaunchKernelGGL(vc::move_rows_kernel<true>, dim3(per_list, n_kv_heads, 1), dim3(256), 0, c->copy_stream, p);
+      VC_HIP(hipGetLastError());
+    }
+    VC_HIP(hipEventRecord(c->events[slot], c->copy_stream));
+    c->issued++;
+  }
+  (void)max_nd;
+  return VC_OK;
+}
+
 static vc_status ticket_event(vc_ctx* c, int64_t ticket, hipEvent_t* ev, const char* who) {
   VC_REQUIRE(c != nullptr, VC_ERR_INVALID_ARG, "%s: ctx is NULL", who);
   VC_REQUIRE(ticket >= 0 && ticket < c->issued, VC_ERR_INVALID_ARG, "%s: ticket %lld was never issued", who,

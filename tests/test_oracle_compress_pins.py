@@ -204,3 +204,44 @@ def test_topk_keep_matches_generator_lists():
     keep, scores = synth.topk_keep(1000, 100, 8, 16, 3, g, return_scores=True)
     got, _ = O.topk_keep(scores.numpy().ravel(), [1000], [100], 3, [8], [16])
     assert np.array_equal(got, keep.numpy().ravel())
+
+
+# ------------------------------------------------------------------ reload of dropped rows
+def test_swap_in_rows_completes_the_pool_and_touches_nothing_else():
+    """kept rows (valid in the pool) + reloaded dropped rows = the full KV, for the chosen
+    sequences only; rows of other sequences and kept rows keep their poison / their values."""
+    rng = np.random.default_rng(0)
+    ctx_len, hkv = [9, 5, 12], 2
+    cu_ctx = np.concatenate([[0], np.cumsum(ctx_len)])
+    total = int(cu_ctx[-1])
+    host_k = rng.integers(0, 65536, (total, hkv, 128)).astype(np.uint16)
+    host_v = rng.integers(0, 65536, (total, hkv, 128)).astype(np.uint16)
+    nd = [4, 2, 7]
+    cu_drop = np.concatenate([[0], np.cumsum(nd)])
+    lists = []
+    for b, n in enumerate(ctx_len):
+        for h in range(hkv):
+            lists.append(np.sort(rng.choice(n, nd[b], replace=False)))
+    dropped = np.concatenate(lists)
+    keep, cu_keep = O.keep_from_dropped(dropped, cu_drop, ctx_len, hkv)
+    dev_k = np.full_like(host_k, 0xDEAD); dev_v = np.full_like(host_v, 0xBEEF)
+    # the resident part: kept rows
+    for b, n in enumerate(ctx_len):
+        nk = n - nd[b]
+        for h in range(hkv):
+            for t in keep[cu_keep[b] * hkv + h * nk: cu_keep[b] * hkv + (h + 1) * nk]:
+                dev_k[cu_ctx[b] + t, h] = host_k[cu_ctx[b] + t, h]
+                dev_v[cu_ctx[b] + t, h] = host_v[cu_ctx[b] + t, h]
+    pk, pv = O.pack_rows(host_k, host_v, dropped, cu_drop, cu_ctx, hkv)
+    assert pk.shape == (int(cu_drop[-1]) * hkv, 128)
+    # packed row order: list (b, h) after list, entries in list order (checked on one planted row)
+    b, h, i = 2, 1, 3
+    start = cu_drop[b] * hkv + h * nd[b]
+    assert np.array_equal(pk[start + i], host_k[cu_ctx[b] + dropped[start + i], h])
+    k2, v2 = O.swap_in_rows(pk, pv, dev_k, dev_v, dropped, cu_drop, cu_ctx, hkv, [0, 2])
+    for b in (0, 2):
+        lo, hi = cu_ctx[b], cu_ctx[b + 1]
+        assert np.array_equal(k2[lo:hi], host_k[lo:hi]) and np.array_equal(v2[lo:hi], host_v[lo:hi])
+    lo, hi = cu_ctx[1], cu_ctx[2]
+    assert np.array_equal(k2[lo:hi], dev_k[lo:hi]) and np.array_equal(v2[lo:hi], dev_v[lo:hi])
+    assert (k2[lo:hi] == 0xDEAD).sum() == nd[1] * hkv * 128
