@@ -294,6 +294,51 @@ vc_status vc_topk_keep(vc_ctx* ctx, const float* scores, const int32_t* cu_ctx, 
                        const int32_t* forced_first, const int32_t* forced_last, int32_t n_seqs,
                        int32_t n_kv_heads, int32_t* keep_idx, void* stream);
 
+/* ------------------------------------------------------------------------------------------
+ * Admission control (paper section 5; host code only, no GPU call, no stream).
+ *
+ * The runtime looks W iterations ("windows") ahead; window 0 is the current iteration.  Two
+ * reserve rings (section 5.1): T[i], the interconnect time booked in window i (constraint
+ * T[i] <= T_iter), and B[i], the bytes of full KV in flight in window i (constraint
+ * M + KV_resident + B[i] <= HBM).  A reload of KV_full bytes takes KV_full / BW seconds and spans
+ * S_r = max(1, ceil(KV_full / (BW * T_iter))) windows; it books an equal share of its time in
+ * each of them and its bytes in all of them.  All quantities are doubles (seconds, bytes,
+ * bytes per second).
+ *
+ * vc_iter_time_model: section 4.2.1, Eq. 3.  T_gpu = (M + B*KV_full*(c + 1/x)) / BW_hbm,
+ *   T_xfer = B*KV_full / (x * BW_inter), T_iter = max of the two.  t_gpu / t_xfer may be NULL.
+ * vc_sched_create: W windows, all empty, at iteration 0.  The caller owns the handle.
+ * vc_sched_set_resident: KV_resident changes as requests come and go.
+ * vc_sched_span: S_r for a request of that size.
+ * vc_sched_admit (Algorithm 1): places the next verify of request `req`, which drafts x tokens
+ *   per horizon.  Candidates are tried in the order anchor, anchor-1, anchor+1, anchor-2, ...,
+ *   anchor = clamp(x, S_r, W-1), skipping those outside [S_r, W-1]; the first window d whose
+ *   span [d-S_r+1, d] satisfies both constraints is reserved and returned in *window.  *window
+ *   = -1 when none does (the request goes back to the caller's waiting queue; nothing is
+ *   reserved).  A request that already holds a reservation is VC_ERR_INVALID_ARG.
+ * vc_sched_cancel: gives a reservation back (a request that finished or was aborted).
+ * vc_sched_step (section 5.2): one iteration.  Writes the ids (ascending) of the requests whose
+ *   reload must start now (the first window of their span is the current one) to kick[0..*n_kick)
+ *   and of the requests that verify now to verify[0..*n_verify); verified requests lose their
+ *   reservation (the caller admits them again); then the horizon slides by one window.  If
+ *   either list would exceed `capacity` entries the call fails and changes nothing.
+ * vc_sched_rings: copies T[0..W) and B[0..W) (window 0 first; either may be NULL) and the
+ *   absolute iteration number of window 0.
+ * ------------------------------------------------------------------------------------------ */
+typedef struct vc_sched vc_sched;
+vc_status vc_iter_time_model(double model_bytes, double batch, double kv_full_bytes, double c, double x,
+                             double bw_hbm, double bw_inter, double* t_iter, double* t_gpu, double* t_xfer);
+vc_status vc_sched_create(int32_t windows, double t_iter_s, double bw_bytes_per_s, double hbm_bytes,
+                          double model_bytes, double resident_bytes, vc_sched** out);
+vc_status vc_sched_destroy(vc_sched* sched);
+vc_status vc_sched_set_resident(vc_sched* sched, double resident_bytes);
+vc_status vc_sched_span(const vc_sched* sched, double kv_full_bytes, int32_t* span);
+vc_status vc_sched_admit(vc_sched* sched, int64_t req, double kv_full_bytes, int32_t x, int32_t* window);
+vc_status vc_sched_cancel(vc_sched* sched, int64_t req);
+vc_status vc_sched_step(vc_sched* sched, int64_t* kick, int32_t* n_kick, int64_t* verify, int32_t* n_verify,
+                        int32_t capacity);
+vc_status vc_sched_rings(const vc_sched* sched, double* t_ring, double* b_ring, int64_t* now);
+
 #ifdef __cplusplus
 }
 #endif

@@ -48,7 +48,9 @@ EXPORTS = ["vc_create", "vc_destroy", "vc_last_error", "vc_version", "vc_time_ma
            "vc_draft_workspace_bytes", "vc_draft_attn", "vc_verify_workspace_bytes", "vc_verify_attn",
            "vc_verify_plan", "vc_verify_attn_range", "vc_verify_finish",
            "vc_accept_workspace_bytes", "vc_accept_len", "vc_swap_in", "vc_swap_in_rows", "vc_pack_rows", "vc_swap_wait", "vc_swap_query", "vc_swap_sync",
-           "vc_keep_from_dropped", "vc_compress_quant", "vc_decompress_quant", "vc_topk_keep"]
+           "vc_keep_from_dropped", "vc_compress_quant", "vc_decompress_quant", "vc_topk_keep",
+           "vc_iter_time_model", "vc_sched_create", "vc_sched_destroy", "vc_sched_set_resident", "vc_sched_span",
+           "vc_sched_admit", "vc_sched_cancel", "vc_sched_step", "vc_sched_rings"]
 
 
 def library_path() -> str:
@@ -104,6 +106,16 @@ def load():
                                         C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
     lib.vc_topk_keep.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
                                  C.c_int32, C.c_void_p, C.c_void_p]
+    lib.vc_iter_time_model.argtypes = [C.c_double] * 7 + [C.POINTER(C.c_double)] * 3
+    lib.vc_sched_create.argtypes = [C.c_int32] + [C.c_double] * 5 + [C.POINTER(C.c_void_p)]
+    lib.vc_sched_destroy.argtypes = [C.c_void_p]
+    lib.vc_sched_set_resident.argtypes = [C.c_void_p, C.c_double]
+    lib.vc_sched_span.argtypes = [C.c_void_p, C.c_double, C.POINTER(C.c_int32)]
+    lib.vc_sched_admit.argtypes = [C.c_void_p, C.c_int64, C.c_double, C.c_int32, C.POINTER(C.c_int32)]
+    lib.vc_sched_cancel.argtypes = [C.c_void_p, C.c_int64]
+    lib.vc_sched_step.argtypes = [C.c_void_p, C.POINTER(C.c_int64), C.POINTER(C.c_int32), C.POINTER(C.c_int64),
+                                  C.POINTER(C.c_int32), C.c_int32]
+    lib.vc_sched_rings.argtypes = [C.c_void_p, C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(C.c_int64)]
     _LIB = lib
     return lib
 
@@ -376,3 +388,63 @@ def vc_topk_keep(ctx: Context, scores, cu_ctx, cu_keep, n_kv_heads, keep_idx, fo
                                _ptr(cu_keep, torch.int32, "cu_keep"), _ptr(forced_first, torch.int32, "forced_first"),
                                _ptr(forced_last, torch.int32, "forced_last"), n_seqs, n_kv_heads,
                                _ptr(keep_idx, torch.int32, "keep_idx"), _stream(stream)))
+
+
+def vc_iter_time_model(model_bytes, batch, kv_full_bytes, c, x, bw_hbm, bw_inter):
+    """Eq. 3 of the paper: returns (t_iter, t_gpu, t_xfer) in seconds."""
+    ti, tg, tx = C.c_double(), C.c_double(), C.c_double()
+    _check(load().vc_iter_time_model(model_bytes, batch, kv_full_bytes, c, x, bw_hbm, bw_inter,
+                                     C.byref(ti), C.byref(tg), C.byref(tx)))
+    return ti.value, tg.value, tx.value
+
+
+class Sched:
+    """vc_sched: the reserve rings, Admit and the execution loop (host side only)."""
+
+    def __init__(self, windows, t_iter, bw, hbm_bytes, model_bytes, resident_bytes=0.0, capacity=1024):
+        self._h = C.c_void_p()
+        _check(load().vc_sched_create(int(windows), t_iter, bw, hbm_bytes, model_bytes, resident_bytes,
+                                      C.byref(self._h)))
+        self.windows = int(windows)
+        self._cap = int(capacity)
+        self._kick = (C.c_int64 * self._cap)()
+        self._ver = (C.c_int64 * self._cap)()
+
+    def close(self):
+        if self._h:
+            load().vc_sched_destroy(self._h)
+            self._h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def set_resident(self, resident_bytes):
+        _check(load().vc_sched_set_resident(self._h, resident_bytes))
+
+    def span(self, kv_full_bytes) -> int:
+        n = C.c_int32()
+        _check(load().vc_sched_span(self._h, kv_full_bytes, C.byref(n)))
+        return n.value
+
+    def admit(self, req, kv_full_bytes, x) -> int:
+        d = C.c_int32()
+        _check(load().vc_sched_admit(self._h, int(req), kv_full_bytes, int(x), C.byref(d)))
+        return d.value
+
+    def cancel(self, req):
+        _check(load().vc_sched_cancel(self._h, int(req)))
+
+    def step(self):
+        nk, nv = C.c_int32(), C.c_int32()
+        _check(load().vc_sched_step(self._h, self._kick, C.byref(nk), self._ver, C.byref(nv), self._cap))
+        return list(self._kick[:nk.value]), list(self._ver[:nv.value])
+
+    def rings(self):
+        t = (C.c_double * self.windows)()
+        b = (C.c_double * self.windows)()
+        now = C.c_int64()
+        _check(load().vc_sched_rings(self._h, t, b, C.byref(now)))
+        return list(t), list(b), now.value

@@ -1,22 +1,29 @@
 """CPU pins of the admission-control oracle against what the paper fixes: the worked example of
 section 4.2.1 (Mistral 24B on one 96 GB GPU, 10 requests, KV_comp 1 GB, KV_full 4 GB, x = 30) and
 the constraints of section 5.1."""
+import json
 import math
+import os
 
 import pytest
 
 from oracle import sched_oracle as S
 
 GB = 1e9
-# the example's figures: 64 GB/s link, ~80 ms per full-KV transfer (i.e. ~50 GB/s effective),
-# ~35 ms per draft-only iteration for M + B*KV_comp = 60 GB, ~37 ms with one verify folded in
-M, KV_FULL, KV_COMP, NREQ, X = 50 * GB, 4 * GB, 1 * GB, 10, 30
-BW_EFF = KV_FULL / 0.080
-BW_HBM = (M + NREQ * KV_COMP) / 0.035
+# the example's figures (tests/golden/worked_example_section_4_2_1.json): 64 GB/s link, ~80 ms per
+# full-KV transfer (i.e. ~50 GB/s effective), ~35 ms per draft-only iteration for M + B*KV_comp,
+# ~37 ms with one verify folded in, peak HBM 64 GB = M + B*KV_comp + KV_full  ->  M = 50 GB
+with open(os.path.join(os.path.dirname(__file__), "golden", "worked_example_section_4_2_1.json")) as f:
+    EX = json.load(f)
+KV_FULL, KV_COMP, NREQ, X = EX["kv_full_GB"] * GB, EX["kv_comp_GB"] * GB, EX["requests"], EX["draft_length_x"]
+M = EX["peak_hbm_staggered_GB"] * GB - NREQ * KV_COMP - KV_FULL
+BW_EFF = KV_FULL / (EX["transfer_ms_per_verify_approx"] * 1e-3)
+BW_HBM = (M + NREQ * KV_COMP) / (EX["draft_only_iteration_ms_approx"] * 1e-3)
+LINK = EX["link_GBps_nominal"] * GB
 
 
 def test_eq3_reproduces_the_example_iteration_times():
-    t_iter, t_gpu, t_xfer = S.t_iter_model(M, NREQ, KV_FULL, KV_COMP / KV_FULL, X, BW_HBM, 64 * GB)
+    t_iter, t_gpu, t_xfer = S.t_iter_model(M, NREQ, KV_FULL, KV_COMP / KV_FULL, X, BW_HBM, LINK)
     # draft traffic plus one thirtieth of each request's full KV per iteration: between the
     # example's 35 ms (draft only) and 37 ms (one whole verify folded in)
     assert 0.035 < t_gpu < 0.037
@@ -35,14 +42,19 @@ def example_rings(hbm=96 * GB):
 
 def test_worked_example_verifies_land_one_every_three_iterations():
     r = example_rings()
-    assert r.span_windows(KV_FULL) == 3                   # 80 ms of link time over 37 ms windows
+    assert r.span_windows(KV_FULL) == EX["verify_spacing_iterations"] == 3   # 80 ms of link time over 37 ms windows
     ds = [r.admit(i, KV_FULL, X) for i in range(NREQ)]
     assert ds[0] == X                                     # the first request gets its anchor
     assert ds[:4] == [30, 27, 33, 24]                     # then x-1, x+1, x-2, ... until a free span
     assert sorted(ds) == list(range(15, 45, 3))           # "spread one every 3 draft iterations"
     assert all(t <= r.t_iter for t in r.T)
     # only one full KV is ever in flight: peak HBM = M + B*KV_comp + 1*KV_full = 64 GB
-    assert r.peak_hbm() == 64 * GB
+    assert r.peak_hbm() == EX["peak_hbm_staggered_GB"] * GB
+    # the lock-step alternative of the example: all full KVs resident at once, 40 GB serialised
+    assert M + NREQ * KV_FULL == EX["lock_step_peak_hbm_GB"] * GB
+    lock_ms = NREQ * KV_FULL / BW_EFF * 1e3
+    assert lock_ms == pytest.approx(EX["lock_step_transfer_ms_approx"])
+    assert 20 <= lock_ms / 37 < 23 and EX["lock_step_transfer_over_window_approx"] == 20
     # link time booked in total = 10 transfers of 80 ms
     assert math.isclose(sum(r.T), NREQ * 0.080, rel_tol=1e-12)
 
