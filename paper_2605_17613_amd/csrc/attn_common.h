@@ -51,4 +51,43 @@ __device__ __forceinline__ int ceil_div_dev(int a, int b) { return (a + b - 1) /
 // 2^(a - b) that is 0 (not NaN) when a = -inf, whatever b is
 __device__ __forceinline__ float exp2_diff(float a, float b) { return (a == -INFINITY) ? 0.f : exp2f(a - b); }
 
+// ---- LDS accesses by raw LDS byte address, and direct HBM -> LDS loads ----
+typedef uint32_t u32x4v __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2v __attribute__((ext_vector_type(2)));
+typedef short short4v __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) u32x4v lds_u32x4v;
+typedef __attribute__((address_space(3))) u32x2v lds_u32x2v;
+typedef __attribute__((address_space(3))) short4v lds_short4v;
+__device__ __forceinline__ u32x4v lds_load_u32x4(uint32_t addr) {   // ds_read_b128
+  return *reinterpret_cast<const lds_u32x4v*>(static_cast<size_t>(addr));
+}
+__device__ __forceinline__ u32x2v lds_load_u32x2(uint32_t addr) {   // ds_read_b64
+  return *reinterpret_cast<const lds_u32x2v*>(static_cast<size_t>(addr));
+}
+__device__ __forceinline__ uint32_t lds_address(const void* shared_ptr) {
+  return static_cast<uint32_t>(reinterpret_cast<size_t>((const __attribute__((address_space(3))) char*)shared_ptr));
+}
+
+// Direct HBM -> LDS load of 16 bytes per lane: lane i's data lands at lds_addr + 16*i (lds_addr is
+// wave-uniform and travels in M0).  Issued as inline assembly so that the compiler's own wait-count
+// bookkeeping does not force every later LDS read to wait for all loads in flight; the rings built
+// on this wait for exactly the data they are about to read (wait_vm).
+__device__ __forceinline__ void load_to_lds(const uint16_t* gsrc, uint32_t lds_addr) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(lds_addr), "v"(gsrc) : "memory");
+}
+// Same with a wave-uniform 64-bit base plus a 32-bit per-lane byte offset.
+__device__ __forceinline__ void load_to_lds(const uint8_t* gbase_uniform, uint32_t lane_off, uint32_t lds_addr) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+               : : "s"(lds_addr), "v"(lane_off), "s"(gbase_uniform) : "memory");
+}
+
+template <int N_OUTSTANDING>
+__device__ __forceinline__ void wait_vm() {
+  // s_waitcnt with only the vector-memory counter constrained (gfx9 encoding: vmcnt in bits 3:0
+  // and 15:14, expcnt 6:4 and lgkmcnt 11:8 left at "don't wait")
+  __builtin_amdgcn_s_waitcnt((N_OUTSTANDING & 15) | ((N_OUTSTANDING >> 4) << 14) | 0x0F70);
+}
+// every LDS read issued so far has returned (needed before a direct load may overwrite what they read)
+__device__ __forceinline__ void wait_lds_reads() { __builtin_amdgcn_s_waitcnt(0xC07F); }
+
 }  // namespace vc

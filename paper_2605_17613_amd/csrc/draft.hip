@@ -310,11 +310,25 @@ __device__ __forceinline__ void u4_to_arr(const uint4& v, uint32_t (&a)[4]) {
 
 constexpr float kLazyMargin = 4.f;  // the running maximum may lag the true one by this much (log2 units)
 
+// Records travel HBM -> LDS directly, into a private ring of kQuantSlots records per wave, two
+// records ahead of the one being consumed, so that every wave keeps loads in flight while it
+// computes (no barrier: a wave only ever reads what it loaded itself).  The LDS image of a record
+// is the record itself except that the 16-byte chunks of the key codes are permuted into the order
+// the lanes read them (a direct load writes lane i's chunk at position i, so the permutation is a
+// choice of source address and costs nothing):
+//   int4: chunk 64*T + lane           <- key bytes of token 8*(n>>2) + 4*T + (n&3), chunk j
+//   int2: chunk 32*T + 2*n + m        <- key bytes of token 16*(n>>2) + 4*T + (n&3), chunk m
+//         (lane (n, j) then reads the 8 bytes at 512*T + 32*n + 8*j: a linear, conflict-free sweep)
+// (three slots at two workgroups per CU measured 2-3 % slower than two slots at three)
+constexpr int kQuantSlots = 2;
+constexpr int kQuantRingBytes = 4 * kQuantSlots * kRecordBytes;   // per workgroup of 4 waves
+
 template <int BITS>
 __global__ __launch_bounds__(256, 3) void draft_quant_kernel(DraftQuantParams p) {
   constexpr int TB = (BITS == 4) ? 32 : 64;   // tokens per block record
   constexpr int NT = TB / 16;                 // 16-token score tiles per record
   constexpr int NKS = TB / 32;                // 32-token k-steps of the output product per record
+  extern __shared__ __attribute__((aligned(1024))) char ring[];
   const int b = blockIdx.z, sp = blockIdx.x;
   const int kvh = blockIdx.y / p.nquad, quad = blockIdx.y % p.nquad;
   const int nb = p.cu_blk[b + 1] - p.cu_blk[b];
@@ -323,10 +337,40 @@ __global__ __launch_bounds__(256, 3) void draft_quant_kernel(DraftQuantParams p)
   const int blk1 = min(nb, blk0 + p.bps);
   const uint8_t* rec_base =
       p.blocks + (static_cast<size_t>(p.cu_blk[b]) * p.n_kv_heads + static_cast<size_t>(kvh) * nb) * kRecordBytes;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int n = lane & 15, j = lane >> 4;     // n: column / operand row, j: k-block and D row block
   const int slot = n >> 2, hq = n & 3;
   const int G = (BITS == 4) ? slot : (slot & 1);   // value channel group this column carries
+
+  // ---- the ring: source offsets of this lane's five 16-byte chunks, and the request itself ----
+  uint32_t src_key[2];
+#pragma unroll
+  for (int c = 0; c < 2; ++c) {
+    if constexpr (BITS == 4) {
+      src_key[c] = (8 * (n >> 2) + 4 * c + (n & 3)) * 64 + 16 * j;
+    } else {
+      const int T = 2 * c + (lane >> 5), nn = (lane & 31) >> 1, mm = lane & 1;
+      src_key[c] = (16 * (nn >> 2) + 4 * T + (nn & 3)) * 32 + 16 * mm;
+    }
+  }
+  const uint32_t src_lin = 2048 + 16 * lane;
+  const uint32_t ring_base = lds_address(ring) + wave * (kQuantSlots * kRecordBytes);
+  const int nrec = blk1 > blk0 + wave ? (blk1 - blk0 - wave + 3) / 4 : 0;   // records of this wave
+  auto request = [&](int i) {                 // record i of this wave -> ring slot i % kQuantSlots
+    const size_t off = static_cast<size_t>(blk0 + wave + 4 * i) * kRecordBytes;
+    const uint64_t ga = reinterpret_cast<uint64_t>(rec_base) + off;
+    // the address is wave-uniform; readfirstlane (which returns a signed int: widen it unsigned)
+    // tells the compiler so, and the load can take it from scalar registers
+    const uint32_t ga_lo = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(static_cast<uint32_t>(ga))));
+    const uint32_t ga_hi = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(static_cast<uint32_t>(ga >> 32))));
+    const uint8_t* rec = reinterpret_cast<const uint8_t*>((static_cast<uint64_t>(ga_hi) << 32) | static_cast<uint64_t>(ga_lo));
+    const uint32_t dst = ring_base + (i % kQuantSlots) * kRecordBytes;
+    load_to_lds(rec, src_key[0], dst);
+    load_to_lds(rec, src_key[1], dst + 1024);
+    load_to_lds(rec, src_lin, dst + 2048);
+    load_to_lds(rec + 1024, src_lin, dst + 3072);
+    load_to_lds(rec + 2048, src_lin, dst + 4096);
+  };
   const int hloc = quad * 4 + hq;
   const bool head_ok = hloc < p.g;
 
@@ -377,41 +421,68 @@ __global__ __launch_bounds__(256, 3) void draft_quant_kernel(DraftQuantParams p)
 #pragma unroll
   for (int i = 0; i < 16; ++i) qnf[i] = as_u32(as_half2(qn[i]) * as_half2(finv[i & 3]));
 
-  for (int blk = blk0 + wave; blk < blk1; blk += 4) {
-    const uint8_t* rec = rec_base + static_cast<size_t>(blk) * kRecordBytes;
-    // ---------------- loads of the whole record share of this lane ----------------
+  // the query loads above must have landed before the ring starts: a wait for them inside the
+  // loop would also drain the records in flight
+#pragma unroll
+  for (int i = 0; i < 16; ++i) asm volatile("" : "+v"(qn[i]));
+#pragma unroll
+  for (int i = 0; i < kQuantSlots; ++i)
+    if (i < nrec) request(i);
+
+  for (int it = 0; it < nrec; ++it) {
+    // this record has landed once only the younger requests are outstanding
+    const int younger = nrec - 1 - it;
+    if (younger >= kQuantSlots - 1) wait_vm<5 * (kQuantSlots - 1)>();
+    else if (younger == 1) wait_vm<5>();
+    else wait_vm<0>();
+    const uint32_t rec = ring_base + (it % kQuantSlots) * kRecordBytes;
+    // ---------------- this lane's share of the record, LDS -> registers ----------------
     uint32_t kw[NT][BITS == 4 ? 4 : 2];
 #pragma unroll
     for (int T = 0; T < NT; ++T) {
       // tile row m = n is token (TB/4)*(m>>2) + 4*T + (m&3) of the block
-      const int tok = (TB / 4) * (n >> 2) + 4 * T + (n & 3);
       if constexpr (BITS == 4) {
-        const uint4 v = *reinterpret_cast<const uint4*>(rec + tok * 64 + 16 * j);
-        kw[T][0] = v.x; kw[T][1] = v.y; kw[T][2] = v.z; kw[T][3] = v.w;
+        const u32x4v v = lds_load_u32x4(rec + (64 * T + lane) * 16);
+        kw[T][0] = v[0]; kw[T][1] = v[1]; kw[T][2] = v[2]; kw[T][3] = v[3];
       } else {
-        const uint2 v = *reinterpret_cast<const uint2*>(rec + tok * 32 + 8 * j);
-        kw[T][0] = v.x; kw[T][1] = v.y;
+        const u32x2v v = lds_load_u32x2(rec + 512 * T + 32 * n + 8 * j);
+        kw[T][0] = v[0]; kw[T][1] = v[1];
       }
     }
     uint32_t ksc[16], kzr[16];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const uint4 s4 = *reinterpret_cast<const uint4*>(rec + 4096 + 64 * j + 16 * i);
-      const uint4 z4 = *reinterpret_cast<const uint4*>(rec + 4096 + 256 + 64 * j + 16 * i);
-      ksc[4 * i] = s4.x; ksc[4 * i + 1] = s4.y; ksc[4 * i + 2] = s4.z; ksc[4 * i + 3] = s4.w;
-      kzr[4 * i] = z4.x; kzr[4 * i + 1] = z4.y; kzr[4 * i + 2] = z4.z; kzr[4 * i + 3] = z4.w;
+      const u32x4v s4 = lds_load_u32x4(rec + 4096 + 64 * j + 16 * i);
+      const u32x4v z4 = lds_load_u32x4(rec + 4096 + 256 + 64 * j + 16 * i);
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        ksc[4 * i + k] = s4[k];
+        kzr[4 * i + k] = z4[k];
+      }
     }
     uint32_t vsl[2][4];
 #pragma unroll
-    for (int c = 0; c < 2; ++c) u4_to_arr(*reinterpret_cast<const uint4*>(rec + 2048 + (64 * c + lane) * 16), vsl[c]);
+    for (int c = 0; c < 2; ++c) {
+      const u32x4v v = lds_load_u32x4(rec + 2048 + (64 * c + lane) * 16);
+#pragma unroll
+      for (int k = 0; k < 4; ++k) vsl[c][k] = v[k];
+    }
     uint32_t vsc[NKS][4], vzr[NKS][4];
 #pragma unroll
     for (int a = 0; a < NKS; ++a) {
       // value scale / zero of channel group G for the 8 tokens (TB/4)*j + 8a .. +7
       const int off = 2 * (G * TB + (TB / 4) * j + 8 * a);
-      u4_to_arr(*reinterpret_cast<const uint4*>(rec + 4608 + off), vsc[a]);
-      u4_to_arr(*reinterpret_cast<const uint4*>(rec + 4608 + 256 + off), vzr[a]);
+      const u32x4v sv = lds_load_u32x4(rec + 4608 + off);
+      const u32x4v zv = lds_load_u32x4(rec + 4608 + 256 + off);
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        vsc[a][k] = sv[k];
+        vzr[a][k] = zv[k];
+      }
     }
+    // the slot is free once those reads have returned: request the record kQuantSlots ahead
+    wait_lds_reads();
+    if (it + kQuantSlots < nrec) request(it + kQuantSlots);
 
     // ---------------- scores ----------------
     uint32_t qf[16], qz[16];
@@ -860,8 +931,8 @@ extern "C" vc_status vc_draft_attn(vc_ctx* ctx, const vc_comp_kv* kv, const void
     qp.bps = pl.bps; qp.slot0 = pl.s1; qp.ns = pl.ns;
     qp.scale_log2e = sl2;
     dim3 grid(pl.s2, kv->n_kv_heads * qp.nquad, kv->n_seqs);
-    if (kv->bits == 4) hipLaunchKernelGGL(draft_quant_kernel<4>, grid, dim3(256), 0, st, qp);
-    else hipLaunchKernelGGL(draft_quant_kernel<2>, grid, dim3(256), 0, st, qp);
+    if (kv->bits == 4) hipLaunchKernelGGL(draft_quant_kernel<4>, grid, dim3(256), kQuantRingBytes, st, qp);
+    else hipLaunchKernelGGL(draft_quant_kernel<2>, grid, dim3(256), kQuantRingBytes, st, qp);
   }
   mark_end(ctx, st);
   DraftMergeParams mp{};

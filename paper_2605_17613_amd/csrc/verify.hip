@@ -50,15 +50,8 @@ __device__ __forceinline__ bf16x8v load_bf16x8(const uint16_t* p) {
   return r;
 }
 
-// LDS accesses by raw LDS byte address
-typedef uint32_t u32x4v __attribute__((ext_vector_type(4)));
-typedef short short4v __attribute__((ext_vector_type(4)));
-typedef short short8v __attribute__((ext_vector_type(8)));
-typedef __attribute__((address_space(3))) u32x4v lds_u32x4v;
-typedef __attribute__((address_space(3))) short4v lds_short4v;
 __device__ __forceinline__ bf16x8v lds_load_bf16x8(uint32_t addr) {   // ds_read_b128
-  const u32x4v raw = *reinterpret_cast<const lds_u32x4v*>(static_cast<size_t>(addr));
-  return __builtin_bit_cast(bf16x8v, raw);
+  return __builtin_bit_cast(bf16x8v, lds_load_u32x4(addr));
 }
 // Transposing LDS read: the 16 lanes of a block fetch a 4 x 16 patch of 16-bit values (lane 4k+c:
 // row k, columns 4c..4c+3) and lane i of the block receives column i of the patch (4 rows).
@@ -73,21 +66,6 @@ __device__ __forceinline__ short4v lds_read_tr(uint32_t addr) {
 // patch put their two adjacent chunks on eight different positions (V operand reads).
 __device__ __forceinline__ int rot_row(int row) { return ((row << 1) & 14) | ((row >> 3) & 1); }
 __device__ __forceinline__ int swz(int row, int chunk) { return row * 256 + ((chunk ^ rot_row(row)) << 4); }
-
-// Direct HBM -> LDS load of 16 bytes per lane: lane i's data lands at lds_addr + 16*i (lds_addr is
-// wave-uniform and travels in M0).  Issued as inline assembly so that the compiler's own wait-count
-// bookkeeping does not force every later LDS read to wait for all tiles in flight; the ring below
-// waits for exactly the tile it is about to read.
-__device__ __forceinline__ void load_to_lds(const uint16_t* gsrc, uint32_t lds_addr) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(lds_addr), "v"(gsrc) : "memory");
-}
-
-template <int N_OUTSTANDING>
-__device__ __forceinline__ void wait_vm() {
-  // s_waitcnt with only the vector-memory counter constrained (gfx9 encoding: vmcnt in bits 3:0
-  // and 15:14, expcnt 6:4 and lgkmcnt 11:8 left at "don't wait")
-  __builtin_amdgcn_s_waitcnt((N_OUTSTANDING & 15) | ((N_OUTSTANDING >> 4) << 14) | 0x0F70);
-}
 
 // One wave owns RT row tiles of 32 rows and, of every LDS tile, one 32-token slice.  With RT = 2
 // every K and V^T operand read from LDS feeds two matrix instructions, which halves the LDS
