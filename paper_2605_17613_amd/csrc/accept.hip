@@ -92,8 +92,15 @@ __global__ void accept_finish_kernel(const unsigned long long* __restrict__ keys
   }
 }
 
-// keep = [0, len) minus dropped: position p is kept iff it is not in the (ascending) dropped list;
-// its rank among the kept ones is p minus the number of dropped positions below it.
+// keep = [0, len) minus dropped.  A workgroup owns kKeepSpan consecutive positions [p0, p1) of one
+// list: one binary search finds the first dropped entry >= p0 (every thread walks the same path, so
+// the loads are broadcasts); the at most kKeepSpan entries that can fall below p1 are then read
+// coalesced and set bits in an LDS bitmap; a position's rank among the kept ones is p0 minus the
+// entries below p0, plus the kept positions before it in the span (workgroup prefix sum), so the
+// dropped list is streamed once and the kept list is written in order.
+constexpr int kKeepPerThread = 16;
+constexpr int kKeepSpan = 256 * kKeepPerThread;
+
 __global__ __launch_bounds__(256) void keep_from_dropped_kernel(const int* __restrict__ dropped,
                                                                 const int* __restrict__ cu_drop,
                                                                 const int* __restrict__ cu_ctx, int n_kv_heads,
@@ -106,17 +113,49 @@ __global__ __launch_bounds__(256) void keep_from_dropped_kernel(const int* __res
     cu_keep[b] = keep_base;
     if (b == gridDim.z - 1) cu_keep[b + 1] = keep_base + len - nd;
   }
-  const int p = blockIdx.x * 256 + threadIdx.x;
-  if (p >= len) return;
+  const int p0 = blockIdx.x * kKeepSpan;
+  if (p0 >= len) return;
+  const int p1 = min(len, p0 + kKeepSpan);
   const int nk = len - nd;
   const int* dl = dropped + (static_cast<size_t>(cu_drop[b]) * n_kv_heads + static_cast<size_t>(h) * nd);
-  int lo = 0, hi = nd;  // lower bound: first entry >= p
+  int lo = 0, hi = nd;  // lower bound: first entry >= p0
   while (lo < hi) {
-    int mid = (lo + hi) >> 1;
-    if (dl[mid] < p) lo = mid + 1; else hi = mid;
+    const int mid = (lo + hi) >> 1;
+    if (dl[mid] < p0) lo = mid + 1; else hi = mid;
   }
-  if (lo < nd && dl[lo] == p) return;  // dropped
-  keep_idx[static_cast<size_t>(keep_base) * n_kv_heads + static_cast<size_t>(h) * nk + (p - lo)] = p;
+  __shared__ uint32_t bits[kKeepSpan / 32];
+  __shared__ int wave_total[4];
+  if (threadIdx.x < kKeepSpan / 32) bits[threadIdx.x] = 0u;
+  __syncthreads();
+  for (int i = threadIdx.x; i < kKeepSpan && lo + i < nd; i += 256) {
+    const int v = dl[lo + i];
+    if (v < p1) atomicOr(&bits[(v - p0) >> 5], 1u << ((v - p0) & 31));
+  }
+  __syncthreads();
+  // thread t owns positions p0 + 16t .. p0 + 16t + 15
+  const int q0 = p0 + kKeepPerThread * threadIdx.x;
+  uint32_t mask = (bits[threadIdx.x >> 1] >> (16 * (threadIdx.x & 1))) & 0xFFFFu;   // 1 = dropped
+  const int valid = min(kKeepPerThread, max(0, p1 - q0));
+  uint32_t kept = ~mask & ((1u << valid) - 1u);
+  const int cnt = __popc(kept);
+  // exclusive prefix sum of cnt over the workgroup
+  int incl = cnt;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const int o = __shfl_up(incl, off, 64);
+    if (lane >= off) incl += o;
+  }
+  if (lane == 63) wave_total[wave] = incl;
+  __syncthreads();
+  int before = incl - cnt;
+  for (int w = 0; w < wave; ++w) before += wave_total[w];
+  int* out = keep_idx + (static_cast<size_t>(keep_base) * n_kv_heads + static_cast<size_t>(h) * nk) + (p0 - lo) + before;
+  while (kept) {
+    const int e = __ffs(kept) - 1;
+    kept &= kept - 1;
+    *out++ = q0 + e;
+  }
 }
 
 }  // namespace vc
@@ -171,7 +210,7 @@ extern "C" vc_status vc_keep_from_dropped(vc_ctx* ctx, const int32_t* dropped, c
   VC_REQUIRE(cu_drop && cu_ctx && cu_keep, VC_ERR_INVALID_ARG, "vc_keep_from_dropped: NULL cu array");
   VC_REQUIRE(max_ctx == 0 || keep_idx, VC_ERR_INVALID_ARG, "vc_keep_from_dropped: keep_idx is NULL");
   VC_REQUIRE(n_seqs <= 65535 && n_kv_heads <= 65535, VC_ERR_UNSUPPORTED, "vc_keep_from_dropped: grid too large");
-  dim3 grid(max_ctx > 0 ? ceil_div(max_ctx, 256) : 1, n_kv_heads, n_seqs);
+  dim3 grid(max_ctx > 0 ? ceil_div(max_ctx, kKeepSpan) : 1, n_kv_heads, n_seqs);
   hipLaunchKernelGGL(keep_from_dropped_kernel, grid, dim3(256), 0, static_cast<hipStream_t>(stream), dropped, cu_drop,
                      cu_ctx, n_kv_heads, keep_idx, cu_keep);
   VC_HIP(hipGetLastError());
