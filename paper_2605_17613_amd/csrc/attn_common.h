@@ -81,13 +81,20 @@ __device__ __forceinline__ void load_to_lds(const uint8_t* gbase_uniform, uint32
                : : "s"(lds_addr), "v"(lane_off), "s"(gbase_uniform) : "memory");
 }
 
+// Same, four bytes per lane: lane i's word lands at lds_addr + 4*i.
+__device__ __forceinline__ void load_to_lds_b32(const int* gsrc, uint32_t lds_addr) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, off" : : "s"(lds_addr), "v"(gsrc) : "memory");
+}
+
+// Wait until at most N_OUTSTANDING vector-memory operations of this wave are in flight (they
+// complete in order, so everything older has landed).  A compiler-level memory barrier as well:
+// no LDS read may move above the wait that makes its data valid.
 template <int N_OUTSTANDING>
 __device__ __forceinline__ void wait_vm() {
-  // s_waitcnt with only the vector-memory counter constrained (gfx9 encoding: vmcnt in bits 3:0
-  // and 15:14, expcnt 6:4 and lgkmcnt 11:8 left at "don't wait")
-  __builtin_amdgcn_s_waitcnt((N_OUTSTANDING & 15) | ((N_OUTSTANDING >> 4) << 14) | 0x0F70);
+  static_assert(N_OUTSTANDING >= 0 && N_OUTSTANDING < 64, "vmcnt is a 6-bit counter");
+  asm volatile("s_waitcnt vmcnt(%0)" : : "n"(N_OUTSTANDING) : "memory");
 }
 // every LDS read issued so far has returned (needed before a direct load may overwrite what they read)
-__device__ __forceinline__ void wait_lds_reads() { __builtin_amdgcn_s_waitcnt(0xC07F); }
+__device__ __forceinline__ void wait_lds_reads() { asm volatile("s_waitcnt lgkmcnt(0)" : : : "memory"); }
 
 }  // namespace vc

@@ -27,39 +27,44 @@ struct DraftBf16Params {
   float scale_log2e;
 };
 
-// Lane layout: 16 lanes share one token row (lane c holds channels 8c..8c+7), so one wave load
-// instruction fetches four 256-byte rows; a wave step covers 16 tokens (4 per 16-lane slot).
-// Arithmetic stays in packed bf16 pairs: scores are v_dot2 over (q, k) pairs reduced across the 16
-// lanes with DPP adds; the output is v_dot2 over token pairs (values of two tokens interleaved with
-// one byte-permute per pair, probabilities rounded to bf16).  Indices are fetched two steps ahead
-// and rows one step ahead of their use.
-typedef __bf16 bf16x2v __attribute__((ext_vector_type(2)));
+// Formulation (bf16 MFMA 16x16x32, fp32 accumulation), per step of 32 tokens of one wave:
+//   S^T[token][head]  = K[token][:] . Q[head][:]          A = K rows from LDS, B = Q^T (registers)
+//   O^T[d][head]     += V^T[d][token] * P[token][head]    A = V^T through the transposing LDS read
+// The columns are the (up to 16) query heads of the KV head, so GQA packing is the tile's N
+// dimension; the D layout of the first product hands every lane 4 tokens of one head per 16-token
+// tile, and the 8 tokens a lane gets from the two tiles of a step are taken as its k-slots of the
+// second product (token 16*(e/4) + 4*j + e%4 for slot e of lane block j) - the transposing reads
+// fetch V in that same order, so probabilities never cross lanes.
+//
+// Rows travel HBM -> LDS directly: every wave owns a ring of two 32-token stages (K rows, then V
+// rows, 256 bytes each) and requests the stage two steps ahead as soon as it has read the current
+// one, so there is no barrier and loads stay in flight while the wave computes.  The 16-byte chunk
+// c of row r is stored at chunk position c ^ (r & 15): the 16 rows an operand read touches then
+// sit in 16 different bank groups.  Kept positions are streamed the same way (a ring of four
+// 32-entry index stages per wave), so every load of the loop is accounted for in one wait counter.
+constexpr float kLazyMargin = 4.f;  // the running maximum may lag the true one by this much (log2 units)
+constexpr int kRowsIdxStage = 256;                              // 64 lanes x 4 bytes (one step's entries, mirrored)
+constexpr int rows_wave_lds(int step) { return 2 * step * 512 + 4 * kRowsIdxStage; }   // two stages + index ring
+constexpr int rows_lds(int step, int nw) { return nw * rows_wave_lds(step); }
 
-__device__ __forceinline__ float dot2_bf16(uint32_t a, uint32_t b, float c) {
-  return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2v, a), __builtin_bit_cast(bf16x2v, b), c, false);
+__device__ __forceinline__ float4v mfma16_bf16(bf16x8v a, bf16x8v b, float4v c) {
+  return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
 }
-template <int CTRL>
-__device__ __forceinline__ float dpp_add(float v) {
-  const int moved = __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xF, 0xF, true);
-  return v + __builtin_bit_cast(float, moved);
-}
-// sum over the 16 lanes of a DPP row, result in every lane
-__device__ __forceinline__ float row_sum16(float v) {
-  v = dpp_add<0xB1>(v);    // quad_perm [1,0,3,2]
-  v = dpp_add<0x4E>(v);    // quad_perm [2,3,0,1]
-  v = dpp_add<0x124>(v);   // row_ror 4
-  v = dpp_add<0x128>(v);   // row_ror 8
-  return v;
-}
-__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
-  bf16x2v r;
-  r[0] = (__bf16)lo;
-  r[1] = (__bf16)hi;
-  return __builtin_bit_cast(uint32_t, r);
+__device__ __forceinline__ uint32_t rows_lds_off(int row, int chunk) { return row * 256 + ((chunk ^ (row & 15)) << 4); }
+
+__device__ __forceinline__ float4v mfma16_bf16_k16(short4v a, short4v b, float4v c) {
+  return __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(a, b, c, 0, 0, 0);
 }
 
-template <int GP, bool GATHER>
-__global__ __launch_bounds__(256) void draft_bf16_kernel(DraftBf16Params p) {
+// kRowsStep: tokens per step (32: the second product is one 16x16x32 per output tile; 16: one
+// 16x16x16, whose k-slots are exactly the 4 tokens a lane holds); NW: waves per workgroup.
+template <bool GATHER, int kRowsStep, int NW>
+__global__ __launch_bounds__(NW * 64, 1) void draft_bf16_kernel(DraftBf16Params p) {
+  constexpr int kRowsStage = kRowsStep * 512;                   // K rows then V rows
+  constexpr int kRowsWaveLds = rows_wave_lds(kRowsStep);
+  constexpr int NT = kRowsStep / 16;                            // 16-token score tiles per step
+  constexpr int NLD = kRowsStep / 4;                            // wave loads per matrix per step
+  extern __shared__ __attribute__((aligned(1024))) char ring[];
   const int b = blockIdx.z, kvh = blockIdx.y, sp = blockIdx.x;
   const int row0 = p.cu_rows[b];
   const int count = GATHER ? (p.cu_keep[b + 1] - p.cu_keep[b]) : (p.cu_rows[b + 1] - row0);
@@ -68,157 +73,202 @@ __global__ __launch_bounds__(256) void draft_bf16_kernel(DraftBf16Params p) {
   const int end = min(count, start + p.split_tok);
   const int* idx = GATHER ? p.keep_idx + (static_cast<size_t>(p.cu_keep[b]) * p.n_kv_heads + static_cast<size_t>(kvh) * count)
                           : nullptr;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int c = lane & 15, ts = lane >> 4;
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int n = lane & 15, j = lane >> 4;     // n: head column / operand row, j: k-block and D row block
+  const int hn = min(n, p.g - 1);             // columns beyond the group replicate its last head (never stored)
 
-  uint32_t qpk[GP][4];                        // query, channels 8c..8c+7 as bf16 pairs (unscaled, exact)
+  // query as B operand: k-step ks covers channels 32ks .. 32ks+31, this lane holds 32ks + 8j .. +7
+  bf16x8v qb[4];
+  {
+    const uint16_t* qp = p.q + (static_cast<size_t>(b) * p.n_q_heads + kvh * p.g + hn) * kHeadDim + 8 * j;
 #pragma unroll
-  for (int hq = 0; hq < GP; ++hq) {
-    uint4 raw = {0u, 0u, 0u, 0u};
-    if (hq < p.g)
-      raw = *reinterpret_cast<const uint4*>(p.q + (static_cast<size_t>(b) * p.n_q_heads + kvh * p.g + hq) * kHeadDim + 8 * c);
-    qpk[hq][0] = raw.x; qpk[hq][1] = raw.y; qpk[hq][2] = raw.z; qpk[hq][3] = raw.w;
+    for (int ks = 0; ks < 4; ++ks) {
+      const uint4 raw = *reinterpret_cast<const uint4*>(qp + 32 * ks);
+      qb[ks] = __builtin_bit_cast(bf16x8v, raw);
+    }
   }
-
-  float m[GP], l[GP], o[GP][8];
+  // the query loads must have landed before the ring starts (a wait for them inside the loop
+  // would also drain the rows in flight)
 #pragma unroll
-  for (int hq = 0; hq < GP; ++hq) {
-    m[hq] = kNoKeyYet;
-    l[hq] = 0.f;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) o[hq][e] = 0.f;
-  }
+  for (int ks = 0; ks < 4; ++ks) asm volatile("" : "+v"(qb[ks]));
 
-  const size_t head_off = static_cast<size_t>(kvh) * kHeadDim + 8 * c;
   const size_t row_stride = static_cast<size_t>(p.n_kv_heads) * kHeadDim;
-  const uint16_t* kbase = p.pk + static_cast<size_t>(row0) * row_stride + head_off;
-  const uint16_t* vbase = p.pv + static_cast<size_t>(row0) * row_stride + head_off;
+  const uint16_t* kbase = p.pk + static_cast<size_t>(row0) * row_stride + static_cast<size_t>(kvh) * kHeadDim;
+  const uint16_t* vbase = p.pv + static_cast<size_t>(row0) * row_stride + static_cast<size_t>(kvh) * kHeadDim;
+  const uint16_t* dummy = p.q + static_cast<size_t>(b) * p.n_q_heads * kHeadDim;   // any valid 16 bytes
 
-  // token of (step t0, sub-step u) for this lane's slot, clamped into the split
-  auto token_of = [&](int t0, int u) { return min(t0 + u * 4 + ts, end - 1); };
-  auto load_idx = [&](int t0, int (&r)[4]) {
-#pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      const int tok = token_of(t0, u);
-      r[u] = GATHER ? idx[tok] : tok;
+  // steps of this wave: step `it` covers tokens tok0(it) .. tok0(it) + 31 of the list
+  auto tok0 = [&](int it) { return start + kRowsStep * (wave + NW * it); };
+  const int nst = end > start + kRowsStep * wave ? (end - start - kRowsStep * wave + NW * kRowsStep - 1) / (NW * kRowsStep) : 0;
+  const uint32_t wave_lds = lds_address(ring) + wave * kRowsWaveLds;
+  const uint32_t idx_lds = wave_lds + 2 * kRowsStage;
+  const int ts = lane >> 4, c = lane & 15;    // direct loads: 16 lanes per row, lane c brings one 16-byte chunk
+
+  auto request_idx = [&](int it) {            // kept positions of step `it` -> index stage it % 4 (one load)
+    if constexpr (GATHER) {
+      const int t = it < nst ? min(tok0(it) + (lane & (kRowsStep - 1)), end - 1) : end - 1;
+      load_to_lds_b32(idx + t, idx_lds + (it & 3) * kRowsIdxStage);
     }
   };
-  auto load_rows = [&](const int (&r)[4], uint4 (&kk)[4], uint4 (&vv)[4]) {
+  auto request_rows = [&](int it) {           // rows of step `it` -> stage it % 2 (16 loads, real or dummy)
+    const uint32_t stage = wave_lds + (it & 1) * kRowsStage;
+    if (it < nst) {
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      const size_t off = static_cast<size_t>(r[u]) * row_stride;
-      kk[u] = *reinterpret_cast<const uint4*>(kbase + off);
-      vv[u] = *reinterpret_cast<const uint4*>(vbase + off);
+      for (int i = 0; i < NLD; ++i) {
+        const int r = 4 * i + ts;             // row of the stage
+        int row;
+        if constexpr (GATHER) {
+          row = *reinterpret_cast<const __attribute__((address_space(3))) int*>(
+              static_cast<size_t>(idx_lds + (it & 3) * kRowsIdxStage + 4 * r));
+        } else {
+          row = min(tok0(it) + r, end - 1);
+        }
+        const size_t off = static_cast<size_t>(row) * row_stride + 8 * (c ^ (r & 15));
+        load_to_lds(kbase + off, stage + i * 1024);
+        load_to_lds(vbase + off, stage + kRowsStep * 256 + i * 1024);
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < 2 * NLD; ++i) load_to_lds(dummy, stage + i * 1024);
     }
   };
 
-  const int first = start + wave * 16;
-  int rcur[4], rnext[4];
-  uint4 kk[4], vv[4];
-  if (first < end) {
-    load_idx(first, rcur);
-    load_idx(min(first + 64, end - 1), rnext);
-    load_rows(rcur, kk, vv);
-  }
-  for (int t0 = first; t0 < end; t0 += 64) {
-    // rows of the next step (their indices arrived during the previous step), indices of the one after
-    uint4 kn[4], vn[4];
-    const bool has_next = t0 + 64 < end;
-    if (has_next) {
-      load_rows(rnext, kn, vn);
-      load_idx(min(t0 + 128, end - 1), rnext);
-    }
-    // ---- scores of the 4 tokens of this slot ----
-    float s[4][GP];
+  // LDS read offsets of this lane inside a stage
+  uint32_t kaddr[NT][4];                      // K operand: row 16T + n, chunk 4ks + j
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      const uint32_t w[4] = {kk[u].x, kk[u].y, kk[u].z, kk[u].w};
-      const bool valid = t0 + u * 4 + ts < end;
+  for (int T = 0; T < NT; ++T)
 #pragma unroll
-      for (int hq = 0; hq < GP; ++hq) {
-        float a = 0.f;
+    for (int ks = 0; ks < 4; ++ks) kaddr[T][ks] = rows_lds_off(16 * T + n, 4 * ks + j);
+  // transposing read: lane L of block j addresses row 4j + L/4 (+16), 8 bytes at channel 16dt + 4(L%4)
+  uint32_t vaddr[8][NT];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) a = dot2_bf16(qpk[hq][i], w[i], a);
-        a = row_sum16(a);
-        s[u][hq] = valid ? a * p.scale_log2e : -INFINITY;
-      }
-    }
-    // ---- online softmax per slot, output by token pairs ----
-    uint32_t ve[2][4], vo[2][4];              // values of token pairs (0,1), (2,3): even / odd channels interleaved
+  for (int dt = 0; dt < 8; ++dt)
 #pragma unroll
-    for (int pr = 0; pr < 2; ++pr) {
-      const uint32_t wa[4] = {vv[2 * pr].x, vv[2 * pr].y, vv[2 * pr].z, vv[2 * pr].w};
-      const uint32_t wb[4] = {vv[2 * pr + 1].x, vv[2 * pr + 1].y, vv[2 * pr + 1].z, vv[2 * pr + 1].w};
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        ve[pr][i] = __builtin_amdgcn_perm(wb[i], wa[i], 0x05040100u);   // (a.lo, b.lo): channel 2i of both tokens
-        vo[pr][i] = __builtin_amdgcn_perm(wb[i], wa[i], 0x07060302u);   // (a.hi, b.hi): channel 2i+1
-      }
-    }
-#pragma unroll
-    for (int hq = 0; hq < GP; ++hq) {
-      const float mn = fmaxf(fmaxf(m[hq], fmaxf(s[0][hq], s[1][hq])), fmaxf(s[2][hq], s[3][hq]));
-      const float alpha = __builtin_amdgcn_exp2f(m[hq] - mn);
-      float pu[4];
-#pragma unroll
-      for (int u = 0; u < 4; ++u) pu[u] = __builtin_amdgcn_exp2f(s[u][hq] - mn);
-      l[hq] = l[hq] * alpha + (pu[0] + pu[1]) + (pu[2] + pu[3]);
-      const uint32_t p01 = pack_bf16x2(pu[0], pu[1]), p23 = pack_bf16x2(pu[2], pu[3]);
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        float e0 = o[hq][2 * i] * alpha, e1 = o[hq][2 * i + 1] * alpha;
-        e0 = dot2_bf16(ve[0][i], p01, e0);
-        e1 = dot2_bf16(vo[0][i], p01, e1);
-        e0 = dot2_bf16(ve[1][i], p23, e0);
-        e1 = dot2_bf16(vo[1][i], p23, e1);
-        o[hq][2 * i] = e0;
-        o[hq][2 * i + 1] = e1;
-      }
-      m[hq] = mn;
-    }
-    if (has_next) {
-#pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        kk[u] = kn[u];
-        vv[u] = vn[u];
-      }
-    }
-  }
+    for (int h2 = 0; h2 < NT; ++h2)
+      vaddr[dt][h2] = kRowsStep * 256 + rows_lds_off(16 * h2 + 4 * j + (n >> 2), 2 * dt + ((n & 3) >> 1)) + 8 * (n & 1);
 
-  // merge the four 16-lane slots of the wave, then the four waves through LDS
-  __shared__ float st[4][GP][kPartialFloats];
+  float m_run = kNoKeyYet;                    // running maximum of this column's head (log2 domain)
+  float l_part = 0.f;                         // this lane's share of sum 2^(s - m_run)
+  float4v oacc[8];
 #pragma unroll
-  for (int hq = 0; hq < GP; ++hq) {
-    float mw = fmaxf(m[hq], __shfl_xor(m[hq], 16, 64));
-    mw = fmaxf(mw, __shfl_xor(mw, 32, 64));
-    const float a = __builtin_amdgcn_exp2f(m[hq] - mw);
-    float lw = l[hq] * a;
-    lw += __shfl_xor(lw, 16, 64);
-    lw += __shfl_xor(lw, 32, 64);
+  for (int dt = 0; dt < 8; ++dt) oacc[dt] = float4v{0.f, 0.f, 0.f, 0.f};
+
+  // prologue, in the issue order the loop's wait counts assume:
+  // idx(0) idx(1) | rows(0) idx(2) | rows(1)
+  constexpr int kYounger = 2 * NLD + (GATHER ? 1 : 0);   // loads issued after the rows of a step, before its use
+  request_idx(0);
+  request_idx(1);
+  if constexpr (GATHER) wait_vm<1>();
+  request_rows(0);
+  request_idx(2);
+  if constexpr (GATHER) wait_vm<kYounger>();
+  request_rows(1);
+
+  for (int it = 0; it < nst; ++it) {
+    wait_vm<kYounger>();                      // rows(it) have landed
+    const uint32_t stage = wave_lds + (it & 1) * kRowsStage;
+    // ---------------- scores ----------------
+    float4v sacc[NT];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      float x = o[hq][e] * a;
-      x += __shfl_xor(x, 16, 64);
-      x += __shfl_xor(x, 32, 64);
-      if (ts == 0) st[wave][hq][2 + 8 * c + e] = x;
+    for (int T = 0; T < NT; ++T) {
+      sacc[T] = float4v{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) {
+        const bf16x8v a = __builtin_bit_cast(bf16x8v, lds_load_u32x4(stage + kaddr[T][ks]));
+        sacc[T] = mfma16_bf16(a, qb[ks], sacc[T]);
+      }
     }
-    if (lane == 0) {
-      st[wave][hq][0] = mw;
-      st[wave][hq][1] = lw;
+    // register i of tile T is token 16T + 4j + i of the step, for head column n
+    const int tbase = tok0(it) + 4 * j;
+    float smax = -INFINITY;
+#pragma unroll
+    for (int T = 0; T < NT; ++T)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const bool valid = tbase + 16 * T + i < end;
+        sacc[T][i] = valid ? sacc[T][i] * p.scale_log2e : -INFINITY;
+        smax = fmaxf(smax, sacc[T][i]);
+      }
+    if (__any(smax > m_run + kLazyMargin)) {
+      float mx = fmaxf(smax, __shfl_xor(smax, 16, 64));   // the four row blocks of this head
+      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      const float mn = fmaxf(m_run, mx);
+      const float alpha = __builtin_amdgcn_exp2f(m_run - mn);
+      l_part *= alpha;
+#pragma unroll
+      for (int dt = 0; dt < 8; ++dt) oacc[dt] *= alpha;
+      m_run = mn;
+    }
+    float pe[4 * NT];
+#pragma unroll
+    for (int e = 0; e < 4 * NT; ++e) {
+      pe[e] = __builtin_amdgcn_exp2f(sacc[e >> 2][e & 3] - m_run);
+      l_part += pe[e];
+    }
+    // ---------------- output ----------------
+    if constexpr (NT == 2) {
+      bf16x8v pb;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) pb[e] = (__bf16)pe[e];
+#pragma unroll
+      for (int dt = 0; dt < 8; ++dt) {
+        const short4v lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(reinterpret_cast<lds_short4v*>(static_cast<size_t>(stage + vaddr[dt][0])));
+        const short4v hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(reinterpret_cast<lds_short4v*>(static_cast<size_t>(stage + vaddr[dt][1])));
+        const bf16x8v av = __builtin_bit_cast(bf16x8v, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+        oacc[dt] = mfma16_bf16(av, pb, oacc[dt]);
+      }
+    } else {
+      typedef __bf16 bf16x4v __attribute__((ext_vector_type(4)));
+      bf16x4v pb4;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) pb4[e] = (__bf16)pe[e];
+      const short4v pbs = __builtin_bit_cast(short4v, pb4);
+#pragma unroll
+      for (int dt = 0; dt < 8; ++dt) {
+        const short4v av = __builtin_amdgcn_ds_read_tr16_b64_v4i16(reinterpret_cast<lds_short4v*>(static_cast<size_t>(stage + vaddr[dt][0])));
+        oacc[dt] = mfma16_bf16_k16(av, pbs, oacc[dt]);
+      }
+    }
+    // the stage is free once those reads have returned: request the rows two steps ahead
+    wait_lds_reads();
+    request_idx(it + 3);
+    if constexpr (GATHER) wait_vm<kYounger>();   // idx(it + 2) has landed (younger: rows(it + 1), idx(it + 3))
+    request_rows(it + 2);
+  }
+  wait_vm<0>();                               // nothing may land in the ring any more: it is reused below
+
+  // ---------------- end of split: wave state -> LDS -> merged partial ----------------
+  float* st = reinterpret_cast<float*>(ring);                 // [wave][head][kPartialFloats], wave-private part first
+  constexpr int kWaveFloats = kRowsWaveLds / 4;
+  {
+    float lsum = l_part + __shfl_xor(l_part, 16, 64);
+    lsum += __shfl_xor(lsum, 32, 64);
+    if (n < p.g) {
+      float* mine = st + wave * kWaveFloats + n * kPartialFloats;
+      if (j == 0) {
+        mine[0] = m_run;
+        mine[1] = lsum;
+      }
+#pragma unroll
+      for (int dt = 0; dt < 8; ++dt)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) mine[2 + 16 * dt + 4 * j + i] = oacc[dt][i];
     }
   }
   __syncthreads();
   const int slot = p.slot0 + sp;
-  for (int i = threadIdx.x; i < GP * kHeadDim; i += 256) {
+  for (int i = threadIdx.x; i < p.g * kHeadDim; i += NW * 64) {
     const int hq = i >> 7, d = i & 127;
-    if (hq >= p.g) continue;
-    float mm = fmaxf(fmaxf(st[0][hq][0], st[1][hq][0]), fmaxf(st[2][hq][0], st[3][hq][0]));
+    const float* s0 = st + hq * kPartialFloats;
+    float mm = s0[0];
+#pragma unroll
+    for (int w = 1; w < NW; ++w) mm = fmaxf(mm, s0[w * kWaveFloats]);
     float acc = 0.f, lsum = 0.f;
 #pragma unroll
-    for (int w = 0; w < 4; ++w) {
-      const float a = __builtin_amdgcn_exp2f(st[w][hq][0] - mm);
-      acc = fmaf(a, st[w][hq][2 + d], acc);
-      lsum = fmaf(a, st[w][hq][1], lsum);
+    for (int w = 0; w < NW; ++w) {
+      const float a = __builtin_amdgcn_exp2f(s0[w * kWaveFloats] - mm);
+      acc = fmaf(a, s0[w * kWaveFloats + 2 + d], acc);
+      lsum = fmaf(a, s0[w * kWaveFloats + 1], lsum);
     }
     float* dst = p.ws + ((static_cast<size_t>(b) * p.n_q_heads + kvh * p.g + hq) * p.ns + slot) * kPartialFloats;
     dst[2 + d] = acc;
@@ -308,7 +358,6 @@ __device__ __forceinline__ void u4_to_arr(const uint4& v, uint32_t (&a)[4]) {
   a[0] = v.x; a[1] = v.y; a[2] = v.z; a[3] = v.w;
 }
 
-constexpr float kLazyMargin = 4.f;  // the running maximum may lag the true one by this much (log2 units)
 
 // Records travel HBM -> LDS directly, into a private ring of kQuantSlots records per wave, two
 // records ahead of the one being consumed, so that every wave keeps loads in flight while it
@@ -815,10 +864,10 @@ static DraftPlan make_plan(const vc_comp_kv* kv) {
   const int lists = kv->n_seqs * kv->n_kv_heads;
   const bool has_a = kv->pool_k != nullptr && kv->max_keep > 0;
   const bool has_b = kv->blocks != nullptr && kv->max_blk > 0;
-  const int target_a = env_int("VC_DRAFT_BF16_WGS", 512, 1, 1 << 20);
+  const int target_a = env_int("VC_DRAFT_BF16_WGS", 256, 1, 1 << 20);   // one workgroup per CU (its ring fills the LDS)
   const int target_b = env_int("VC_DRAFT_QUANT_WGS", 768, 1, 1 << 20);
-  pl.split_a = pick_chunk(static_cast<int64_t>(kv->sum_keep) * kv->n_kv_heads, kv->max_keep, lists, 64,
-                          env_int("VC_DRAFT_MIN_TOK", 256, 64, 1 << 20), target_a);
+  pl.split_a = pick_chunk(static_cast<int64_t>(kv->sum_keep) * kv->n_kv_heads, kv->max_keep, lists, 128,
+                          env_int("VC_DRAFT_MIN_TOK", 256, 128, 1 << 20), target_a);
   pl.s1 = has_a ? ceil_div(kv->max_keep, pl.split_a) : 0;
   const int nquad = ceil_div(g, 4);
   pl.bps = pick_chunk(static_cast<int64_t>(kv->sum_blk) * kv->n_kv_heads * nquad, kv->max_blk, lists * nquad, 4,
@@ -857,17 +906,6 @@ static vc_status check_comp(const vc_comp_kv* kv, const char* who) {
   return VC_OK;
 }
 
-template <bool GATHER>
-static void launch_bf16(int gp, dim3 grid, hipStream_t st, const DraftBf16Params& bp) {
-  switch (gp) {
-    case 1: hipLaunchKernelGGL((draft_bf16_kernel<1, GATHER>), grid, dim3(256), 0, st, bp); break;
-    case 2: hipLaunchKernelGGL((draft_bf16_kernel<2, GATHER>), grid, dim3(256), 0, st, bp); break;
-    case 4: hipLaunchKernelGGL((draft_bf16_kernel<4, GATHER>), grid, dim3(256), 0, st, bp); break;
-    case 8: hipLaunchKernelGGL((draft_bf16_kernel<8, GATHER>), grid, dim3(256), 0, st, bp); break;
-    default: hipLaunchKernelGGL((draft_bf16_kernel<16, GATHER>), grid, dim3(256), 0, st, bp); break;
-  }
-}
-
 }  // namespace vc
 
 using namespace vc;
@@ -899,8 +937,6 @@ extern "C" vc_status vc_draft_attn(vc_ctx* ctx, const vc_comp_kv* kv, const void
   const DraftPlan pl = make_plan(kv);
   hipStream_t st = static_cast<hipStream_t>(stream);
   const int g = kv->n_q_heads / kv->n_kv_heads;
-  int gp = 1;
-  while (gp < g) gp <<= 1;
   const float sl2 = softmax_scale * kLog2e;
   float* ws = static_cast<float*>(workspace);
 
@@ -918,7 +954,18 @@ extern "C" vc_status vc_draft_attn(vc_ctx* ctx, const vc_comp_kv* kv, const void
     bp.split_tok = pl.split_a; bp.slot0 = 0; bp.ns = pl.ns;
     bp.scale_log2e = sl2;
     dim3 grid(pl.s1, kv->n_kv_heads, kv->n_seqs);
-    if (kv->keep_idx) launch_bf16<true>(gp, grid, st, bp); else launch_bf16<false>(gp, grid, st, bp);
+    // 32-token steps, 4 waves (16-token steps with 8 waves measured the same: the gather itself binds)
+    constexpr int kLds = rows_lds(32, 4);
+    static bool lds_attr_set = false;
+    if (!lds_attr_set) {
+      VC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(draft_bf16_kernel<true, 32, 4>),
+                                 hipFuncAttributeMaxDynamicSharedMemorySize, kLds));
+      VC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(draft_bf16_kernel<false, 32, 4>),
+                                 hipFuncAttributeMaxDynamicSharedMemorySize, kLds));
+      lds_attr_set = true;
+    }
+    if (kv->keep_idx) hipLaunchKernelGGL((draft_bf16_kernel<true, 32, 4>), grid, dim3(256), kLds, st, bp);
+    else hipLaunchKernelGGL((draft_bf16_kernel<false, 32, 4>), grid, dim3(256), kLds, st, bp);
   }
   if (pl.s2 > 0) {
     DraftQuantParams qp{};
