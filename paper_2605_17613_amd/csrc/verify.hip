@@ -72,12 +72,17 @@ __device__ __forceinline__ int swz(int row, int chunk) { return row * 256 + ((ch
 // traffic per flop: at RT = 1 the matrix cores could at best be fed at the full LDS bandwidth.
 // NW = 8/RT waves per workgroup; NTG = token slices per tile; NRG = NW/NTG row groups.
 // Tiles travel HBM -> LDS directly (no registers) through a ring of NSTAGE stages, one barrier per tile.
-template <int NTG, int RT>
+// SUB = 32-token slices a wave takes per tile.  With SUB = 2 the wave issues the score products of
+// both slices before the softmax of the first, so that the matrix pipe works on one slice while
+// the vector unit does the other's exponentials (software pipelining inside the wave; used when
+// every wave has rows, i.e. above 128 rows, where the kernel is matrix-core and LDS bound).
+template <int NTG, int RT, int SUB>
 __device__ __forceinline__ void verify_body(const VerifyParams& p, char* smem, int kvh, int chunk, int w0, int w,
                                             int c0, int N) {
   constexpr int NW = 8 / RT;
   constexpr int NRG = NW / NTG;
-  constexpr int TT = 32 * NTG;                 // tokens per tile
+  constexpr int TT = 32 * NTG * SUB;           // tokens per tile
+  constexpr int SLICE_BYTES = 32 * NTG * 256;  // LDS distance between two slices of one wave
   constexpr int STAGE_BYTES = TT * 512;        // K tile then V tile, 256 bytes per row
   constexpr int NSTAGE = (kVerifyLds / STAGE_BYTES) > 8 ? 8 : (kVerifyLds / STAGE_BYTES);
   constexpr int LPT = TT / (4 * NW);           // 1 KB wave-loads per matrix per wave per tile
@@ -187,12 +192,9 @@ __device__ __forceinline__ void verify_body(const VerifyParams& p, char* smem, i
       for (int h2 = 0; h2 < 2; ++h2)
         vaddr[dt][kk][h2] = TT * 256 + swz(32 * tg + 16 * kk + 8 * h2 + tr_row, 4 * dt + tr_chunk) + tr_sub;
 
-  auto compute = [&](int j) {
-    const int ts = t_begin + j * TT + 32 * tg;  // first token of this wave's slice
-    if (!(wave_rows && ts < t_end)) return;
-    const uint32_t sbase = lds_base + (j % NSTAGE) * STAGE_BYTES;
-    // ---- S^T = K Q^T : one K operand read feeds RT products ----
-    float16v sacc[RT];
+  // One slice = 32 tokens of the tile for this wave's rows, in three stages.
+  auto scores = [&](int j, int sl, float16v (&sacc)[RT]) {       // S^T = K Q^T : one K operand read feeds RT products
+    const uint32_t sbase = lds_base + (j % NSTAGE) * STAGE_BYTES + sl * SLICE_BYTES;
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt)
 #pragma unroll
@@ -203,8 +205,9 @@ __device__ __forceinline__ void verify_body(const VerifyParams& p, char* smem, i
 #pragma unroll
       for (int rt = 0; rt < RT; ++rt) sacc[rt] = mfma32(a, qb[rt][ks], sacc[rt]);
     }
+  };
+  auto softmax = [&](int ts, float16v (&sacc)[RT], bf16x8v (&pb)[RT][2]) {
     // register i of this lane is token row 8*(i/4) + 4*hh + i%4 of the slice, for row n
-    bf16x8v pb[RT][2];
     const bool edge = ts + 32 > min(N, t_end);  // slice touches the window or the end of the chunk
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt) {
@@ -244,7 +247,10 @@ __device__ __forceinline__ void verify_body(const VerifyParams& p, char* smem, i
       }
       l[rt] += ps0 + ps1;
     }
-    // ---- O^T += V^T P^T ; A element e of k-step kk is token row 16kk + 8(e/4) + 4hh + e%4 ----
+  };
+  auto output = [&](int j, int sl, bf16x8v (&pb)[RT][2]) {
+    // O^T += V^T P^T ; A element e of k-step kk is token row 16kk + 8(e/4) + 4hh + e%4
+    const uint32_t sbase = lds_base + (j % NSTAGE) * STAGE_BYTES + sl * SLICE_BYTES;
 #pragma unroll
     for (int kk = 0; kk < 2; ++kk) {
 #pragma unroll
@@ -254,6 +260,32 @@ __device__ __forceinline__ void verify_body(const VerifyParams& p, char* smem, i
         const bf16x8v av = __builtin_bit_cast(bf16x8v, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
 #pragma unroll
         for (int rt = 0; rt < RT; ++rt) oacc[rt][dt] = mfma32(av, pb[rt][kk], oacc[rt][dt]);
+      }
+    }
+  };
+  auto compute = [&](int j) {
+    if (!wave_rows) return;
+    const int ts0 = t_begin + j * TT + 32 * tg;   // first token of this wave's first slice
+    if constexpr (SUB == 1) {
+      if (ts0 >= t_end) return;
+      float16v sacc[RT];
+      bf16x8v pb[RT][2];
+      scores(j, 0, sacc);
+      softmax(ts0, sacc, pb);
+      output(j, 0, pb);
+    } else {
+      const int ts1 = ts0 + 32 * NTG;
+      if (ts0 >= t_end) return;
+      const bool second = ts1 < t_end;
+      float16v sa[RT], sb[RT];
+      bf16x8v pa[RT][2], pbb[RT][2];
+      scores(j, 0, sa);
+      if (second) scores(j, 1, sb);            // in the matrix pipe while the first softmax runs
+      softmax(ts0, sa, pa);
+      output(j, 0, pa);
+      if (second) {
+        softmax(ts1, sb, pbb);                 // overlaps the first slice's output products
+        output(j, 1, pbb);
       }
     }
   };
@@ -310,8 +342,8 @@ __global__ __launch_bounds__(512) void verify_kernel(VerifyParams p) {
   if (w == 0) return;
   const int c0 = p.cu_ctx[b], N = p.cu_ctx[b + 1] - c0;
   if (chunk * p.chunk_tok >= min(N + w, p.tok_hi)) return;
-  if (tokens_split(w * p.g, false) == 2) verify_body<2, 1>(p, smem, kvh, chunk, w0, w, c0, N);
-  else verify_body<1, 1>(p, smem, kvh, chunk, w0, w, c0, N);
+  if (tokens_split(w * p.g, false) == 2) verify_body<2, 1, 1>(p, smem, kvh, chunk, w0, w, c0, N);
+  else verify_body<1, 1, 2>(p, smem, kvh, chunk, w0, w, c0, N);
 }
 
 // 4 waves x 64 rows: used when some window has more than 128 rows (matrix-core / LDS bound)
@@ -322,8 +354,8 @@ __global__ __launch_bounds__(256) void verify_wide_kernel(VerifyParams p) {
   if (w == 0) return;
   const int c0 = p.cu_ctx[b], N = p.cu_ctx[b + 1] - c0;
   if (chunk * p.chunk_tok >= min(N + w, p.tok_hi)) return;
-  if (tokens_split(w * p.g, true) == 2) verify_body<2, 2>(p, smem, kvh, chunk, w0, w, c0, N);
-  else verify_body<1, 2>(p, smem, kvh, chunk, w0, w, c0, N);
+  if (tokens_split(w * p.g, true) == 2) verify_body<2, 2, 1>(p, smem, kvh, chunk, w0, w, c0, N);
+  else verify_body<1, 2, 1>(p, smem, kvh, chunk, w0, w, c0, N);
 }
 
 struct VerifyMergeParams {
@@ -508,7 +540,8 @@ extern "C" vc_status vc_verify_attn_range(vc_ctx* ctx, const vc_full_kv* kv, con
   const int nchunk = ceil_div(hi, pl.chunk_tok) - vp.chunk0;
   dim3 grid(nchunk, kv->n_kv_heads, seq_end - seq_begin);
   // The 64-rows-per-wave variant halves the LDS traffic per flop but leaves one wave per SIMD;
-  // measured slower at every window (1781 vs 1409 us at w = 64, config-2 shape), so it is opt-in.
+  // measured slower at every window (1781 vs 1363 us at w = 64, config-2 shape; 2503 us with two
+  // slices in flight, which spills), so it is opt-in.
   const bool wide = env_int("VC_VERIFY_WIDE", 0, 0, 1) != 0;
   mark_begin(ctx, st);
   if (wide) hipLaunchKernelGGL(verify_wide_kernel, grid, dim3(256), kVerifyLds, st, vp);
