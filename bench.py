@@ -314,6 +314,23 @@ def measure_compressor(vc, ctx, lay, torch, HKV, N, B, reps=5):
     ms = timed(lambda: vc.vc_topk_keep(ctx, scores, lay.cu_ctx, cu_keep, HKV, keep, forced_first=first, forced_last=last))
     res["topk_keep"] = {"us": ms * 1e3, "lists": B * HKV, "positions": N, "kept": keep_n,
                         "GBps": (scores.numel() * 4 + keep.numel() * 4) / (ms * 1e-3) / 1e9}
+    del scores, keep
+    # sampling-based acceptance on the round's logits: draft logits = verify logits + noise
+    if lay.logits is not None:
+        rows, vocab = lay.logits.shape
+        tw = lay.draft_ids.numel()
+        sel = torch.cat([torch.arange(int(lay.cu_rows[b]), int(lay.cu_rows[b]) + lay.win[b], device=dev) for b in range(B)])
+        dlog = lay.logits[sel] + 0.3 * torch.randn((tw, vocab), device=dev)
+        ua = torch.rand(tw, device=dev)
+        ur = torch.rand(B, device=dev)
+        acc = torch.empty(B, dtype=torch.int32, device=dev)
+        nxt = torch.empty(B, dtype=torch.int32, device=dev)
+        sws = torch.empty(vc.vc_accept_sample_workspace_bytes(rows, tw, B, vocab), dtype=torch.uint8, device=dev)
+        ms = timed(lambda: vc.vc_accept_sample(ctx, lay.logits, dlog, lay.cu_rows, lay.draft_ids, lay.cu_win, 0.8, ua, ur,
+                                               acc, nxt, workspace=sws))
+        res["accept_sample"] = {"us": ms * 1e3, "rows": rows + tw, "vocab": vocab,
+                                "GBps": (rows + tw) * vocab * 4 / (ms * 1e-3) / 1e9,
+                                "mean_accept_len": float(acc.float().mean())}
     return res
 
 

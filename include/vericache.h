@@ -184,6 +184,32 @@ vc_status vc_accept_len(vc_ctx* ctx, const float* logits, int32_t vocab, const i
                         int32_t* argmax_ids, void* workspace, size_t workspace_bytes,
                         void* stream);
 
+/* Sampling-based acceptance (the footnote of paper section 4.1: the method "extends to
+ * sampling-based decoding via standard rejection sampling"; the paper gives no further text, so
+ * this is the textbook speculative-sampling rule, with every random number an input).
+ *   p_j = softmax(target row j / T)   full-KV distribution for drafted position j
+ *   q_j = softmax(draft row j / T)    the distribution drafted token t_j was sampled from
+ *   position j is accepted iff u_accept[j] * q_j(t_j) < p_j(t_j); accept_len = first rejected
+ *   position, else w_b.  next_token: at a rejection, drawn from max(0, p_a - q_a) by inverse CDF
+ *   (the smallest v whose running sum over v' <= v exceeds u_resample[b] * total); when everything
+ *   was accepted, drawn the same way from p_w if the bonus row is supplied, else -1.
+ * Probabilities are evaluated in double precision (row maximum, sum of exponentials, running
+ * sums), so the integers equal a plain double-precision evaluation unless a draw lies within
+ * rounding distance of a boundary.
+ *   target_logits  device fp32 [total_rows, vocab]; rows per sequence as for vc_accept_len
+ *   draft_logits   device fp32 [total_win, vocab]; row cu_win[b] + j belongs to drafted position j
+ *   draft_ids      device int32 [total_win], in [0, vocab)
+ *   u_accept       device fp32 [total_win], u_resample device fp32 [n_seqs]; values in [0, 1)
+ *   temperature    T > 0
+ *   accept_len, next_token   device int32 [n_seqs] */
+vc_status vc_accept_sample_workspace_bytes(int32_t total_rows, int32_t total_win, int32_t n_seqs, int32_t vocab,
+                                           size_t* bytes);
+vc_status vc_accept_sample(vc_ctx* ctx, const float* target_logits, const float* draft_logits, int32_t vocab,
+                           const int32_t* cu_rows, int32_t total_rows, const int32_t* draft_ids,
+                           const int32_t* cu_win, int32_t total_win, int32_t n_seqs, float temperature,
+                           const float* u_accept, const float* u_resample, int32_t* accept_len,
+                           int32_t* next_token, void* workspace, size_t workspace_bytes, void* stream);
+
 /* Full-KV reload (paper section 4.2.1 and section 5.2 step (i): the full KV lives in CPU memory
  * and is reloaded asynchronously, overlapped with draft forward passes).
  * One hipMemcpyAsync and one event per chunk, on the context's own copy stream.

@@ -47,7 +47,7 @@ class vc_chunk(C.Structure):
 EXPORTS = ["vc_create", "vc_destroy", "vc_last_error", "vc_version", "vc_time_main_kernel",
            "vc_draft_workspace_bytes", "vc_draft_attn", "vc_verify_workspace_bytes", "vc_verify_attn",
            "vc_verify_plan", "vc_verify_attn_range", "vc_verify_finish",
-           "vc_accept_workspace_bytes", "vc_accept_len", "vc_swap_in", "vc_swap_in_rows", "vc_pack_rows", "vc_swap_wait", "vc_swap_query", "vc_swap_sync",
+           "vc_accept_workspace_bytes", "vc_accept_len", "vc_accept_sample_workspace_bytes", "vc_accept_sample", "vc_swap_in", "vc_swap_in_rows", "vc_pack_rows", "vc_swap_wait", "vc_swap_query", "vc_swap_sync",
            "vc_keep_from_dropped", "vc_compress_quant", "vc_decompress_quant", "vc_topk_keep",
            "vc_iter_time_model", "vc_sched_create", "vc_sched_destroy", "vc_sched_set_resident", "vc_sched_span",
            "vc_sched_admit", "vc_sched_cancel", "vc_sched_step", "vc_sched_rings"]
@@ -88,6 +88,10 @@ def load():
     lib.vc_accept_len.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p,
                                   C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                   C.c_size_t, C.c_void_p]
+    lib.vc_accept_sample_workspace_bytes.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_size_t)]
+    lib.vc_accept_sample.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p,
+                                     C.c_void_p, C.c_int32, C.c_int32, C.c_float, C.c_void_p, C.c_void_p, C.c_void_p,
+                                     C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
     lib.vc_swap_in.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.POINTER(vc_chunk), C.c_int32,
                                C.POINTER(C.c_int64)]
     lib.vc_swap_in_rows.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p,
@@ -292,6 +296,29 @@ def vc_accept_len(ctx: Context, logits, cu_rows, draft_ids, cu_win, accept_len, 
                                 _ptr(next_token, torch.int32, "next_token"),
                                 _ptr(argmax_ids, torch.int32, "argmax_ids"),
                                 _ptr(workspace, None, "workspace"), ws_bytes, _stream(stream)))
+    return accept_len, next_token
+
+
+def vc_accept_sample_workspace_bytes(total_rows: int, total_win: int, n_seqs: int, vocab: int) -> int:
+    n = C.c_size_t()
+    _check(load().vc_accept_sample_workspace_bytes(int(total_rows), int(total_win), int(n_seqs), int(vocab), C.byref(n)))
+    return n.value
+
+
+def vc_accept_sample(ctx: Context, target_logits, draft_logits, cu_rows, draft_ids, cu_win, temperature, u_accept,
+                     u_resample, accept_len, next_token, workspace=None, stream=None):
+    total_rows, vocab = target_logits.shape
+    total_win = draft_logits.shape[0]
+    n_seqs = cu_rows.numel() - 1
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    _check(load().vc_accept_sample(ctx.handle, _ptr(target_logits, torch.float32, "target_logits"),
+                                   _ptr(draft_logits, torch.float32, "draft_logits"), int(vocab),
+                                   _ptr(cu_rows, torch.int32, "cu_rows"), int(total_rows),
+                                   _ptr(draft_ids, torch.int32, "draft_ids"), _ptr(cu_win, torch.int32, "cu_win"),
+                                   int(total_win), int(n_seqs), float(temperature),
+                                   _ptr(u_accept, torch.float32, "u_accept"), _ptr(u_resample, torch.float32, "u_resample"),
+                                   _ptr(accept_len, torch.int32, "accept_len"), _ptr(next_token, torch.int32, "next_token"),
+                                   _ptr(workspace, None, "workspace"), ws_bytes, _stream(stream)))
     return accept_len, next_token
 
 
