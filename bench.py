@@ -48,6 +48,8 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-swap", action="store_true")
     ap.add_argument("--no-compressor", action="store_true", help="skip the compress / decompress / top-k legs")
+    ap.add_argument("--round3", action="store_true",
+                    help="also run BASELINE config 3 end to end: 32 layers, ctx 131072, 64-token horizon (17 GB pinned)")
     ap.add_argument("--only", default="", help="comma list of legs to run per step: keep,d1,d2,d3,verify,accept")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
@@ -254,6 +256,12 @@ def main():
     if not args.no_compressor and not args.only:
         comp = measure_compressor(vc, ctx, lay, torch, HKV, N, B)
 
+    round3 = None
+    if args.round3:
+        del lay, ws
+        torch.cuda.empty_cache()
+        round3 = measure_round3(vc, ctx, torch)
+
     cpu = None
     if not args.no_cpu_baseline:
         cpu = cpu_baseline(lay, torch, np, HQ, HKV, N)
@@ -267,7 +275,7 @@ def main():
                    "step": f"keep-index + {W} draft steps x (bf16 gather, int4, int2) + verify + accept"},
         "legs": res,
         "verify_TFLOPs": res.get("verify", {}).get("TFLOPs"),
-        "roofline": roofline, "swap": swap, "compressor": comp, "cpu_baseline": cpu,
+        "roofline": roofline, "swap": swap, "compressor": comp, "config3_round": round3, "cpu_baseline": cpu,
     }
     print(json.dumps(line))
     ctx.close()
@@ -485,6 +493,126 @@ def measure_swap(vc, ctx, lay, torch, draft_kw, out, ws, HKV, N, B, W):
             "draft_steps": n_steps, "draft_alone_ms": t_draft * 1e3, "both_ms": t_both * 1e3,
             "overlap": (t_draft + t_swap - t_both) / min(t_draft, t_swap), "bytes_ok": ok,
             "model_max_ms": max(t_draft, t_swap) * 1e3, "streamed_verify": streamed}
+
+
+def measure_round3(vc, ctx, torch, layers=32, N=131072, W=64, vocab=128256, chunk_tok=8192):
+    """BASELINE config 3: one request, `layers` attention layers of the 8B shape at context N.  The
+    int4 KV of every layer sits on the GPU, the full bf16 KV in pinned host memory.  One round =
+    start the reload of all layers, draft W tokens (W x layers draft calls, the bf16 tail growing),
+    verify every layer as its reload lands, accept.  The draft horizon is measured eagerly and as
+    one captured HIP graph per step (32 layers x 2 kernels), replayed W times."""
+    from paper_2605_17613_amd import synth
+    dev = "cuda:0"
+    HQ, HKV = 32, 8
+    g = torch.Generator(device=dev); g.manual_seed(synth.SEED_BASE + 3)
+    row = HKV * 128
+    cu_ctx = torch.tensor([0, N], dtype=torch.int32, device=dev)
+    nb = N // 32
+    cu_blk = torch.tensor([0, nb], dtype=torch.int32, device=dev)
+    host_k = torch.empty((layers, N, HKV, 128), dtype=torch.bfloat16, pin_memory=True)
+    host_v = torch.empty((layers, N, HKV, 128), dtype=torch.bfloat16, pin_memory=True)
+    blocks = torch.empty((layers, HKV * nb, 5120), dtype=torch.uint8, device=dev)
+    for l in range(layers):      # full KV made on the GPU, compressed by the library, then moved to the host
+        k = torch.randn((N, HKV, 128), generator=g, device=dev, dtype=torch.float32).to(torch.bfloat16)
+        v = torch.randn((N, HKV, 128), generator=g, device=dev, dtype=torch.float32).to(torch.bfloat16)
+        vc.vc_compress_quant(ctx, k, v, cu_ctx, cu_blk, 4, nb, blocks[l])
+        host_k[l].copy_(k); host_v[l].copy_(v)
+    del k, v
+    q = torch.randn((layers, 1, HQ, 128), generator=g, device=dev).to(torch.bfloat16)
+    q_win = torch.randn((layers, W, HQ, 128), generator=g, device=dev).to(torch.bfloat16)
+    k_win = torch.randn((layers, W, HKV, 128), generator=g, device=dev).to(torch.bfloat16)
+    v_win = torch.randn((layers, W, HKV, 128), generator=g, device=dev).to(torch.bfloat16)
+    logits, ids_star = synth.planted_logits(W, vocab, g)
+    prefix = int(torch.randint(0, W + 1, (1,), generator=g, device=dev))
+    cu_win = torch.tensor([0, W], dtype=torch.int32, device=dev)
+    draft_ids = synth.drafts_with_prefix(ids_star.clone(), [0, W], [prefix], vocab).to(torch.int32).contiguous()
+    stage_k = torch.empty((layers, N, HKV, 128), dtype=torch.bfloat16, device=dev)
+    stage_v = torch.empty_like(stage_k)
+    scale = 1.0 / math.sqrt(128)
+    out = torch.empty((layers, 1, HQ, 128), dtype=torch.bfloat16, device=dev)
+    vout = torch.empty_like(q_win)
+    cu_tail = torch.zeros(2, dtype=torch.int32, device=dev)
+    cu_tail_steps = [torch.tensor([0, s], dtype=torch.int32, device=dev) for s in range(W)]
+    dkw = lambda l: dict(blocks=blocks[l], cu_blk=cu_blk, max_blk=nb, bits=4, sum_blk=nb, tail_k=k_win[l], tail_v=v_win[l],
+                         cu_tail=cu_tail, max_tail=W - 1)
+    vkw = lambda l: dict(k=stage_k[l], v=stage_v[l], cu_ctx=cu_ctx, max_ctx=N, max_win=W, sum_ctx=N)
+    ws = torch.empty(max(vc.vc_draft_workspace_bytes(HQ, HKV, 1, **dkw(0)),
+                         vc.vc_verify_workspace_bytes(HQ, HKV, 1, total_win=W, **vkw(0))), dtype=torch.uint8, device=dev)
+    acc = torch.empty(1, dtype=torch.int32, device=dev); nxt = torch.empty_like(acc)
+    amax = torch.empty(W, dtype=torch.int32, device=dev)
+    aws = torch.empty(vc.vc_accept_workspace_bytes(W, vocab), dtype=torch.uint8, device=dev)
+    layer_bytes = N * row * 2
+    chunks = [(t * row * 2, t * row * 2, min(chunk_tok, N - t) * row * 2) for t in range(0, N, chunk_tok)]
+
+    def draft_step():
+        for l in range(layers):
+            vc.vc_draft_attn(ctx, q[l], scale, out[l], n_kv_heads=HKV, workspace=ws, **dkw(l))
+
+    def horizon_eager():
+        for s in range(W):
+            cu_tail.copy_(cu_tail_steps[s])
+            draft_step()
+
+    def swap_all():
+        last = []
+        for l in range(layers):
+            vc.vc_swap_in(ctx, host_k[l], stage_k[l], chunks)
+            last.append(vc.vc_swap_in(ctx, host_v[l], stage_v[l], chunks) + len(chunks) - 1)
+        return last
+
+    def verify_all(last):
+        for l in range(layers):
+            if last is not None:
+                vc.vc_swap_wait(ctx, last[l])
+            vc.vc_verify_attn(ctx, q_win[l], k_win[l], v_win[l], cu_win, scale, vout[l], n_seqs=1, workspace=ws, **vkw(l))
+        vc.vc_accept_len(ctx, logits, cu_win, draft_ids, cu_win, acc, nxt, amax, workspace=aws)
+
+    def wall(fn):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter(); r = fn(); torch.cuda.synchronize(); vc.vc_swap_sync(ctx)
+        return time.perf_counter() - t0, r
+
+    draft_step(); torch.cuda.synchronize()
+    t_eager, _ = wall(horizon_eager)
+    # one draft step (all layers) as a HIP graph; the tail length lives in device memory, so the
+    # same graph serves every step of the horizon
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        draft_step()
+        side.synchronize()
+        with torch.cuda.graph(graph, stream=side):
+            draft_step()
+    torch.cuda.synchronize()
+
+    def horizon_graph():
+        for s in range(W):
+            cu_tail.copy_(cu_tail_steps[s])
+            graph.replay()
+
+    ref = None
+    cu_tail.copy_(cu_tail_steps[W - 1]); draft_step(); torch.cuda.synchronize(); ref = out.clone()
+    t_graph, _ = wall(horizon_graph)
+    graph_same = bool(torch.equal(ref.view(torch.int16), out.view(torch.int16)))
+    t_swap, last = wall(swap_all)
+    t_verify, _ = wall(lambda: verify_all(None))
+
+    def round_():
+        last = swap_all()
+        horizon_graph()
+        verify_all(last)
+
+    t_round, _ = wall(round_)
+    a = int(acc)
+    draft_bytes = sum(layers * (HKV * nb * 5120 + s * HKV * 512 + 2 * HQ * 256) for s in range(W))
+    return {"layers": layers, "ctx": N, "window": W, "int4_GB": blocks.numel() / 1e9, "full_kv_GB": 2 * layers * layer_bytes / 1e9,
+            "draft_horizon_eager_ms": t_eager * 1e3, "draft_horizon_graph_ms": t_graph * 1e3, "graph_equals_eager": graph_same,
+            "draft_GBps_graph": draft_bytes / t_graph / 1e9, "ms_per_drafted_token": t_graph / W * 1e3,
+            "swap_alone_ms": t_swap * 1e3, "swap_GBps": 2 * layers * layer_bytes / t_swap / 1e9,
+            "verify_accept_ms": t_verify * 1e3, "round_ms": t_round * 1e3,
+            "model_max_ms": max(t_graph, t_swap) * 1e3 + t_verify / layers * 1e3,
+            "accept_len": a, "planted_prefix": prefix, "accept_exact": a == prefix,
+            "tokens_per_round": a + 1, "tokens_per_s": (a + 1) / t_round}
 
 
 def cpu_baseline(lay, torch, np, HQ, HKV, N):
