@@ -716,15 +716,22 @@ struct DraftMergeParams {
   float scale_log2e;
 };
 
-// One workgroup of 128 threads per (sequence, query head).  The tail holds at most a few tens of
-// tokens (this horizon's drafts plus a partial block), so it is attended to here instead of in a
-// launch of its own: thread t scores token t, thread d accumulates channel d.  Everything the
-// kernel needs (partials, q, the thread's key row, the first value rows) is requested up front so
-// that the launch costs one memory round trip, not one per stage.
-constexpr int kTailPrefetch = 32;
-
-__global__ __launch_bounds__(128) void draft_merge_kernel(DraftMergeParams p) {
-  const int b = blockIdx.y, h = blockIdx.x, d = threadIdx.x;
+// One workgroup of 512 threads per (sequence, query head): four groups of 128 threads; thread d of a
+// group owns output channel d.  Group k merges the splits k, k+4, ... and accumulates the tail
+// tokens k, k+4, ...; the groups are combined through LDS at the end.  The tail holds at most a few
+// tens of tokens (this horizon's drafts plus a partial block), so it is attended to here instead of in
+// a launch of its own: thread t of group 0 scores token t.  The kernel is pure latency (a few
+// kilobytes per workgroup), so everything is requested before anything is consumed - the key row,
+// the first value rows, then eight partials at a time - and the work of a head is spread over the
+// groups so that even a single-sequence batch, whose heads each own ~100 splits, needs only a few
+// memory round trips.
+// kMergeGroups = 4 when the batch has few (sequence, head) pairs (latency is everything), 1 when it
+// has hundreds (the groups' barriers and idle lanes then cost more than they save).
+template <int kMergeGroups>
+__global__ __launch_bounds__(128 * kMergeGroups) void draft_merge_kernel(DraftMergeParams p) {
+  constexpr int kTailPrefetch = 64 / kMergeGroups > 32 ? 32 : 64 / kMergeGroups;   // value rows per group requested up front
+  const int b = blockIdx.y, h = blockIdx.x;
+  const int d = threadIdx.x & 127, grp = threadIdx.x >> 7;
   const int n1 = p.cu_a ? ceil_div_dev(p.cu_a[b + 1] - p.cu_a[b], p.split_a) : 0;
   const int n2 = p.cu_blk ? ceil_div_dev(p.cu_blk[b + 1] - p.cu_blk[b], p.bps) : 0;
   const int nsl = n1 + n2;
@@ -735,29 +742,40 @@ __global__ __launch_bounds__(128) void draft_merge_kernel(DraftMergeParams p) {
   }
   const int kvh = h / p.g;
   const size_t row_stride = static_cast<size_t>(p.n_kv_heads) * kHeadDim;
-  // requests for the tail first (they are consumed last)
+  __shared__ float qs[kHeadDim];
+  __shared__ float ps[128];
+  __shared__ float red[2];
+  __shared__ float gm[kMergeGroups], gl[kMergeGroups], gtl[kMergeGroups];
+  __shared__ float gacc[kMergeGroups][kHeadDim], gtacc[kMergeGroups][kHeadDim];
+
+  // ---- requests for the tail first (they are consumed last) ----
   uint4 kraw[16];
   uint16_t vpre[kTailPrefetch];
   float qd = 0.f;
+  const uint16_t* vcol = p.tail_v + static_cast<size_t>(t0) * row_stride + static_cast<size_t>(kvh) * kHeadDim + d;
   if (nt > 0) {
-    qd = bf16_bits_to_float(p.q[(static_cast<size_t>(b) * p.n_q_heads + h) * kHeadDim + d]) * p.scale_log2e;
-    const int tk = min(d, nt - 1);
-    const uint16_t* kr = p.tail_k + static_cast<size_t>(t0 + tk) * row_stride + static_cast<size_t>(kvh) * kHeadDim;
+    if (grp == 0) {
+      qd = bf16_bits_to_float(p.q[(static_cast<size_t>(b) * p.n_q_heads + h) * kHeadDim + d]) * p.scale_log2e;
+      const int tk = min(d, nt - 1);
+      const uint16_t* kr = p.tail_k + static_cast<size_t>(t0 + tk) * row_stride + static_cast<size_t>(kvh) * kHeadDim;
 #pragma unroll
-    for (int i = 0; i < 16; ++i) kraw[i] = *reinterpret_cast<const uint4*>(kr + 8 * i);
-    const uint16_t* vr = p.tail_v + static_cast<size_t>(t0) * row_stride + static_cast<size_t>(kvh) * kHeadDim + d;
+      for (int i = 0; i < 16; ++i) kraw[i] = *reinterpret_cast<const uint4*>(kr + 8 * i);
+    }
 #pragma unroll
-    for (int t = 0; t < kTailPrefetch; ++t) vpre[t] = vr[static_cast<size_t>(min(t, nt - 1)) * row_stride];
+    for (int i = 0; i < kTailPrefetch; ++i) vpre[i] = vcol[static_cast<size_t>(min(grp + kMergeGroups * i, nt - 1)) * row_stride];
   }
+
+  // ---- this group's share of the split partials, eight at a time ----
   const float* base = p.ws + (static_cast<size_t>(b) * p.n_q_heads + h) * p.ns * kPartialFloats;
   float mm = -INFINITY, acc = 0.f, lsum = 0.f;
-  for (int s0 = 0; s0 < nsl; s0 += 8) {
+  for (int s0 = grp; s0 < nsl; s0 += 8 * kMergeGroups) {
     float m8[8], l8[8], o8[8];
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-      const int s = min(s0 + i, nsl - 1);
+      const int si = s0 + kMergeGroups * i;
+      const int s = min(si, nsl - 1);
       const float* pp = base + static_cast<size_t>(s < n1 ? s : p.s1 + (s - n1)) * kPartialFloats;
-      m8[i] = s0 + i < nsl ? pp[0] : -INFINITY;
+      m8[i] = si < nsl ? pp[0] : -INFINITY;
       l8[i] = pp[1];
       o8[i] = pp[2 + d];
     }
@@ -775,66 +793,105 @@ __global__ __launch_bounds__(128) void draft_merge_kernel(DraftMergeParams p) {
     }
     mm = mn;
   }
+
+  // ---- the tail, 128 tokens at a time: one more partial (mt, tl, tacc) spread over the groups ----
+  float mt = -INFINITY, tacc = 0.f, tl = 0.f;
   if (nt > 0) {
-    __shared__ float qs[kHeadDim];
-    __shared__ float ps[128];
-    __shared__ float red[2];
-    qs[d] = qd;
+    if (grp == 0) qs[d] = qd;
     __syncthreads();
     for (int c0 = 0; c0 < nt; c0 += 128) {
-      const int t = c0 + d;
-      float s = -INFINITY;
-      if (c0 > 0 && t < nt) {
-        const uint16_t* kr = p.tail_k + static_cast<size_t>(t0 + t) * row_stride + static_cast<size_t>(kvh) * kHeadDim;
-#pragma unroll
-        for (int i = 0; i < 16; ++i) kraw[i] = *reinterpret_cast<const uint4*>(kr + 8 * i);
-      }
-      if (t < nt) {
-        float a = 0.f;
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          const uint32_t w[4] = {kraw[i].x, kraw[i].y, kraw[i].z, kraw[i].w};
-#pragma unroll
-          for (int k = 0; k < 4; ++k) {
-            a = fmaf(qs[8 * i + 2 * k], bf16_lo(w[k]), a);
-            a = fmaf(qs[8 * i + 2 * k + 1], bf16_hi(w[k]), a);
-          }
-        }
-        s = a;
-      }
-      const float wm = wave_max(s);
-      if ((d & 63) == 0) red[d >> 6] = wm;
-      __syncthreads();
-      const float mn = fmaxf(mm, fmaxf(red[0], red[1]));
-      const float alpha = exp2_diff(mm, mn);
-      ps[d] = exp2_diff(s, mn);
-      __syncthreads();
-      acc *= alpha;
-      lsum *= alpha;
       const int cn = min(128, nt - c0);
-      int t2 = 0;
+      float s = -INFINITY;
+      if (grp == 0) {
+        const int t = c0 + d;
+        if (c0 > 0 && t < nt) {
+          const uint16_t* kr = p.tail_k + static_cast<size_t>(t0 + t) * row_stride + static_cast<size_t>(kvh) * kHeadDim;
+#pragma unroll
+          for (int i = 0; i < 16; ++i) kraw[i] = *reinterpret_cast<const uint4*>(kr + 8 * i);
+        }
+        if (t < nt) {
+          float a = 0.f;
+#pragma unroll
+          for (int i = 0; i < 16; ++i) {
+            const uint32_t w[4] = {kraw[i].x, kraw[i].y, kraw[i].z, kraw[i].w};
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+              a = fmaf(qs[8 * i + 2 * k], bf16_lo(w[k]), a);
+              a = fmaf(qs[8 * i + 2 * k + 1], bf16_hi(w[k]), a);
+            }
+          }
+          s = a;
+        }
+        const float wm = wave_max(s);
+        if ((d & 63) == 0) red[d >> 6] = wm;
+      }
+      __syncthreads();
+      const float mn = fmaxf(mt, fmaxf(red[0], red[1]));
+      const float alpha = exp2_diff(mt, mn);
+      if (grp == 0) ps[d] = exp2_diff(s, mn);
+      __syncthreads();
+      tacc *= alpha;
+      tl *= alpha;
+      // this group's tokens of the chunk: grp, grp + 4, ...
+      int i = 0;
       if (c0 == 0) {
 #pragma unroll
-        for (int u = 0; u < kTailPrefetch; ++u) {
-          const float pv = u < cn ? ps[u] : 0.f;
-          acc = fmaf(pv, bf16_bits_to_float(vpre[u]), acc);
-          lsum += pv;
+        for (; i < kTailPrefetch; ++i) {
+          const int u = grp + kMergeGroups * i;
+          const float pv = u < cn ? ps[min(u, 127)] : 0.f;
+          tacc = fmaf(pv, bf16_bits_to_float(vpre[i]), tacc);
+          tl += pv;
         }
-        t2 = min(cn, kTailPrefetch);
       }
-      const uint16_t* vr = p.tail_v + static_cast<size_t>(t0 + c0) * row_stride + static_cast<size_t>(kvh) * kHeadDim + d;
-      for (; t2 < cn; ++t2) {
-        const float pv = ps[t2];
-        acc = fmaf(pv, bf16_bits_to_float(vr[static_cast<size_t>(t2) * row_stride]), acc);
-        lsum += pv;
+      for (; grp + kMergeGroups * i < cn; i += 8) {
+        uint16_t v8[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+          const int u = min(grp + kMergeGroups * (i + k), cn - 1);
+          v8[k] = vcol[static_cast<size_t>(c0 + u) * row_stride];
+        }
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+          const int u = grp + kMergeGroups * (i + k);
+          const float pv = u < cn ? ps[min(u, 127)] : 0.f;
+          tacc = fmaf(pv, bf16_bits_to_float(v8[k]), tacc);
+          tl += pv;
+        }
       }
-      mm = mn;
+      mt = mn;
       __syncthreads();
     }
   }
-  const float o = lsum > 0.f ? acc / lsum : 0.f;
-  p.out[(static_cast<size_t>(b) * p.n_q_heads + h) * kHeadDim + d] = static_cast<uint16_t>(float_to_bf16_bits(o));
-  if (p.lse && d == 0) p.lse[static_cast<size_t>(b) * p.n_q_heads + h] = lsum > 0.f ? (mm + log2f(lsum)) * kLn2 : -INFINITY;
+
+  // ---- combine the groups ----
+  gacc[grp][d] = acc;
+  gtacc[grp][d] = tacc;
+  if (d == 0) {
+    gm[grp] = mm;
+    gl[grp] = lsum;
+    gtl[grp] = tl;
+  }
+  __syncthreads();
+  if (grp == 0) {
+    float M = mt;
+#pragma unroll
+    for (int k = 0; k < kMergeGroups; ++k) M = fmaxf(M, gm[k]);
+    const float at = exp2_diff(mt, M);
+    float num = 0.f, den = 0.f, tnum = 0.f, tden = 0.f;
+#pragma unroll
+    for (int k = 0; k < kMergeGroups; ++k) {
+      const float a = exp2_diff(gm[k], M);
+      num = fmaf(a, gacc[k][d], num);
+      den = fmaf(a, gl[k], den);
+      tnum += gtacc[k][d];
+      tden += gtl[k];
+    }
+    num = fmaf(at, tnum, num);
+    den = fmaf(at, tden, den);
+    const float o = den > 0.f ? num / den : 0.f;
+    p.out[(static_cast<size_t>(b) * p.n_q_heads + h) * kHeadDim + d] = static_cast<uint16_t>(float_to_bf16_bits(o));
+    if (p.lse && d == 0) p.lse[static_cast<size_t>(b) * p.n_q_heads + h] = den > 0.f ? (M + log2f(den)) * kLn2 : -INFINITY;
+  }
 }
 
 // --------------------------------------------------------------------------------------------
@@ -996,7 +1053,10 @@ extern "C" vc_status vc_draft_attn(vc_ctx* ctx, const vc_comp_kv* kv, const void
   mp.n_q_heads = kv->n_q_heads; mp.n_kv_heads = kv->n_kv_heads; mp.g = g; mp.ns = pl.ns;
   mp.split_a = pl.split_a; mp.s1 = pl.s1; mp.bps = pl.bps;
   mp.scale_log2e = sl2;
-  hipLaunchKernelGGL(draft_merge_kernel, dim3(kv->n_q_heads, kv->n_seqs), dim3(128), 0, st, mp);
+  if (static_cast<int64_t>(kv->n_seqs) * kv->n_q_heads < 256)
+    hipLaunchKernelGGL(draft_merge_kernel<4>, dim3(kv->n_q_heads, kv->n_seqs), dim3(512), 0, st, mp);
+  else
+    hipLaunchKernelGGL(draft_merge_kernel<1>, dim3(kv->n_q_heads, kv->n_seqs), dim3(128), 0, st, mp);
   VC_HIP(hipGetLastError());
   return VC_OK;
 }
