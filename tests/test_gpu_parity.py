@@ -71,6 +71,19 @@ def test_draft_quant_long_with_tail(lib, ctx, bits):
     check_draft(lib, ctx, lay, f"int{bits} long", bits=bits, use_tail=True)
 
 
+@pytest.mark.parametrize("nseq", [2, 32])
+def test_draft_long_tails_in_both_merge_variants(lib, ctx, nseq):
+    """Tails beyond 128 tokens take the merge kernel's chunk loop; a small batch runs its four-group
+    variant, a batch of 256 (sequence, head) pairs the one-group variant."""
+    rng = np.random.default_rng(nseq)
+    lens = [int(x) * 32 for x in rng.integers(1, 9, nseq)]
+    tails = [200, 130] if nseq == 2 else [int(x) for x in rng.integers(0, 150, nseq)]
+    lay = synth.make_layer(60 + nseq, DEV, ctx_len=lens, n_q_heads=8, n_kv_heads=2, quant_bits=(4,), tail_len=tails)
+    check_draft(lib, ctx, lay, f"long tails, {nseq} sequences", bits=4, use_tail=True)
+    lay = synth.make_layer(70 + nseq, DEV, ctx_len=lens, n_q_heads=8, n_kv_heads=2, tail_len=tails)
+    check_draft(lib, ctx, lay, f"tail only, {nseq} sequences", use_tail=True)     # no split at all: the merge does everything
+
+
 @pytest.mark.parametrize("bits", [4, 2])
 def test_draft_lossless_grid_equals_bf16_path(lib, ctx, bits):
     """Cross-kernel: records built from exact grid values dequantise to the bf16 values, so the
