@@ -40,7 +40,7 @@ __global__ __launch_bounds__(kAcceptThreads) void argmax_segment_kernel(const fl
     const int nvec = (seg1 - seg0) >> 2;
     const float4* b4 = reinterpret_cast<const float4*>(base + seg0);
     for (int i = threadIdx.x; i < nvec; i += kAcceptThreads) {
-      float4 x = b4[i];
+      float4 x = ld_stream(b4 + i);
       int e = seg0 + 4 * i;
       // ascending index order inside a thread, strict '>' keeps the first of equal values
       if (x.x > best || bidx == 0x7fffffff) { best = x.x; bidx = e; }
@@ -49,12 +49,12 @@ __global__ __launch_bounds__(kAcceptThreads) void argmax_segment_kernel(const fl
       if (x.w > best) { best = x.w; bidx = e + 3; }
     }
     for (int e = seg0 + 4 * nvec + threadIdx.x; e < seg1; e += kAcceptThreads) {
-      float x = base[e];
+      float x = ld_stream(base + e);
       if (x > best || bidx == 0x7fffffff) { best = x; bidx = e; }
     }
   } else {
     for (int e = seg0 + threadIdx.x; e < seg1; e += kAcceptThreads) {
-      float x = base[e];
+      float x = ld_stream(base + e);
       if (x > best || bidx == 0x7fffffff) { best = x; bidx = e; }
     }
   }

@@ -80,8 +80,8 @@ __global__ __launch_bounds__(256) void compress_quant_kernel(QuantParams p) {
   if (live) {
 #pragma unroll
     for (int i = 0; i < NL; ++i) {
-      kraw[i] = *reinterpret_cast<const uint4*>(p.k + row0 + static_cast<size_t>(4 * i + lg) * rs);
-      vraw[i] = *reinterpret_cast<const uint4*>(p.v + row0 + static_cast<size_t>(4 * i + lg) * rs);
+      kraw[i] = ld_stream(reinterpret_cast<const uint4*>(p.k + row0 + static_cast<size_t>(4 * i + lg) * rs));
+      vraw[i] = ld_stream(reinterpret_cast<const uint4*>(p.v + row0 + static_cast<size_t>(4 * i + lg) * rs));
     }
     // ---- keys: one group per channel over the TB tokens
     float mn[8], mx[8];
@@ -211,7 +211,7 @@ __global__ __launch_bounds__(256) void decompress_quant_kernel(QuantParams p) {
                                         kRecordBytes;
 #pragma unroll
     for (int m = 0; m < 5; ++m)
-      *reinterpret_cast<uint4*>(rec + 16 * (64 * m + lane)) = *reinterpret_cast<const uint4*>(src + 16 * (64 * m + lane));
+      *reinterpret_cast<uint4*>(rec + 16 * (64 * m + lane)) = ld_stream(reinterpret_cast<const uint4*>(src + 16 * (64 * m + lane)));
   }
   __syncthreads();
   if (!live) return;
@@ -250,8 +250,8 @@ __global__ __launch_bounds__(256) void decompress_quant_kernel(QuantParams p) {
       const uint32_t vb = float_to_bf16_bits(fmaf(vs, static_cast<float>(vcode), vz));
       if (e & 1) { ko[e >> 1] |= kb << 16; vo[e >> 1] |= vb << 16; } else { ko[e >> 1] = kb; vo[e >> 1] = vb; }
     }
-    *reinterpret_cast<uint4*>(p.k_out + row0 + static_cast<size_t>(tk) * rs) = make_uint4(ko[0], ko[1], ko[2], ko[3]);
-    *reinterpret_cast<uint4*>(p.v_out + row0 + static_cast<size_t>(tk) * rs) = make_uint4(vo[0], vo[1], vo[2], vo[3]);
+    st_stream(reinterpret_cast<uint4*>(p.k_out + row0 + static_cast<size_t>(tk) * rs), make_uint4(ko[0], ko[1], ko[2], ko[3]));
+    st_stream(reinterpret_cast<uint4*>(p.v_out + row0 + static_cast<size_t>(tk) * rs), make_uint4(vo[0], vo[1], vo[2], vo[3]));
   }
 }
 

@@ -171,8 +171,8 @@ __global__ __launch_bounds__(256) void move_rows_kernel(MoveRowsParams p) {
 #pragma unroll
     for (int u = 0; u < kMoveRowsUnroll; ++u) {
       if (ok[u]) {
-        kr[u] = *reinterpret_cast<const uint4*>((SCATTER ? p.packed_k + pack_off[u] : p.pool_k + pool_off[u]));
-        vr[u] = *reinterpret_cast<const uint4*>((SCATTER ? p.packed_v + pack_off[u] : p.pool_v + pool_off[u]));
+        kr[u] = ld_stream(reinterpret_cast<const uint4*>((SCATTER ? p.packed_k + pack_off[u] : p.pool_k + pool_off[u])));
+        vr[u] = ld_stream(reinterpret_cast<const uint4*>((SCATTER ? p.packed_v + pack_off[u] : p.pool_v + pool_off[u])));
       }
     }
 #pragma unroll

@@ -65,14 +65,14 @@ __global__ __launch_bounds__(kSampleThreads) void sample_stats_kernel(SamplePara
     for (int i = 0; i < kSamplePerThread / 4; ++i) {
       const int e = seg0 + (i * kSampleThreads + threadIdx.x) * 4;
       float4 v = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
-      if (e < p.vocab) v = *reinterpret_cast<const float4*>(row + e);
+      if (e < p.vocab) v = ld_stream(reinterpret_cast<const float4*>(row + e));
       x[4 * i] = v.x; x[4 * i + 1] = v.y; x[4 * i + 2] = v.z; x[4 * i + 3] = v.w;
     }
   } else {
 #pragma unroll
     for (int i = 0; i < kSamplePerThread; ++i) {
       const int e = seg0 + i * kSampleThreads + threadIdx.x;
-      x[i] = e < p.vocab ? row[e] : -INFINITY;
+      x[i] = e < p.vocab ? ld_stream(row + e) : -INFINITY;
     }
   }
   float m = -INFINITY;
