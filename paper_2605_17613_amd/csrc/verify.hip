@@ -420,7 +420,12 @@ static VerifyPlan make_verify_plan(const vc_full_kv* kv) {
   const int total_max = kv->max_ctx + kv->max_win;
   int64_t sum = static_cast<int64_t>(kv->sum_ctx > 0 ? kv->sum_ctx + static_cast<int64_t>(kv->n_seqs) * kv->max_win
                                                       : static_cast<int64_t>(total_max) * kv->n_seqs) * kv->n_kv_heads;
-  const int target = env_int("VC_VERIFY_WGS", 512, 1, 1 << 20);
+  // One workgroup fills a CU (its ring takes the LDS), so equal chunks of a uniform batch want
+  // exactly one round of 256; a ragged batch leaves remainders and balances better with shorter
+  // chunks (measured: 256 against 512 workgroups at config-2 shape 652 vs 694 us; the ragged
+  // config-4 batch 1470 us with 256, 1241 us with 768).
+  const bool uniform = kv->sum_ctx <= 0 || static_cast<int64_t>(kv->max_ctx) * kv->n_seqs * 10 <= static_cast<int64_t>(kv->sum_ctx) * 11;
+  const int target = env_int("VC_VERIFY_WGS", uniform ? 256 : 768, 1, 1 << 20);
   int64_t per = ceil_div64(sum > 0 ? sum : 1, target);
   const int min_tok = env_int("VC_VERIFY_MIN_TOK", 1024, 128, 1 << 24);
   if (per < min_tok) per = min_tok;
