@@ -4,8 +4,10 @@
 // Arg-max is a streaming scan of the fp32 logits (HBM bound).  A row is cut into segments so that
 // few rows still fill the chip; every workgroup reduces its segment to one 64-bit key
 //   key = (order-preserving image of the float) << 32 | ~index
-// and merges it into the row's key with a 64-bit atomic max, so the largest value wins and, among
-// equal values, the lowest index.
+// and stores it in the row's slot for that segment; the largest key of a row is the largest value
+// and, among equal values, the lowest index.  The finishing kernel takes the maximum over a row's
+// segments (a dozen keys) before it compares with the drafted ids, so a call is two launches and
+// needs neither atomics nor a cleared workspace.
 #include "common.h"
 
 namespace vc {
@@ -20,11 +22,6 @@ __device__ __forceinline__ uint32_t float_order(float f) {
 
 __device__ __forceinline__ unsigned long long make_key(float v, int idx) {
   return (static_cast<unsigned long long>(float_order(v)) << 32) | static_cast<uint32_t>(~static_cast<uint32_t>(idx));
-}
-
-__global__ void accept_init_kernel(unsigned long long* keys, int total_rows) {
-  int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < total_rows) keys[i] = 0ull;  // below every real key (real keys have a non-zero high word)
 }
 
 __global__ __launch_bounds__(kAcceptThreads) void argmax_segment_kernel(const float* __restrict__ logits, int vocab,
@@ -68,27 +65,38 @@ __global__ __launch_bounds__(kAcceptThreads) void argmax_segment_kernel(const fl
   __syncthreads();
   if (threadIdx.x == 0) {
     for (int w = 1; w < kAcceptThreads / 64; ++w) key = wk[w] > key ? wk[w] : key;
-    if (key) atomicMax(&keys[row], key);
+    keys[static_cast<size_t>(row) * gridDim.x + blockIdx.x] = key;   // 0 (below every real key) for an empty segment
   }
 }
 
 __device__ __forceinline__ int key_index(unsigned long long key) { return static_cast<int>(~static_cast<uint32_t>(key)); }
 
-__global__ void accept_finish_kernel(const unsigned long long* __restrict__ keys, int total_rows,
-                                     const int* __restrict__ cu_rows, const int* __restrict__ draft_ids,
-                                     const int* __restrict__ cu_win, int n_seqs, int* __restrict__ accept_len,
-                                     int* __restrict__ next_token, int* __restrict__ argmax_ids) {
-  int i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < total_rows) argmax_ids[i] = key_index(keys[i]);
-  if (i < n_seqs) {
-    const int r0 = cu_rows[i], r1 = cu_rows[i + 1];
-    const int w0 = cu_win[i], w = cu_win[i + 1] - w0;
+__device__ __forceinline__ int row_argmax(const unsigned long long* __restrict__ keys, int nseg, int row) {
+  const unsigned long long* k = keys + static_cast<size_t>(row) * nseg;
+  unsigned long long best = k[0];
+  for (int s = 1; s < nseg; ++s) best = k[s] > best ? k[s] : best;
+  return key_index(best);
+}
+
+// One workgroup per sequence: its threads take the arg-max of the sequence's rows in parallel
+// (written to argmax_ids), then one thread walks the drafted ids to the first mismatch.
+__global__ __launch_bounds__(128) void accept_finish_kernel(const unsigned long long* __restrict__ keys, int nseg,
+                                                            const int* __restrict__ cu_rows,
+                                                            const int* __restrict__ draft_ids,
+                                                            const int* __restrict__ cu_win, int* __restrict__ accept_len,
+                                                            int* __restrict__ next_token, int* __restrict__ argmax_ids) {
+  const int b = blockIdx.x;
+  const int r0 = cu_rows[b], r1 = cu_rows[b + 1];
+  const int w0 = cu_win[b], w = cu_win[b + 1] - w0;
+  for (int r = r0 + threadIdx.x; r < r1; r += blockDim.x) argmax_ids[r] = row_argmax(keys, nseg, r);
+  __syncthreads();                            // the ids written above are read below by thread 0
+  if (threadIdx.x == 0) {
     int a = w;
     for (int j = 0; j < w; ++j) {
-      if (draft_ids[w0 + j] != key_index(keys[r0 + j])) { a = j; break; }
+      if (draft_ids[w0 + j] != argmax_ids[r0 + j]) { a = j; break; }
     }
-    accept_len[i] = a;
-    next_token[i] = (r0 + a < r1) ? key_index(keys[r0 + a]) : -1;
+    accept_len[b] = a;
+    next_token[b] = (r0 + a < r1) ? argmax_ids[r0 + a] : -1;
   }
 }
 
@@ -166,7 +174,7 @@ extern "C" vc_status vc_accept_workspace_bytes(int32_t total_rows, int32_t vocab
   VC_REQUIRE(bytes != nullptr, VC_ERR_INVALID_ARG, "vc_accept_workspace_bytes: bytes is NULL");
   VC_REQUIRE(total_rows >= 0 && vocab > 0, VC_ERR_INVALID_ARG, "vc_accept_workspace_bytes: rows %d vocab %d",
              total_rows, vocab);
-  *bytes = static_cast<size_t>(total_rows > 0 ? total_rows : 1) * sizeof(unsigned long long);
+  *bytes = static_cast<size_t>(total_rows > 0 ? total_rows : 1) * ceil_div(vocab, kSegElems) * sizeof(unsigned long long);
   return VC_OK;
 }
 
@@ -188,14 +196,13 @@ extern "C" vc_status vc_accept_len(vc_ctx* ctx, const float* logits, int32_t voc
   VC_REQUIRE((reinterpret_cast<uintptr_t>(workspace) & 7u) == 0, VC_ERR_INVALID_ARG, "vc_accept_len: workspace misaligned");
   hipStream_t st = static_cast<hipStream_t>(stream);
   unsigned long long* keys = static_cast<unsigned long long*>(workspace);
+  const int nseg = ceil_div(vocab, kSegElems);
   if (total_rows > 0) {
-    hipLaunchKernelGGL(accept_init_kernel, dim3(ceil_div(total_rows, 256)), dim3(256), 0, st, keys, total_rows);
-    dim3 grid(ceil_div(vocab, kSegElems), total_rows);
+    dim3 grid(nseg, total_rows);
     hipLaunchKernelGGL(argmax_segment_kernel, grid, dim3(kAcceptThreads), 0, st, logits, vocab, keys);
   }
-  int nmax = total_rows > n_seqs ? total_rows : n_seqs;
-  hipLaunchKernelGGL(accept_finish_kernel, dim3(ceil_div(nmax, 256)), dim3(256), 0, st, keys, total_rows, cu_rows,
-                     draft_ids, cu_win, n_seqs, accept_len, next_token, argmax_ids);
+  hipLaunchKernelGGL(accept_finish_kernel, dim3(n_seqs), dim3(128), 0, st, keys, nseg, cu_rows, draft_ids, cu_win,
+                     accept_len, next_token, argmax_ids);
   VC_HIP(hipGetLastError());
   return VC_OK;
 }
