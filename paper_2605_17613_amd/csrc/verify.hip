@@ -30,7 +30,7 @@ struct VerifyParams {
   const int* cu_win;
   float* ws;
   int n_q_heads, n_kv_heads, g;
-  int chunk_tok, ns;   // ns = 4 * chunks of the longest sequence
+  int chunk_tok, ns;   // ns = chunks of the longest sequence (one partial per row and chunk)
   int seq0, chunk0, tok_hi;   // this launch: first sequence, first chunk, end of the token range
   float scale_log2e;
 };
@@ -310,13 +310,42 @@ __device__ __forceinline__ void verify_body(const VerifyParams& p, char* smem, i
     compute(j);
   }
 
+  // With two token slices per tile, the two waves that share a row group merge their states
+  // through LDS (the ring is idle now), so a workgroup leaves one partial per row and chunk.
+  if constexpr (NTG == 2) {
+    static_assert(RT == 1, "the slice merge is written for one row tile per wave");
+    constexpr int kStateFloats = 66;             // m, l, O[4][16] of one lane
+    float* xch = reinterpret_cast<float*>(smem) + rg * (kStateFloats * 64);
+    __syncthreads();                             // nobody reads tiles any more
+    if (tg == 1 && wave_rows) {
+      xch[lane] = m[0];
+      xch[64 + lane] = l[0];
+#pragma unroll
+      for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) xch[(2 + 16 * dt + i) * 64 + lane] = oacc[0][dt][i];
+    }
+    __syncthreads();
+    if (tg == 1) return;
+    if (wave_rows) {
+      const float m1 = xch[lane], l1 = xch[64 + lane];
+      const float mn = fmaxf(m[0], m1);
+      const float a0 = __builtin_amdgcn_exp2f(m[0] - mn), a1 = __builtin_amdgcn_exp2f(m1 - mn);
+      l[0] = l[0] * a0 + l1 * a1;
+#pragma unroll
+      for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) oacc[0][dt][i] = oacc[0][dt][i] * a0 + xch[(2 + 16 * dt + i) * 64 + lane] * a1;
+      m[0] = mn;
+    }
+  }
   if (!wave_rows) return;
 #pragma unroll
   for (int rt = 0; rt < RT; ++rt) {
     const float lt = l[rt] + __shfl_xor(l[rt], 32, 64);
     if (!row_ok[rt]) continue;
     const size_t grow = static_cast<size_t>(w0 + iw[rt]) * p.n_q_heads + kvh * p.g + hq[rt];
-    float* dst = p.ws + (grow * p.ns + chunk * 4 + tg) * kPartialFloats;
+    float* dst = p.ws + (grow * p.ns + chunk) * kPartialFloats;
     if (hh == 0) {
       dst[0] = m[rt];
       dst[1] = lt;
@@ -328,11 +357,8 @@ __device__ __forceinline__ void verify_body(const VerifyParams& p, char* smem, i
   }
 }
 
-// token slices per tile for a given row count; `wide` = the 4-wave kernel with 64 rows per wave
-__device__ __forceinline__ int tokens_split(int rows, bool wide) {
-  (void)wide;                                  // both kernels: two slices up to 128 rows, one above
-  return rows <= 128 ? 2 : 1;
-}
+// token slices per tile for a given row count: two up to 128 rows (4 row groups x 2 slices), one above
+__device__ __forceinline__ int tokens_split(int rows) { return rows <= 128 ? 2 : 1; }
 
 // 8 waves x 32 rows: windows with up to 128 rows per KV head (HBM bound)
 __global__ __launch_bounds__(512) void verify_kernel(VerifyParams p) {
@@ -342,20 +368,8 @@ __global__ __launch_bounds__(512) void verify_kernel(VerifyParams p) {
   if (w == 0) return;
   const int c0 = p.cu_ctx[b], N = p.cu_ctx[b + 1] - c0;
   if (chunk * p.chunk_tok >= min(N + w, p.tok_hi)) return;
-  if (tokens_split(w * p.g, false) == 2) verify_body<2, 1, 1>(p, smem, kvh, chunk, w0, w, c0, N);
+  if (tokens_split(w * p.g) == 2) verify_body<2, 1, 1>(p, smem, kvh, chunk, w0, w, c0, N);
   else verify_body<1, 1, 2>(p, smem, kvh, chunk, w0, w, c0, N);
-}
-
-// 4 waves x 64 rows: used when some window has more than 128 rows (matrix-core / LDS bound)
-__global__ __launch_bounds__(256) void verify_wide_kernel(VerifyParams p) {
-  extern __shared__ __attribute__((aligned(1024))) char smem[];
-  const int b = p.seq0 + blockIdx.z, kvh = blockIdx.y, chunk = p.chunk0 + blockIdx.x;
-  const int w0 = p.cu_win[b], w = p.cu_win[b + 1] - w0;
-  if (w == 0) return;
-  const int c0 = p.cu_ctx[b], N = p.cu_ctx[b + 1] - c0;
-  if (chunk * p.chunk_tok >= min(N + w, p.tok_hi)) return;
-  if (tokens_split(w * p.g, true) == 2) verify_body<2, 2, 1>(p, smem, kvh, chunk, w0, w, c0, N);
-  else verify_body<1, 2, 1>(p, smem, kvh, chunk, w0, w, c0, N);
 }
 
 struct VerifyMergeParams {
@@ -364,7 +378,7 @@ struct VerifyMergeParams {
   float* lse;
   const int* cu_ctx;
   const int* cu_win;
-  int n_seqs, n_q_heads, g, ns, chunk_tok, wide;
+  int n_seqs, n_q_heads, g, ns, chunk_tok;
 };
 
 // One workgroup of 128 threads per (window row, query head); slots are fetched eight at a time so
@@ -376,8 +390,7 @@ __global__ __launch_bounds__(128) void verify_merge_kernel(VerifyMergeParams p) 
   const int w = p.cu_win[b + 1] - p.cu_win[b];
   const int total = (p.cu_ctx[b + 1] - p.cu_ctx[b]) + w;
   const int nchunk = ceil_div_dev(total, p.chunk_tok);
-  const int ntg = tokens_split(w * p.g, p.wide != 0);
-  const int nsl = nchunk * ntg;
+  const int nsl = nchunk;
   const float* base = p.ws + (static_cast<size_t>(row) * p.n_q_heads + h) * p.ns * kPartialFloats;
   float mm = -INFINITY, acc = 0.f, lsum = 0.f;
   for (int s0 = 0; s0 < nsl; s0 += 8) {
@@ -385,8 +398,7 @@ __global__ __launch_bounds__(128) void verify_merge_kernel(VerifyMergeParams p) 
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       const int s = min(s0 + i, nsl - 1);
-      const int slot = ntg == 2 ? 4 * (s >> 1) + (s & 1) : 4 * s;
-      const float* pp = base + static_cast<size_t>(slot) * kPartialFloats;
+      const float* pp = base + static_cast<size_t>(s) * kPartialFloats;
       m8[i] = s0 + i < nsl ? pp[0] : -INFINITY;
       l8[i] = pp[1];
       o8[i] = pp[2 + d];
@@ -434,7 +446,7 @@ static VerifyPlan make_verify_plan(const vc_full_kv* kv) {
   if (kv->chunk_tokens > 0) per = kv->chunk_tokens;
   pl.chunk_tok = static_cast<int>(per);
   pl.nchunk = ceil_div(total_max > 0 ? total_max : 1, pl.chunk_tok);
-  pl.ns = 4 * pl.nchunk;
+  pl.ns = pl.nchunk;
   (void)lists;
   return pl;
 }
@@ -521,8 +533,6 @@ extern "C" vc_status vc_verify_attn_range(vc_ctx* ctx, const vc_full_kv* kv, con
   if (!lds_attr_set) {
     VC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(verify_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
                                kVerifyLds));
-    VC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(verify_wide_kernel),
-                               hipFuncAttributeMaxDynamicSharedMemorySize, kVerifyLds));
     lds_attr_set = true;
   }
   hipStream_t st = static_cast<hipStream_t>(stream);
@@ -544,13 +554,10 @@ extern "C" vc_status vc_verify_attn_range(vc_ctx* ctx, const vc_full_kv* kv, con
   const int hi = tok_end < total_max ? tok_end : total_max;
   const int nchunk = ceil_div(hi, pl.chunk_tok) - vp.chunk0;
   dim3 grid(nchunk, kv->n_kv_heads, seq_end - seq_begin);
-  // The 64-rows-per-wave variant halves the LDS traffic per flop but leaves one wave per SIMD;
-  // measured slower at every window (1781 vs 1363 us at w = 64, config-2 shape; 2503 us with two
-  // slices in flight, which spills), so it is opt-in.
-  const bool wide = env_int("VC_VERIFY_WIDE", 0, 0, 1) != 0;
+  // (A variant with 64 rows per wave halves the LDS traffic per flop but leaves one wave per SIMD;
+  // it measured slower at every window - 1781 vs 1363 us at w = 64, config-2 shape - and was dropped.)
   mark_begin(ctx, st);
-  if (wide) hipLaunchKernelGGL(verify_wide_kernel, grid, dim3(256), kVerifyLds, st, vp);
-  else hipLaunchKernelGGL(verify_kernel, grid, dim3(512), kVerifyLds, st, vp);
+  hipLaunchKernelGGL(verify_kernel, grid, dim3(512), kVerifyLds, st, vp);
   mark_end(ctx, st);
   VC_HIP(hipGetLastError());
   return VC_OK;
@@ -572,7 +579,6 @@ extern "C" vc_status vc_verify_finish(vc_ctx* ctx, const vc_full_kv* kv, const i
   mp.cu_win = cu_win;
   mp.n_seqs = kv->n_seqs; mp.n_q_heads = kv->n_q_heads; mp.g = kv->n_q_heads / kv->n_kv_heads; mp.ns = pl.ns;
   mp.chunk_tok = pl.chunk_tok;
-  mp.wide = env_int("VC_VERIFY_WIDE", 0, 0, 1);
   hipLaunchKernelGGL(verify_merge_kernel, dim3(kv->n_q_heads, total_win), dim3(128), 0, static_cast<hipStream_t>(stream), mp);
   VC_HIP(hipGetLastError());
   return VC_OK;
