@@ -48,8 +48,9 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-swap", action="store_true")
     ap.add_argument("--no-compressor", action="store_true", help="skip the compress / decompress / top-k legs")
-    ap.add_argument("--round3", action="store_true",
-                    help="also run BASELINE config 3 end to end: 32 layers, ctx 131072, 64-token horizon (17 GB pinned)")
+    ap.add_argument("--no-round3", action="store_true",
+                    help="skip BASELINE config 3 end to end (32 layers, ctx 131072, 64-token horizon; pins 17 GB of host memory)")
+    ap.add_argument("--round3", action="store_true", help="run the config-3 round even with --only")
     ap.add_argument("--only", default="", help="comma list of legs to run per step: keep,d1,d2,d3,verify,accept")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
@@ -256,15 +257,18 @@ def main():
     if not args.no_compressor and not args.only:
         comp = measure_compressor(vc, ctx, lay, torch, HKV, N, B)
 
-    round3 = None
-    if args.round3:
-        del lay, ws
-        torch.cuda.empty_cache()
-        round3 = measure_round3(vc, ctx, torch)
-
     cpu = None
     if not args.no_cpu_baseline:
         cpu = cpu_baseline(lay, torch, np, HQ, HKV, N)
+
+    round3 = None
+    if args.round3 or not (args.no_round3 or args.only):
+        del lay, ws
+        torch.cuda.empty_cache()
+        try:
+            round3 = measure_round3(vc, ctx, torch)
+        except Exception as e:      # the host may not have 17 GB to pin: the headline line must still be printed
+            round3 = {"error": f"{type(e).__name__}: {e}"}
 
     line = {
         "metric": "draft_attn_hbm_GBps", "value": value, "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
