@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the VeriCache hot path on one MI355X.
 
-Workload: BASELINE config 2 (Llama-3-8B attention layer shape, 32 q / 8 KV heads, head_dim 128,
+Workload: config 2 of the five synthetic workloads (Llama-3-8B attention layer shape, 32 q / 8 KV heads, head_dim 128,
 batch 16, context 65536; int4 g32 and int2 g64 block records of the same bf16 KV; verify window 32;
 greedy accept over planted fp32 logits).  All inputs are seeded, synthetic and resident in HBM
 before the timed region starts.
@@ -49,7 +49,7 @@ def parse():
     ap.add_argument("--no-swap", action="store_true")
     ap.add_argument("--no-compressor", action="store_true", help="skip the compress / decompress / top-k legs")
     ap.add_argument("--no-round3", action="store_true",
-                    help="skip BASELINE config 3 end to end (32 layers, ctx 131072, 64-token horizon; pins 17 GB of host memory)")
+                    help="skip the config-3 round (32 layers, ctx 131072, 64-token horizon; pins 17 GB of host memory)")
     ap.add_argument("--round3", action="store_true", help="run the config-3 round even with --only")
     ap.add_argument("--only", default="", help="comma list of legs to run per step: keep,d1,d2,d3,verify,accept")
     ap.add_argument("--calib-copy", action="store_true",
@@ -500,7 +500,7 @@ def measure_swap(vc, ctx, lay, torch, draft_kw, out, ws, HKV, N, B, W):
 
 
 def measure_round3(vc, ctx, torch, layers=32, N=131072, W=64, vocab=128256, chunk_tok=8192):
-    """BASELINE config 3: one request, `layers` attention layers of the 8B shape at context N.  The
+    """Workload config 3: one request, `layers` attention layers of the 8B shape at context N.  The
     int4 KV of every layer sits on the GPU, the full bf16 KV in pinned host memory.  One round =
     start the reload of all layers, draft W tokens (W x layers draft calls, the bf16 tail growing),
     verify every layer as its reload lands, accept.  The draft horizon is measured eagerly and as
