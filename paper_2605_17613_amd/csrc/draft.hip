@@ -305,7 +305,7 @@ struct DraftQuantParams {
   const uint8_t* blocks;
   const int* cu_blk;
   float* ws;
-  int n_q_heads, n_kv_heads, g, nquad;
+  int n_q_heads, n_kv_heads, g, npass;
   int bps, slot0, ns;
   float scale_log2e;
 };
@@ -372,14 +372,22 @@ __device__ __forceinline__ void u4_to_arr(const uint4& v, uint32_t (&a)[4]) {
 constexpr int kQuantSlots = 2;
 constexpr int kQuantRingBytes = 4 * kQuantSlots * kRecordBytes;   // per workgroup of 4 waves
 
-template <int BITS>
-__global__ __launch_bounds__(256, 3) void draft_quant_kernel(DraftQuantParams p) {
+// HPW = query heads per pass (the 16 MFMA columns are HPW heads x 16/HPW slots).  GQA ratios up to 4
+// use 4 heads x 4 slots, one slot per value channel group (int2 has two groups: slots repeat);
+// ratios of 5 to 8 use 8 heads x 2 slots so that the records are still read once for all heads -
+// for int4 a slot then carries two channel groups and scales its probabilities once per group.
+template <int BITS, int HPW>
+__global__ __launch_bounds__(256, (BITS == 4 && HPW == 8) ? 2 : 3) void draft_quant_kernel(DraftQuantParams p) {
   constexpr int TB = (BITS == 4) ? 32 : 64;   // tokens per block record
   constexpr int NT = TB / 16;                 // 16-token score tiles per record
   constexpr int NKS = TB / 32;                // 32-token k-steps of the output product per record
+  constexpr int NSLOT = 16 / HPW;             // column slots per head
+  constexpr int NG = 128 / TB;                // value channel groups (4 for int4, 2 for int2)
+  constexpr int GPS = NG > NSLOT ? NG / NSLOT : 1;   // channel groups a slot carries
+  constexpr int TPG = 8 / NG;                 // 16-channel output tiles per channel group
   extern __shared__ __attribute__((aligned(1024))) char ring[];
   const int b = blockIdx.z, sp = blockIdx.x;
-  const int kvh = blockIdx.y / p.nquad, quad = blockIdx.y % p.nquad;
+  const int kvh = blockIdx.y / p.npass, pass = blockIdx.y % p.npass;
   const int nb = p.cu_blk[b + 1] - p.cu_blk[b];
   const int blk0 = sp * p.bps;
   if (blk0 >= nb) return;
@@ -388,8 +396,11 @@ __global__ __launch_bounds__(256, 3) void draft_quant_kernel(DraftQuantParams p)
       p.blocks + (static_cast<size_t>(p.cu_blk[b]) * p.n_kv_heads + static_cast<size_t>(kvh) * nb) * kRecordBytes;
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int n = lane & 15, j = lane >> 4;     // n: column / operand row, j: k-block and D row block
-  const int slot = n >> 2, hq = n & 3;
-  const int G = (BITS == 4) ? slot : (slot & 1);   // value channel group this column carries
+  const int slot = n / HPW, hq = n % HPW;
+  // value channel group gi of this column's slot; the slot that carries group G, and G's index in it
+  auto group_of = [&](int gi) { return NG >= NSLOT ? slot * GPS + gi : slot % NG; };
+  auto slot_of = [](int G) { return NG >= NSLOT ? G / GPS : G; };
+  auto index_in_slot = [](int G) { return NG >= NSLOT ? G % GPS : 0; };
 
   // ---- the ring: source offsets of this lane's five 16-byte chunks, and the request itself ----
   uint32_t src_key[2];
@@ -420,7 +431,7 @@ __global__ __launch_bounds__(256, 3) void draft_quant_kernel(DraftQuantParams p)
     load_to_lds(rec + 1024, src_lin, dst + 3072);
     load_to_lds(rec + 2048, src_lin, dst + 4096);
   };
-  const int hloc = quad * 4 + hq;
+  const int hloc = pass * HPW + hq;
   const bool head_ok = hloc < p.g;
 
   uint32_t magic = 0x64006400u;
@@ -460,10 +471,11 @@ __global__ __launch_bounds__(256, 3) void draft_quant_kernel(DraftQuantParams p)
   // register index i of score tile T is token 4*T' + i of the word, see below
   float m_run = -INFINITY;                    // running maximum of this column's head (log2 domain)
   float l_part = 0.f;                         // this lane's share of sum 2^(s - m_run)
-  float4v oacc[8], ozero;
+  float4v oacc[8], ozero[GPS];
 #pragma unroll
   for (int dt = 0; dt < 8; ++dt) oacc[dt] = float4v{0.f, 0.f, 0.f, 0.f};
-  ozero = float4v{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int gi = 0; gi < GPS; ++gi) ozero[gi] = float4v{0.f, 0.f, 0.f, 0.f};
 
   // query with the field factor undone again, for the key-zero product
   uint32_t qnf[16];
@@ -516,19 +528,21 @@ __global__ __launch_bounds__(256, 3) void draft_quant_kernel(DraftQuantParams p)
 #pragma unroll
       for (int k = 0; k < 4; ++k) vsl[c][k] = v[k];
     }
-    uint32_t vsc[NKS][4], vzr[NKS][4];
+    uint32_t vsc[NKS][GPS][4], vzr[NKS][GPS][4];
 #pragma unroll
-    for (int a = 0; a < NKS; ++a) {
-      // value scale / zero of channel group G for the 8 tokens (TB/4)*j + 8a .. +7
-      const int off = 2 * (G * TB + (TB / 4) * j + 8 * a);
-      const u32x4v sv = lds_load_u32x4(rec + 4608 + off);
-      const u32x4v zv = lds_load_u32x4(rec + 4608 + 256 + off);
+    for (int a = 0; a < NKS; ++a)
 #pragma unroll
-      for (int k = 0; k < 4; ++k) {
-        vsc[a][k] = sv[k];
-        vzr[a][k] = zv[k];
+      for (int gi = 0; gi < GPS; ++gi) {
+        // value scale / zero of this slot's channel group gi for the 8 tokens (TB/4)*j + 8a .. +7
+        const int off = 2 * (group_of(gi) * TB + (TB / 4) * j + 8 * a);
+        const u32x4v sv = lds_load_u32x4(rec + 4608 + off);
+        const u32x4v zv = lds_load_u32x4(rec + 4608 + 256 + off);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          vsc[a][gi][k] = sv[k];
+          vzr[a][gi][k] = zv[k];
+        }
       }
-    }
     // the slot is free once those reads have returned: request the record kQuantSlots ahead
     wait_lds_reads();
     if (it + kQuantSlots < nrec) request(it + kQuantSlots);
@@ -585,9 +599,9 @@ __global__ __launch_bounds__(256, 3) void draft_quant_kernel(DraftQuantParams p)
 #pragma unroll
       for (int i = 0; i < 4; ++i) smax = fmaxf(smax, sacc[T][i]);
     if (__any(smax > m_run + kLazyMargin)) {
-      // agree on the new maximum among the 16 lanes of this head (all slots, all row blocks)
+      // agree on the new maximum among the lanes of this head (all slots, all row blocks)
       float mx = smax;
-      mx = fmaxf(mx, __shfl_xor(mx, 4, 64));
+      if constexpr (HPW == 4) mx = fmaxf(mx, __shfl_xor(mx, 4, 64));
       mx = fmaxf(mx, __shfl_xor(mx, 8, 64));
       mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
       mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
@@ -596,7 +610,8 @@ __global__ __launch_bounds__(256, 3) void draft_quant_kernel(DraftQuantParams p)
       l_part *= alpha;
 #pragma unroll
       for (int dt = 0; dt < 8; ++dt) oacc[dt] *= alpha;
-      ozero *= alpha;
+#pragma unroll
+      for (int gi = 0; gi < GPS; ++gi) ozero[gi] *= alpha;
       m_run = mn;
     }
     // probabilities, pre-divided by the field factor of the value code they will meet:
@@ -619,35 +634,38 @@ __global__ __launch_bounds__(256, 3) void draft_quant_kernel(DraftQuantParams p)
     }
 
     // ---------------- output ----------------
-    uint32_t pg[NKS][4];
+    uint32_t pg[NKS][GPS][4];
 #pragma unroll
-    for (int a = 0; a < NKS; ++a) {
-      uint32_t pz[4];
+    for (int a = 0; a < NKS; ++a)
 #pragma unroll
-      for (int k = 0; k < 4; ++k) {
-        pg[a][k] = as_u32(as_half2(pb[a][k]) * as_half2(vsc[a][k]));                            // p * sV / f
-        const int r = (BITS == 4) ? k : (4 * a + k);
-        pz[k] = as_u32(as_half2(pb[a][k]) * as_half2(finv[(BITS == 4) ? (r & 1) : (r & 3)]) * as_half2(vzr[a][k]));   // p * zV
+      for (int gi = 0; gi < GPS; ++gi) {
+        uint32_t pz[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          pg[a][gi][k] = as_u32(as_half2(pb[a][k]) * as_half2(vsc[a][gi][k]));                            // p * sV / f
+          const int r = (BITS == 4) ? k : (4 * a + k);
+          pz[k] = as_u32(as_half2(pb[a][k]) * as_half2(finv[(BITS == 4) ? (r & 1) : (r & 3)]) * as_half2(vzr[a][gi][k]));   // p * zV
+        }
+        ozero[gi] = mfma16(ones, pz, ozero[gi]);           // + sum_t p[t] zV[t][G]
+        ozero[gi] = mfma16(m1024, pg[a][gi], ozero[gi]);   // - 1024 * sum_t p'[t]: cancels the code offset
       }
-      ozero = mfma16(ones, pz, ozero);        // + sum_t p[t] zV[t][G]
-      ozero = mfma16(m1024, pg[a], ozero);    // - 1024 * sum_t p'[t]: cancels the code offset
-    }
 #pragma unroll
     for (int c = 0; c < 2; ++c) {
 #pragma unroll
       for (int qq = 0; qq < 4; ++qq) {
         const int dt = 4 * c + qq;
+        const int gi = index_in_slot(dt / TPG);   // which of its groups a column uses for this tile
         if constexpr (BITS == 4) {
           uint32_t va[4];
           unpack_i4(vsl[c][qq], magic, va);
-          oacc[dt] = mfma16(va, pg[0], oacc[dt]);
+          oacc[dt] = mfma16(va, pg[0][gi], oacc[dt]);
         } else {
           uint32_t v8[8];
           unpack_i2(vsl[c][qq], magic, v8);
 #pragma unroll
           for (int a = 0; a < NKS; ++a) {
             const uint32_t va[4] = {v8[4 * a], v8[4 * a + 1], v8[4 * a + 2], v8[4 * a + 3]};
-            oacc[dt] = mfma16(va, pg[a], oacc[dt]);
+            oacc[dt] = mfma16(va, pg[a][gi], oacc[dt]);
           }
         }
       }
@@ -655,39 +673,43 @@ __global__ __launch_bounds__(256, 3) void draft_quant_kernel(DraftQuantParams p)
   }
 
   // ---------------- end of split: wave state -> LDS -> merged partial ----------------
-  __shared__ float st[4][4][kPartialFloats];
+  wait_vm<0>();                               // nothing may land in the ring any more: it is reused below
+  constexpr int kWaveFloats = kQuantSlots * kRecordBytes / 4;
+  float* st = reinterpret_cast<float*>(ring);                 // [wave][head][kPartialFloats], each wave in its own ring
   {
-    // the 16 lanes of a head agree on m_run; sum l over the row blocks j (slots are replicas)
+    float* mine = st + wave * kWaveFloats + hq * kPartialFloats;
+    // the lanes of a head agree on m_run; sum l over the row blocks j (slots are replicas)
     float lsum = l_part;
     lsum += __shfl_xor(lsum, 16, 64);
     lsum += __shfl_xor(lsum, 32, 64);
     if (j == 0 && slot == 0) {
-      st[wave][hq][0] = m_run;
-      st[wave][hq][1] = lsum;
+      mine[0] = m_run;
+      mine[1] = lsum;
     }
     // output tile dt (channels 16dt..16dt+15) is valid in the columns whose slot carries its group
 #pragma unroll
     for (int dt = 0; dt < 8; ++dt) {
-      const int Gd = (BITS == 4) ? (dt >> 1) : (dt >> 2);
-      if (slot == Gd) {
+      const int Gd = dt / TPG;
+      if (slot == slot_of(Gd)) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) st[wave][hq][2 + 16 * dt + 4 * j + i] = oacc[dt][i] + ozero[i];
+        for (int i = 0; i < 4; ++i) mine[2 + 16 * dt + 4 * j + i] = oacc[dt][i] + ozero[index_in_slot(Gd)][i];
       }
     }
   }
   __syncthreads();
   const int oslot = p.slot0 + sp;
-  for (int idx = threadIdx.x; idx < 4 * kHeadDim; idx += 256) {
+  for (int idx = threadIdx.x; idx < HPW * kHeadDim; idx += 256) {
     const int i = idx >> 7, d = idx & 127;
-    const int hl = quad * 4 + i;
+    const int hl = pass * HPW + i;
     if (hl >= p.g) continue;
-    const float mm = fmaxf(fmaxf(st[0][i][0], st[1][i][0]), fmaxf(st[2][i][0], st[3][i][0]));
+    const float* s0 = st + i * kPartialFloats;
+    const float mm = fmaxf(fmaxf(s0[0], s0[kWaveFloats]), fmaxf(s0[2 * kWaveFloats], s0[3 * kWaveFloats]));
     float acc = 0.f, lsum = 0.f;
 #pragma unroll
     for (int w = 0; w < 4; ++w) {
-      const float a = exp2_diff(st[w][i][0], mm);
-      acc = fmaf(a, st[w][i][2 + d], acc);
-      lsum = fmaf(a, st[w][i][1], lsum);
+      const float a = exp2_diff(s0[w * kWaveFloats], mm);
+      acc = fmaf(a, s0[w * kWaveFloats + 2 + d], acc);
+      lsum = fmaf(a, s0[w * kWaveFloats + 1], lsum);
     }
     float* dst = p.ws + ((static_cast<size_t>(b) * p.n_q_heads + kvh * p.g + hl) * p.ns + oslot) * kPartialFloats;
     dst[2 + d] = acc;
@@ -932,8 +954,8 @@ static DraftPlan make_plan(const vc_comp_kv* kv) {
   pl.split_a = pick_chunk(static_cast<int64_t>(kv->sum_keep) * kv->n_kv_heads, kv->max_keep, lists, 128,
                           env_int("VC_DRAFT_MIN_TOK", 256, 128, 1 << 20), target_a);
   pl.s1 = has_a ? ceil_div(kv->max_keep, pl.split_a) : 0;
-  const int nquad = ceil_div(g, 4);
-  pl.bps = pick_chunk(static_cast<int64_t>(kv->sum_blk) * kv->n_kv_heads * nquad, kv->max_blk, lists * nquad, 4,
+  const int npass = ceil_div(g, g > 4 ? 8 : 4);
+  pl.bps = pick_chunk(static_cast<int64_t>(kv->sum_blk) * kv->n_kv_heads * npass, kv->max_blk, lists * npass, 4,
                       env_int("VC_DRAFT_MIN_BLK", 16, 4, 1 << 20), target_b);
   pl.s2 = has_b ? ceil_div(kv->max_blk, pl.bps) : 0;
   pl.ns = pl.s1 + pl.s2;
@@ -1037,12 +1059,15 @@ extern "C" vc_status vc_draft_attn(vc_ctx* ctx, const vc_comp_kv* kv, const void
     qp.cu_blk = kv->cu_blk;
     qp.ws = ws;
     qp.n_q_heads = kv->n_q_heads; qp.n_kv_heads = kv->n_kv_heads; qp.g = g;
-    qp.nquad = ceil_div(g, 4);
+    const int hpw = g > 4 ? 8 : 4;
+    qp.npass = ceil_div(g, hpw);
     qp.bps = pl.bps; qp.slot0 = pl.s1; qp.ns = pl.ns;
     qp.scale_log2e = sl2;
-    dim3 grid(pl.s2, kv->n_kv_heads * qp.nquad, kv->n_seqs);
-    if (kv->bits == 4) hipLaunchKernelGGL(draft_quant_kernel<4>, grid, dim3(256), kQuantRingBytes, st, qp);
-    else hipLaunchKernelGGL(draft_quant_kernel<2>, grid, dim3(256), kQuantRingBytes, st, qp);
+    dim3 grid(pl.s2, kv->n_kv_heads * qp.npass, kv->n_seqs);
+    if (kv->bits == 4 && hpw == 4) hipLaunchKernelGGL((draft_quant_kernel<4, 4>), grid, dim3(256), kQuantRingBytes, st, qp);
+    else if (kv->bits == 4) hipLaunchKernelGGL((draft_quant_kernel<4, 8>), grid, dim3(256), kQuantRingBytes, st, qp);
+    else if (hpw == 4) hipLaunchKernelGGL((draft_quant_kernel<2, 4>), grid, dim3(256), kQuantRingBytes, st, qp);
+    else hipLaunchKernelGGL((draft_quant_kernel<2, 8>), grid, dim3(256), kQuantRingBytes, st, qp);
   }
   mark_end(ctx, st);
   DraftMergeParams mp{};

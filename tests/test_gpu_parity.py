@@ -56,7 +56,7 @@ def test_draft_bf16_many_splits(lib, ctx):
 
 # ------------------------------------------------------------------ draft, block records
 @pytest.mark.parametrize("bits", [4, 2])
-@pytest.mark.parametrize("hq,hkv", [(8, 2), (2, 2), (16, 2), (6, 2)])
+@pytest.mark.parametrize("hq,hkv", [(8, 2), (2, 2), (16, 2), (6, 2), (10, 2), (32, 2), (14, 2)])
 def test_draft_quant(lib, ctx, bits, hq, hkv):
     tb = synth.tokens_per_block(bits)
     lay = synth.make_layer(20 + bits, DEV, ctx_len=[tb * 37, tb, tb * 8 + 5], n_q_heads=hq, n_kv_heads=hkv,
