@@ -937,6 +937,11 @@ static int pick_chunk(int64_t sum_units, int max_units, int lists, int unit, int
   return static_cast<int>(per);
 }
 
+// Query heads per pass of the record kernel: int4 takes 4 heads x 4 slots up to a GQA ratio of 4
+// (one slot per channel group, three workgroups per CU) and 8 x 2 above; int2 has only two channel
+// groups, so 8 x 2 wastes no column and measured 3-4 % faster at every ratio.
+static int heads_per_pass(int bits, int g) { return (bits == 2 || g > 4) ? 8 : 4; }
+
 static DraftPlan make_plan(const vc_comp_kv* kv) {
   DraftPlan pl{};
   const int g = kv->n_q_heads / kv->n_kv_heads;
@@ -954,7 +959,7 @@ static DraftPlan make_plan(const vc_comp_kv* kv) {
   pl.split_a = pick_chunk(static_cast<int64_t>(kv->sum_keep) * kv->n_kv_heads, kv->max_keep, lists, 128,
                           env_int("VC_DRAFT_MIN_TOK", 256, 128, 1 << 20), target_a);
   pl.s1 = has_a ? ceil_div(kv->max_keep, pl.split_a) : 0;
-  const int npass = ceil_div(g, g > 4 ? 8 : 4);
+  const int npass = ceil_div(g, heads_per_pass(kv->bits, g));
   pl.bps = pick_chunk(static_cast<int64_t>(kv->sum_blk) * kv->n_kv_heads * npass, kv->max_blk, lists * npass, 4,
                       env_int("VC_DRAFT_MIN_BLK", 16, 4, 1 << 20), target_b);
   pl.s2 = has_b ? ceil_div(kv->max_blk, pl.bps) : 0;
@@ -1059,7 +1064,7 @@ extern "C" vc_status vc_draft_attn(vc_ctx* ctx, const vc_comp_kv* kv, const void
     qp.cu_blk = kv->cu_blk;
     qp.ws = ws;
     qp.n_q_heads = kv->n_q_heads; qp.n_kv_heads = kv->n_kv_heads; qp.g = g;
-    const int hpw = g > 4 ? 8 : 4;
+    const int hpw = heads_per_pass(kv->bits, g);
     qp.npass = ceil_div(g, hpw);
     qp.bps = pl.bps; qp.slot0 = pl.s1; qp.ns = pl.ns;
     qp.scale_log2e = sl2;
