@@ -381,45 +381,66 @@ struct VerifyMergeParams {
   int n_seqs, n_q_heads, g, ns, chunk_tok;
 };
 
-// One workgroup of 128 threads per (window row, query head); slots are fetched eight at a time so
-// that a launch costs about one memory round trip.
-__global__ __launch_bounds__(128) void verify_merge_kernel(VerifyMergeParams p) {
-  const int row = blockIdx.y, h = blockIdx.x, d = threadIdx.x;
-  int b = 0;
-  while (b + 1 < p.n_seqs && p.cu_win[b + 1] <= row) ++b;
+// One workgroup of 256 threads per window row and 8 query heads: thread (half, d) merges channel d
+// of 4 heads, with the partials of all four requested before any is consumed - the kernel is pure
+// latency, so the fewer, fatter workgroups finish in one resident round.
+constexpr int kMergeHeads = 4;
+
+__global__ __launch_bounds__(256) void verify_merge_kernel(VerifyMergeParams p) {
+  const int row = blockIdx.y, d = threadIdx.x & 127;
+  const int h0 = (blockIdx.x * 2 + (threadIdx.x >> 7)) * kMergeHeads;
+  if (h0 >= p.n_q_heads) return;
+  int b = 0;                                   // the sequence that owns this window row: last b with cu_win[b] <= row
+  for (int hi = p.n_seqs; hi - b > 1;) {
+    const int mid = (b + hi) >> 1;
+    if (p.cu_win[mid] <= row) b = mid; else hi = mid;
+  }
   const int w = p.cu_win[b + 1] - p.cu_win[b];
   const int total = (p.cu_ctx[b + 1] - p.cu_ctx[b]) + w;
-  const int nchunk = ceil_div_dev(total, p.chunk_tok);
-  const int nsl = nchunk;
-  const float* base = p.ws + (static_cast<size_t>(row) * p.n_q_heads + h) * p.ns * kPartialFloats;
-  float mm = -INFINITY, acc = 0.f, lsum = 0.f;
-  for (int s0 = 0; s0 < nsl; s0 += 8) {
-    float m8[8], l8[8], o8[8];
+  const int nsl = ceil_div_dev(total, p.chunk_tok);
+  float mm[kMergeHeads], acc[kMergeHeads], lsum[kMergeHeads];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const int s = min(s0 + i, nsl - 1);
-      const float* pp = base + static_cast<size_t>(s) * kPartialFloats;
-      m8[i] = s0 + i < nsl ? pp[0] : -INFINITY;
-      l8[i] = pp[1];
-      o8[i] = pp[2 + d];
+  for (int k = 0; k < kMergeHeads; ++k) { mm[k] = -INFINITY; acc[k] = 0.f; lsum[k] = 0.f; }
+  for (int s0 = 0; s0 < nsl; s0 += 4) {
+    float m4[kMergeHeads][4], l4[kMergeHeads][4], o4[kMergeHeads][4];
+#pragma unroll
+    for (int k = 0; k < kMergeHeads; ++k) {
+      const int h = min(h0 + k, p.n_q_heads - 1);
+      const float* base = p.ws + (static_cast<size_t>(row) * p.n_q_heads + h) * p.ns * kPartialFloats;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int s = min(s0 + i, nsl - 1);
+        const float* pp = base + static_cast<size_t>(s) * kPartialFloats;
+        m4[k][i] = s0 + i < nsl ? pp[0] : -INFINITY;
+        l4[k][i] = pp[1];
+        o4[k][i] = pp[2 + d];
+      }
     }
-    float mn = mm;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) mn = fmaxf(mn, m8[i]);
-    const float alpha = exp2_diff(mm, mn);
-    acc *= alpha;
-    lsum *= alpha;
+    for (int k = 0; k < kMergeHeads; ++k) {
+      float mn = mm[k];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      const float a = exp2_diff(m8[i], mn);
-      acc = fmaf(a, o8[i], acc);
-      lsum = fmaf(a, l8[i], lsum);
+      for (int i = 0; i < 4; ++i) mn = fmaxf(mn, m4[k][i]);
+      const float alpha = exp2_diff(mm[k], mn);
+      acc[k] *= alpha;
+      lsum[k] *= alpha;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const float a = exp2_diff(m4[k][i], mn);
+        acc[k] = fmaf(a, o4[k][i], acc[k]);
+        lsum[k] = fmaf(a, l4[k][i], lsum[k]);
+      }
+      mm[k] = mn;
     }
-    mm = mn;
   }
-  const float o = lsum > 0.f ? acc / lsum : 0.f;
-  p.out[(static_cast<size_t>(row) * p.n_q_heads + h) * kHeadDim + d] = static_cast<uint16_t>(float_to_bf16_bits(o));
-  if (p.lse && d == 0) p.lse[static_cast<size_t>(row) * p.n_q_heads + h] = lsum > 0.f ? (mm + log2f(lsum)) * kLn2 : -INFINITY;
+#pragma unroll
+  for (int k = 0; k < kMergeHeads; ++k) {
+    const int h = h0 + k;
+    if (h >= p.n_q_heads) break;
+    const float o = lsum[k] > 0.f ? acc[k] / lsum[k] : 0.f;
+    p.out[(static_cast<size_t>(row) * p.n_q_heads + h) * kHeadDim + d] = static_cast<uint16_t>(float_to_bf16_bits(o));
+    if (p.lse && d == 0) p.lse[static_cast<size_t>(row) * p.n_q_heads + h] = lsum[k] > 0.f ? (mm[k] + log2f(lsum[k])) * kLn2 : -INFINITY;
+  }
 }
 
 struct VerifyPlan {
@@ -579,7 +600,8 @@ extern "C" vc_status vc_verify_finish(vc_ctx* ctx, const vc_full_kv* kv, const i
   mp.cu_win = cu_win;
   mp.n_seqs = kv->n_seqs; mp.n_q_heads = kv->n_q_heads; mp.g = kv->n_q_heads / kv->n_kv_heads; mp.ns = pl.ns;
   mp.chunk_tok = pl.chunk_tok;
-  hipLaunchKernelGGL(verify_merge_kernel, dim3(kv->n_q_heads, total_win), dim3(128), 0, static_cast<hipStream_t>(stream), mp);
+  hipLaunchKernelGGL(verify_merge_kernel, dim3(ceil_div(kv->n_q_heads, 2 * kMergeHeads), total_win), dim3(256), 0,
+                     static_cast<hipStream_t>(stream), mp);
   VC_HIP(hipGetLastError());
   return VC_OK;
 }
