@@ -39,8 +39,8 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=5)
-    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--steps", type=int, default=8)
+    ap.add_argument("--warmup", type=int, default=4)
     ap.add_argument("--batch", type=int, default=16, help="sequences (config 2: 16)")
     ap.add_argument("--ctx", type=int, default=65536, help="context tokens (config 2: 65536)")
     ap.add_argument("--window", type=int, default=32)
