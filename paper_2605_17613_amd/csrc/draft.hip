@@ -377,7 +377,7 @@ constexpr int kQuantRingBytes = 4 * kQuantSlots * kRecordBytes;   // per workgro
 // ratios of 5 to 8 use 8 heads x 2 slots so that the records are still read once for all heads -
 // for int4 a slot then carries two channel groups and scales its probabilities once per group.
 template <int BITS, int HPW>
-__global__ __launch_bounds__(256, (BITS == 4 && HPW == 8) ? 2 : 3) void draft_quant_kernel(DraftQuantParams p) {
+__global__ __launch_bounds__(256, 3) void draft_quant_kernel(DraftQuantParams p) {
   constexpr int TB = (BITS == 4) ? 32 : 64;   // tokens per block record
   constexpr int NT = TB / 16;                 // 16-token score tiles per record
   constexpr int NKS = TB / 32;                // 32-token k-steps of the output product per record
