@@ -135,7 +135,9 @@ typedef struct {
 } vc_full_kv;
 
 /* Verify attention (paper section 4.1 step 2).  Sequence b brings w_b = cu_win[b+1]-cu_win[b]
- * drafted positions (w_b * n_q_heads / n_kv_heads <= 256, i.e. w_b <= 64 at a GQA ratio of 4; 0 allowed).  Window row i of head h attends to the sequence's
+ * drafted positions (0 allowed; w_b * n_q_heads / n_kv_heads <= 4096 rows per KV head - up to 256 rows, i.e.
+ * w_b <= 64 at a GQA ratio of 4 or 32 at a ratio of 8, the full KV is streamed once; beyond that once per
+ * 256 rows).  Window row i of head h attends to the sequence's
  * full KV and to window rows 0..i (its own position included):
  *   q_win         device bf16 [sum w, n_q_heads, 128]
  *   k_win, v_win  device bf16 pools [sum w, n_kv_heads, 128]

@@ -32,6 +32,7 @@ struct VerifyParams {
   int n_q_heads, n_kv_heads, g;
   int chunk_tok, ns;   // ns = chunks of the longest sequence (one partial per row and chunk)
   int seq0, chunk0, tok_hi;   // this launch: first sequence, first chunk, end of the token range
+  int nrb;                    // row blocks of 256 rows per (sequence, KV head); above one, K/V are streamed once per block
   float scale_log2e;
 };
 
@@ -78,7 +79,7 @@ __device__ __forceinline__ int swz(int row, int chunk) { return row * 256 + ((ch
 // every wave has rows, i.e. above 128 rows, where the kernel is matrix-core and LDS bound).
 template <int NTG, int RT, int SUB>
 __device__ __forceinline__ void verify_body(const VerifyParams& p, char* smem, int kvh, int chunk, int w0, int w,
-                                            int c0, int N) {
+                                            int c0, int N, int row0) {
   constexpr int NW = 8 / RT;
   constexpr int NRG = NW / NTG;
   constexpr int TT = 32 * NTG * SUB;           // tokens per tile
@@ -88,7 +89,7 @@ __device__ __forceinline__ void verify_body(const VerifyParams& p, char* smem, i
   constexpr int LPT = TT / (4 * NW);           // 1 KB wave-loads per matrix per wave per tile
   constexpr int DEPTH = NSTAGE - 1;            // tiles in flight
   static_assert(NSTAGE >= 3 && NSTAGE <= 8 && LPT >= 1, "ring geometry");
-  const int R = w * p.g;
+  const int R = w * p.g;                       // rows of the (sequence, KV head); this workgroup owns row0 .. row0 + 255
   const int total = N + w;
   const int t_begin = chunk * p.chunk_tok;
   const int t_end = min(min(total, p.tok_hi), t_begin + p.chunk_tok);
@@ -96,14 +97,14 @@ __device__ __forceinline__ void verify_body(const VerifyParams& p, char* smem, i
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int rg = wave % NRG, tg = wave / NRG;
   const int n = lane & 31, hh = lane >> 5;
-  const bool wave_rows = rg * 32 * RT < R;
+  const bool wave_rows = row0 + rg * 32 * RT < R;
 
   int iw[RT], hq[RT];
   bool row_ok[RT];
   bf16x8v qb[RT][8];
 #pragma unroll
   for (int rt = 0; rt < RT; ++rt) {
-    const int r = (rg * RT + rt) * 32 + n;
+    const int r = row0 + (rg * RT + rt) * 32 + n;
     row_ok[rt] = r < R;
     const int rc = row_ok[rt] ? r : R - 1;
     iw[rt] = rc / p.g;
@@ -363,13 +364,14 @@ __device__ __forceinline__ int tokens_split(int rows) { return rows <= 128 ? 2 :
 // 8 waves x 32 rows: windows with up to 128 rows per KV head (HBM bound)
 __global__ __launch_bounds__(512) void verify_kernel(VerifyParams p) {
   extern __shared__ __attribute__((aligned(1024))) char smem[];
-  const int b = p.seq0 + blockIdx.z, kvh = blockIdx.y, chunk = p.chunk0 + blockIdx.x;
+  const int b = p.seq0 + blockIdx.z, kvh = blockIdx.y / p.nrb, chunk = p.chunk0 + blockIdx.x;
+  const int row0 = (blockIdx.y % p.nrb) * 256;
   const int w0 = p.cu_win[b], w = p.cu_win[b + 1] - w0;
-  if (w == 0) return;
+  if (row0 >= w * p.g) return;
   const int c0 = p.cu_ctx[b], N = p.cu_ctx[b + 1] - c0;
   if (chunk * p.chunk_tok >= min(N + w, p.tok_hi)) return;
-  if (tokens_split(w * p.g) == 2) verify_body<2, 1, 1>(p, smem, kvh, chunk, w0, w, c0, N);
-  else verify_body<1, 1, 2>(p, smem, kvh, chunk, w0, w, c0, N);
+  if (tokens_split(min(256, w * p.g - row0)) == 2) verify_body<2, 1, 1>(p, smem, kvh, chunk, w0, w, c0, N, row0);
+  else verify_body<1, 1, 2>(p, smem, kvh, chunk, w0, w, c0, N, row0);
 }
 
 struct VerifyMergeParams {
@@ -481,8 +483,9 @@ static vc_status check_full(const vc_full_kv* kv, const char* who) {
   VC_REQUIRE(kv->max_ctx >= 0 && kv->max_win >= 0 && kv->sum_ctx >= 0, VC_ERR_INVALID_ARG, "%s: negative count", who);
   VC_REQUIRE(kv->chunk_tokens >= 0 && kv->chunk_tokens % 128 == 0, VC_ERR_INVALID_ARG,
              "%s: chunk_tokens %d is not a multiple of 128", who, kv->chunk_tokens);
-  VC_REQUIRE(kv->max_win * (kv->n_q_heads / kv->n_kv_heads) <= 256, VC_ERR_UNSUPPORTED,
-             "%s: window %d x GQA ratio %d exceeds 256 rows", who, kv->max_win, kv->n_q_heads / kv->n_kv_heads);
+  VC_REQUIRE(static_cast<int64_t>(kv->max_win) * (kv->n_q_heads / kv->n_kv_heads) <= 4096, VC_ERR_UNSUPPORTED,
+             "%s: window %d x GQA ratio %d exceeds 4096 rows", who, kv->max_win, kv->n_q_heads / kv->n_kv_heads);
+  VC_REQUIRE(kv->n_q_heads / kv->n_kv_heads <= 256, VC_ERR_UNSUPPORTED, "%s: GQA ratio above 256", who);
   VC_REQUIRE(kv->n_seqs <= 65535 && kv->n_kv_heads <= 65535 && kv->n_q_heads <= 65535, VC_ERR_UNSUPPORTED,
              "%s: batch too large for one launch", who);
   VC_REQUIRE(kv->cu_ctx != nullptr, VC_ERR_INVALID_ARG, "%s: cu_ctx is NULL", who);
@@ -574,7 +577,8 @@ extern "C" vc_status vc_verify_attn_range(vc_ctx* ctx, const vc_full_kv* kv, con
   vp.scale_log2e = softmax_scale * kLog2e;
   const int hi = tok_end < total_max ? tok_end : total_max;
   const int nchunk = ceil_div(hi, pl.chunk_tok) - vp.chunk0;
-  dim3 grid(nchunk, kv->n_kv_heads, seq_end - seq_begin);
+  vp.nrb = ceil_div(kv->max_win * vp.g, 256);
+  dim3 grid(nchunk, kv->n_kv_heads * vp.nrb, seq_end - seq_begin);
   // (A variant with 64 rows per wave halves the LDS traffic per flop but leaves one wave per SIMD;
   // it measured slower at every window - 1781 vs 1363 us at w = 64, config-2 shape - and was dropped.)
   mark_begin(ctx, st);

@@ -75,15 +75,15 @@ def test_draft_workspace_grows_with_work_and_covers_every_split():
 def test_verify_and_accept_host_validation():
     lib = vc.load()
     d = B.vc_full_kv()
-    d.n_seqs, d.n_q_heads, d.n_kv_heads, d.head_dim, d.max_ctx, d.max_win = 2, 8, 2, 128, 1000, 65
+    d.n_seqs, d.n_q_heads, d.n_kv_heads, d.head_dim, d.max_ctx, d.max_win = 2, 8, 2, 128, 1000, 1025
     d.k, d.v, d.cu_ctx = 0x1000, 0x2000, 0x3000
     n = C.c_size_t()
-    assert lib.vc_verify_workspace_bytes(C.byref(d), 10, C.byref(n)) == B.VC_ERR_UNSUPPORTED   # window above 64
+    assert lib.vc_verify_workspace_bytes(C.byref(d), 10, C.byref(n)) == B.VC_ERR_UNSUPPORTED   # more than 4096 rows per KV head
     d.max_win = 64
     assert lib.vc_verify_workspace_bytes(C.byref(d), 10, C.byref(n)) == B.VC_OK and n.value >= 10 * 8 * 130 * 4
     d.cu_ctx = None
     assert lib.vc_verify_workspace_bytes(C.byref(d), 10, C.byref(n)) == B.VC_ERR_INVALID_ARG
-    assert lib.vc_accept_workspace_bytes(64, 128256, C.byref(n)) == B.VC_OK and n.value == 64 * 8
+    assert lib.vc_accept_workspace_bytes(64, 128256, C.byref(n)) == B.VC_OK and n.value == 64 * 16 * 8   # one key per row and 8192-logit segment
     assert lib.vc_accept_workspace_bytes(64, 0, C.byref(n)) == B.VC_ERR_INVALID_ARG
     # calls that need a context reject a NULL one without touching the device
     assert lib.vc_swap_sync(None) == B.VC_ERR_INVALID_ARG
