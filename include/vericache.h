@@ -126,7 +126,12 @@ vc_status vc_draft_attn(vc_ctx* ctx, const vc_comp_kv* kv, const void* q, float 
 typedef struct {
   int32_t n_seqs, n_q_heads, n_kv_heads, head_dim;
   int32_t max_ctx, max_win;
-  int32_t sum_ctx;         /* host hint: sum of context lengths (0 = unknown); load balance only */
+  int32_t sum_ctx;         /* host hint: sum of context lengths (0 = unknown); load balance only.  A batch
+                              whose sum is well below n_seqs * max_ctx is cut into shorter chunks, and a
+                              large one (up to 512 sequences) is verified from a work list that a small
+                              kernel builds in the workspace, by one workgroup per CU.  Results do not
+                              depend on the hint; the workspace size does, so pass the same value to
+                              every call of one verify. */
   int32_t chunk_tokens;    /* tokens per workgroup chunk (a multiple of 128), 0 = the library picks;
                               set it to the swap-in chunk length to verify chunk by chunk */
   const void* k;           /* device bf16 pools; sequence b owns rows cu_ctx[b] .. cu_ctx[b+1]-1 */

@@ -1,0 +1,99 @@
+"""Ragged verify launches that run from the device-built work list (pieces of per-sequence length
+taken off a queue by one workgroup per CU): results against the oracle, streamed launches against
+the one-shot call bit for bit, and the walk over every (sequence, chunk) that replaces a list too
+long to hold.  VC_VERIFY_LIST_MIN = 0 sends these small batches down the path large ones take."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2605_17613_amd import synth
+from tests import helpers as H
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+@pytest.fixture(scope="module")
+def ctx(lib):
+    c = lib.Context(0)
+    yield c
+    c.close()
+
+
+def _kv(lay, ctx_len, win, **extra):
+    return dict(k=lay.k_full, v=lay.v_full, cu_ctx=lay.cu_ctx, max_ctx=max(ctx_len), max_win=max(win),
+                n_seqs=len(ctx_len), **extra)
+
+
+@pytest.mark.parametrize("ctx_len,win,hq,hkv", [
+    ([5000, 2048, 700, 9000], [16, 5, 33, 64], 8, 2),           # rows 64, 20, 132, 256: both cost classes
+    ([12000, 300, 0, 4100, 6000, 2500], [40, 3, 7, 0, 64, 1], 16, 4),   # an empty context and an empty window
+    ([3000, 20000], [80, 9], 8, 2),                             # 320 rows: two row blocks per KV head
+])
+def test_worklist_verify_matches_oracle(lib, ctx, monkeypatch, ctx_len, win, hq, hkv):
+    monkeypatch.setenv("VC_VERIFY_LIST_MIN", "0")
+    lay = synth.make_layer(95, DEV, ctx_len=ctx_len, n_q_heads=hq, n_kv_heads=hkv, win=win)
+    kv = _kv(lay, ctx_len, win, sum_ctx=sum(ctx_len))
+    tw = lay.q_win.shape[0]
+    nbytes = lib.vc_verify_workspace_bytes(hq, hkv, total_win=tw, **kv)
+    monkeypatch.setenv("VC_VERIFY_WORKLIST", "0")
+    plain = lib.vc_verify_workspace_bytes(hq, hkv, total_win=tw, **kv)
+    monkeypatch.setenv("VC_VERIFY_WORKLIST", "1")
+    assert nbytes > plain                                        # the list is on: its area follows the partials
+    ws = torch.full((nbytes,), 0xFF, dtype=torch.uint8, device=DEV)       # poison (NaN partials, huge counters)
+    out = torch.empty_like(lay.q_win)
+    lse = torch.empty((tw, hq), dtype=torch.float32, device=DEV)
+    for _ in range(2):                                           # the second call finds the first one's list and counter
+        lib.vc_verify_attn(ctx, lay.q_win, lay.k_win, lay.v_win, lay.cu_win, lay.scale, out, workspace=ws, lse=lse, **kv)
+    torch.cuda.synchronize()
+    ref, ref_lse = H.oracle_verify(lay)
+    assert H.rel_err(out, ref) <= H.TOL
+    assert np.abs(lse.cpu().numpy() - ref_lse).max() <= H.LSE_TOL
+
+
+def test_worklist_streamed_launches_equal_one_shot(lib, ctx, monkeypatch):
+    monkeypatch.setenv("VC_VERIFY_LIST_MIN", "0")
+    ctx_len, win, chunk = [7000, 2048, 700, 3100], [16, 5, 33, 64], 1024
+    lay = synth.make_layer(96, DEV, ctx_len=ctx_len, n_q_heads=8, n_kv_heads=2, win=win)
+    kv = _kv(lay, ctx_len, win, sum_ctx=sum(ctx_len), chunk_tokens=chunk)
+    tw = lay.q_win.shape[0]
+    nbytes = lib.vc_verify_workspace_bytes(8, 2, total_win=tw, **kv)
+    ws = torch.empty(nbytes, dtype=torch.uint8, device=DEV)
+    out1 = torch.empty_like(lay.q_win)
+    lib.vc_verify_attn(ctx, lay.q_win, lay.k_win, lay.v_win, lay.cu_win, lay.scale, out1, workspace=ws, **kv)
+    # the same verify as launches over token ranges (all sequences), then over sequence ranges
+    ws2 = torch.empty(nbytes, dtype=torch.uint8, device=DEV)
+    total_max = max(ctx_len) + max(win)
+    for t0 in range(0, total_max, 2 * chunk):
+        last = t0 + 2 * chunk >= total_max
+        lib.vc_verify_attn_range(ctx, lay.q_win, lay.k_win, lay.v_win, lay.cu_win, lay.scale, 0, 4, t0,
+                                 (1 << 30) if last else t0 + 2 * chunk, workspace=ws2, **kv)
+    out2 = torch.empty_like(out1)
+    lib.vc_verify_finish(ctx, lay.cu_win, out2, n_q_heads=8, n_kv_heads=2, workspace=ws2, **kv)
+    ws3 = torch.empty(nbytes, dtype=torch.uint8, device=DEV)
+    for b0, b1 in ((2, 4), (0, 1), (1, 2)):
+        lib.vc_verify_attn_range(ctx, lay.q_win, lay.k_win, lay.v_win, lay.cu_win, lay.scale, b0, b1, 0, 1 << 30,
+                                 workspace=ws3, **kv)
+    out3 = torch.empty_like(out1)
+    lib.vc_verify_finish(ctx, lay.cu_win, out3, n_q_heads=8, n_kv_heads=2, workspace=ws3, **kv)
+    torch.cuda.synchronize()
+    assert torch.equal(out1.view(torch.int16), out2.view(torch.int16))
+    assert torch.equal(out1.view(torch.int16), out3.view(torch.int16))
+    ref, _ = H.oracle_verify(lay)
+    assert H.rel_err(out1, ref) <= H.TOL
+
+
+def test_worklist_overflow_walks_every_chunk(lib, ctx, monkeypatch):
+    """A caller that understates sum_ctx gets a list with room for too few pieces; the kernels then
+    walk every (sequence, chunk) of the launch, with the same results."""
+    monkeypatch.setenv("VC_VERIFY_LIST_MIN", "0")
+    ctx_len, win = [150000, 50000, 128], [4, 2, 1]
+    lay = synth.make_layer(97, DEV, ctx_len=ctx_len, n_q_heads=8, n_kv_heads=2, win=win)
+    kv = _kv(lay, ctx_len, win, sum_ctx=20000, chunk_tokens=128)        # 1564 pieces exist, the bound says 160
+    tw = lay.q_win.shape[0]
+    ws = torch.empty(lib.vc_verify_workspace_bytes(8, 2, total_win=tw, **kv), dtype=torch.uint8, device=DEV)
+    out = torch.empty_like(lay.q_win)
+    lib.vc_verify_attn(ctx, lay.q_win, lay.k_win, lay.v_win, lay.cu_win, lay.scale, out, workspace=ws, **kv)
+    torch.cuda.synchronize()
+    ref, _ = H.oracle_verify(lay)
+    assert H.rel_err(out, ref) <= H.TOL
