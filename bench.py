@@ -318,7 +318,9 @@ def measure_compressor(vc, ctx, lay, torch, HKV, N, B, reps=5):
             del ko, vo
         del blocks
     keep_n = N // 10
-    scores = torch.randn(B * HKV * N, device=dev, dtype=torch.float32)
+    g = torch.Generator(device=dev)
+    g.manual_seed(20260517)
+    scores = torch.randn(B * HKV * N, device=dev, dtype=torch.float32, generator=g)
     cu_keep = torch.arange(0, (B + 1) * keep_n, keep_n, dtype=torch.int32, device=dev)
     first = torch.full((B,), 64, dtype=torch.int32, device=dev)
     last = torch.full((B,), 256, dtype=torch.int32, device=dev)
@@ -332,9 +334,9 @@ def measure_compressor(vc, ctx, lay, torch, HKV, N, B, reps=5):
         rows, vocab = lay.logits.shape
         tw = lay.draft_ids.numel()
         sel = torch.cat([torch.arange(int(lay.cu_rows[b]), int(lay.cu_rows[b]) + lay.win[b], device=dev) for b in range(B)])
-        dlog = lay.logits[sel] + 0.3 * torch.randn((tw, vocab), device=dev)
-        ua = torch.rand(tw, device=dev)
-        ur = torch.rand(B, device=dev)
+        dlog = lay.logits[sel] + 0.3 * torch.randn((tw, vocab), device=dev, generator=g)
+        ua = torch.rand(tw, device=dev, generator=g)
+        ur = torch.rand(B, device=dev, generator=g)
         acc = torch.empty(B, dtype=torch.int32, device=dev)
         nxt = torch.empty(B, dtype=torch.int32, device=dev)
         sws = torch.empty(vc.vc_accept_sample_workspace_bytes(rows, tw, B, vocab), dtype=torch.uint8, device=dev)
