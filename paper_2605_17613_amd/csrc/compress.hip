@@ -57,7 +57,9 @@ __device__ __forceinline__ uint32_t code_of(float x, float zf, float inv) {
 }
 
 // ---------------------------------------------------------------------------------------------
-// compress: grid (ceil(max_blk / 4), Hkv, n_seqs), 4 waves, one record per wave
+// compress: grid (Hkv, ceil(max_blk / 4), n_seqs), 4 waves, one record per wave.  The KV head is the
+// fastest grid dimension: the workgroups that are resident together then read all the heads' 256-byte
+// pieces of the same token rows, instead of one head's piece of eight times as many rows.
 // ---------------------------------------------------------------------------------------------
 template <int BITS>
 __global__ __launch_bounds__(256) void compress_quant_kernel(QuantParams p) {
@@ -66,7 +68,7 @@ __global__ __launch_bounds__(256) void compress_quant_kernel(QuantParams p) {
   __shared__ __attribute__((aligned(16))) uint8_t stage_all[4][kHeadDim * SR];   // value codes, [channel][token]
   __shared__ __attribute__((aligned(16))) uint16_t vmeta_all[4][256];            // value scale[g][t], zero[g][t]
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, lg = lane >> 4, lc = lane & 15;
-  const int b = blockIdx.z, kvh = blockIdx.y, blk = blockIdx.x * 4 + wave;
+  const int b = blockIdx.z, kvh = blockIdx.x, blk = blockIdx.y * 4 + wave;
   const int nb = p.cu_blk[b + 1] - p.cu_blk[b];
   const bool live = blk < nb;                        // the barriers below are reached by every wave
   uint8_t* stage = stage_all[wave];
@@ -202,7 +204,7 @@ __global__ __launch_bounds__(256) void decompress_quant_kernel(QuantParams p) {
   constexpr uint32_t MASK = (1u << BITS) - 1u;
   __shared__ __attribute__((aligned(16))) uint8_t rec_all[4][kRecordBytes];
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, lg = lane >> 4, lc = lane & 15;
-  const int b = blockIdx.z, kvh = blockIdx.y, blk = blockIdx.x * 4 + wave;
+  const int b = blockIdx.z, kvh = blockIdx.x, blk = blockIdx.y * 4 + wave;
   const int nb = p.cu_blk[b + 1] - p.cu_blk[b];
   const bool live = blk < nb;
   uint8_t* rec = rec_all[wave];
@@ -478,7 +480,7 @@ static vc_status check_quant_call(vc_ctx* ctx, const int32_t* cu_ctx, const int3
   VC_REQUIRE(n_seqs >= 0 && n_kv_heads > 0 && max_blk >= 0, VC_ERR_INVALID_ARG, "%s: n_seqs %d n_kv_heads %d max_blk %d",
              who, n_seqs, n_kv_heads, max_blk);
   VC_REQUIRE(bits == 4 || bits == 2, VC_ERR_UNSUPPORTED, "%s: bits %d (block records are 4 or 2 bit)", who, bits);
-  VC_REQUIRE(n_seqs <= 65535 && n_kv_heads <= 65535, VC_ERR_UNSUPPORTED, "%s: grid too large", who);
+  VC_REQUIRE(n_seqs <= 65535 && max_blk <= 4 * 65535, VC_ERR_UNSUPPORTED, "%s: grid too large", who);
   if (n_seqs > 0) VC_REQUIRE(cu_ctx && cu_blk, VC_ERR_INVALID_ARG, "%s: NULL cu array", who);
   return VC_OK;
 }
@@ -501,7 +503,7 @@ extern "C" vc_status vc_compress_quant(vc_ctx* ctx, const void* k, const void* v
   p.v = static_cast<const uint16_t*>(v);
   p.blocks_out = static_cast<uint8_t*>(blocks);
   p.cu_ctx = cu_ctx; p.cu_blk = cu_blk; p.n_kv_heads = n_kv_heads;
-  dim3 grid(ceil_div(max_blk, 4), n_kv_heads, n_seqs);
+  dim3 grid(n_kv_heads, ceil_div(max_blk, 4), n_seqs);
   if (bits == 4) hipLaunchKernelGGL(compress_quant_kernel<4>, grid, dim3(256), 0, static_cast<hipStream_t>(stream), p);
   else hipLaunchKernelGGL(compress_quant_kernel<2>, grid, dim3(256), 0, static_cast<hipStream_t>(stream), p);
   VC_HIP(hipGetLastError());
@@ -522,7 +524,7 @@ extern "C" vc_status vc_decompress_quant(vc_ctx* ctx, const void* blocks, const 
   p.k_out = static_cast<uint16_t*>(k_out);
   p.v_out = static_cast<uint16_t*>(v_out);
   p.cu_ctx = cu_ctx; p.cu_blk = cu_blk; p.n_kv_heads = n_kv_heads;
-  dim3 grid(ceil_div(max_blk, 4), n_kv_heads, n_seqs);
+  dim3 grid(n_kv_heads, ceil_div(max_blk, 4), n_seqs);
   if (bits == 4) hipLaunchKernelGGL(decompress_quant_kernel<4>, grid, dim3(256), 0, static_cast<hipStream_t>(stream), p);
   else hipLaunchKernelGGL(decompress_quant_kernel<2>, grid, dim3(256), 0, static_cast<hipStream_t>(stream), p);
   VC_HIP(hipGetLastError());
