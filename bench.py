@@ -51,6 +51,8 @@ def parse():
     ap.add_argument("--no-round3", action="store_true",
                     help="skip the config-3 round (32 layers, ctx 131072, 64-token horizon; pins 17 GB of host memory)")
     ap.add_argument("--round3", action="store_true", help="run the config-3 round even with --only")
+    ap.add_argument("--no-config4", action="store_true", help="skip the ragged mixed batch (config 4)")
+    ap.add_argument("--config4", action="store_true", help="run the ragged mixed batch even with --only")
     ap.add_argument("--only", default="", help="comma list of legs to run per step: keep,d1,d2,d3,verify,accept")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
@@ -262,9 +264,17 @@ def main():
         cpu = cpu_baseline(lay, torch, np, HQ, HKV, N)
 
     round3 = None
-    if args.round3 or not (args.no_round3 or args.only):
+    ragged = None
+    if args.round3 or args.config4 or not ((args.no_round3 and args.no_config4) or args.only):
         del lay, ws
         torch.cuda.empty_cache()
+    if args.config4 or not (args.no_config4 or args.only):
+        try:
+            ragged = measure_config4(vc, ctx, torch)
+        except Exception as e:
+            ragged = {"error": f"{type(e).__name__}: {e}"}
+        torch.cuda.empty_cache()
+    if args.round3 or not (args.no_round3 or args.only):
         try:
             round3 = measure_round3(vc, ctx, torch)
         except Exception as e:      # the host may not have 17 GB to pin: the headline line must still be printed
@@ -279,7 +289,8 @@ def main():
                    "step": f"keep-index + {W} draft steps x (bf16 gather, int4, int2) + verify + accept"},
         "legs": res,
         "verify_TFLOPs": res.get("verify", {}).get("TFLOPs"),
-        "roofline": roofline, "swap": swap, "compressor": comp, "config3_round": round3, "cpu_baseline": cpu,
+        "roofline": roofline, "swap": swap, "compressor": comp, "config3_round": round3, "config4_ragged": ragged,
+        "cpu_baseline": cpu,
     }
     print(json.dumps(line))
     ctx.close()
@@ -499,6 +510,60 @@ def measure_swap(vc, ctx, lay, torch, draft_kw, out, ws, HKV, N, B, W):
             "draft_steps": n_steps, "draft_alone_ms": t_draft * 1e3, "both_ms": t_both * 1e3,
             "overlap": (t_draft + t_swap - t_both) / min(t_draft, t_swap), "bytes_ok": ok,
             "model_max_ms": max(t_draft, t_swap) * 1e3, "streamed_verify": streamed}
+
+
+def measure_config4(vc, ctx, torch, reps=40, warm=25):
+    """Workload config 4: 32 sequences of 2048 ... 131072 tokens, each either token-dropped (10 %) or
+    int4, verify windows of 4 ... 64 tokens: one draft call, one verify call, one accept call."""
+    from paper_2605_17613_amd import synth
+    dev = "cuda:0"
+    lay = synth.config(4, dev)
+    nseq = len(lay.ctx_len)
+    HQ, HKV = lay.n_q_heads, lay.n_kv_heads
+    kw = dict(pool_k=lay.k_full, pool_v=lay.v_full, cu_ctx=lay.cu_ctx, keep_idx=lay.keep_idx, cu_keep=lay.cu_keep,
+              max_keep=lay.max_keep, blocks=lay.blocks[4], cu_blk=lay.cu_blk[4], max_blk=lay.max_blk[4], bits=4,
+              sum_keep=int(lay.cu_keep[-1]), sum_blk=int(lay.cu_blk[4][-1]))
+    if lay.tail_k is not None:
+        kw.update(tail_k=lay.tail_k, tail_v=lay.tail_v, cu_tail=lay.cu_tail, max_tail=lay.max_tail)
+    out = torch.empty_like(lay.q)
+    ws = torch.empty(max(16, vc.vc_draft_workspace_bytes(HQ, HKV, nseq, **kw)), dtype=torch.uint8, device=dev)
+    tw = lay.q_win.shape[0]
+    va = dict(k=lay.k_full, v=lay.v_full, cu_ctx=lay.cu_ctx, max_ctx=max(lay.ctx_len), max_win=max(lay.win),
+              sum_ctx=sum(lay.ctx_len))
+    vws = torch.empty(max(16, vc.vc_verify_workspace_bytes(HQ, HKV, nseq, total_win=tw, **va)), dtype=torch.uint8, device=dev)
+    vout = torch.empty_like(lay.q_win)
+    rows, vocab = lay.logits.shape
+    acc = torch.empty(nseq, dtype=torch.int32, device=dev)
+    nxt = torch.empty(nseq, dtype=torch.int32, device=dev)
+    amax = torch.empty(rows, dtype=torch.int32, device=dev)
+    aws = torch.empty(max(16, vc.vc_accept_workspace_bytes(rows, vocab)), dtype=torch.uint8, device=dev)
+
+    def timed(f):
+        for _ in range(warm):
+            f()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            f()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps * 1e3
+
+    t_draft = timed(lambda: vc.vc_draft_attn(ctx, lay.q, lay.scale, out, n_kv_heads=HKV, workspace=ws, **kw))
+    t_verify = timed(lambda: vc.vc_verify_attn(ctx, lay.q_win, lay.k_win, lay.v_win, lay.cu_win, lay.scale, vout,
+                                               n_seqs=nseq, workspace=vws, **va))
+    t_accept = timed(lambda: vc.vc_accept_len(ctx, lay.logits, lay.cu_rows, lay.draft_ids, lay.cu_win, acc, nxt, amax,
+                                              workspace=aws))
+    kept_bytes = int(lay.cu_keep[-1]) * HKV * 512
+    rec_bytes = int(lay.cu_blk[4][-1]) * HKV * 5120
+    full_bytes = sum(lay.ctx_len) * HKV * 512
+    g = HQ // HKV
+    flops = sum(4.0 * w * g * 128 * (n + (w + 1) / 2) for n, w in zip(lay.ctx_len, lay.win)) * HKV
+    return {"sequences": nseq, "tokens": int(sum(lay.ctx_len)), "int4_sequences": int(sum(1 for b in range(nseq) if int(lay.cu_blk[4][b + 1]) > int(lay.cu_blk[4][b]))),
+            "draft_us": t_draft, "draft_GBps": (kept_bytes + rec_bytes) / t_draft / 1e3,
+            "verify_us": t_verify, "verify_GBps": full_bytes / t_verify / 1e3, "verify_TFLOPs": flops / t_verify / 1e6,
+            "accept_us": t_accept, "accept_GBps": rows * vocab * 4 / t_accept / 1e3}
 
 
 def measure_round3(vc, ctx, torch, layers=32, N=131072, W=64, vocab=128256, chunk_tok=8192):
