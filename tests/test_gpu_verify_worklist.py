@@ -97,3 +97,44 @@ def test_worklist_overflow_walks_every_chunk(lib, ctx, monkeypatch):
     torch.cuda.synchronize()
     ref, _ = H.oracle_verify(lay)
     assert H.rel_err(out, ref) <= H.TOL
+
+
+def test_worklist_verify_in_a_captured_graph(lib, ctx, monkeypatch):
+    """The list kernel zeroes the queue's counter itself, so a captured verify replays correctly: every
+    replay, with the queries changed in place and eager work in between, equals the eager call."""
+    monkeypatch.setenv("VC_VERIFY_LIST_MIN", "0")
+    ctx_len, win = [6000, 1500, 300, 4100], [16, 40, 3, 64]
+    lay = synth.make_layer(98, DEV, ctx_len=ctx_len, n_q_heads=8, n_kv_heads=2, win=win)
+    kv = _kv(lay, ctx_len, win, sum_ctx=sum(ctx_len))
+    tw = lay.q_win.shape[0]
+    ws = torch.empty(lib.vc_verify_workspace_bytes(8, 2, total_win=tw, **kv), dtype=torch.uint8, device=DEV)
+    qw = lay.q_win.clone()
+    out = torch.empty_like(qw)
+
+    def step():
+        lib.vc_verify_attn(ctx, qw, lay.k_win, lay.v_win, lay.cu_win, lay.scale, out, workspace=ws, **kv)
+
+    step()                                    # first call sets kernel attributes: outside the capture
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            step()
+    torch.cuda.synchronize()
+    g = synth.gen(6, DEV)
+    for rep in range(3):
+        qw.copy_(synth.randn_bf16(tuple(qw.shape), g))
+        torch.cuda.synchronize()
+        step()
+        torch.cuda.synchronize()
+        want = out.clone()
+        out.zero_()
+        scratch = torch.randn(1 << 20, device=DEV).sum()      # unrelated eager work between replays
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out.view(torch.int16), want.view(torch.int16)), rep
+        assert torch.isfinite(scratch)
+    lay.q_win.copy_(qw)
+    ref, _ = H.oracle_verify(lay)
+    assert H.rel_err(out, ref) <= H.TOL
