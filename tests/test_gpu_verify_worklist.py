@@ -138,3 +138,29 @@ def test_worklist_verify_in_a_captured_graph(lib, ctx, monkeypatch):
     lay.q_win.copy_(qw)
     ref, _ = H.oracle_verify(lay)
     assert H.rel_err(out, ref) <= H.TOL
+
+
+@pytest.mark.parametrize("nseq", [400, 600])
+def test_many_short_sequences(lib, ctx, monkeypatch, nseq):
+    """400 sequences still go through the list (its ranking loops run over all of them); 600 are more
+    than a list holds and take the plain grid."""
+    monkeypatch.setenv("VC_VERIFY_LIST_MIN", "0")
+    rng = np.random.default_rng(nseq)
+    ctx_len = [int(x) for x in rng.integers(0, 700, nseq)]
+    ctx_len[7] = 5000                                            # one long sequence makes the batch ragged
+    win = [int(x) for x in rng.integers(0, 5, nseq)]
+    win[7] = 40
+    lay = synth.make_layer(99, DEV, ctx_len=ctx_len, n_q_heads=8, n_kv_heads=2, win=win)
+    kv = _kv(lay, ctx_len, win, sum_ctx=sum(ctx_len))
+    tw = lay.q_win.shape[0]
+    nbytes = lib.vc_verify_workspace_bytes(8, 2, total_win=tw, **kv)
+    monkeypatch.setenv("VC_VERIFY_WORKLIST", "0")
+    plain = lib.vc_verify_workspace_bytes(8, 2, total_win=tw, **kv)
+    monkeypatch.setenv("VC_VERIFY_WORKLIST", "1")
+    assert (nbytes > plain) == (nseq <= 512)
+    ws = torch.full((nbytes,), 0xFF, dtype=torch.uint8, device=DEV)
+    out = torch.empty_like(lay.q_win)
+    lib.vc_verify_attn(ctx, lay.q_win, lay.k_win, lay.v_win, lay.cu_win, lay.scale, out, workspace=ws, **kv)
+    torch.cuda.synchronize()
+    ref, _ = H.oracle_verify(lay)
+    assert H.rel_err(out, ref) <= H.TOL

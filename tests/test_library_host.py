@@ -91,6 +91,33 @@ def test_verify_and_accept_host_validation():
     assert lib.vc_destroy(None) == B.VC_OK
 
 
+def test_verify_plan_of_a_ragged_batch():
+    """Host logic of the verify plan: a batch whose sum of lengths is well below n_seqs x max_ctx gets
+    shorter chunks, and a large one also room for the work list behind its partials."""
+    lib = vc.load()
+    d = B.vc_full_kv()
+    d.n_seqs, d.n_q_heads, d.n_kv_heads, d.head_dim, d.max_ctx, d.max_win = 32, 32, 8, 128, 131072, 64
+    d.k, d.v, d.cu_ctx = 0x1000, 0x2000, 0x3000
+    chunk, nchunk, n = C.c_int32(), C.c_int32(), C.c_size_t()
+
+    def plan(sum_ctx):
+        d.sum_ctx = sum_ctx
+        assert lib.vc_verify_plan(C.byref(d), C.byref(chunk), C.byref(nchunk)) == B.VC_OK
+        assert lib.vc_verify_workspace_bytes(C.byref(d), 1000, C.byref(n)) == B.VC_OK
+        partials = 1000 * 32 * nchunk.value * 130 * 4
+        return chunk.value, nchunk.value, n.value - partials
+
+    uniform = plan(0)                        # unknown sum: planned as 32 sequences of max_ctx, one round of 256 workgroups
+    assert uniform[2] == 0 and uniform[0] * uniform[1] >= 131072 + 64
+    ragged = plan(949359)                    # the mixed batch of 32 sequences, 2048 ... 131072 tokens
+    assert ragged[0] < uniform[0] and ragged[0] % 512 == 0      # shorter chunks, whole tiles after two halvings
+    assert ragged[2] > 0 and ragged[2] % 4 == 0                 # the list area
+    small = plan(40000)                      # ragged but small: the plain grid, no list
+    assert small[2] == 0
+    d.n_seqs = 600                           # more sequences than a list ranks
+    assert plan(600 * 20000)[2] == 0
+
+
 def test_binding_rejects_wrong_dtypes_before_calling_the_library():
     import torch
     with pytest.raises(TypeError):
