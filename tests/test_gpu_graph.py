@@ -35,17 +35,22 @@ def test_captured_draft_and_verify_replays_equal_eager(lib, ctx):
     cu_tail = lay.cu_tail.clone()
     kq = H.draft_kwargs(lay, bits=4, use_tail=True); kq["cu_tail"] = cu_tail
     kg = H.draft_kwargs(lay, use_pool=True, use_keep=True, use_tail=True); kg["cu_tail"] = cu_tail
+    # both sources in one call (as for a batch that mixes compressors)
+    kb = H.draft_kwargs(lay, bits=4, use_pool=True, use_keep=True, use_tail=True); kb["cu_tail"] = cu_tail
     q = lay.q.clone()
     out_q, out_g = torch.empty_like(q), torch.empty_like(q)
+    out_b = torch.empty_like(q)
     vout = torch.empty_like(lay.q_win)
     vargs = dict(k=lay.k_full, v=lay.v_full, cu_ctx=lay.cu_ctx, max_ctx=max(lay.ctx_len), max_win=max(lay.win))
     ws = torch.empty(max(vc.vc_draft_workspace_bytes(8, 2, nseq, **kq), vc.vc_draft_workspace_bytes(8, 2, nseq, **kg),
+                         vc.vc_draft_workspace_bytes(8, 2, nseq, **kb),
                          vc.vc_verify_workspace_bytes(8, 2, nseq, total_win=lay.q_win.shape[0], **vargs)),
                      dtype=torch.uint8, device=dev)
 
     def step():
         vc.vc_draft_attn(ctx, q, lay.scale, out_q, n_kv_heads=2, workspace=ws, **kq)
         vc.vc_draft_attn(ctx, q, lay.scale, out_g, n_kv_heads=2, workspace=ws, **kg)
+        vc.vc_draft_attn(ctx, q, lay.scale, out_b, n_kv_heads=2, workspace=ws, **kb)
         vc.vc_verify_attn(ctx, lay.q_win, lay.k_win, lay.v_win, lay.cu_win, lay.scale, vout, n_seqs=nseq, workspace=ws, **vargs)
 
     step()                                    # first calls set kernel attributes: outside the capture
@@ -69,12 +74,13 @@ def test_captured_draft_and_verify_replays_equal_eager(lib, ctx):
         torch.cuda.synchronize()
         step()
         torch.cuda.synchronize()
-        want = (out_q.clone(), out_g.clone(), vout.clone())
-        out_q.zero_(); out_g.zero_(); vout.zero_()
+        want = (out_q.clone(), out_g.clone(), vout.clone(), out_b.clone())
+        out_q.zero_(); out_g.zero_(); vout.zero_(); out_b.zero_()
         scratch = torch.randn(1 << 20, device=dev).sum()      # unrelated eager work between replays
         graph.replay()
         torch.cuda.synchronize()
         assert torch.equal(out_q.view(torch.int16), want[0].view(torch.int16)), rep
         assert torch.equal(out_g.view(torch.int16), want[1].view(torch.int16)), rep
         assert torch.equal(vout.view(torch.int16), want[2].view(torch.int16)), rep
+        assert torch.equal(out_b.view(torch.int16), want[3].view(torch.int16)), rep
         assert torch.isfinite(scratch)
