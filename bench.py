@@ -59,6 +59,17 @@ def parse():
     return ap.parse_args()
 
 
+def device_clocks():
+    """Clock lines of rocm-smi (clocks cannot be pinned here; logged beside the figures), or None."""
+    import subprocess
+    try:
+        r = subprocess.run(["rocm-smi", "--showclocks"], capture_output=True, text=True, timeout=20)
+        lines = [l.strip() for l in r.stdout.splitlines() if "clk" in l.lower() and "GPU[0]" in l]
+        return [l for l in lines if any(k in l for k in ("sclk", "mclk", "fclk"))] or None
+    except Exception:
+        return None
+
+
 def draft_bytes(n_seqs, hq, hkv, *, blocks=0, kept=0, tail=0):
     """Algorithmic bytes of one draft call: records + retained rows + index + tail + q + out."""
     per_head = blocks * 5120 + kept * (512 + 4) + tail * 512
@@ -203,6 +214,11 @@ def main():
         dur.setdefault(name, []).append(e0.elapsed_time(e1))
     mean_ms = {k: sum(v) / len(v) for k, v in dur.items()}
 
+    def spread(name):
+        """median and minimum of a leg's per-call times, microseconds"""
+        v = sorted(dur[name])
+        return {"median_us": v[len(v) // 2] * 1e3, "min_us": v[0] * 1e3, "calls": len(v)}
+
     # algorithmic bytes / flops per call
     tail_avg = (W - 1) / 2.0
     by = {
@@ -220,7 +236,7 @@ def main():
             res[k] = {"us": mean_ms[k] * 1e3, "GBps": by[k] / (mean_ms[k] * 1e-3) / 1e9,
                       "frac_hbm": by[k] / (mean_ms[k] * 1e-3) / 1e9 / HBM_PEAK_GBPS,
                       "kernel_us": mean_ms[k + "_kernel"] * 1e3,
-                      "kernel_frac_hbm": by[k] / (mean_ms[k + "_kernel"] * 1e-3) / 1e9 / HBM_PEAK_GBPS}
+                      "kernel_frac_hbm": by[k] / (mean_ms[k + "_kernel"] * 1e-3) / 1e9 / HBM_PEAK_GBPS, **spread(k)}
             tot_b += by[k] * len(dur[k])
             tot_t += sum(dur[k]) * 1e-3
     value = tot_b / tot_t / 1e9 if tot_t > 0 else 0.0
@@ -229,11 +245,13 @@ def main():
         ai = verify_flops / verify_bytes
         attainable = min(MFMA_BF16_PEAK_TFLOPS, ai * HBM_PEAK_GBPS / 1e3)
         res["verify"] = {"us": mean_ms["verify"] * 1e3, "kernel_us": mean_ms["verify_kernel"] * 1e3, "TFLOPs": tf, "frac_mfma": tf / MFMA_BF16_PEAK_TFLOPS,
-                         "frac_attainable": tf / attainable, "GBps": verify_bytes / (mean_ms["verify"] * 1e-3) / 1e9}
+                         "frac_attainable": tf / attainable, "GBps": verify_bytes / (mean_ms["verify"] * 1e-3) / 1e9,
+                         **spread("verify")}
     if "accept" in mean_ms:
-        res["accept"] = {"us": mean_ms["accept"] * 1e3, "GBps": accept_bytes / (mean_ms["accept"] * 1e-3) / 1e9}
+        res["accept"] = {"us": mean_ms["accept"] * 1e3, "GBps": accept_bytes / (mean_ms["accept"] * 1e-3) / 1e9,
+                         **spread("accept")}
     if "keep" in mean_ms:
-        res["keep"] = {"us": mean_ms["keep"] * 1e3}
+        res["keep"] = {"us": mean_ms["keep"] * 1e3, **spread("keep")}
 
     # roofline of the dominant kernel of a round: the int4 record draft kernel (32 launches per
     # step against one verify); duration = HIP events the library records on the call's stream
@@ -258,6 +276,13 @@ def main():
     comp = None
     if not args.no_compressor and not args.only:
         comp = measure_compressor(vc, ctx, lay, torch, HKV, N, B)
+
+    loop32 = None
+    if not args.no_compressor and not args.only:
+        try:
+            loop32 = measure_layer_loop(vc, ctx, lay, torch, HQ, HKV, N, B)
+        except Exception as e:
+            loop32 = {"error": f"{type(e).__name__}: {e}"}
 
     cpu = None
     if not args.no_cpu_baseline:
@@ -289,11 +314,51 @@ def main():
                    "step": f"keep-index + {W} draft steps x (bf16 gather, int4, int2) + verify + accept"},
         "legs": res,
         "verify_TFLOPs": res.get("verify", {}).get("TFLOPs"),
-        "roofline": roofline, "swap": swap, "compressor": comp, "config3_round": round3, "config4_ragged": ragged,
+        "roofline": roofline, "swap": swap, "compressor": comp, "layer_loop": loop32, "config3_round": round3, "config4_ragged": ragged,
+        "clocks_after_run": device_clocks(),
         "cpu_baseline": cpu,
     }
     print(json.dumps(line))
     ctx.close()
+
+
+def measure_layer_loop(vc, ctx, lay, torch, HQ, HKV, N, B, layers=32, reps=3):
+    """int4 draft attention over `layers` distinct layers back to back (each layer its own records,
+    43 GB at config-2 size, so that no cache level can hold a layer from one pass to the next):
+    microseconds per layer call and the rate over the records."""
+    dev = lay.k_full.device
+    nb = lay.max_blk[4]
+    blocks = torch.empty((layers,) + tuple(lay.blocks[4].shape), dtype=torch.uint8, device=dev)
+    g = torch.Generator(device=dev)
+    g.manual_seed(20260518)
+    k = torch.empty_like(lay.k_full)
+    v = torch.empty_like(lay.v_full)
+    for l in range(layers):
+        k.copy_(torch.randn(k.shape, device=dev, dtype=torch.float32, generator=g))
+        v.copy_(torch.randn(v.shape, device=dev, dtype=torch.float32, generator=g))
+        vc.vc_compress_quant(ctx, k, v, lay.cu_ctx, lay.cu_blk[4], 4, nb, blocks[l])
+    del k, v
+    q = torch.randn((layers,) + tuple(lay.q.shape), device=dev, generator=g).to(torch.bfloat16)
+    out = torch.empty_like(q)
+    kw = dict(cu_blk=lay.cu_blk[4], max_blk=nb, bits=4, sum_blk=nb * B)
+    ws = torch.empty(vc.vc_draft_workspace_bytes(HQ, HKV, B, blocks=blocks[0], **kw), dtype=torch.uint8, device=dev)
+
+    def one_pass():
+        for l in range(layers):
+            vc.vc_draft_attn(ctx, q[l], lay.scale, out[l], n_kv_heads=HKV, workspace=ws, blocks=blocks[l], **kw)
+
+    one_pass()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        one_pass()
+    e1.record()
+    torch.cuda.synchronize()
+    us = e0.elapsed_time(e1) * 1e3 / (reps * layers)
+    bytes_call = draft_bytes(B, HQ, HKV, blocks=N // 32)
+    return {"layers": layers, "records_GB": blocks.numel() / 1e9, "us_per_layer_call": us,
+            "GBps": bytes_call / us / 1e3, "frac_hbm": bytes_call / us / 1e3 / HBM_PEAK_GBPS}
 
 
 def measure_compressor(vc, ctx, lay, torch, HKV, N, B, reps=5):
