@@ -131,7 +131,9 @@ typedef struct {
                               large one (up to 512 sequences) is verified from a work list that a small
                               kernel builds in the workspace, by one workgroup per CU.  Results do not
                               depend on the hint; the workspace size does, so pass the same value to
-                              every call of one verify. */
+                              every call of one verify.  Every vc_verify_attn_range call on such a
+                              batch rebuilds the list (about 15 us): a caller that streams sequence by
+                              sequence does better with one descriptor per sequence (n_seqs = 1). */
   int32_t chunk_tokens;    /* tokens per workgroup chunk (a multiple of 128), 0 = the library picks;
                               set it to the swap-in chunk length to verify chunk by chunk */
   const void* k;           /* device bf16 pools; sequence b owns rows cu_ctx[b] .. cu_ctx[b+1]-1 */
