@@ -393,6 +393,14 @@ def measure_compressor(vc, ctx, lay, torch, HKV, N, B, reps=5):
             res["decompress_int4"] = {"us": ms * 1e3, "GBps": (kv_bytes + blocks.numel()) / (ms * 1e-3) / 1e9}
             del ko, vo
         del blocks
+    # decode attention over the uncompressed bf16 KV (what drafting would cost without a compressor)
+    HQ = lay.n_q_heads
+    fkw = dict(pool_k=lay.k_full, pool_v=lay.v_full, cu_ctx=lay.cu_ctx, max_keep=N, sum_keep=N * B)
+    fout = torch.empty_like(lay.q)
+    fws = torch.empty(vc.vc_draft_workspace_bytes(HQ, HKV, B, **fkw), dtype=torch.uint8, device=dev)
+    ms = timed(lambda: vc.vc_draft_attn(ctx, lay.q, lay.scale, fout, n_kv_heads=HKV, workspace=fws, **fkw))
+    res["full_bf16_decode"] = {"us": ms * 1e3, "GBps": B * N * HKV * 512 / (ms * 1e-3) / 1e9}
+    del fout, fws
     keep_n = N // 10
     g = torch.Generator(device=dev)
     g.manual_seed(20260517)
