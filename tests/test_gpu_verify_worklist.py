@@ -51,6 +51,26 @@ def test_worklist_verify_matches_oracle(lib, ctx, monkeypatch, ctx_len, win, hq,
     assert np.abs(lse.cpu().numpy() - ref_lse).max() <= H.LSE_TOL
 
 
+def test_few_resident_workgroups_take_many_pieces_each(lib, ctx, monkeypatch):
+    """Three resident workgroups instead of one per CU: each takes dozens of pieces in turn, of both row
+    variants, reusing its LDS ring every time; the result is the same bits as with the full grid."""
+    monkeypatch.setenv("VC_VERIFY_LIST_MIN", "0")
+    ctx_len, win = [9000, 2048, 700, 5000, 3300], [64, 5, 33, 16, 40]
+    lay = synth.make_layer(94, DEV, ctx_len=ctx_len, n_q_heads=8, n_kv_heads=2, win=win)
+    kv = _kv(lay, ctx_len, win, sum_ctx=sum(ctx_len))
+    tw = lay.q_win.shape[0]
+    ws = torch.empty(lib.vc_verify_workspace_bytes(8, 2, total_win=tw, **kv), dtype=torch.uint8, device=DEV)
+    out_full = torch.empty_like(lay.q_win)
+    lib.vc_verify_attn(ctx, lay.q_win, lay.k_win, lay.v_win, lay.cu_win, lay.scale, out_full, workspace=ws, **kv)
+    monkeypatch.setenv("VC_VERIFY_QUEUE_WGS", "3")
+    out_few = torch.empty_like(lay.q_win)
+    lib.vc_verify_attn(ctx, lay.q_win, lay.k_win, lay.v_win, lay.cu_win, lay.scale, out_few, workspace=ws, **kv)
+    torch.cuda.synchronize()
+    assert torch.equal(out_full.view(torch.int16), out_few.view(torch.int16))
+    ref, _ = H.oracle_verify(lay)
+    assert H.rel_err(out_few, ref) <= H.TOL
+
+
 def test_worklist_streamed_launches_equal_one_shot(lib, ctx, monkeypatch):
     monkeypatch.setenv("VC_VERIFY_LIST_MIN", "0")
     ctx_len, win, chunk = [7000, 2048, 700, 3100], [16, 5, 33, 64], 1024
