@@ -86,7 +86,7 @@ def main():
     import torch
 
     import paper_2605_17613_amd as vc
-    from paper_2605_17613_amd import synth
+    from tests import synth
 
     vc.load()
     if not torch.cuda.is_available():
@@ -588,7 +588,7 @@ def measure_swap(vc, ctx, lay, torch, draft_kw, out, ws, HKV, N, B, W):
 def measure_config4(vc, ctx, torch, reps=40, warm=25):
     """Workload config 4: 32 sequences of 2048 ... 131072 tokens, each either token-dropped (10 %) or
     int4, verify windows of 4 ... 64 tokens: one draft call, one verify call, one accept call."""
-    from paper_2605_17613_amd import synth
+    from tests import synth
     dev = "cuda:0"
     lay = synth.config(4, dev)
     nseq = len(lay.ctx_len)
@@ -645,7 +645,7 @@ def measure_round3(vc, ctx, torch, layers=32, N=131072, W=64, vocab=128256, chun
     start the reload of all layers, draft W tokens (W x layers draft calls, the bf16 tail growing),
     verify every layer as its reload lands, accept.  The draft horizon is measured eagerly and as
     one captured HIP graph per step (32 layers x 2 kernels), replayed W times."""
-    from paper_2605_17613_amd import synth
+    from tests import synth
     dev = "cuda:0"
     HQ, HKV = 32, 8
     g = torch.Generator(device=dev); g.manual_seed(synth.SEED_BASE + 3)

@@ -21,7 +21,7 @@ from . import binding as B
 class StaggeredLayer:
     def __init__(self, ctx: B.Context, lay, bits: int, host_k, host_v, *, windows: int, x: int, t_iter: float,
                  link_bw: float, hbm_bytes: float, model_bytes: float = 0.0, chunk_tokens: int = 8192):
-        """lay: synth.Layer with R sequences, block records of `bits` for every sequence, windows of
+        """lay: a layer description (the fields of the test harness's Layer record) with R sequences, block records of `bits` for every sequence, windows of
         at least `windows` rows and planted logits; host_k / host_v: pinned copies of lay.k_full /
         lay.v_full (the requests' full KV in CPU memory)."""
         if windows > min(lay.win):

@@ -6,7 +6,7 @@ import pytest
 import torch
 
 import paper_2605_17613_amd as vc
-from paper_2605_17613_amd import synth
+from tests import synth
 from tests import helpers as H
 
 pytestmark = pytest.mark.gpu

@@ -8,7 +8,7 @@ import torch
 
 import paper_2605_17613_amd as vc
 from oracle import vc_oracle as O
-from paper_2605_17613_amd import synth
+from tests import synth
 from paper_2605_17613_amd.runtime import StaggeredLayer
 from tests import helpers as H
 

@@ -5,7 +5,7 @@ import numpy as np
 import pytest
 import torch
 
-from paper_2605_17613_amd import synth
+from tests import synth
 from tests import helpers as H
 
 pytestmark = pytest.mark.gpu

@@ -9,7 +9,7 @@ import pytest
 import torch
 
 from oracle import vc_oracle as O
-from paper_2605_17613_amd import synth
+from tests import synth
 
 D = 128
 
