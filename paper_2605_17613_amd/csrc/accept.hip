@@ -15,8 +15,9 @@ namespace vc {
 constexpr int kAcceptThreads = 256;
 constexpr int kSegElems = 8192;  // logits per workgroup
 
+// -0 and +0 are equal logits (the lower index must win between them), so -0 is mapped to +0 first.
 __device__ __forceinline__ uint32_t float_order(float f) {
-  uint32_t u = __float_as_uint(f);
+  uint32_t u = __float_as_uint(f + 0.0f);
   return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
 }
 

@@ -35,6 +35,11 @@ def make_ragged(bits, lens, hkv, seed):
         k[0:tb, hkv - 1, 17] = 0.75                     # a constant key group
         v[3, 0, 0:tb] = -1.25                           # a constant value group
         v[4, 0, tb:2 * tb] = 0.0                        # zeros
+        k[0:tb, 0, 40] = k[0:tb, 0, 40].abs()           # a key group whose minimum is -0.0 (stored zero point: +0)
+        k[tb // 2, 0, 40] = -0.0
+        k[1, 0, 40] = 0.0
+        v[6, 0, 0:tb] = v[6, 0, 0:tb].abs()             # a value group whose minimum is -0.0
+        v[6, 0, tb - 1] = -0.0
     nb = [n // tb for n in lens]
     cu_ctx = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
     cu_blk = np.concatenate([[0], np.cumsum(nb)]).astype(np.int32)

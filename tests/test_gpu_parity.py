@@ -163,6 +163,22 @@ def test_accept_planted_ties_bonus(lib, ctx):
     assert np.array_equal(am, ram) and np.array_equal(a, ra) and np.array_equal(n, rn)
 
 
+def test_accept_signed_zero_ties_across_segments(lib, ctx):
+    """Row maximum 0 held by -0.0 at a low index and +0.0 in another thread / another 8192-logit
+    segment (and the other way round): the lower index wins, as in the oracle."""
+    lay = synth.make_layer(52, DEV, ctx_len=[8] * 2, n_q_heads=4, n_kv_heads=2, win=[3, 2], vocab=32000)
+    lay.logits.clamp_(max=-0.5)
+    lay.logits[0, 5] = -0.0; lay.logits[0, 20000] = 0.0          # different segments
+    lay.logits[1, 5] = 0.0; lay.logits[1, 20000] = -0.0
+    lay.logits[2, 40] = -0.0; lay.logits[2, 41] = 0.0            # same segment, neighbouring threads
+    lay.logits[3, 9000] = -0.0; lay.logits[3, 9000 + 4 * 256] = 0.0   # same thread's next vector
+    lay.logits[4, :] = -0.0; lay.logits[4, 31999] = 0.0
+    a, n, am = H.gpu_accept(lib, ctx, lay)
+    ra, rn, ram = H.oracle_accept(lay)
+    assert ram.tolist() == [5, 5, 40, 9000, 0]
+    assert np.array_equal(am, ram) and np.array_equal(a, ra) and np.array_equal(n, rn)
+
+
 @pytest.mark.parametrize("vocab", [128256, 32000, 1001, 7])
 def test_accept_vocab_sizes(lib, ctx, vocab):
     lay = synth.make_layer(51, DEV, ctx_len=[8] * 5, n_q_heads=4, n_kv_heads=2, win=[4, 9, 1, 0, 33], vocab=vocab)

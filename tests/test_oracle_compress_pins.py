@@ -45,6 +45,46 @@ def test_quantise_groups_uses_stored_fp16_values():
     assert code[0].tolist() == [0, 15, int(np.rint((1.0 - z) / s))]
 
 
+def test_quantise_groups_stores_negative_zero_minimum_as_positive_zero():
+    """Reading of the quantiser (the paper names only the axes, section 2 and section 6): a group whose
+    minimum is -0.0 stores the zero point +0.0 (fp16 bits 0x0000, never 0x8000).  The two zeros compare
+    equal, so a minimum taken in any order may come out as either; adding +0.0 makes the stored byte
+    unique.  Dequantised values are unaffected: scale * code + (-0.0) and scale * code + 0.0 are the
+    same number for every code."""
+    neg0 = np.float32(-0.0)
+    # -0.0 alone as the minimum; -0.0 before +0.0; +0.0 before -0.0
+    for grp in ([neg0, 1.0, 2.0, 3.0], [neg0, 0.0, 1.5, 3.0], [0.0, neg0, 1.5, 3.0]):
+        code, scale, zero = O.quantise_groups(np.array([grp], dtype=np.float32), 3)
+        assert zero.view(np.uint16)[0] == 0x0000
+        assert float(scale[0]) == 1.0 and code[0, 0] == 0 and code[0, -1] == 3
+    # a constant group of -0.0: scale 0, zero +0, codes 0
+    code, scale, zero = O.quantise_groups(np.full((1, 8), neg0, dtype=np.float32), 15)
+    assert zero.view(np.uint16)[0] == 0x0000 and scale.view(np.uint16)[0] == 0x0000 and not code.any()
+
+
+@pytest.mark.parametrize("bits", [4, 2])
+def test_quantize_records_negative_zero_minimum_bytes(bits):
+    """The same rule in the record: a key group (one channel over the block's tokens) and a value
+    group (one token over TB channels) whose minimum is -0.0 store zero-point bytes 00 00."""
+    tb = O.tokens_per_block(bits)
+    levels = (1 << bits) - 1
+    k = np.ones((tb, 1, 128), dtype=np.float32)
+    v = np.ones((tb, 1, 128), dtype=np.float32)
+    k[:, 0, 9] = np.arange(tb) % (levels + 1)          # channel 9: values 0..levels, minimum stored as -0.0
+    k[0, 0, 9] = -0.0
+    v[5, 0, tb:2 * tb] = np.arange(tb) % (levels + 1) if 2 * tb <= 128 else 0
+    v[5, 0, 0:tb] = np.arange(tb) % (levels + 1)       # token 5, channel group 0
+    v[5, 0, 0] = -0.0
+    kb, vb = bf16_bits_of(k), bf16_bits_of(v)
+    assert kb[0, 0, 9] == 0x8000 and vb[5, 0, 0] == 0x8000          # the inputs really are -0.0
+    rec = O.quantize_records(kb, vb, bits)[0, 0]
+    kzero = rec[4096 + 256:4096 + 512].view("<u2")                   # key zero[128]
+    vzero = rec[4608 + 256:4608 + 512].view("<u2")                   # value zero[g][t]
+    assert kzero[9] == 0x0000 and vzero[0 * tb + 5] == 0x0000
+    kscale = rec[4096:4096 + 256].view("<u2").view(np.float16)
+    assert float(kscale[9]) == 1.0
+
+
 @pytest.mark.parametrize("bits", [4, 2])
 def test_quantize_records_equals_hand_packed_closed_form(bits):
     """Keys: channel d of token t holds zero_d + step_d * ((t + d) mod L1); values: token t, channel

@@ -422,6 +422,18 @@ def test_accept_bonus_row_and_ties_and_neg_inf():
     assert a.tolist() == [0, 1] and nxt.tolist() == [2, 4]
 
 
+def test_argmax_signed_zero_tie_goes_to_the_lower_index():
+    """-0.0 and +0.0 are the same logit value: the tie rule (lowest index) applies between them in
+    either order (section 4.1 step 3 compares token ids, so the arg-max must be unique)."""
+    row = np.full(20000, -1.0, dtype=np.float32)
+    row[3] = -0.0; row[15000] = 0.0
+    assert O.argmax_row(row) == 3
+    row[3] = 0.0; row[15000] = -0.0
+    assert O.argmax_row(row) == 3
+    row[:] = -0.0; row[19999] = 0.0
+    assert O.argmax_row(row) == 0
+
+
 def test_accept_brute_force_tiny_vocab():
     rng = np.random.default_rng(3)
     for trial in range(30):
