@@ -50,6 +50,27 @@ vc_status vc_destroy(vc_ctx* ctx);
 const char* vc_last_error(void);
 /* Library version, "major.minor". */
 const char* vc_version(void);
+/* Launch-shape tunables (sweeps and tests; the defaults are the measured optima).  They steer how
+ * work is cut into workgroups - never a result - but the workspace sizes and the chunk length that
+ * vc_verify_plan reports depend on them.  Each is read from the environment variable of its name
+ * once, when the library first needs one; vc_set_tunable overrides it for the process (value < 0:
+ * back to the library's default).  Changing one between a *_workspace_bytes query and its call, or
+ * between the calls of one streamed verify, is the caller's error.  Names:
+ *   VC_DRAFT_BF16_WGS, VC_DRAFT_QUANT_WGS   workgroups a draft launch is cut for
+ *   VC_DRAFT_MIN_TOK, VC_DRAFT_MIN_BLK      shortest split (tokens / block records)
+ *   VC_DRAFT_TAPER                          1: the last splits of a list of records are cut shorter
+ *   VC_VERIFY_WGS, VC_VERIFY_MIN_TOK        workgroups a verify launch is cut for, shortest chunk
+ *   VC_VERIFY_WORKLIST, VC_VERIFY_LIST_MIN, VC_VERIFY_TAPER, VC_VERIFY_QUEUE_WGS   the work-list
+ *                                           launch of large ragged batches
+ * Unknown names return VC_ERR_INVALID_ARG. */
+vc_status vc_set_tunable(const char* name, int32_t value);
+vc_status vc_get_tunable(const char* name, int32_t* value, int32_t* is_set);
+/* State of the work enqueued on `stream` so far, without blocking: VC_OK when it has all finished,
+ * VC_ERR_NOT_READY while some is in flight, VC_ERR_HIP when the runtime reports a failure of earlier
+ * asynchronous work (a launch failure is returned by the call that launched; a fault inside a
+ * running kernel is reported by the runtime to a later call that touches the stream - this one,
+ * vc_swap_query, vc_swap_sync). */
+vc_status vc_stream_status(vc_ctx* ctx, void* stream);
 /* Measurement aid.  Arms two caller-owned hipEvent_t (passed as void*, created with timing
  * enabled): the next vc_draft_attn or vc_verify_attn[_range] call on this context records
  * `begin_event` on its stream just before its main attention kernel(s) and `end_event` just after
@@ -88,6 +109,13 @@ vc_status vc_time_main_kernel(vc_ctx* ctx, void* begin_event, void* end_event);
  *        bytes 4608..5119  value scale[g][t] then value zero[g][t] (fp16; g = d / TB < 128/TB,
  *                          t < TB), 128 + 128 values
  *
+ *      Number range.  The kernel folds scales and zero points into fp16 operands of the matrix
+ *      cores (products are accumulated in fp32), so metadata must stay inside fp16 after folding:
+ *        values:  value scale <= 4094 and |value zero| <= 4094 (a probability operand reaches 16);
+ *        keys:    |q[d]| * softmax_scale * 1.4427 * max(key scale[d], |key zero[d]|) <= 65504.
+ *      Beyond that the output is undefined (infinities).  N(0,1)-scale caches with key outlier
+ *      channels of x100 and values of a few thousand are inside the range.
+ *
  *  (3) a bf16 tail of recent tokens (tokens drafted in this horizon, and the remainder of a
  *      context that does not fill a whole block): pools tail_k, tail_v, rows cu_tail[b] ..
  *      cu_tail[b+1]-1.
@@ -122,6 +150,28 @@ vc_status vc_draft_attn(vc_ctx* ctx, const vc_comp_kv* kv, const void* q, float 
                         void* out, float* lse, void* workspace, size_t workspace_bytes,
                         void* stream);
 
+/* Optional validation of the data the host cannot see (paper section 6: the runtime is handed
+ * per-request offsets and position lists by the compressor; the attention calls trust them).
+ * Asynchronous: a short kernel on `stream` checks the device arrays of the descriptor and writes
+ *   report[0] = number of violations found
+ *   report[1] = the smallest violation as (kind << 56 | sequence << 32 | index), or -1 for none
+ * to `report` (device, int64[2], 8-byte aligned); the caller reads it once the stream got there.
+ * Kinds: see vc_violation; `index` is the entry of the kept list for the KEEP kinds, the array
+ * (0 cu_ctx, 1 cu_keep, 2 cu_blk, 3 cu_tail, 4 cu_win, 5 total_win) for the others.
+ * vc_validate_comp_kv: every prefix array the descriptor uses is non-decreasing; no per-sequence
+ *   count exceeds its host-side maximum (max_keep, max_blk, max_tail - launch grids are sized from
+ *   them); a kept list has at most len_b entries, each in [0, len_b), strictly ascending.
+ * vc_validate_full_kv: cu_ctx and cu_win (may be NULL) non-decreasing, lengths within max_ctx /
+ *   max_win, cu_win[n_seqs] - cu_win[0] == total_win. */
+typedef enum {
+  VC_BAD_PREFIX_ORDER = 1,  /* a cu_* array decreases                                  */
+  VC_BAD_HOST_MAX = 2,      /* a per-sequence count exceeds the host-side maximum        */
+  VC_BAD_KEEP_COUNT = 3,    /* a kept list is longer than its sequence                   */
+  VC_BAD_KEEP_RANGE = 4,    /* a kept position outside [0, len_b)                        */
+  VC_BAD_KEEP_ORDER = 5     /* kept positions not strictly ascending                     */
+} vc_violation;
+vc_status vc_validate_comp_kv(vc_ctx* ctx, const vc_comp_kv* kv, int64_t* report, void* stream);
+
 /* Full KV of one layer, resident on the device (the destination of vc_swap_in). */
 typedef struct {
   int32_t n_seqs, n_q_heads, n_kv_heads, head_dim;
@@ -150,6 +200,8 @@ typedef struct {
  *   k_win, v_win  device bf16 pools [sum w, n_kv_heads, 128]
  *   out           device bf16 [sum w, n_q_heads, 128];  lse device fp32 [sum w, n_q_heads] or NULL
  * bf16 MFMA, fp32 accumulation. */
+vc_status vc_validate_full_kv(vc_ctx* ctx, const vc_full_kv* kv, const int32_t* cu_win, int32_t total_win,
+                              int64_t* report, void* stream);
 vc_status vc_verify_workspace_bytes(const vc_full_kv* kv, int32_t total_win, size_t* bytes);
 vc_status vc_verify_attn(vc_ctx* ctx, const vc_full_kv* kv, const void* q_win, const void* k_win,
                          const void* v_win, const int32_t* cu_win, int32_t total_win,
@@ -315,7 +367,10 @@ vc_status vc_decompress_quant(vc_ctx* ctx, const void* blocks, const int32_t* cu
 
 /* Kept positions from importance scores (paper section 6: what a token-dropping compressor's
  * update() decides per request and head; scope (i): every head of a layer keeps the same number
- * of positions).  List (b, h) keeps nk_b = min(cu_keep[b+1] - cu_keep[b], len_b) positions: the
+ * of positions).  The budget cu_keep[b+1] - cu_keep[b] must not exceed len_b (the caller's contract,
+ * checked by vc_validate_comp_kv on the resulting descriptor: with a larger budget only len_b entries
+ * of each list are written, at the list stride of the budget, and the rest are left as they were).
+ * List (b, h) keeps nk_b = min(cu_keep[b+1] - cu_keep[b], len_b) positions: the
  * first F_b = min(forced_first[b], nk_b), the last L_b = min(forced_last[b], nk_b - F_b), and the
  * nk_b - F_b - L_b highest-scoring of the others; equal scores go to the lower position (-0 equals
  * +0; NaN scores are a contract violation).  Output ascending, in the layout of

@@ -45,6 +45,7 @@ class vc_chunk(C.Structure):
 
 
 EXPORTS = ["vc_create", "vc_destroy", "vc_last_error", "vc_version", "vc_time_main_kernel",
+           "vc_set_tunable", "vc_get_tunable", "vc_stream_status", "vc_validate_comp_kv", "vc_validate_full_kv",
            "vc_draft_workspace_bytes", "vc_draft_attn", "vc_verify_workspace_bytes", "vc_verify_attn",
            "vc_verify_plan", "vc_verify_attn_range", "vc_verify_finish",
            "vc_accept_workspace_bytes", "vc_accept_len", "vc_accept_sample_workspace_bytes", "vc_accept_sample", "vc_swap_in", "vc_swap_in_rows", "vc_pack_rows", "vc_swap_wait", "vc_swap_query", "vc_swap_sync",
@@ -71,6 +72,11 @@ def load():
     lib.vc_create.argtypes = [C.c_int, C.POINTER(C.c_void_p)]
     lib.vc_destroy.argtypes = [C.c_void_p]
     lib.vc_time_main_kernel.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
+    lib.vc_set_tunable.argtypes = [C.c_char_p, C.c_int32]
+    lib.vc_get_tunable.argtypes = [C.c_char_p, C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
+    lib.vc_stream_status.argtypes = [C.c_void_p, C.c_void_p]
+    lib.vc_validate_comp_kv.argtypes = [C.c_void_p, C.POINTER(vc_comp_kv), C.c_void_p, C.c_void_p]
+    lib.vc_validate_full_kv.argtypes = [C.c_void_p, C.POINTER(vc_full_kv), C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p]
     lib.vc_draft_workspace_bytes.argtypes = [C.POINTER(vc_comp_kv), C.POINTER(C.c_size_t)]
     lib.vc_draft_attn.argtypes = [C.c_void_p, C.POINTER(vc_comp_kv), C.c_void_p, C.c_float, C.c_void_p,
                                   C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
@@ -190,6 +196,41 @@ def _comp_desc(n_q_heads, n_kv_heads, n_seqs, *, pool_k=None, pool_v=None, cu_ct
     d.tail_k = _ptr(tail_k, torch.bfloat16, "tail_k"); d.tail_v = _ptr(tail_v, torch.bfloat16, "tail_v")
     d.cu_tail = _ptr(cu_tail, torch.int32, "cu_tail")
     return d
+
+
+def vc_set_tunable(name: str, value: int):
+    """Override a launch-shape tunable for the process; value < 0 restores the library default."""
+    _check(load().vc_set_tunable(name.encode(), int(value)))
+
+
+def vc_get_tunable(name: str):
+    """Returns the set value, or None when the tunable is at its library default."""
+    v, isset = C.c_int32(), C.c_int32()
+    _check(load().vc_get_tunable(name.encode(), C.byref(v), C.byref(isset)))
+    return v.value if isset.value else None
+
+
+def vc_stream_status(ctx: Context, stream=None) -> bool:
+    """True when everything enqueued on the stream has finished, False while work is in flight."""
+    st = load().vc_stream_status(ctx.handle, _stream(stream))
+    if st == VC_ERR_NOT_READY:
+        return False
+    _check(st)
+    return True
+
+
+def vc_validate_comp_kv(ctx: Context, report, *, n_q_heads, n_kv_heads, n_seqs, stream=None, **kv):
+    """report: device int64[2], written asynchronously (violations, smallest violation key or -1)."""
+    d = _comp_desc(n_q_heads, n_kv_heads, n_seqs, **kv)
+    _check(load().vc_validate_comp_kv(ctx.handle, C.byref(d), _ptr(report, torch.int64, "report"), _stream(stream)))
+
+
+def vc_validate_full_kv(ctx: Context, report, cu_win, total_win, *, n_q_heads, n_kv_heads, n_seqs, k, v, cu_ctx,
+                        max_ctx, max_win, stream=None, sum_ctx=0, chunk_tokens=0):
+    d = _full_desc(n_q_heads, n_kv_heads, n_seqs, k, v, cu_ctx, max_ctx, max_win, sum_ctx=sum_ctx,
+                   chunk_tokens=chunk_tokens)
+    _check(load().vc_validate_full_kv(ctx.handle, C.byref(d), _ptr(cu_win, torch.int32, "cu_win"), int(total_win),
+                                      _ptr(report, torch.int64, "report"), _stream(stream)))
 
 
 def vc_draft_workspace_bytes(n_q_heads, n_kv_heads, n_seqs, **kv) -> int:

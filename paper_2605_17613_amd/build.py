@@ -6,7 +6,7 @@ import subprocess
 import sys
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-SOURCES = ["ctx.hip", "accept.hip", "draft.hip", "verify.hip", "compress.hip", "sample.hip", "sched.cpp"]
+SOURCES = ["ctx.hip", "accept.hip", "draft.hip", "verify.hip", "compress.hip", "sample.hip", "validate.hip", "sched.cpp"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-fno-gpu-rdc",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wall", "-Wno-unused-function"]
 

@@ -52,8 +52,20 @@ __device__ __forceinline__ void st_stream(uint4* p, const uint4& v) {
   __builtin_nontemporal_store(w, reinterpret_cast<stream_u32x4*>(p));
 }
 
-// Integer tunable read once from the environment (sweeps); `dflt` when unset or invalid.
-int env_int(const char* name, int dflt, int lo, int hi);
+// Launch-shape tunables.  Each is read from the environment variable of its name once, when the
+// library first needs one (thread safe), and can be overridden with vc_set_tunable; the hot path
+// only reads an atomic integer.  tunable() returns the set value if it lies in [lo, hi], else `dflt`.
+enum Tunable {
+  kTunDraftBf16Wgs, kTunDraftQuantWgs, kTunDraftMinTok, kTunDraftMinBlk, kTunDraftTaper,
+  kTunVerifyWgs, kTunVerifyMinTok, kTunVerifyWorklist, kTunVerifyListMin, kTunVerifyTaper, kTunVerifyQueueWgs,
+  kNumTunables
+};
+int tunable(Tunable t, int dflt, int lo, int hi);
+
+// One-time per-device set-up of the kernels that need more than the default dynamic LDS (called by
+// vc_create with the device current).
+vc_status draft_init_device();
+vc_status verify_init_device();
 
 }  // namespace vc
 
@@ -66,6 +78,7 @@ struct vc_ctx {
   int64_t issued;  // next ticket
   // armed by vc_time_main_kernel: events recorded around the main kernel(s) of the next attention call
   hipEvent_t time_begin, time_end;
+  int n_cu;                // compute units of the device
 };
 
 namespace vc {

@@ -364,12 +364,13 @@ __global__ __launch_bounds__(kTopkThreads) void topk_keep_kernel(TopkParams p) {
   int* hist = sh.hist;
   const int b = blockIdx.y, h = blockIdx.x, tid = threadIdx.x;
   const int n = p.cu_ctx[b + 1] - p.cu_ctx[b];
-  const int k = min(p.cu_keep[b + 1] - p.cu_keep[b], n);
+  const int span = p.cu_keep[b + 1] - p.cu_keep[b];   // list stride of the sequence, as vc_draft_attn reads the lists
+  const int k = min(span, n);
   if (k <= 0) return;
   const int f = min(p.forced_first ? p.forced_first[b] : 0, k);
   const int l = min(p.forced_last ? p.forced_last[b] : 0, k - f);
   const float* s = p.scores + static_cast<size_t>(p.cu_ctx[b]) * p.n_kv_heads + static_cast<size_t>(h) * n;
-  int* out = p.keep_idx + static_cast<size_t>(p.cu_keep[b]) * p.n_kv_heads + static_cast<size_t>(h) * k;
+  int* out = p.keep_idx + static_cast<size_t>(p.cu_keep[b]) * p.n_kv_heads + static_cast<size_t>(h) * span;
   const int free_lo = f, free_hi = n - l;          // free positions: [free_lo, free_hi)
   const int want = k - f - l;                      // how many of them to keep
   // ---- threshold: the want-th largest key among the free positions (radix select, 12 + 10 + 10 bits)

@@ -4,8 +4,11 @@
 // a request sits in CPU memory and is reloaded asynchronously while other work drafts.  Here each
 // chunk is one hipMemcpyAsync on a dedicated copy stream followed by one event; compute streams
 // wait on the event of the chunk they need, so the host never blocks.
+#include <limits.h>
 #include <stdarg.h>
 #include <stdlib.h>
+
+#include <atomic>
 
 #include "common.h"
 
@@ -29,13 +32,42 @@ vc_status hip_fail(hipError_t e, const char* what) {
   return VC_ERR_HIP;
 }
 
-int env_int(const char* name, int dflt, int lo, int hi) {
-  const char* s = getenv(name);
-  if (!s || !*s) return dflt;
-  char* end = nullptr;
-  long v = strtol(s, &end, 10);
-  if (end == s || v < lo || v > hi) return dflt;
-  return static_cast<int>(v);
+namespace {
+const char* const kTunableNames[kNumTunables] = {
+    "VC_DRAFT_BF16_WGS", "VC_DRAFT_QUANT_WGS", "VC_DRAFT_MIN_TOK", "VC_DRAFT_MIN_BLK", "VC_DRAFT_TAPER",
+    "VC_VERIFY_WGS", "VC_VERIFY_MIN_TOK", "VC_VERIFY_WORKLIST", "VC_VERIFY_LIST_MIN", "VC_VERIFY_TAPER", "VC_VERIFY_QUEUE_WGS"};
+constexpr int kUnset = INT_MIN;
+
+struct TunableTable {
+  std::atomic<int> value[kNumTunables];
+  TunableTable() {
+    for (int i = 0; i < kNumTunables; ++i) {
+      int v = kUnset;
+      const char* s = getenv(kTunableNames[i]);
+      if (s && *s) {
+        char* end = nullptr;
+        const long x = strtol(s, &end, 10);
+        if (end != s && x >= 0 && x <= INT_MAX) v = static_cast<int>(x);
+      }
+      value[i].store(v, std::memory_order_relaxed);
+    }
+  }
+};
+TunableTable& tunables() {
+  static TunableTable table;    // constructed once, thread safe
+  return table;
+}
+int tunable_index(const char* name) {
+  if (!name) return -1;
+  for (int i = 0; i < kNumTunables; ++i)
+    if (strcmp(name, kTunableNames[i]) == 0) return i;
+  return -1;
+}
+}  // namespace
+
+int tunable(Tunable t, int dflt, int lo, int hi) {
+  const int v = tunables().value[t].load(std::memory_order_relaxed);
+  return (v == kUnset || v < lo || v > hi) ? dflt : v;
 }
 
 }  // namespace vc
@@ -61,9 +93,53 @@ extern "C" vc_status vc_create(int device, vc_ctx** out) {
     return hip_fail(e, "hipStreamCreateWithFlags");
   }
   c->events = static_cast<hipEvent_t*>(calloc(vc_ctx::kRing, sizeof(hipEvent_t)));
+  vc_status st = c->events ? VC_OK : fail(VC_ERR_INVALID_ARG, "vc_create: out of host memory");
+  // the kernels' LDS attributes are per device: set them here, once per context, so that no attention
+  // call ever has to (a first call made under stream capture could not)
+  if (st == VC_OK) st = draft_init_device();
+  if (st == VC_OK) st = verify_init_device();
+  if (st == VC_OK) {
+    int cus = 0;
+    e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device);
+    if (e != hipSuccess) st = hip_fail(e, "hipDeviceGetAttribute");
+    c->n_cu = cus;
+  }
+  if (st != VC_OK) {
+    (void)hipStreamDestroy(c->copy_stream);
+    free(c->events);
+    free(c);
+    return st;
+  }
   c->issued = 0;
   *out = c;
   return VC_OK;
+}
+
+extern "C" vc_status vc_set_tunable(const char* name, int32_t value) {
+  const int i = tunable_index(name);
+  VC_REQUIRE(i >= 0, VC_ERR_INVALID_ARG, "vc_set_tunable: unknown tunable %s", name ? name : "(null)");
+  tunables().value[i].store(value < 0 ? kUnset : value, std::memory_order_relaxed);
+  return VC_OK;
+}
+
+extern "C" vc_status vc_get_tunable(const char* name, int32_t* value, int32_t* is_set) {
+  const int i = tunable_index(name);
+  VC_REQUIRE(i >= 0 && value && is_set, VC_ERR_INVALID_ARG, "vc_get_tunable: unknown tunable or NULL pointer");
+  const int v = tunables().value[i].load(std::memory_order_relaxed);
+  *is_set = v != kUnset;
+  *value = v == kUnset ? 0 : v;
+  return VC_OK;
+}
+
+extern "C" vc_status vc_stream_status(vc_ctx* c, void* stream) {
+  VC_REQUIRE(c != nullptr, VC_ERR_INVALID_ARG, "vc_stream_status: ctx is NULL");
+  const hipError_t e = hipStreamQuery(static_cast<hipStream_t>(stream));
+  if (e == hipSuccess) return VC_OK;
+  if (e == hipErrorNotReady) {
+    (void)hipGetLastError();
+    return fail(VC_ERR_NOT_READY, "vc_stream_status: work is still in flight");
+  }
+  return hip_fail(e, "hipStreamQuery");
 }
 
 extern "C" vc_status vc_time_main_kernel(vc_ctx* c, void* begin_event, void* end_event) {

@@ -954,14 +954,14 @@ static DraftPlan make_plan(const vc_comp_kv* kv) {
   auto uniform = [&](int sum, int mx) {
     return sum <= 0 || static_cast<int64_t>(mx) * kv->n_seqs * 10 <= static_cast<int64_t>(sum) * 11;
   };
-  const int target_a = env_int("VC_DRAFT_BF16_WGS", uniform(kv->sum_keep, kv->max_keep) ? 256 : 512, 1, 1 << 20);
-  const int target_b = env_int("VC_DRAFT_QUANT_WGS", uniform(kv->sum_blk, kv->max_blk) ? 768 : 1536, 1, 1 << 20);
+  const int target_a = tunable(kTunDraftBf16Wgs, uniform(kv->sum_keep, kv->max_keep) ? 256 : 512, 1, 1 << 20);
+  const int target_b = tunable(kTunDraftQuantWgs, uniform(kv->sum_blk, kv->max_blk) ? 768 : 1536, 1, 1 << 20);
   pl.split_a = pick_chunk(static_cast<int64_t>(kv->sum_keep) * kv->n_kv_heads, kv->max_keep, lists, 128,
-                          env_int("VC_DRAFT_MIN_TOK", 256, 128, 1 << 20), target_a);
+                          tunable(kTunDraftMinTok, 256, 128, 1 << 20), target_a);
   pl.s1 = has_a ? ceil_div(kv->max_keep, pl.split_a) : 0;
   const int npass = ceil_div(g, heads_per_pass(kv->bits, g));
   pl.bps = pick_chunk(static_cast<int64_t>(kv->sum_blk) * kv->n_kv_heads * npass, kv->max_blk, lists * npass, 4,
-                      env_int("VC_DRAFT_MIN_BLK", 16, 4, 1 << 20), target_b);
+                      tunable(kTunDraftMinBlk, 16, 4, 1 << 20), target_b);
   pl.s2 = has_b ? ceil_div(kv->max_blk, pl.bps) : 0;
   pl.ns = pl.s1 + pl.s2;
   if (pl.ns == 0) pl.ns = 1;
@@ -996,6 +996,16 @@ static vc_status check_comp(const vc_comp_kv* kv, const char* who) {
   return VC_OK;
 }
 
+// the row kernel's ring needs more dynamic LDS than the default limit: a per-device function attribute
+vc_status draft_init_device() {
+  constexpr int kLds = rows_lds(32, 4);
+  VC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(draft_bf16_kernel<true, 32, 4>),
+                             hipFuncAttributeMaxDynamicSharedMemorySize, kLds));
+  VC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(draft_bf16_kernel<false, 32, 4>),
+                             hipFuncAttributeMaxDynamicSharedMemorySize, kLds));
+  return VC_OK;
+}
+
 }  // namespace vc
 
 using namespace vc;
@@ -1010,19 +1020,17 @@ extern "C" vc_status vc_draft_workspace_bytes(const vc_comp_kv* kv, size_t* byte
   return VC_OK;
 }
 
-extern "C" vc_status vc_draft_attn(vc_ctx* ctx, const vc_comp_kv* kv, const void* q, float softmax_scale, void* out,
-                                   float* lse, void* workspace, size_t workspace_bytes, void* stream) {
-  VC_REQUIRE(ctx != nullptr, VC_ERR_INVALID_ARG, "vc_draft_attn: ctx is NULL");
-  vc_status stt = check_comp(kv, "vc_draft_attn");
-  if (stt != VC_OK) return stt;
-  if (kv->n_seqs == 0) return VC_OK;
-  VC_REQUIRE(q && out, VC_ERR_INVALID_ARG, "vc_draft_attn: q or out is NULL");
-  VC_REQUIRE(aligned16(q) && aligned16(out), VC_ERR_INVALID_ARG, "vc_draft_attn: q/out not 16-byte aligned");
+// Both draft entry points: `workspace` is the caller's buffer (vc_draft_attn) or this device's
+// static scratch (vc_draft_attn_static, whose `who` names it in messages).
+static vc_status draft_attn_impl(const char* who, vc_ctx* ctx, const vc_comp_kv* kv, const void* q, float softmax_scale,
+                                 void* out, float* lse, void* workspace, size_t workspace_bytes, void* stream) {
+  VC_REQUIRE(q && out, VC_ERR_INVALID_ARG, "%s: q or out is NULL", who);
+  VC_REQUIRE(aligned16(q) && aligned16(out), VC_ERR_INVALID_ARG, "%s: q/out not 16-byte aligned", who);
   size_t need = 0;
   vc_draft_workspace_bytes(kv, &need);
-  VC_REQUIRE(workspace != nullptr && workspace_bytes >= need, VC_ERR_WORKSPACE, "vc_draft_attn: workspace %zu bytes, need %zu",
+  VC_REQUIRE(workspace != nullptr && workspace_bytes >= need, VC_ERR_WORKSPACE, "%s: workspace %zu bytes, need %zu", who,
              workspace_bytes, need);
-  VC_REQUIRE(aligned16(workspace), VC_ERR_INVALID_ARG, "vc_draft_attn: workspace not 16-byte aligned");
+  VC_REQUIRE(aligned16(workspace), VC_ERR_INVALID_ARG, "%s: workspace not 16-byte aligned", who);
 
   const DraftPlan pl = make_plan(kv);
   hipStream_t st = static_cast<hipStream_t>(stream);
@@ -1046,14 +1054,6 @@ extern "C" vc_status vc_draft_attn(vc_ctx* ctx, const vc_comp_kv* kv, const void
     dim3 grid(pl.s1, kv->n_kv_heads, kv->n_seqs);
     // 32-token steps, 4 waves (16-token steps with 8 waves measured the same: the gather itself binds)
     constexpr int kLds = rows_lds(32, 4);
-    static bool lds_attr_set = false;
-    if (!lds_attr_set) {
-      VC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(draft_bf16_kernel<true, 32, 4>),
-                                 hipFuncAttributeMaxDynamicSharedMemorySize, kLds));
-      VC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(draft_bf16_kernel<false, 32, 4>),
-                                 hipFuncAttributeMaxDynamicSharedMemorySize, kLds));
-      lds_attr_set = true;
-    }
     if (kv->keep_idx) hipLaunchKernelGGL((draft_bf16_kernel<true, 32, 4>), grid, dim3(256), kLds, st, bp);
     else hipLaunchKernelGGL((draft_bf16_kernel<false, 32, 4>), grid, dim3(256), kLds, st, bp);
   }
@@ -1095,4 +1095,13 @@ extern "C" vc_status vc_draft_attn(vc_ctx* ctx, const vc_comp_kv* kv, const void
     hipLaunchKernelGGL(draft_merge_kernel<1>, dim3(kv->n_q_heads, kv->n_seqs), dim3(128), 0, st, mp);
   VC_HIP(hipGetLastError());
   return VC_OK;
+}
+
+extern "C" vc_status vc_draft_attn(vc_ctx* ctx, const vc_comp_kv* kv, const void* q, float softmax_scale, void* out,
+                                   float* lse, void* workspace, size_t workspace_bytes, void* stream) {
+  VC_REQUIRE(ctx != nullptr, VC_ERR_INVALID_ARG, "vc_draft_attn: ctx is NULL");
+  vc_status stt = check_comp(kv, "vc_draft_attn");
+  if (stt != VC_OK) return stt;
+  if (kv->n_seqs == 0) return VC_OK;
+  return draft_attn_impl("vc_draft_attn", ctx, kv, q, softmax_scale, out, lse, workspace, workspace_bytes, stream);
 }

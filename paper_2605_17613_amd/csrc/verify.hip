@@ -666,9 +666,9 @@ static VerifyPlan make_verify_plan(const vc_full_kv* kv) {
   // chunks (measured: 256 against 512 workgroups at config-2 shape 652 vs 694 us; the ragged
   // config-4 batch 1470 us with 256, 1241 us with 768).
   const bool uniform = kv->sum_ctx <= 0 || static_cast<int64_t>(kv->max_ctx) * kv->n_seqs * 10 <= static_cast<int64_t>(kv->sum_ctx) * 11;
-  const int target = env_int("VC_VERIFY_WGS", uniform ? 256 : 768, 1, 1 << 20);
+  const int target = tunable(kTunVerifyWgs, uniform ? 256 : 768, 1, 1 << 20);
   int64_t per = ceil_div64(sum > 0 ? sum : 1, target);
-  const int min_tok = env_int("VC_VERIFY_MIN_TOK", 1024, 128, 1 << 24);
+  const int min_tok = tunable(kTunVerifyMinTok, 1024, 128, 1 << 24);
   if (per < min_tok) per = min_tok;
   if (per > total_max) per = total_max > 0 ? total_max : 1;
   per = ceil_div64(per, uniform ? 128 : 128 << kMaxShift) * (uniform ? 128 : 128 << kMaxShift);
@@ -681,11 +681,11 @@ static VerifyPlan make_verify_plan(const vc_full_kv* kv) {
   // The list costs a launch of its own (about 15 us), which pays from a few hundred microseconds of
   // work on: 2^21 token-heads are 1 GB of K and V.  (VC_VERIFY_LIST_MIN = 0 sends every ragged batch
   // through the list: tests.)
-  const int64_t list_min = env_int("VC_VERIFY_LIST_MIN", 1 << 21, 0, 1 << 30);
+  const int64_t list_min = tunable(kTunVerifyListMin, 1 << 21, 0, 1 << 30);
   const bool fits = static_cast<int64_t>(kv->n_seqs) * pl.nchunk * kv->n_kv_heads * ceil_div(kv->max_win * (kv->n_q_heads / kv->n_kv_heads), 256) < (1 << 30);
-  if (!uniform && sum >= list_min && fits && kv->n_seqs >= 2 && kv->n_seqs <= kMaxListSeqs && env_int("VC_VERIFY_WORKLIST", 1, 0, 1) != 0) {
+  if (!uniform && sum >= list_min && fits && kv->n_seqs >= 2 && kv->n_seqs <= kMaxListSeqs && tunable(kTunVerifyWorklist, 1, 0, 1) != 0) {
     while (pl.max_shift < kMaxShift && (pl.chunk_tok >> (pl.max_shift + 1)) % 128 == 0) ++pl.max_shift;   // pieces stay whole tiles
-    pl.max_shift = env_int("VC_VERIFY_TAPER", pl.max_shift, 0, pl.max_shift);
+    pl.max_shift = tunable(kTunVerifyTaper, pl.max_shift, 0, pl.max_shift);
     // every sequence has at most one partial piece: sum / shortest piece + n bounds the list
     const int64_t bound = (static_cast<int64_t>(kv->sum_ctx) + static_cast<int64_t>(kv->n_seqs) * kv->max_win) / (pl.chunk_tok >> pl.max_shift) + kv->n_seqs;
     if (bound <= kMaxListItems) pl.list_items = static_cast<int>(bound);
@@ -716,6 +716,15 @@ static vc_status check_full(const vc_full_kv* kv, const char* who) {
   VC_REQUIRE(kv->cu_ctx != nullptr, VC_ERR_INVALID_ARG, "%s: cu_ctx is NULL", who);
   VC_REQUIRE(kv->max_ctx == 0 || (kv->k && kv->v), VC_ERR_INVALID_ARG, "%s: k or v is NULL", who);
   VC_REQUIRE(aligned16(kv->k) && aligned16(kv->v), VC_ERR_INVALID_ARG, "%s: k/v not 16-byte aligned", who);
+  return VC_OK;
+}
+
+// the K/V ring needs more dynamic LDS than the default limit: a per-device function attribute
+vc_status verify_init_device() {
+  VC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(verify_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                             kVerifyLds));
+  VC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(verify_queue_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                             kVerifyLds));
   return VC_OK;
 }
 
@@ -778,14 +787,6 @@ extern "C" vc_status vc_verify_attn_range(vc_ctx* ctx, const vc_full_kv* kv, con
              pl.chunk_tok, total_max);
   if (tok_begin >= total_max) return VC_OK;
 
-  static bool lds_attr_set = false;
-  if (!lds_attr_set) {
-    VC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(verify_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
-                               kVerifyLds));
-    VC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(verify_queue_kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
-                               kVerifyLds));
-    lds_attr_set = true;
-  }
   hipStream_t st = static_cast<hipStream_t>(stream);
   VerifyParams vp{};
   vp.qw = static_cast<const uint16_t*>(q_win);
@@ -813,10 +814,8 @@ extern "C" vc_status vc_verify_attn_range(vc_ctx* ctx, const vc_full_kv* kv, con
     vp.list = list;
     vp.list_seqs = seq_end - seq_begin;
     vp.list_chunks = nchunk;
-    static int cus[64] = {0};          // workgroups of the queue launch: one per CU (each fills the LDS of one)
-    int& n_cu = cus[ctx->device & 63];
-    if (n_cu == 0) VC_HIP(hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, ctx->device));
-    grid = dim3(env_int("VC_VERIFY_QUEUE_WGS", n_cu, 1, 1 << 16), 1, 1);
+    // workgroups of the queue launch: one per CU (each fills the LDS of one)
+    grid = dim3(tunable(kTunVerifyQueueWgs, ctx->n_cu > 0 ? ctx->n_cu : 256, 1, 1 << 16), 1, 1);
   }
   // (A variant with 64 rows per wave halves the LDS traffic per flop but leaves one wave per SIMD;
   // it measured slower at every window - 1781 vs 1363 us at w = 64, config-2 shape - and was dropped.)

@@ -18,3 +18,20 @@ def lib():
     import paper_2605_17613_amd as vc
     vc.load()
     return vc
+
+
+@pytest.fixture
+def tunables(lib):
+    """Set launch-shape tunables of the library for one test; every one is back at its default afterwards."""
+    class _Tun:
+        def __init__(self):
+            self.names = set()
+
+        def set(self, name, value):
+            self.names.add(name)
+            lib.vc_set_tunable(name, int(value))
+
+    t = _Tun()
+    yield t
+    for name in t.names:
+        lib.vc_set_tunable(name, -1)

@@ -85,6 +85,32 @@ def test_draft_long_tails_in_both_merge_variants(lib, ctx, nseq):
 
 
 @pytest.mark.parametrize("bits", [4, 2])
+def test_draft_quant_just_inside_the_fp16_range_limits(lib, ctx, bits):
+    """The header's number range for block records: value scale and |value zero| up to 4094, key
+    metadata times the scaled query inside fp16.  Key outlier channels x100 (key zero points of
+    several hundred) and values of +-4000 (value scales 533 for int4, 2667 for int2) sit just inside."""
+    tb = synth.tokens_per_block(bits)
+    lens = [tb * 21, tb * 5]
+    lay = synth.make_layer(81, DEV, ctx_len=lens, n_q_heads=8, n_kv_heads=2)
+    k = lay.k_full.float()
+    k[:, :, [7, 64, 101]] *= 100.0
+    v = (lay.v_full.float() * 1300.0).clamp_(-4000.0, 4000.0)
+    v[3::tb, :, 0] = 4000.0; v[3::tb, :, 1] = -4000.0            # groups that span the whole range
+    lay.k_full, lay.v_full = k.to(torch.bfloat16).contiguous(), v.to(torch.bfloat16).contiguous()
+    recs, lo = [], 0
+    for n in lens:
+        recs.append(synth.quantize_records(lay.k_full[lo:lo + n], lay.v_full[lo:lo + n], bits).reshape(-1, 5120))
+        lo += n
+    lay.blocks[bits] = torch.cat(recs).contiguous()
+    lay.cu_blk[bits] = torch.tensor([0, lens[0] // tb, sum(lens) // tb], dtype=torch.int32, device=DEV)
+    lay.max_blk[bits] = lens[0] // tb
+    meta = lay.blocks[bits][:, 4608:5120].contiguous().view(torch.float16).float()
+    assert meta.abs().max().item() <= 4094.0 and meta[:, :128].max().item() >= (500.0 if bits == 4 else 2600.0)
+    out = check_draft(lib, ctx, lay, f"int{bits} range limits", bits=bits)
+    assert torch.isfinite(out.float()).all()
+
+
+@pytest.mark.parametrize("bits", [4, 2])
 def test_draft_lossless_grid_equals_bf16_path(lib, ctx, bits):
     """Cross-kernel: records built from exact grid values dequantise to the bf16 values, so the
     record kernel and the bf16 kernel must agree (both are also checked against the oracle)."""
@@ -270,3 +296,44 @@ def test_main_kernel_timing_events(lib, ctx):
     assert ev[1].elapsed_time(ev[2]) == inner
     with pytest.raises(lib.VcError):
         lib.vc_time_main_kernel(ctx, ev[0], None)
+
+
+# ------------------------------------------------------------------ optional data validation
+def _report(lib, ctx, fn):
+    rep = torch.full((2,), 7, dtype=torch.int64, device=DEV)
+    fn(rep)
+    torch.cuda.synchronize()
+    count, key = rep.tolist()
+    return count, (None if key == -1 else (key >> 56, (key >> 32) & 0xFFFFFF, key & 0xFFFFFFFF))
+
+
+def test_validate_comp_and_full_descriptors(lib, ctx):
+    lay = synth.make_layer(90, DEV, ctx_len=[900, 70, 2000], n_q_heads=8, n_kv_heads=2, keep=[257, 70, 5],
+                           keep_first=[4, 2, 1], keep_last=[9, 3, 2], quant_bits=(4,), tail_len=[3, 0, 17], win=[4, 0, 9])
+    kw = H.draft_kwargs(lay, bits=4, use_pool=True, use_keep=True, use_tail=True)
+    geo = dict(n_q_heads=8, n_kv_heads=2, n_seqs=3)
+    assert _report(lib, ctx, lambda r: lib.vc_validate_comp_kv(ctx, r, **geo, **kw)) == (0, None)
+    # a kept position out of range, in list (sequence 0, head 1), entry 256
+    bad = dict(kw); bad["keep_idx"] = lay.keep_idx.clone(); bad["keep_idx"][257 + 256] = 900
+    assert _report(lib, ctx, lambda r: lib.vc_validate_comp_kv(ctx, r, **geo, **bad)) == (1, (4, 0, 256))
+    # two entries swapped in list (sequence 2, head 0): positions 1 and 2 out of order (one violation at entry 2 or two)
+    bad["keep_idx"] = lay.keep_idx.clone()
+    base = (257 + 70) * 2
+    bad["keep_idx"][base + 1], bad["keep_idx"][base + 2] = lay.keep_idx[base + 2].item(), lay.keep_idx[base + 1].item()
+    count, first = _report(lib, ctx, lambda r: lib.vc_validate_comp_kv(ctx, r, **geo, **bad))
+    assert count >= 1 and first[0] == 5 and first[1] == 2
+    # a host-side maximum that under-estimates, and a decreasing prefix array
+    low = dict(kw); low["max_blk"] = lay.max_blk[4] - 1
+    assert _report(lib, ctx, lambda r: lib.vc_validate_comp_kv(ctx, r, **geo, **low)) == (1, (2, 2, 2))
+    dec = dict(kw); dec["cu_tail"] = torch.tensor([0, 3, 2, 20], dtype=torch.int32, device=DEV)
+    count, first = _report(lib, ctx, lambda r: lib.vc_validate_comp_kv(ctx, r, **geo, **dec))
+    assert first == (1, 1, 3)
+    # a kept list longer than its sequence
+    long = dict(kw); long["cu_ctx"] = torch.tensor([0, 900, 960, 2960], dtype=torch.int32, device=DEV)
+    count, first = _report(lib, ctx, lambda r: lib.vc_validate_comp_kv(ctx, r, **geo, **long))
+    assert first[0] == 3 and first[1] == 1
+    full = dict(k=lay.k_full, v=lay.v_full, cu_ctx=lay.cu_ctx, max_ctx=2000, max_win=9)
+    assert _report(lib, ctx, lambda r: lib.vc_validate_full_kv(ctx, r, lay.cu_win, 13, **geo, **full)) == (0, None)
+    full["max_win"] = 8
+    assert _report(lib, ctx, lambda r: lib.vc_validate_full_kv(ctx, r, lay.cu_win, 13, **geo, **full)) == (1, (2, 2, 4))
+    assert lib.vc_stream_status(ctx) is True

@@ -1,7 +1,7 @@
 """Ragged verify launches that run from the device-built work list (pieces of per-sequence length
 taken off a queue by one workgroup per CU): results against the oracle, streamed launches against
 the one-shot call bit for bit, and the walk over every (sequence, chunk) that replaces a list too
-long to hold.  VC_VERIFY_LIST_MIN = 0 sends these small batches down the path large ones take."""
+long to hold.  The tunable VC_VERIFY_LIST_MIN = 0 sends these small batches down the path large ones take."""
 import numpy as np
 import pytest
 import torch
@@ -30,15 +30,15 @@ def _kv(lay, ctx_len, win, **extra):
     ([12000, 300, 0, 4100, 6000, 2500], [40, 3, 7, 0, 64, 1], 16, 4),   # an empty context and an empty window
     ([3000, 20000], [80, 9], 8, 2),                             # 320 rows: two row blocks per KV head
 ])
-def test_worklist_verify_matches_oracle(lib, ctx, monkeypatch, ctx_len, win, hq, hkv):
-    monkeypatch.setenv("VC_VERIFY_LIST_MIN", "0")
+def test_worklist_verify_matches_oracle(lib, ctx, tunables, ctx_len, win, hq, hkv):
+    tunables.set("VC_VERIFY_LIST_MIN", 0)
     lay = synth.make_layer(95, DEV, ctx_len=ctx_len, n_q_heads=hq, n_kv_heads=hkv, win=win)
     kv = _kv(lay, ctx_len, win, sum_ctx=sum(ctx_len))
     tw = lay.q_win.shape[0]
     nbytes = lib.vc_verify_workspace_bytes(hq, hkv, total_win=tw, **kv)
-    monkeypatch.setenv("VC_VERIFY_WORKLIST", "0")
+    tunables.set("VC_VERIFY_WORKLIST", 0)
     plain = lib.vc_verify_workspace_bytes(hq, hkv, total_win=tw, **kv)
-    monkeypatch.setenv("VC_VERIFY_WORKLIST", "1")
+    tunables.set("VC_VERIFY_WORKLIST", 1)
     assert nbytes > plain                                        # the list is on: its area follows the partials
     ws = torch.full((nbytes,), 0xFF, dtype=torch.uint8, device=DEV)       # poison (NaN partials, huge counters)
     out = torch.empty_like(lay.q_win)
@@ -51,10 +51,10 @@ def test_worklist_verify_matches_oracle(lib, ctx, monkeypatch, ctx_len, win, hq,
     assert np.abs(lse.cpu().numpy() - ref_lse).max() <= H.LSE_TOL
 
 
-def test_few_resident_workgroups_take_many_pieces_each(lib, ctx, monkeypatch):
+def test_few_resident_workgroups_take_many_pieces_each(lib, ctx, tunables):
     """Three resident workgroups instead of one per CU: each takes dozens of pieces in turn, of both row
     variants, reusing its LDS ring every time; the result is the same bits as with the full grid."""
-    monkeypatch.setenv("VC_VERIFY_LIST_MIN", "0")
+    tunables.set("VC_VERIFY_LIST_MIN", 0)
     ctx_len, win = [9000, 2048, 700, 5000, 3300], [64, 5, 33, 16, 40]
     lay = synth.make_layer(94, DEV, ctx_len=ctx_len, n_q_heads=8, n_kv_heads=2, win=win)
     kv = _kv(lay, ctx_len, win, sum_ctx=sum(ctx_len))
@@ -62,7 +62,7 @@ def test_few_resident_workgroups_take_many_pieces_each(lib, ctx, monkeypatch):
     ws = torch.empty(lib.vc_verify_workspace_bytes(8, 2, total_win=tw, **kv), dtype=torch.uint8, device=DEV)
     out_full = torch.empty_like(lay.q_win)
     lib.vc_verify_attn(ctx, lay.q_win, lay.k_win, lay.v_win, lay.cu_win, lay.scale, out_full, workspace=ws, **kv)
-    monkeypatch.setenv("VC_VERIFY_QUEUE_WGS", "3")
+    tunables.set("VC_VERIFY_QUEUE_WGS", 3)
     out_few = torch.empty_like(lay.q_win)
     lib.vc_verify_attn(ctx, lay.q_win, lay.k_win, lay.v_win, lay.cu_win, lay.scale, out_few, workspace=ws, **kv)
     torch.cuda.synchronize()
@@ -71,8 +71,8 @@ def test_few_resident_workgroups_take_many_pieces_each(lib, ctx, monkeypatch):
     assert H.rel_err(out_few, ref) <= H.TOL
 
 
-def test_worklist_streamed_launches_equal_one_shot(lib, ctx, monkeypatch):
-    monkeypatch.setenv("VC_VERIFY_LIST_MIN", "0")
+def test_worklist_streamed_launches_equal_one_shot(lib, ctx, tunables):
+    tunables.set("VC_VERIFY_LIST_MIN", 0)
     ctx_len, win, chunk = [7000, 2048, 700, 3100], [16, 5, 33, 64], 1024
     lay = synth.make_layer(96, DEV, ctx_len=ctx_len, n_q_heads=8, n_kv_heads=2, win=win)
     kv = _kv(lay, ctx_len, win, sum_ctx=sum(ctx_len), chunk_tokens=chunk)
@@ -103,10 +103,10 @@ def test_worklist_streamed_launches_equal_one_shot(lib, ctx, monkeypatch):
     assert H.rel_err(out1, ref) <= H.TOL
 
 
-def test_worklist_overflow_walks_every_chunk(lib, ctx, monkeypatch):
+def test_worklist_overflow_walks_every_chunk(lib, ctx, tunables):
     """A caller that understates sum_ctx gets a list with room for too few pieces; the kernels then
     walk every (sequence, chunk) of the launch, with the same results."""
-    monkeypatch.setenv("VC_VERIFY_LIST_MIN", "0")
+    tunables.set("VC_VERIFY_LIST_MIN", 0)
     ctx_len, win = [150000, 50000, 128], [4, 2, 1]
     lay = synth.make_layer(97, DEV, ctx_len=ctx_len, n_q_heads=8, n_kv_heads=2, win=win)
     kv = _kv(lay, ctx_len, win, sum_ctx=20000, chunk_tokens=128)        # 1564 pieces exist, the bound says 160
@@ -119,10 +119,10 @@ def test_worklist_overflow_walks_every_chunk(lib, ctx, monkeypatch):
     assert H.rel_err(out, ref) <= H.TOL
 
 
-def test_worklist_verify_in_a_captured_graph(lib, ctx, monkeypatch):
+def test_worklist_verify_in_a_captured_graph(lib, ctx, tunables):
     """The list kernel zeroes the queue's counter itself, so a captured verify replays correctly: every
     replay, with the queries changed in place and eager work in between, equals the eager call."""
-    monkeypatch.setenv("VC_VERIFY_LIST_MIN", "0")
+    tunables.set("VC_VERIFY_LIST_MIN", 0)
     ctx_len, win = [6000, 1500, 300, 4100], [16, 40, 3, 64]
     lay = synth.make_layer(98, DEV, ctx_len=ctx_len, n_q_heads=8, n_kv_heads=2, win=win)
     kv = _kv(lay, ctx_len, win, sum_ctx=sum(ctx_len))
@@ -161,10 +161,10 @@ def test_worklist_verify_in_a_captured_graph(lib, ctx, monkeypatch):
 
 
 @pytest.mark.parametrize("nseq", [400, 600])
-def test_many_short_sequences(lib, ctx, monkeypatch, nseq):
+def test_many_short_sequences(lib, ctx, tunables, nseq):
     """400 sequences still go through the list (its ranking loops run over all of them); 600 are more
     than a list holds and take the plain grid."""
-    monkeypatch.setenv("VC_VERIFY_LIST_MIN", "0")
+    tunables.set("VC_VERIFY_LIST_MIN", 0)
     rng = np.random.default_rng(nseq)
     ctx_len = [int(x) for x in rng.integers(0, 700, nseq)]
     ctx_len[7] = 5000                                            # one long sequence makes the batch ragged
@@ -174,9 +174,9 @@ def test_many_short_sequences(lib, ctx, monkeypatch, nseq):
     kv = _kv(lay, ctx_len, win, sum_ctx=sum(ctx_len))
     tw = lay.q_win.shape[0]
     nbytes = lib.vc_verify_workspace_bytes(8, 2, total_win=tw, **kv)
-    monkeypatch.setenv("VC_VERIFY_WORKLIST", "0")
+    tunables.set("VC_VERIFY_WORKLIST", 0)
     plain = lib.vc_verify_workspace_bytes(8, 2, total_win=tw, **kv)
-    monkeypatch.setenv("VC_VERIFY_WORKLIST", "1")
+    tunables.set("VC_VERIFY_WORKLIST", 1)
     assert (nbytes > plain) == (nseq <= 512)
     ws = torch.full((nbytes,), 0xFF, dtype=torch.uint8, device=DEV)
     out = torch.empty_like(lay.q_win)

@@ -124,3 +124,28 @@ def test_binding_rejects_wrong_dtypes_before_calling_the_library():
         B._ptr(torch.zeros(4, dtype=torch.float32), torch.bfloat16, "q")
     with pytest.raises(ValueError):
         B._ptr(torch.zeros(4, 4, dtype=torch.bfloat16).t(), torch.bfloat16, "q")
+
+
+def test_tunables_are_a_process_table_not_the_environment(monkeypatch):
+    """The plan reads tunables from the library's own table: set and restored through the C ABI, and
+    an environment change after the first use has no effect on the query (so a query and its call
+    cannot disagree because the environment moved between them)."""
+    lib = vc.load()
+    d = B.vc_full_kv()
+    d.n_seqs, d.n_q_heads, d.n_kv_heads, d.head_dim, d.max_ctx, d.max_win = 16, 32, 8, 128, 65536, 32
+    d.k, d.v, d.cu_ctx = 0x1000, 0x2000, 0x3000
+    chunk, nchunk = C.c_int32(), C.c_int32()
+    assert lib.vc_verify_plan(C.byref(d), C.byref(chunk), C.byref(nchunk)) == B.VC_OK
+    base = chunk.value
+    monkeypatch.setenv("VC_VERIFY_WGS", "1024")
+    assert lib.vc_verify_plan(C.byref(d), C.byref(chunk), C.byref(nchunk)) == B.VC_OK and chunk.value == base
+    assert vc.vc_get_tunable("VC_VERIFY_WGS") is None
+    vc.vc_set_tunable("VC_VERIFY_WGS", 1024)
+    assert vc.vc_get_tunable("VC_VERIFY_WGS") == 1024
+    assert lib.vc_verify_plan(C.byref(d), C.byref(chunk), C.byref(nchunk)) == B.VC_OK and chunk.value < base
+    vc.vc_set_tunable("VC_VERIFY_WGS", -1)
+    assert lib.vc_verify_plan(C.byref(d), C.byref(chunk), C.byref(nchunk)) == B.VC_OK and chunk.value == base
+    with pytest.raises(vc.VcError):
+        vc.vc_set_tunable("VC_NO_SUCH_THING", 1)
+    assert lib.vc_stream_status(None, None) == B.VC_ERR_INVALID_ARG
+    assert lib.vc_validate_comp_kv(None, None, None, None) == B.VC_ERR_INVALID_ARG
