@@ -20,7 +20,7 @@ def ctx(lib):
     c.close()
 
 
-def check_draft(lib, ctx, lay, tag, **sel):
+def check_draft(lib, ctx, lay, tag, lse_tol=H.LSE_TOL, **sel):
     kw = H.draft_kwargs(lay, **sel)
     print(f"[draft] {tag} {sel}", flush=True)
     out, lse = H.gpu_draft(lib, ctx, lay, **kw)
@@ -28,7 +28,7 @@ def check_draft(lib, ctx, lay, tag, **sel):
     err = H.rel_err(out, ref)
     assert err <= H.TOL, f"{tag}: rel err {err}"
     fin = np.isfinite(ref_lse)
-    assert np.abs(lse.cpu().numpy()[fin] - ref_lse[fin]).max() <= H.LSE_TOL
+    assert np.abs(lse.cpu().numpy()[fin] - ref_lse[fin]).max() <= lse_tol
     assert np.array_equal(np.isneginf(lse.cpu().numpy()), np.isneginf(ref_lse))
     return out
 
@@ -106,7 +106,9 @@ def test_draft_quant_just_inside_the_fp16_range_limits(lib, ctx, bits):
     lay.max_blk[bits] = lens[0] // tb
     meta = lay.blocks[bits][:, 4608:5120].contiguous().view(torch.float16).float()
     assert meta.abs().max().item() <= 4094.0 and meta[:, :128].max().item() >= (500.0 if bits == 4 else 2600.0)
-    out = check_draft(lib, ctx, lay, f"int{bits} range limits", bits=bits)
+    # scores reach +-60 here (x100 key channels), and an fp16 operand carries 2^-11 relative rounding: the
+    # log-sum-exp is held to 1e-3 of its magnitude instead of the absolute bound used at N(0,1) scale
+    out = check_draft(lib, ctx, lay, f"int{bits} range limits", lse_tol=0.06, bits=bits)
     assert torch.isfinite(out.float()).all()
 
 
