@@ -172,6 +172,20 @@ typedef enum {
 } vc_violation;
 vc_status vc_validate_comp_kv(vc_ctx* ctx, const vc_comp_kv* kv, int64_t* report, void* stream);
 
+/* vc_draft_attn for callers that cannot allocate device memory or hand over a workspace: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, checks,
+ * kernels and results as vc_draft_attn, but the split partials go to a fixed scratch array that is
+ * part of the library's device image (vc_draft_static_scratch_bytes reports its size, 8 MiB; every
+ * GPU the library runs on holds one until the process ends).  The call allocates nothing.  A batch
+ * whose vc_draft_workspace_bytes exceeds the scratch is refused with VC_ERR_WORKSPACE and nothing is
+ * enqueued.  All calls on one GPU share that GPU's array: calls that may overlap on one GPU (two
+ * streams, two threads) race - serialise them or use vc_draft_attn with separate workspaces.
+ * Nothing in the scratch has to start at zero (every partial is written before it is read), so the
+ * contents a previous call left behind are harmless. */
+vc_status vc_draft_static_scratch_bytes(size_t* bytes);
+vc_status vc_draft_attn_static(vc_ctx* ctx, const vc_comp_kv* kv, const void* q, float softmax_scale,
+                               void* out, float* lse, void* stream);
+
 /* Full KV of one layer, resident on the device (the destination of vc_swap_in). */
 typedef struct {
   int32_t n_seqs, n_q_heads, n_kv_heads, head_dim;

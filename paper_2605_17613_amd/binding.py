@@ -46,7 +46,7 @@ class vc_chunk(C.Structure):
 
 EXPORTS = ["vc_create", "vc_destroy", "vc_last_error", "vc_version", "vc_time_main_kernel",
            "vc_set_tunable", "vc_get_tunable", "vc_stream_status", "vc_validate_comp_kv", "vc_validate_full_kv",
-           "vc_draft_workspace_bytes", "vc_draft_attn", "vc_verify_workspace_bytes", "vc_verify_attn",
+           "vc_draft_workspace_bytes", "vc_draft_attn", "vc_draft_static_scratch_bytes", "vc_draft_attn_static", "vc_verify_workspace_bytes", "vc_verify_attn",
            "vc_verify_plan", "vc_verify_attn_range", "vc_verify_finish",
            "vc_accept_workspace_bytes", "vc_accept_len", "vc_accept_sample_workspace_bytes", "vc_accept_sample", "vc_swap_in", "vc_swap_in_rows", "vc_pack_rows", "vc_swap_wait", "vc_swap_query", "vc_swap_sync",
            "vc_keep_from_dropped", "vc_compress_quant", "vc_decompress_quant", "vc_topk_keep",
@@ -80,6 +80,9 @@ def load():
     lib.vc_draft_workspace_bytes.argtypes = [C.POINTER(vc_comp_kv), C.POINTER(C.c_size_t)]
     lib.vc_draft_attn.argtypes = [C.c_void_p, C.POINTER(vc_comp_kv), C.c_void_p, C.c_float, C.c_void_p,
                                   C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+    lib.vc_draft_static_scratch_bytes.argtypes = [C.POINTER(C.c_size_t)]
+    lib.vc_draft_attn_static.argtypes = [C.c_void_p, C.POINTER(vc_comp_kv), C.c_void_p, C.c_float, C.c_void_p,
+                                         C.c_void_p, C.c_void_p]
     lib.vc_verify_workspace_bytes.argtypes = [C.POINTER(vc_full_kv), C.c_int32, C.POINTER(C.c_size_t)]
     lib.vc_verify_attn.argtypes = [C.c_void_p, C.POINTER(vc_full_kv), C.c_void_p, C.c_void_p, C.c_void_p,
                                    C.c_void_p, C.c_int32, C.c_float, C.c_void_p, C.c_void_p, C.c_void_p,
@@ -248,6 +251,22 @@ def vc_draft_attn(ctx: Context, q, softmax_scale, out, *, n_kv_heads, lse=None, 
     _check(load().vc_draft_attn(ctx.handle, C.byref(d), _ptr(q, torch.bfloat16, "q"), float(softmax_scale),
                                 _ptr(out, torch.bfloat16, "out"), _ptr(lse, torch.float32, "lse"),
                                 _ptr(workspace, None, "workspace"), ws_bytes, _stream(stream)))
+    return out
+
+
+def vc_draft_static_scratch_bytes() -> int:
+    n = C.c_size_t()
+    _check(load().vc_draft_static_scratch_bytes(C.byref(n)))
+    return n.value
+
+
+def vc_draft_attn_static(ctx: Context, q, softmax_scale, out, *, n_kv_heads, lse=None, stream=None, **kv):
+    """vc_draft_attn without a workspace: the split partials live in the library's static scratch."""
+    n_seqs, n_q_heads = q.shape[0], q.shape[1]
+    d = _comp_desc(n_q_heads, n_kv_heads, n_seqs, head_dim=q.shape[2], **kv)
+    _check(load().vc_draft_attn_static(ctx.handle, C.byref(d), _ptr(q, torch.bfloat16, "q"), float(softmax_scale),
+                                       _ptr(out, torch.bfloat16, "out"), _ptr(lse, torch.float32, "lse"),
+                                       _stream(stream)))
     return out
 
 

@@ -6,6 +6,8 @@
 // over their tokens; one workgroup turns one split of one (sequence, KV head) into a partial
 // (m, l, O) for the g query heads of that KV head (GQA packing: K/V are read once for all of them)
 // and a merge kernel combines the partials of all sources.
+#include <atomic>
+
 #include "attn_common.h"
 #include "common.h"
 
@@ -996,8 +998,24 @@ static vc_status check_comp(const vc_comp_kv* kv, const char* who) {
   return VC_OK;
 }
 
+// Scratch of the entry point that allocates nothing (vc_draft_attn_static): the split partials live in
+// this file-scope device array instead of a caller workspace.  Every GPU holds its own copy at its
+// own address; the address is looked up once per device (draft_init_device, with that device
+// current) and host code only ever uses that pointer, never the symbol itself.
+constexpr size_t kStaticScratchBytes = static_cast<size_t>(8) << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+constexpr int kMaxDevices = 64;
+static std::atomic<void*> scratch_ptr[kMaxDevices];
+
 // the row kernel's ring needs more dynamic LDS than the default limit: a per-device function attribute
 vc_status draft_init_device() {
+  int dev = -1;
+  VC_HIP(hipGetDevice(&dev));
+  if (dev >= 0 && dev < kMaxDevices && scratch_ptr[dev].load(std::memory_order_acquire) == nullptr) {
+    void* ptr = nullptr;
+    VC_HIP(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+    scratch_ptr[dev].store(ptr, std::memory_order_release);
+  }
   constexpr int kLds = rows_lds(32, 4);
   VC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(draft_bf16_kernel<true, 32, 4>),
                              hipFuncAttributeMaxDynamicSharedMemorySize, kLds));
@@ -1104,4 +1122,28 @@ extern "C" vc_status vc_draft_attn(vc_ctx* ctx, const vc_comp_kv* kv, const void
   if (stt != VC_OK) return stt;
   if (kv->n_seqs == 0) return VC_OK;
   return draft_attn_impl("vc_draft_attn", ctx, kv, q, softmax_scale, out, lse, workspace, workspace_bytes, stream);
+}
+
+extern "C" vc_status vc_draft_static_scratch_bytes(size_t* bytes) {
+  VC_REQUIRE(bytes != nullptr, VC_ERR_INVALID_ARG, "vc_draft_static_scratch_bytes: bytes is NULL");
+  *bytes = kStaticScratchBytes;
+  return VC_OK;
+}
+
+extern "C" vc_status vc_draft_attn_static(vc_ctx* ctx, const vc_comp_kv* kv, const void* q, float softmax_scale, void* out,
+                                          float* lse, void* stream) {
+  const char* who = "vc_draft_attn_static";
+  VC_REQUIRE(ctx != nullptr, VC_ERR_INVALID_ARG, "%s: ctx is NULL", who);
+  vc_status stt = check_comp(kv, who);
+  if (stt != VC_OK) return stt;
+  if (kv->n_seqs == 0) return VC_OK;
+  size_t need = 0;
+  vc_draft_workspace_bytes(kv, &need);
+  VC_REQUIRE(need <= kStaticScratchBytes, VC_ERR_WORKSPACE,
+             "%s: this batch needs %zu bytes of split partials, the static scratch holds %zu; use vc_draft_attn with a workspace",
+             who, need, kStaticScratchBytes);
+  VC_REQUIRE(ctx->device >= 0 && ctx->device < kMaxDevices, VC_ERR_UNSUPPORTED, "%s: device %d", who, ctx->device);
+  void* ptr = scratch_ptr[ctx->device].load(std::memory_order_acquire);   // looked up by vc_create on this device
+  VC_REQUIRE(ptr != nullptr, VC_ERR_HIP, "%s: the scratch address of device %d is unknown", who, ctx->device);
+  return draft_attn_impl(who, ctx, kv, q, softmax_scale, out, lse, ptr, kStaticScratchBytes, stream);
 }
