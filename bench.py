@@ -51,9 +51,13 @@ def parse():
     ap.add_argument("--no-round3", action="store_true",
                     help="skip the config-3 round (32 layers, ctx 131072, 64-token horizon; pins 17 GB of host memory)")
     ap.add_argument("--round3", action="store_true", help="run the config-3 round even with --only")
+    ap.add_argument("--no-small", action="store_true", help="skip the legs of workload configs 0 and 1")
     ap.add_argument("--no-config4", action="store_true", help="skip the ragged mixed batch (config 4)")
     ap.add_argument("--config4", action="store_true", help="run the ragged mixed batch even with --only")
     ap.add_argument("--only", default="", help="comma list of legs to run per step: keep,d1,d2,d3,verify,accept")
+    ap.add_argument("--verify-series", action="store_true",
+                    help="also time the verify kernel launch by launch under different preludes (back to back, after an "
+                         "idle gap, between draft calls): shows how the clock management of the GPU shapes its timing")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     return ap.parse_args()
@@ -68,6 +72,23 @@ def device_clocks():
         return [l for l in lines if any(k in l for k in ("sclk", "mclk", "fclk"))] or None
     except Exception:
         return None
+
+
+TRAFFIC_PROFILE = os.path.join("profiles", "hbm_traffic_config2_round.txt")
+
+
+def profile_traffic(kernel):
+    """HBM bytes per launch of `kernel` from the committed rocprofv3 counter summary: the table row
+    'kernel  FETCH KiB  scaled MB  WRITE KiB  scaled MB ...' -> (read + written bytes, source), or
+    (None, None) when the file or the row is missing."""
+    try:
+        for line in open(os.path.join(ROOT, TRAFFIC_PROFILE)):
+            f = line.split()
+            if len(f) >= 5 and f[0] == kernel:
+                return (float(f[2]) + float(f[4])) * 1e6, f"{TRAFFIC_PROFILE} (rocprofv3 --pmc FETCH_SIZE, WRITE_SIZE; not measured in this run)"
+    except (OSError, ValueError):
+        pass
+    return None, None
 
 
 def draft_bytes(n_seqs, hq, hkv, *, blocks=0, kept=0, tail=0):
@@ -153,8 +174,8 @@ def main():
         """One pass of the hot path; `record` collects (leg, start_event, end_event).  With
         `hooks` the library also records events around the main kernel of each attention call
         (a pass of its own after the timed steps: the extra events cost a few microseconds)."""
-        def timed(name, fn, main_kernel=False):
-            if main_kernel and hooks:
+        def timed(name, fn, main_kernel=False, always_hook=False):
+            if main_kernel and (hooks or always_hook):
                 # a second pair of events, recorded by the library around its main kernel only
                 # (record once first: torch creates the HIP event on first use)
                 k0, k1 = ev(), ev()
@@ -177,7 +198,8 @@ def main():
                                                                workspace=ws, **kw), main_kernel=True)
         if "verify" in legs:
             timed("verify", lambda: vc.vc_verify_attn(ctx, lay.q_win, lay.k_win, lay.v_win, lay.cu_win, lay.scale,
-                                                      vout, n_seqs=B, workspace=ws, **vargs), main_kernel=True)
+                                                      vout, n_seqs=B, workspace=ws, **vargs), main_kernel=True,
+                  always_hook=True)      # one call per step: the kernel and the call are timed on the same launches
         if "accept" in legs:
             timed("accept", lambda: vc.vc_accept_len(ctx, lay.logits, lay.cu_rows, lay.draft_ids, lay.cu_win,
                                                      acc, nxt, amax, workspace=aws))
@@ -210,8 +232,13 @@ def main():
     torch.cuda.synchronize()
 
     dur = {}
-    for name, e0, e1 in rec + [r for r in rec_k if r[0].endswith("_kernel")]:
+    for name, e0, e1 in rec + [r for r in rec_k if r[0].endswith("_kernel") and r[0] != "verify_kernel"]:
         dur.setdefault(name, []).append(e0.elapsed_time(e1))
+    # the draft calls of the pass that carried the library's kernel events (their call times include
+    # the two extra event records; the kernel times are compared with THESE call times)
+    for name, e0, e1 in rec_k:
+        if name in ("d1", "d2", "d3"):
+            dur.setdefault(name + "_hookpass", []).append(e0.elapsed_time(e1))
     mean_ms = {k: sum(v) / len(v) for k, v in dur.items()}
 
     def spread(name):
@@ -235,7 +262,7 @@ def main():
         if k in mean_ms:
             res[k] = {"us": mean_ms[k] * 1e3, "GBps": by[k] / (mean_ms[k] * 1e-3) / 1e9,
                       "frac_hbm": by[k] / (mean_ms[k] * 1e-3) / 1e9 / HBM_PEAK_GBPS,
-                      "kernel_us": mean_ms[k + "_kernel"] * 1e3,
+                      "kernel_us": mean_ms[k + "_kernel"] * 1e3, "call_us_same_launches_as_kernel_us": mean_ms[k + "_hookpass"] * 1e3,
                       "kernel_frac_hbm": by[k] / (mean_ms[k + "_kernel"] * 1e-3) / 1e9 / HBM_PEAK_GBPS, **spread(k)}
             tot_b += by[k] * len(dur[k])
             tot_t += sum(dur[k]) * 1e-3
@@ -260,14 +287,21 @@ def main():
     roofline = None
     if "d2" in mean_ms:
         a = by["d2"] / (mean_ms["d2_kernel"] * 1e-3) / 1e9
-        # HBM bytes per launch from the committed rocprofv3 PMC runs (profiles/hbm_traffic_config2_round.txt:
-        # FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000); only valid for the default config-2 sizes
-        traffic = 1343.1e6 + 1.7e6 if (B, N, W) == (16, 65536, 32) else None
+        # HBM bytes per launch: not measurable from inside the process; read from the committed summary of
+        # the rocprofv3 --pmc runs of this same command (FETCH_SIZE and WRITE_SIZE, each scaled by what the
+        # counter reads for a copy kernel of known size), valid for the default config-2 sizes only
+        traffic, traffic_src = (profile_traffic("draft_quant_kernel<4,4>") if (B, N, W) == (16, 65536, 32) else (None, None))
         roofline = {"bound": "hbm", "kernel": "draft_quant_kernel<4>", "achieved": a, "peak": HBM_PEAK_GBPS,
-                    "unit": "GB/s", "frac": a / HBM_PEAK_GBPS, "traffic": traffic,
+                    "unit": "GB/s", "frac": a / HBM_PEAK_GBPS, "traffic": traffic, "traffic_source": traffic_src,
                     "bytes_per_launch": by["d2"], "avg_us": mean_ms["d2_kernel"] * 1e3,
                     "call_us": mean_ms["d2"] * 1e3, "call_frac": by["d2"] / (mean_ms["d2"] * 1e-3) / 1e9 / HBM_PEAK_GBPS,
                     "timed": "HIP events recorded by the library around draft_quant_kernel<4> on the call's stream"}
+
+    series = None
+    if args.verify_series and "verify" in legs and "d2" in legs:
+        series = measure_verify_series(vc, ctx, torch, lambda: vc.vc_verify_attn(
+            ctx, lay.q_win, lay.k_win, lay.v_win, lay.cu_win, lay.scale, vout, n_seqs=B, workspace=ws, **vargs),
+            lambda: vc.vc_draft_attn(ctx, lay.q, lay.scale, out, n_kv_heads=HKV, workspace=ws, **draft_kw("d2", 0)))
 
     swap = None
     if not args.no_swap and "d2" in legs:
@@ -290,8 +324,15 @@ def main():
 
     round3 = None
     ragged = None
-    if args.round3 or args.config4 or not ((args.no_round3 and args.no_config4) or args.only):
+    small = None
+    if args.round3 or args.config4 or not ((args.no_round3 and args.no_config4 and args.no_small) or args.only):
         del lay, ws
+        torch.cuda.empty_cache()
+    if not (args.no_small or args.only):
+        try:
+            small = measure_small_configs(vc, ctx, torch)
+        except Exception as e:
+            small = {"error": f"{type(e).__name__}: {e}"}
         torch.cuda.empty_cache()
     if args.config4 or not (args.no_config4 or args.only):
         try:
@@ -314,12 +355,45 @@ def main():
                    "step": f"keep-index + {W} draft steps x (bf16 gather, int4, int2) + verify + accept"},
         "legs": res,
         "verify_TFLOPs": res.get("verify", {}).get("TFLOPs"),
-        "roofline": roofline, "swap": swap, "compressor": comp, "layer_loop": loop32, "config3_round": round3, "config4_ragged": ragged,
+        "roofline": roofline, "verify_series": series, "swap": swap, "compressor": comp, "layer_loop": loop32, "config0_config1": small, "config3_round": round3, "config4_ragged": ragged,
         "clocks_after_run": device_clocks(),
         "cpu_baseline": cpu,
     }
     print(json.dumps(line))
     ctx.close()
+
+
+def measure_verify_series(vc, ctx, torch, verify, draft):
+    """Verify call times, launch by launch (microseconds), under four preludes.  The kernel keeps the
+    matrix cores, LDS and HBM busy at once; what the series show is the GPU's own clock management."""
+    def clocks():
+        c = device_clocks()
+        return [l.split(":")[-1].strip() for l in c] if c else None
+
+    def run(n, before=None):
+        evs = []
+        for _ in range(n):
+            if before:
+                before()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(); verify(); e1.record()
+            evs.append((e0, e1))
+        torch.cuda.synchronize()
+        return [round(a.elapsed_time(b) * 1e3) for a, b in evs]
+
+    def idle():
+        torch.cuda.synchronize()
+        time.sleep(0.005)
+
+    torch.cuda.synchronize()
+    time.sleep(1.0)
+    res = {"clocks_idle": clocks()}
+    res["back_to_back_after_1s_idle_us"] = run(16)
+    res["clocks_after_back_to_back"] = clocks()
+    res["back_to_back_again_us"] = run(12)
+    res["after_32_int4_draft_calls_each_us"] = run(12, before=lambda: [draft() for _ in range(32)])
+    res["after_5ms_idle_each_us"] = run(12, before=idle)
+    return res
 
 
 def measure_layer_loop(vc, ctx, lay, torch, HQ, HKV, N, B, layers=32, reps=3):
@@ -471,36 +545,78 @@ def measure_swap(vc, ctx, lay, torch, draft_kw, out, ws, HKV, N, B, W):
     vc.vc_swap_sync(ctx)
     t_both = time.perf_counter() - t0
 
-    # chunk-streamed verify: every 8192-token chunk is attended to as soon as its ticket has landed,
-    # so only the last chunk's share of the verify is exposed after the transfer
+    # chunk-streamed verify through a staging ring (section 5.1: the in-flight KV): the full KV never
+    # exists on the device; every 8192-token chunk lands in slot i mod R of a ring, is attended to as soon
+    # as its ticket has landed, and slots are reloaded only after the range calls that read them have run
+    # (vc_mark behind the range call, vc_swap_after before the reload).  The ring is reloaded in groups of
+    # G chunks, one device-side wait per group: every cross-stream wait in front of a copy stalls the copy
+    # engine for a fraction of a millisecond (measured for the 128 chunks, 79.0 ms of pure transfer:
+    # G = 1, R = 3: 88.4 ms; G = 2: 91.0; G = 8, R = 16: 79.7 ms; G = 16: 79.7).
+    # Exposed = from the moment the last chunk has landed to the end of the merge.
     streamed = None
     if N % chunk_tok == 0 and lay.q_win is not None:
-        vkw = dict(k=dst_k, v=dst_v, cu_ctx=lay.cu_ctx, max_ctx=N, max_win=W, n_seqs=B, chunk_tokens=chunk_tok)
+        G = 8
+        R = 2 * G
+        ring_k = torch.empty((R * chunk_tok, HKV, 128), dtype=torch.bfloat16, device=dev)
+        ring_v = torch.empty_like(ring_k)
+        per_seq = N // chunk_tok
+        nch = len(chunks)
+        slot_of = []
+        for i in range(nch):
+            t = torch.zeros(B, dtype=torch.int32, device=dev)
+            t[i // per_seq] = i % R
+            slot_of.append(t)
+        full = dict(k=dst_k, v=dst_v, cu_ctx=lay.cu_ctx, max_ctx=N, max_win=W, n_seqs=B, chunk_tokens=chunk_tok)
+        ring = dict(k=ring_k, v=ring_v, cu_ctx=lay.cu_ctx, max_ctx=N, max_win=W, n_seqs=B, chunk_tokens=chunk_tok, ring_slots=R)
         vws = torch.empty(vc.vc_verify_workspace_bytes(lay.n_q_heads, HKV, B, total_win=B * W, k=dst_k, v=dst_v,
                                                        cu_ctx=lay.cu_ctx, max_ctx=N, max_win=W, chunk_tokens=chunk_tok),
                           dtype=torch.uint8, device=dev)
         vout = torch.empty_like(lay.q_win)
-        per_seq = N // chunk_tok
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        vc.vc_verify_attn(ctx, lay.q_win, lay.k_win, lay.v_win, lay.cu_win, lay.scale, vout, workspace=vws, **vkw)
+        vc.vc_verify_attn(ctx, lay.q_win, lay.k_win, lay.v_win, lay.cu_win, lay.scale, vout, workspace=vws, **full)
         torch.cuda.synchronize()
         t_verify = time.perf_counter() - t0
         ref = vout.clone()
+        vout.zero_()
+        chunk_bytes = chunk_tok * row_bytes
+
+        def issue_group(g0):
+            """chunks g0 .. g0 + G - 1 into their slots: K copies, then V copies; ticket of the last V copy of each"""
+            idx = range(g0, min(nch, g0 + G))
+            cs = [(chunks[i][0], (i % R) * chunk_bytes, chunks[i][2]) for i in idx]
+            vc.vc_swap_in(ctx, host_k, ring_k, cs)
+            first = vc.vc_swap_in(ctx, host_v, ring_v, cs)
+            return {i: first + j for j, i in enumerate(idx)}
+
+        e_landed, e_done = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
         t0 = time.perf_counter()
-        for i, ch in enumerate(chunks):
-            vc.vc_swap_in(ctx, host_k, dst_k, [ch])
-            ticket = vc.vc_swap_in(ctx, host_v, dst_v, [ch])
-            vc.vc_swap_wait(ctx, ticket)
+        tickets = {}
+        tickets.update(issue_group(0))
+        tickets.update(issue_group(G))
+        for i in range(nch):
+            vc.vc_swap_wait(ctx, tickets.pop(i))
+            if i == nch - 1:
+                e_landed.record()
             b, c = divmod(i, per_seq)
             vc.vc_verify_attn_range(ctx, lay.q_win, lay.k_win, lay.v_win, lay.cu_win, lay.scale, b, b + 1, c * chunk_tok,
-                                    (1 << 30) if c == per_seq - 1 else (c + 1) * chunk_tok, workspace=vws, **vkw)
-        vc.vc_verify_finish(ctx, lay.cu_win, vout, n_q_heads=lay.n_q_heads, n_kv_heads=HKV, workspace=vws, **vkw)
+                                    (1 << 30) if c == per_seq - 1 else (c + 1) * chunk_tok, workspace=vws,
+                                    ring_slot=slot_of[i], **ring)
+            if (i + 1) % G == 0 and i + 1 + G < nch:
+                # the group that just finished frees its G slots for the group after the one in flight
+                vc.vc_swap_after(ctx, vc.vc_mark(ctx))
+                tickets.update(issue_group(i + 1 + G))
+        vc.vc_verify_finish(ctx, lay.cu_win, vout, n_q_heads=lay.n_q_heads, n_kv_heads=HKV, workspace=vws, ring_slot=slot_of[0], **ring)
+        e_done.record()
         torch.cuda.synchronize()
         t_stream = time.perf_counter() - t0
         streamed = {"verify_alone_ms": t_verify * 1e3, "swap_then_verify_ms": (t_swap + t_verify) * 1e3,
-                    "streamed_ms": t_stream * 1e3, "exposed_after_swap_ms": (t_stream - t_swap) * 1e3,
+                    "streamed_ms": t_stream * 1e3, "ring_slots": R, "chunks_per_reload_group": G, "ring_chunk_tokens": chunk_tok,
+                    "device_staging_MB": 2 * ring_k.numel() * 2 / 1e6, "full_kv_MB": total / 1e6,
+                    "exposed_after_last_chunk_ms": e_landed.elapsed_time(e_done),
                     "same_bits": bool(torch.equal(ref.view(torch.int16), vout.view(torch.int16)))}
+        del ring_k, ring_v, vws
     # reload of the dropped rows only (token dropping keeps 10 % resident): the host holds them
     # packed; per sequence two contiguous copies into a staging buffer and a short placement kernel,
     # all on the copy stream, alone and under bf16-gather drafting
@@ -583,6 +699,84 @@ def measure_swap(vc, ctx, lay, torch, draft_kw, out, ws, HKV, N, B, W):
             "draft_steps": n_steps, "draft_alone_ms": t_draft * 1e3, "both_ms": t_both * 1e3,
             "overlap": (t_draft + t_swap - t_both) / min(t_draft, t_swap), "bytes_ok": ok,
             "model_max_ms": max(t_draft, t_swap) * 1e3, "streamed_verify": streamed}
+
+
+def measure_small_configs(vc, ctx, torch):
+    """Workload configs 0 and 1 as they are.  Config 0 (one sequence of 4096 tokens, 8 q / 2 KV heads,
+    int4, window 8, vocab 32000) is pure launch latency: 1.3 MB per draft call.  Config 1 (8 sequences of
+    32768 tokens, 2048 kept rows per head, window 16): one draft call moves 68 MB, less than the 256 MB
+    last-level cache, so beside the single call on one layer (cache-assisted, said so) the draft is timed
+    over 32 distinct layers back to back (34 GB of pools, 2.2 GB gathered per pass)."""
+    from tests import synth
+    dev = "cuda:0"
+
+    def timed(f, reps, warm):
+        for _ in range(warm):
+            f()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            f()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps * 1e3
+
+    res = {}
+    for idx in (0, 1):
+        lay = synth.config(idx, dev)
+        nseq, HQ, HKV = len(lay.ctx_len), lay.n_q_heads, lay.n_kv_heads
+        N, W = lay.ctx_len[0], lay.win[0]
+        if idx == 0:
+            kw = dict(blocks=lay.blocks[4], cu_blk=lay.cu_blk[4], max_blk=lay.max_blk[4], bits=4, sum_blk=int(lay.cu_blk[4][-1]))
+            dbytes = draft_bytes(nseq, HQ, HKV, blocks=N // 32)
+        else:
+            kw = dict(pool_k=lay.k_full, pool_v=lay.v_full, cu_ctx=lay.cu_ctx, keep_idx=lay.keep_idx, cu_keep=lay.cu_keep,
+                      max_keep=lay.max_keep, sum_keep=int(lay.cu_keep[-1]))
+            dbytes = draft_bytes(nseq, HQ, HKV, kept=lay.max_keep)
+        out = torch.empty_like(lay.q)
+        ws = torch.empty(max(16, vc.vc_draft_workspace_bytes(HQ, HKV, nseq, **kw)), dtype=torch.uint8, device=dev)
+        va = dict(k=lay.k_full, v=lay.v_full, cu_ctx=lay.cu_ctx, max_ctx=N, max_win=W, sum_ctx=N * nseq)
+        tw = lay.q_win.shape[0]
+        vws = torch.empty(max(16, vc.vc_verify_workspace_bytes(HQ, HKV, nseq, total_win=tw, **va)), dtype=torch.uint8, device=dev)
+        vout = torch.empty_like(lay.q_win)
+        rows, vocab = lay.logits.shape
+        acc = torch.empty(nseq, dtype=torch.int32, device=dev); nxt = torch.empty_like(acc)
+        amax = torch.empty(rows, dtype=torch.int32, device=dev)
+        aws = torch.empty(max(16, vc.vc_accept_workspace_bytes(rows, vocab)), dtype=torch.uint8, device=dev)
+        t_d = timed(lambda: vc.vc_draft_attn(ctx, lay.q, lay.scale, out, n_kv_heads=HKV, workspace=ws, **kw), 200, 20)
+        t_v = timed(lambda: vc.vc_verify_attn(ctx, lay.q_win, lay.k_win, lay.v_win, lay.cu_win, lay.scale, vout, n_seqs=nseq,
+                                              workspace=vws, **va), 50, 10)
+        t_a = timed(lambda: vc.vc_accept_len(ctx, lay.logits, lay.cu_rows, lay.draft_ids, lay.cu_win, acc, nxt, amax,
+                                             workspace=aws), 100, 10)
+        vflops = nseq * 4 * HQ * 128 * (W * N + W * (W + 1) / 2)
+        vbytes = nseq * (2 * HKV * N * 256 + 2 * HKV * W * 256 + 2 * W * HQ * 256)
+        r = {"sequences": nseq, "ctx": N, "window": W,
+             "draft_call_us": t_d, "draft_MB": dbytes / 1e6, "draft_GBps_same_layer": dbytes / t_d / 1e3,
+             "draft_note": "back-to-back calls on ONE layer: its bytes fit the last-level cache",
+             "verify_call_us": t_v, "verify_GBps": vbytes / t_v / 1e3, "verify_TFLOPs": vflops / t_v / 1e6,
+             "accept_call_us": t_a, "accept_GBps": rows * vocab * 4 / t_a / 1e3}
+        if idx == 1:
+            layers = 32
+            g = torch.Generator(device=dev); g.manual_seed(synth.SEED_BASE + 100)
+            pk = torch.randn((layers,) + tuple(lay.k_full.shape), device=dev, dtype=torch.bfloat16, generator=g)
+            pv = torch.randn((layers,) + tuple(lay.v_full.shape), device=dev, dtype=torch.bfloat16, generator=g)
+            ql = torch.randn((layers,) + tuple(lay.q.shape), device=dev, generator=g).to(torch.bfloat16)
+            ol = torch.empty_like(ql)
+
+            def loop():
+                for l in range(layers):
+                    kw2 = dict(kw); kw2.update(pool_k=pk[l], pool_v=pv[l])
+                    vc.vc_draft_attn(ctx, ql[l], lay.scale, ol[l], n_kv_heads=HKV, workspace=ws, **kw2)
+
+            t_l = timed(loop, 5, 2) / layers
+            r.update({"draft_layer_loop_us_per_call": t_l, "draft_layer_loop_GBps": dbytes / t_l / 1e3,
+                      "draft_layer_loop_frac_hbm": dbytes / t_l / 1e3 / HBM_PEAK_GBPS, "draft_layer_loop_layers": layers})
+            del pk, pv, ql, ol
+        res[f"config{idx}"] = r
+        del lay, ws, vws
+        torch.cuda.empty_cache()
+    return res
 
 
 def measure_config4(vc, ctx, torch, reps=40, warm=25):
@@ -760,37 +954,36 @@ def measure_round3(vc, ctx, torch, layers=32, N=131072, W=64, vocab=128256, chun
 
 
 def cpu_baseline(lay, torch, np, HQ, HKV, N):
-    """The fp64 oracle, as it stands, on a bounded sample of the same workload: int4 draft
-    attention of a few (sequence, KV head) pairs at full context; single thread."""
-    from oracle import vc_oracle as O
-    try:
-        from threadpoolctl import threadpool_limits
-    except Exception:  # pragma: no cover
-        threadpool_limits = None
+    """The fp64 oracle, as it stands, on all host cores of the box: int4 draft attention (all g query
+    heads) of a bounded sample of (sequence, KV head) pairs at full context, one pair per task, in
+    worker processes (the oracle is single-threaded numpy).  Rate = record bytes / wall time."""
+    from tests import oracle_pool as P
     blocks = lay.blocks[4]
     nb = N // 32
     cu = np.array([0, nb], dtype=np.int32)
     g = HQ // HKV
-    pairs = [(b, (3 * b + 1) % HKV) for b in range(min(16, lay.q.shape[0]))]     # about 10 s of CPU work
-    t_total, nbytes = 0.0, 0
-    import contextlib
-    limiter = threadpool_limits(limits=1) if threadpool_limits else contextlib.nullcontext()
-    with limiter:
-        for (b, kvh) in pairs:
-            start = (int(lay.cu_blk[4][b]) * HKV + kvh * nb)
-            rec = blocks[start:start + nb].cpu().numpy()
-            qb = lay.q[b, kvh * g:(kvh + 1) * g].contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
-            t0 = time.perf_counter()
-            k, v = O.draft_keys(0, 0, n_kv_heads=1, blocks=rec, cu_blk=cu, bits=4)
-            for h in range(g):
-                O.attend(O.bf16_to_f64(qb[h]), k, v, lay.scale)
-            t_total += time.perf_counter() - t0
-            nbytes += nb * 5120
-    import os
-    cores = 1 if threadpool_limits else (os.cpu_count() or 1)      # without the limiter numpy's BLAS takes what it finds
-    return {"value": nbytes / t_total / 1e9, "unit": "GB/s", "cores": cores, "kind": "oracle",
-            "sample": f"int4 draft attention of {len(pairs)} (sequence, KV head) pairs at ctx {N} "
-                      f"({nbytes / 1e6:.1f} MB of records, {t_total:.1f} s)"}
+    workers = P.n_workers()
+    nseq = lay.q.shape[0]
+    all_pairs = [(b, kvh) for b in range(nseq) for kvh in range(HKV)]
+    pairs = all_pairs[:min(len(all_pairs), 8 * workers)]             # about 10 - 20 s of wall time
+    tasks = []
+    for (b, kvh) in pairs:
+        start = int(lay.cu_blk[4][b]) * HKV + kvh * nb
+        tasks.append({"q": lay.q[b, kvh * g:(kvh + 1) * g].contiguous().view(torch.int16).cpu().numpy().view(np.uint16),
+                      "scale": lay.scale,
+                      "kv": dict(blocks=blocks[start:start + nb].cpu().numpy(), cu_blk=cu, bits=4)})
+    try:
+        P.run(P.draft_task, tasks[:workers])                          # start the workers (imports) outside the timed part
+        t0 = time.perf_counter()
+        res = P.run(P.draft_task, tasks)
+        wall = time.perf_counter() - t0
+    finally:
+        P.shutdown()
+    nbytes = len(pairs) * nb * 5120
+    in_oracle = sum(r[1] for r in res)
+    return {"value": nbytes / wall / 1e9, "unit": "GB/s", "cores": workers, "kind": "oracle",
+            "sample": f"int4 draft attention of {len(pairs)} of {len(all_pairs)} (sequence, KV head) pairs at ctx {N}, all {g} query heads each "
+                      f"({nbytes / 1e6:.1f} MB of records; {wall:.1f} s wall on {workers} worker processes, {in_oracle:.1f} s summed inside the oracle)"}
 
 
 if __name__ == "__main__":

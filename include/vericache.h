@@ -203,6 +203,17 @@ typedef struct {
   const void* k;           /* device bf16 pools; sequence b owns rows cu_ctx[b] .. cu_ctx[b+1]-1 */
   const void* v;
   const int32_t* cu_ctx;
+  /* Staging ring (paper section 5.1, HBM ring: the full KV that is in flight for an upcoming verify
+   * but not yet consumed).  ring_slots = 0: k, v hold every token, as above.  ring_slots = R > 0: k and
+   * v are R slots of chunk_tokens rows each (row s * chunk_tokens + i of the pools is token i of the
+   * chunk in slot s), cu_ctx still gives the sequence lengths, and only vc_verify_attn_range /
+   * vc_verify_finish may be used: a range call covers one chunk [tok_begin, tok_begin + chunk_tokens)
+   * of each of its sequences (a tok_end past the end of every sequence means the rest of that chunk,
+   * window tokens included), and reads that chunk of sequence b from slot ring_slot[b].  A slot may be
+   * overwritten (vc_swap_in) once the range call that reads it has run: vc_mark after that call and
+   * vc_swap_after before the reload order the two on the device. */
+  int32_t ring_slots;
+  const int32_t* ring_slot; /* device int32 [n_seqs], entries in [0, ring_slots); read by the range call */
 } vc_full_kv;
 
 /* Verify attention (paper section 4.1 step 2).  Sequence b brings w_b = cu_win[b+1]-cu_win[b]
@@ -299,6 +310,15 @@ vc_status vc_swap_in(vc_ctx* ctx, const void* host_src, void* dev_dst, const vc_
                      int32_t n_chunks, int64_t* first_ticket);
 /* Make `stream` wait (on the device, the host does not block) until `ticket` has landed. */
 vc_status vc_swap_wait(vc_ctx* ctx, int64_t ticket, void* stream);
+/* Ordering in the other direction (section 5.2 step (i): a request's staging memory is reloaded only
+ * after its previous verify has read it; section 5.1: a ring slot is reused once consumed).
+ * vc_mark records a point on `stream` - everything enqueued on it so far - and returns its number.
+ * vc_swap_after makes the copy stream wait, on the device, for that point: chunks issued by later
+ * vc_swap_in / vc_swap_in_rows calls start only after the marked work has finished.  The host never
+ * blocks, except that vc_mark waits for the mark issued 1024 marks earlier if that one is still
+ * pending (its slot is being reused). */
+vc_status vc_mark(vc_ctx* ctx, void* stream, int64_t* mark);
+vc_status vc_swap_after(vc_ctx* ctx, int64_t mark);
 /* VC_OK once `ticket` has landed, VC_ERR_NOT_READY before. */
 vc_status vc_swap_query(vc_ctx* ctx, int64_t ticket);
 /* Block the host until every issued chunk has landed. */

@@ -37,7 +37,8 @@ class vc_full_kv(C.Structure):
     _fields_ = [("n_seqs", C.c_int32), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32),
                 ("head_dim", C.c_int32), ("max_ctx", C.c_int32), ("max_win", C.c_int32), ("sum_ctx", C.c_int32),
                 ("chunk_tokens", C.c_int32),
-                ("k", C.c_void_p), ("v", C.c_void_p), ("cu_ctx", C.c_void_p)]
+                ("k", C.c_void_p), ("v", C.c_void_p), ("cu_ctx", C.c_void_p),
+                ("ring_slots", C.c_int32), ("ring_slot", C.c_void_p)]
 
 
 class vc_chunk(C.Structure):
@@ -48,7 +49,7 @@ EXPORTS = ["vc_create", "vc_destroy", "vc_last_error", "vc_version", "vc_time_ma
            "vc_set_tunable", "vc_get_tunable", "vc_stream_status", "vc_validate_comp_kv", "vc_validate_full_kv",
            "vc_draft_workspace_bytes", "vc_draft_attn", "vc_draft_static_scratch_bytes", "vc_draft_attn_static", "vc_verify_workspace_bytes", "vc_verify_attn",
            "vc_verify_plan", "vc_verify_attn_range", "vc_verify_finish",
-           "vc_accept_workspace_bytes", "vc_accept_len", "vc_accept_sample_workspace_bytes", "vc_accept_sample", "vc_swap_in", "vc_swap_in_rows", "vc_pack_rows", "vc_swap_wait", "vc_swap_query", "vc_swap_sync",
+           "vc_accept_workspace_bytes", "vc_accept_len", "vc_accept_sample_workspace_bytes", "vc_accept_sample", "vc_swap_in", "vc_swap_in_rows", "vc_pack_rows", "vc_swap_wait", "vc_mark", "vc_swap_after", "vc_swap_query", "vc_swap_sync",
            "vc_keep_from_dropped", "vc_compress_quant", "vc_decompress_quant", "vc_topk_keep",
            "vc_iter_time_model", "vc_sched_create", "vc_sched_destroy", "vc_sched_set_resident", "vc_sched_span",
            "vc_sched_admit", "vc_sched_cancel", "vc_sched_step", "vc_sched_rings"]
@@ -109,6 +110,8 @@ def load():
     lib.vc_pack_rows.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32,
                                  C.c_int32, C.c_int32, C.c_void_p, C.c_void_p, C.c_void_p]
     lib.vc_swap_wait.argtypes = [C.c_void_p, C.c_int64, C.c_void_p]
+    lib.vc_mark.argtypes = [C.c_void_p, C.c_void_p, C.POINTER(C.c_int64)]
+    lib.vc_swap_after.argtypes = [C.c_void_p, C.c_int64]
     lib.vc_swap_query.argtypes = [C.c_void_p, C.c_int64]
     lib.vc_swap_sync.argtypes = [C.c_void_p]
     lib.vc_keep_from_dropped.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32,
@@ -271,8 +274,10 @@ def vc_draft_attn_static(ctx: Context, q, softmax_scale, out, *, n_kv_heads, lse
 
 
 def _full_desc(n_q_heads, n_kv_heads, n_seqs, k, v, cu_ctx, max_ctx, max_win, head_dim=128, sum_ctx=0,
-               chunk_tokens=0):
+               chunk_tokens=0, ring_slots=0, ring_slot=None):
     d = vc_full_kv()
+    d.ring_slots = ring_slots
+    d.ring_slot = _ptr(ring_slot, torch.int32, "ring_slot")
     d.n_seqs, d.n_q_heads, d.n_kv_heads, d.head_dim = n_seqs, n_q_heads, n_kv_heads, head_dim
     d.max_ctx, d.max_win, d.sum_ctx, d.chunk_tokens = max_ctx, max_win, sum_ctx, chunk_tokens
     d.k = _ptr(k, torch.bfloat16, "k"); d.v = _ptr(v, torch.bfloat16, "v")
@@ -281,20 +286,21 @@ def _full_desc(n_q_heads, n_kv_heads, n_seqs, k, v, cu_ctx, max_ctx, max_win, he
 
 
 def vc_verify_workspace_bytes(n_q_heads, n_kv_heads, n_seqs, *, k, v, cu_ctx, max_ctx, max_win, total_win,
-                              sum_ctx=0, chunk_tokens=0) -> int:
+                              sum_ctx=0, chunk_tokens=0, ring_slots=0, ring_slot=None) -> int:
     d = _full_desc(n_q_heads, n_kv_heads, n_seqs, k, v, cu_ctx, max_ctx, max_win, sum_ctx=sum_ctx,
-                   chunk_tokens=chunk_tokens)
+                   chunk_tokens=chunk_tokens, ring_slots=ring_slots, ring_slot=ring_slot)
     n = C.c_size_t()
     _check(load().vc_verify_workspace_bytes(C.byref(d), int(total_win), C.byref(n)))
     return n.value
 
 
 def vc_verify_attn(ctx: Context, q_win, k_win, v_win, cu_win, softmax_scale, out, *, k, v, cu_ctx, max_ctx,
-                   max_win, n_seqs, lse=None, workspace=None, stream=None, sum_ctx=0, chunk_tokens=0):
+                   max_win, n_seqs, lse=None, workspace=None, stream=None, sum_ctx=0, chunk_tokens=0, ring_slots=0,
+                   ring_slot=None):
     total_win, n_q_heads = q_win.shape[0], q_win.shape[1]
     n_kv_heads = k_win.shape[1]
     d = _full_desc(n_q_heads, n_kv_heads, n_seqs, k, v, cu_ctx, max_ctx, max_win, head_dim=q_win.shape[2],
-                   sum_ctx=sum_ctx, chunk_tokens=chunk_tokens)
+                   sum_ctx=sum_ctx, chunk_tokens=chunk_tokens, ring_slots=ring_slots, ring_slot=ring_slot)
     ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
     _check(load().vc_verify_attn(ctx.handle, C.byref(d), _ptr(q_win, torch.bfloat16, "q_win"),
                                  _ptr(k_win, torch.bfloat16, "k_win"), _ptr(v_win, torch.bfloat16, "v_win"),
@@ -304,10 +310,11 @@ def vc_verify_attn(ctx: Context, q_win, k_win, v_win, cu_win, softmax_scale, out
     return out
 
 
-def vc_verify_plan(n_q_heads, n_kv_heads, n_seqs, *, k, v, cu_ctx, max_ctx, max_win, sum_ctx=0, chunk_tokens=0):
+def vc_verify_plan(n_q_heads, n_kv_heads, n_seqs, *, k, v, cu_ctx, max_ctx, max_win, sum_ctx=0, chunk_tokens=0,
+                   ring_slots=0, ring_slot=None):
     """Returns (chunk_tokens, n_chunks) of the verify launch plan."""
     d = _full_desc(n_q_heads, n_kv_heads, n_seqs, k, v, cu_ctx, max_ctx, max_win, sum_ctx=sum_ctx,
-                   chunk_tokens=chunk_tokens)
+                   chunk_tokens=chunk_tokens, ring_slots=ring_slots, ring_slot=ring_slot)
     ct, nc = C.c_int32(), C.c_int32()
     _check(load().vc_verify_plan(C.byref(d), C.byref(ct), C.byref(nc)))
     return ct.value, nc.value
@@ -315,10 +322,10 @@ def vc_verify_plan(n_q_heads, n_kv_heads, n_seqs, *, k, v, cu_ctx, max_ctx, max_
 
 def vc_verify_attn_range(ctx: Context, q_win, k_win, v_win, cu_win, softmax_scale, seq_begin, seq_end, tok_begin,
                          tok_end, *, k, v, cu_ctx, max_ctx, max_win, n_seqs, workspace, stream=None, sum_ctx=0,
-                         chunk_tokens=0):
+                         chunk_tokens=0, ring_slots=0, ring_slot=None):
     total_win, n_q_heads = q_win.shape[0], q_win.shape[1]
     d = _full_desc(n_q_heads, k_win.shape[1], n_seqs, k, v, cu_ctx, max_ctx, max_win, head_dim=q_win.shape[2],
-                   sum_ctx=sum_ctx, chunk_tokens=chunk_tokens)
+                   sum_ctx=sum_ctx, chunk_tokens=chunk_tokens, ring_slots=ring_slots, ring_slot=ring_slot)
     _check(load().vc_verify_attn_range(ctx.handle, C.byref(d), _ptr(q_win, torch.bfloat16, "q_win"),
                                        _ptr(k_win, torch.bfloat16, "k_win"), _ptr(v_win, torch.bfloat16, "v_win"),
                                        _ptr(cu_win, torch.int32, "cu_win"), int(total_win), float(softmax_scale),
@@ -328,9 +335,9 @@ def vc_verify_attn_range(ctx: Context, q_win, k_win, v_win, cu_win, softmax_scal
 
 
 def vc_verify_finish(ctx: Context, cu_win, out, *, n_q_heads, n_kv_heads, k, v, cu_ctx, max_ctx, max_win, n_seqs,
-                     workspace, lse=None, stream=None, sum_ctx=0, chunk_tokens=0):
+                     workspace, lse=None, stream=None, sum_ctx=0, chunk_tokens=0, ring_slots=0, ring_slot=None):
     d = _full_desc(n_q_heads, n_kv_heads, n_seqs, k, v, cu_ctx, max_ctx, max_win, sum_ctx=sum_ctx,
-                   chunk_tokens=chunk_tokens)
+                   chunk_tokens=chunk_tokens, ring_slots=ring_slots, ring_slot=ring_slot)
     _check(load().vc_verify_finish(ctx.handle, C.byref(d), _ptr(cu_win, torch.int32, "cu_win"), int(out.shape[0]),
                                    _ptr(out, torch.bfloat16, "out"), _ptr(lse, torch.float32, "lse"),
                                    _ptr(workspace, None, "workspace"), workspace.numel() * workspace.element_size(),
@@ -421,6 +428,18 @@ def vc_pack_rows(ctx: Context, k, v, idx, cu_idx, cu_ctx, n_kv_heads, max_idx, p
 
 def vc_swap_wait(ctx: Context, ticket: int, stream=None):
     _check(load().vc_swap_wait(ctx.handle, int(ticket), _stream(stream)))
+
+
+def vc_mark(ctx: Context, stream=None) -> int:
+    """Marks the work enqueued on `stream` so far; returns the mark's number."""
+    m = C.c_int64()
+    _check(load().vc_mark(ctx.handle, _stream(stream), C.byref(m)))
+    return m.value
+
+
+def vc_swap_after(ctx: Context, mark: int):
+    """Later reloads start only after the marked work has finished (device-side ordering)."""
+    _check(load().vc_swap_after(ctx.handle, int(mark)))
 
 
 def vc_swap_query(ctx: Context, ticket: int) -> bool:

@@ -79,6 +79,10 @@ struct vc_ctx {
   // armed by vc_time_main_kernel: events recorded around the main kernel(s) of the next attention call
   hipEvent_t time_begin, time_end;
   int n_cu;                // compute units of the device
+  // vc_mark / vc_swap_after: events recorded on compute streams for the copy stream to wait on
+  static constexpr int kMarkRing = 1024;
+  hipEvent_t mark_events[kMarkRing];
+  int64_t marks_issued;
 };
 
 namespace vc {

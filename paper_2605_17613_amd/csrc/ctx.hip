@@ -156,6 +156,8 @@ extern "C" vc_status vc_destroy(vc_ctx* c) {
   (void)hipStreamSynchronize(c->copy_stream);
   for (int i = 0; i < vc_ctx::kRing; ++i)
     if (c->events[i]) (void)hipEventDestroy(c->events[i]);
+  for (int i = 0; i < vc_ctx::kMarkRing; ++i)
+    if (c->mark_events[i]) (void)hipEventDestroy(c->mark_events[i]);
   (void)hipStreamDestroy(c->copy_stream);
   free(c->events);
   free(c);
@@ -384,6 +386,32 @@ extern "C" vc_status vc_swap_wait(vc_ctx* c, int64_t ticket, void* stream) {
   vc_status st = ticket_event(c, ticket, &ev, "vc_swap_wait");
   if (st != VC_OK) return st;
   if (ev) VC_HIP(hipStreamWaitEvent(static_cast<hipStream_t>(stream), ev, 0));
+  return VC_OK;
+}
+
+extern "C" vc_status vc_mark(vc_ctx* c, void* stream, int64_t* mark) {
+  VC_REQUIRE(c != nullptr && mark != nullptr, VC_ERR_INVALID_ARG, "vc_mark: ctx or mark is NULL");
+  VC_HIP(hipSetDevice(c->device));
+  const int slot = static_cast<int>(c->marks_issued % vc_ctx::kMarkRing);
+  if (!c->mark_events[slot]) {
+    VC_HIP(hipEventCreateWithFlags(&c->mark_events[slot], hipEventDisableTiming));
+  } else if (hipEventQuery(c->mark_events[slot]) != hipSuccess) {
+    // the mark issued kMarkRing marks ago is still pending: its event cannot be re-recorded before it
+    // has fired, or a wait for the old mark would be satisfied by the wrong work
+    (void)hipGetLastError();
+    VC_HIP(hipEventSynchronize(c->mark_events[slot]));
+  }
+  VC_HIP(hipEventRecord(c->mark_events[slot], static_cast<hipStream_t>(stream)));
+  *mark = c->marks_issued++;
+  return VC_OK;
+}
+
+extern "C" vc_status vc_swap_after(vc_ctx* c, int64_t mark) {
+  VC_REQUIRE(c != nullptr, VC_ERR_INVALID_ARG, "vc_swap_after: ctx is NULL");
+  VC_REQUIRE(mark >= 0 && mark < c->marks_issued, VC_ERR_INVALID_ARG, "vc_swap_after: mark %lld was never issued",
+             static_cast<long long>(mark));
+  if (c->marks_issued - mark > vc_ctx::kMarkRing) return VC_OK;   // fired before its slot was reused
+  VC_HIP(hipStreamWaitEvent(c->copy_stream, c->mark_events[mark % vc_ctx::kMarkRing], 0));
   return VC_OK;
 }
 

@@ -33,6 +33,8 @@ struct VerifyParams {
   int chunk_tok, ns;   // ns = chunks of the longest sequence (one partial per row and chunk)
   int seq0, chunk0, tok_hi;   // this launch: first sequence, first chunk, end of the token range
   int nrb;                    // row blocks of 256 rows per (sequence, KV head); above one, K/V are streamed once per block
+  const int* ring_slot;       // staging ring: kf / vf are ring_slots slots of chunk_tok rows, and the chunk of sequence b that
+                              // this launch attends to sits in slot ring_slot[b]; nullptr: kf / vf hold every token
   int* list;                  // optional work list of a ragged launch (see verify_worklist_kernel)
   int list_seqs, list_chunks; // sequences and chunks of this launch (the full grid, walked when the list reports an overflow)
   float scale_log2e;
@@ -377,9 +379,12 @@ constexpr int kMaxShift = 2;
 __device__ __forceinline__ void verify_item(const VerifyParams& p, char* smem, int b, int kvh, int row0, int slot, int len) {
   const int w0 = p.cu_win[b], w = p.cu_win[b + 1] - w0;
   if (row0 >= w * p.g) return;
-  const int c0 = p.cu_ctx[b], N = p.cu_ctx[b + 1] - c0;
+  int c0 = p.cu_ctx[b];
+  const int N = p.cu_ctx[b + 1] - c0;
   const int t_begin = slot * len;
   if (t_begin >= min(N + w, p.tok_hi)) return;
+  // ring: token t of this chunk is row ring_slot[b] * chunk_tok + (t - t_begin) of the staging buffers
+  if (p.ring_slot) c0 = p.ring_slot[b] * p.chunk_tok - t_begin;
   if (tokens_split(min(256, w * p.g - row0)) == 2) verify_body<2, 1, 1>(p, smem, kvh, slot, t_begin, len, w0, w, c0, N, row0);
   else verify_body<1, 1, 2>(p, smem, kvh, slot, t_begin, len, w0, w, c0, N, row0);
 }
@@ -683,7 +688,8 @@ static VerifyPlan make_verify_plan(const vc_full_kv* kv) {
   // through the list: tests.)
   const int64_t list_min = tunable(kTunVerifyListMin, 1 << 21, 0, 1 << 30);
   const bool fits = static_cast<int64_t>(kv->n_seqs) * pl.nchunk * kv->n_kv_heads * ceil_div(kv->max_win * (kv->n_q_heads / kv->n_kv_heads), 256) < (1 << 30);
-  if (!uniform && sum >= list_min && fits && kv->n_seqs >= 2 && kv->n_seqs <= kMaxListSeqs && tunable(kTunVerifyWorklist, 1, 0, 1) != 0) {
+  if (!uniform && sum >= list_min && fits && kv->ring_slots == 0 && kv->n_seqs >= 2 && kv->n_seqs <= kMaxListSeqs &&
+      tunable(kTunVerifyWorklist, 1, 0, 1) != 0) {
     while (pl.max_shift < kMaxShift && (pl.chunk_tok >> (pl.max_shift + 1)) % 128 == 0) ++pl.max_shift;   // pieces stay whole tiles
     pl.max_shift = tunable(kTunVerifyTaper, pl.max_shift, 0, pl.max_shift);
     // every sequence has at most one partial piece: sum / shortest piece + n bounds the list
@@ -713,6 +719,13 @@ static vc_status check_full(const vc_full_kv* kv, const char* who) {
   VC_REQUIRE(kv->n_q_heads / kv->n_kv_heads <= 256, VC_ERR_UNSUPPORTED, "%s: GQA ratio above 256", who);
   VC_REQUIRE(kv->n_seqs <= 65535 && kv->n_kv_heads <= 65535 && kv->n_q_heads <= 65535, VC_ERR_UNSUPPORTED,
              "%s: batch too large for one launch", who);
+  VC_REQUIRE(kv->ring_slots >= 0, VC_ERR_INVALID_ARG, "%s: ring_slots %d", who, kv->ring_slots);
+  if (kv->ring_slots > 0) {
+    VC_REQUIRE(kv->chunk_tokens > 0, VC_ERR_INVALID_ARG, "%s: a staging ring needs chunk_tokens (the length of a slot)", who);
+    VC_REQUIRE(kv->ring_slot != nullptr, VC_ERR_INVALID_ARG, "%s: a staging ring needs ring_slot", who);
+    VC_REQUIRE(static_cast<int64_t>(kv->ring_slots) * kv->chunk_tokens < (1ll << 31), VC_ERR_UNSUPPORTED, "%s: ring of %d x %d rows", who,
+               kv->ring_slots, kv->chunk_tokens);
+  }
   VC_REQUIRE(kv->cu_ctx != nullptr, VC_ERR_INVALID_ARG, "%s: cu_ctx is NULL", who);
   VC_REQUIRE(kv->max_ctx == 0 || (kv->k && kv->v), VC_ERR_INVALID_ARG, "%s: k or v is NULL", who);
   VC_REQUIRE(aligned16(kv->k) && aligned16(kv->v), VC_ERR_INVALID_ARG, "%s: k/v not 16-byte aligned", who);
@@ -786,6 +799,14 @@ extern "C" vc_status vc_verify_attn_range(vc_ctx* ctx, const vc_full_kv* kv, con
              "vc_verify_attn_range: tok_end %d is neither a multiple of the chunk length %d nor past the end (%d)", tok_end,
              pl.chunk_tok, total_max);
   if (tok_begin >= total_max) return VC_OK;
+  if (kv->ring_slots > 0) {
+    // one chunk per call: a slot holds no more.  "Past the end" (the last piece of a sequence, which takes its
+    // window tokens along) means the rest of that one chunk.
+    VC_REQUIRE(tok_end - tok_begin <= pl.chunk_tok || tok_end >= total_max, VC_ERR_INVALID_ARG,
+               "vc_verify_attn_range: with a staging ring a call covers one chunk of %d tokens (got [%d, %d))", pl.chunk_tok,
+               tok_begin, tok_end);
+    if (tok_end - tok_begin > pl.chunk_tok) tok_end = tok_begin + pl.chunk_tok;
+  }
 
   hipStream_t st = static_cast<hipStream_t>(stream);
   VerifyParams vp{};
@@ -803,6 +824,7 @@ extern "C" vc_status vc_verify_attn_range(vc_ctx* ctx, const vc_full_kv* kv, con
   vp.chunk0 = tok_begin / pl.chunk_tok;
   vp.tok_hi = tok_end;
   vp.scale_log2e = softmax_scale * kLog2e;
+  vp.ring_slot = kv->ring_slots > 0 ? kv->ring_slot : nullptr;
   const int hi = tok_end < total_max ? tok_end : total_max;
   const int nchunk = ceil_div(hi, pl.chunk_tok) - vp.chunk0;
   vp.nrb = ceil_div(kv->max_win * vp.g, 256);
@@ -857,6 +879,8 @@ extern "C" vc_status vc_verify_attn(vc_ctx* ctx, const vc_full_kv* kv, const voi
   if (stt != VC_OK) return stt;
   if (kv->n_seqs == 0 || total_win == 0 || kv->max_win == 0) return VC_OK;
   VC_REQUIRE(out != nullptr, VC_ERR_INVALID_ARG, "vc_verify_attn: out is NULL");
+  VC_REQUIRE(kv->ring_slots == 0, VC_ERR_INVALID_ARG,
+             "vc_verify_attn: a staging ring holds one chunk per sequence at a time; use vc_verify_attn_range chunk by chunk");
   stt = vc_verify_attn_range(ctx, kv, q_win, k_win, v_win, cu_win, total_win, softmax_scale, 0, kv->n_seqs, 0,
                              kv->max_ctx + kv->max_win, workspace, workspace_bytes, stream);
   if (stt != VC_OK) return stt;

@@ -63,7 +63,7 @@ class StaggeredLayer:
         self.drafted = [0] * self.R
         self.waiting = list(range(self.R))
         self.last_ticket = [None] * self.R
-        self.verified_event = [None] * self.R
+        self.verified = [None] * self.R     # mark behind each request's last verify
         self.log = []            # (iteration, request, window length) of every verify
         self.kicks = 0
         self.bytes_moved = 0.0
@@ -77,8 +77,10 @@ class StaggeredLayer:
 
     def _kick(self, r):
         """Start the reload of request r: chunks of K then V rows on the library's copy stream."""
-        if self.verified_event[r] is not None:
-            self.verified_event[r].synchronize()    # its previous verify no longer reads the staging rows
+        if self.verified[r] is not None:
+            # its previous verify must no longer read the staging rows: the copy stream waits, on the device,
+            # for the mark recorded right behind that verify (the host does not block)
+            B.vc_swap_after(self.ctx, self.verified[r])
         lo, n = self.c0[r], self.lay.ctx_len[r]
         chunks = []
         for t in range(0, n, self.chunk_tokens):
@@ -103,9 +105,7 @@ class StaggeredLayer:
                          **self._vargs(r))
         B.vc_accept_len(self.ctx, lay.logits[r0:r0 + cnt], self.cu_cnt[cnt], lay.draft_ids[w0:w0 + cnt],
                         self.cu_cnt[cnt], self.acc[r:r + 1], self.nxt[r:r + 1], self.amax, workspace=self.aws)
-        ev = torch.cuda.Event()
-        ev.record()
-        self.verified_event[r] = ev
+        self.verified[r] = B.vc_mark(self.ctx)
         self.log.append((it, r, cnt))
         self.drafted[r] = 0
 
