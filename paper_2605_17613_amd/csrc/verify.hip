@@ -72,15 +72,12 @@ __device__ __forceinline__ short4v lds_read_tr(uint32_t addr) {
 __device__ __forceinline__ int rot_row(int row) { return ((row << 1) & 14) | ((row >> 3) & 1); }
 __device__ __forceinline__ int swz(int row, int chunk) { return row * 256 + ((chunk ^ rot_row(row)) << 4); }
 
-// One wave owns RT row tiles of 32 rows and, of every LDS tile, one 32-token slice.  With RT = 2
-// every K and V^T operand read from LDS feeds two matrix instructions, which halves the LDS
-// traffic per flop: at RT = 1 the matrix cores could at best be fed at the full LDS bandwidth.
-// NW = 8/RT waves per workgroup; NTG = token slices per tile; NRG = NW/NTG row groups.
+// One wave owns RT row tiles of 32 rows (RT = 1 in every instantiation in use) and, of every LDS tile,
+// SUB 32-token slices.  NW = 8/RT waves per workgroup; NTG = token slices per tile; NRG = NW/NTG row groups.
 // Tiles travel HBM -> LDS directly (no registers) through a ring of NSTAGE stages, one barrier per tile.
-// SUB = 32-token slices a wave takes per tile.  With SUB = 2 the wave issues the score products of
-// both slices before the softmax of the first, so that the matrix pipe works on one slice while
-// the vector unit does the other's exponentials (software pipelining inside the wave; used when
-// every wave has rows, i.e. above 128 rows, where the kernel is matrix-core and LDS bound).
+// SUB = 2 (more than 128 rows: every wave has rows, and the wave's matrix instructions and its softmax
+// arithmetic each take about half of its time): one code path, compute_pair, pairs the score products of
+// one slice with the exponentials of the other inside the wave's instruction stream.
 template <int NTG, int RT, int SUB>
 __device__ __forceinline__ void verify_body(const VerifyParams& p, char* smem, int kvh, int slot, int t_begin, int t_len,
                                             int w0, int w, int c0, int N, int row0) {
@@ -97,7 +94,7 @@ __device__ __forceinline__ void verify_body(const VerifyParams& p, char* smem, i
   const int total = N + w;
   const int t_end = min(min(total, p.tok_hi), t_begin + t_len);    // tokens [t_begin, t_end) -> partial `slot` of every row
   const int ntiles = (t_end - t_begin + TT - 1) / TT;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int rg = wave % NRG, tg = wave / NRG;
   const int n = lane & 31, hh = lane >> 5;
   const bool wave_rows = row0 + rg * 32 * RT < R;
@@ -140,17 +137,16 @@ __device__ __forceinline__ void verify_body(const VerifyParams& p, char* smem, i
 
   // ---- tile loads: wave-load c of this wave covers tile rows 4*(wave + NW*c) .. +3 ----
   const uint32_t lds_base = static_cast<uint32_t>(reinterpret_cast<size_t>((__attribute__((address_space(3))) char*)smem));
-  // fast path (tile entirely inside the full KV): per-lane pointers that advance by one tile
-  const uint16_t* kfast[LPT];
-  const uint16_t* vfast[LPT];
-#pragma unroll
-  for (int c = 0; c < LPT; ++c) {
-    const int row = 4 * (wave + NW * c) + (lane >> 4);
-    const size_t off = static_cast<size_t>(c0 + t_begin + row) * row_stride + head_off + 8 * ((lane & 15) ^ rot_row(row));
-    kfast[c] = p.kf + off;
-    vfast[c] = p.vf + off;
-  }
-  const size_t tile_step = static_cast<size_t>(TT) * row_stride;
+  // fast path (tile entirely inside the full KV): a wave-uniform base address per wave-load (scalar
+  // registers, advanced by scalar arithmetic) plus one per-lane byte offset that never changes, so that
+  // requesting a tile costs no vector instructions
+  const int wrow = 4 * wave + (lane >> 4);     // tile row of this lane in wave-load 0; wave-load c is 4 NW rows further
+  const uint32_t lane_off = static_cast<uint32_t>((static_cast<size_t>(lane >> 4) * row_stride + 8 * ((lane & 15) ^ rot_row(wrow))) * 2);
+  static_assert((4 * NW) % 16 == 0, "rot_row of a lane's tile row must not depend on the wave-load");
+  const uint8_t* kbase_u = reinterpret_cast<const uint8_t*>(p.kf + (static_cast<size_t>(c0 + t_begin + 4 * wave) * row_stride + head_off));
+  const uint8_t* vbase_u = reinterpret_cast<const uint8_t*>(p.vf + (static_cast<size_t>(c0 + t_begin + 4 * wave) * row_stride + head_off));
+  const size_t tile_step = static_cast<size_t>(TT) * row_stride * 2;          // bytes
+  const size_t load_step = static_cast<size_t>(4 * NW) * row_stride * 2;      // bytes between the rows of two wave-loads
   auto issue = [&](int j) {                    // request tile j into stage j % NSTAGE
     const int t = t_begin + j * TT;
     const uint32_t stage = lds_base + (j % NSTAGE) * STAGE_BYTES;
@@ -158,8 +154,9 @@ __device__ __forceinline__ void verify_body(const VerifyParams& p, char* smem, i
 #pragma unroll
       for (int c = 0; c < LPT; ++c) {
         const int grp = wave + NW * c;
-        load_to_lds(kfast[c] + static_cast<size_t>(j) * tile_step, __builtin_amdgcn_readfirstlane(stage + grp * 1024));
-        load_to_lds(vfast[c] + static_cast<size_t>(j) * tile_step, __builtin_amdgcn_readfirstlane(stage + TT * 256 + grp * 1024));
+        load_to_lds(kbase_u + static_cast<size_t>(j) * tile_step + c * load_step, lane_off, __builtin_amdgcn_readfirstlane(stage + grp * 1024));
+        load_to_lds(vbase_u + static_cast<size_t>(j) * tile_step + c * load_step, lane_off,
+                    __builtin_amdgcn_readfirstlane(stage + TT * 256 + grp * 1024));
       }
     } else {
 #pragma unroll
@@ -179,36 +176,55 @@ __device__ __forceinline__ void verify_body(const VerifyParams& p, char* smem, i
   };
 
   // ---- LDS read addresses of this lane, relative to the stage base ----
-  uint32_t kaddr[8];
-#pragma unroll
-  for (int ks = 0; ks < 8; ++ks) kaddr[ks] = swz(32 * tg + n, 2 * ks + hh);
+  // All operand addresses of a slice derive from three per-lane bases by an xor with a constant and a
+  // constant offset (stage bases are multiples of 256, so the xor only ever touches chunk-position bits):
+  //   K, k-step ks:        swz(row, 2ks + hh) = kx0 ^ (32 ks)                  row = 32 tg + n
+  //   V^T, tile dt, k-step kk, half h2:  swz(row, 4dt + tr_chunk) + tr_sub = (vy0[h2] ^ (64 dt)) + 4096 kk
+  //                                                                         row = 32 tg + 16 kk + 8 h2 + tr_row
+  // (rot_row(row) only depends on the low four row bits: the low three, which tr_row supplies, and bit 3 = h2.)
+  const uint32_t kx0 = swz(32 * tg + n, hh);
   // transposing read: lane -> (token row, 8-byte half of a 16-byte chunk) inside a 4 x 16 patch
   const int blk16 = lane >> 4;
   const int tr_row = 4 * (blk16 >> 1) + ((lane & 15) >> 2);
   const int tr_chunk = 2 * (blk16 & 1) + ((lane & 3) >> 1);
   const int tr_sub = 8 * (lane & 1);
-  uint32_t vaddr[4][2][2];
+  uint32_t vy0[2];
 #pragma unroll
-  for (int dt = 0; dt < 4; ++dt)
+  for (int h2 = 0; h2 < 2; ++h2) vy0[h2] = TT * 256 + swz(32 * tg + 8 * h2 + tr_row, tr_chunk) + tr_sub;
+
+  // One slice = 32 tokens of the tile for this wave's rows.  The operand reads of a slice are issued as a
+  // batch, well ahead of the matrix instructions that take them, so that the LDS latency (a hundred cycles
+  // and more per read) is paid once per batch and overlaps the softmax arithmetic: left to itself the
+  // compiler places every read directly in front of its product and the wave stalls for the full latency
+  // on each of the 24 products of a slice.
+  auto read_k = [&](int j, int sl, bf16x8v (&kb)[8]) {                  // K operand of a slice: 8 reads of 16 bytes per lane
+    const uint32_t sbase = lds_base + (j % NSTAGE) * STAGE_BYTES + sl * SLICE_BYTES;
+    const uint32_t kx = sbase + kx0;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) kb[ks] = lds_load_bf16x8(kx ^ (32u * ks));
+  };
+  auto read_v = [&](int j, int sl, bf16x8v (&vb)[2][4]) {              // V^T operand of a slice: 16 transposing reads
+    // A element e of k-step kk is token row 16kk + 8(e/4) + 4hh + e%4
+    const uint32_t sbase = lds_base + (j % NSTAGE) * STAGE_BYTES + sl * SLICE_BYTES;
+    const uint32_t vy[2] = {sbase + vy0[0], sbase + vy0[1]};
 #pragma unroll
     for (int kk = 0; kk < 2; ++kk)
 #pragma unroll
-      for (int h2 = 0; h2 < 2; ++h2)
-        vaddr[dt][kk][h2] = TT * 256 + swz(32 * tg + 16 * kk + 8 * h2 + tr_row, 4 * dt + tr_chunk) + tr_sub;
-
-  // One slice = 32 tokens of the tile for this wave's rows, in three stages.
-  auto scores = [&](int j, int sl, float16v (&sacc)[RT]) {       // S^T = K Q^T : one K operand read feeds RT products
-    const uint32_t sbase = lds_base + (j % NSTAGE) * STAGE_BYTES + sl * SLICE_BYTES;
+      for (int dt = 0; dt < 4; ++dt) {
+        const short4v lo = lds_read_tr((vy[0] ^ (64u * dt)) + 4096u * kk);
+        const short4v hi = lds_read_tr((vy[1] ^ (64u * dt)) + 4096u * kk);
+        vb[kk][dt] = __builtin_bit_cast(bf16x8v, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+      }
+  };
+  auto scores = [&](const bf16x8v (&kb)[8], float16v (&sacc)[RT]) {    // S^T = K Q^T : one K operand feeds RT products
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt)
 #pragma unroll
       for (int i = 0; i < 16; ++i) sacc[rt][i] = 0.f;
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks) {
-      const bf16x8v a = lds_load_bf16x8(sbase + kaddr[ks]);
+    for (int ks = 0; ks < 8; ++ks)
 #pragma unroll
-      for (int rt = 0; rt < RT; ++rt) sacc[rt] = mfma32(a, qb[rt][ks], sacc[rt]);
-    }
+      for (int rt = 0; rt < RT; ++rt) sacc[rt] = mfma32(kb[ks], qb[rt][ks], sacc[rt]);
   };
   auto softmax = [&](int ts, float16v (&sacc)[RT], bf16x8v (&pb)[RT][2]) {
     // register i of this lane is token row 8*(i/4) + 4*hh + i%4 of the slice, for row n
@@ -252,46 +268,144 @@ __device__ __forceinline__ void verify_body(const VerifyParams& p, char* smem, i
       l[rt] += ps0 + ps1;
     }
   };
-  auto output = [&](int j, int sl, bf16x8v (&pb)[RT][2]) {
-    // O^T += V^T P^T ; A element e of k-step kk is token row 16kk + 8(e/4) + 4hh + e%4
-    const uint32_t sbase = lds_base + (j % NSTAGE) * STAGE_BYTES + sl * SLICE_BYTES;
+  auto output = [&](const bf16x8v (&vb)[2][4], bf16x8v (&pb)[RT][2]) {  // O^T += V^T P^T
 #pragma unroll
-    for (int kk = 0; kk < 2; ++kk) {
+    for (int kk = 0; kk < 2; ++kk)
 #pragma unroll
-      for (int dt = 0; dt < 4; ++dt) {
-        const short4v lo = lds_read_tr(sbase + vaddr[dt][kk][0]);
-        const short4v hi = lds_read_tr(sbase + vaddr[dt][kk][1]);
-        const bf16x8v av = __builtin_bit_cast(bf16x8v, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+      for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
-        for (int rt = 0; rt < RT; ++rt) oacc[rt][dt] = mfma32(av, pb[rt][kk], oacc[rt][dt]);
-      }
-    }
+        for (int rt = 0; rt < RT; ++rt) oacc[rt][dt] = mfma32(vb[kk][dt], pb[rt][kk], oacc[rt][dt]);
   };
   auto compute = [&](int j) {
     if (!wave_rows) return;
     const int ts0 = t_begin + j * TT + 32 * tg;   // first token of this wave's first slice
-    if constexpr (SUB == 1) {
-      if (ts0 >= t_end) return;
+    if (ts0 >= t_end) return;
+#pragma unroll
+    for (int sl = 0; sl < SUB; ++sl) {
+      const int ts = ts0 + sl * 32 * NTG;
+      if (sl > 0 && ts >= t_end) break;          // the chunk ends inside this tile
+      bf16x8v kb[8];
+      read_k(j, sl, kb);
       float16v sacc[RT];
+      scores(kb, sacc);
+      // V^T of this slice is requested before the softmax and lands while it runs
+      bf16x8v vb[2][4];
+      read_v(j, sl, vb);
+      __builtin_amdgcn_sched_barrier(0);         // nothing moves across: the reads stay up here
       bf16x8v pb[RT][2];
-      scores(j, 0, sacc);
-      softmax(ts0, sacc, pb);
-      output(j, 0, pb);
-    } else {
-      const int ts1 = ts0 + 32 * NTG;
-      if (ts0 >= t_end) return;
-      const bool second = ts1 < t_end;
-      float16v sa[RT], sb[RT];
-      bf16x8v pa[RT][2], pbb[RT][2];
-      scores(j, 0, sa);
-      if (second) scores(j, 1, sb);            // in the matrix pipe while the first softmax runs
-      softmax(ts0, sa, pa);
-      output(j, 0, pa);
-      if (second) {
-        softmax(ts1, sb, pbb);                 // overlaps the first slice's output products
-        output(j, 1, pbb);
-      }
+      softmax(ts, sacc, pb);
+      output(vb, pb);
     }
+  };
+
+  // The two-slice form (every wave has rows: the kernel is bound by the matrix cores and the vector unit,
+  // not by HBM).  A wave's matrix instructions and its softmax arithmetic each take about half of its time,
+  // and the waves of a workgroup move in lockstep behind the tile barrier, so nothing overlaps unless the
+  // instruction stream of a single wave does it: a matrix instruction runs for 32 cycles once issued, and
+  // independent vector instructions issued behind it execute meanwhile.  The pairing - scores of slice B
+  // with the exponentials of slice A, output products of A with the exponentials of B - is pinned with
+  // scheduling groups (a few vector instructions, then one matrix instruction).
+  auto row_max = [&](const float16v& sc) {
+    float mt = fmaxf(fmaxf(sc[0], sc[1]), sc[2]);
+#pragma unroll
+    for (int i = 3; i < 15; i += 2) mt = fmaxf(fmaxf(mt, sc[i]), sc[i + 1]);
+    return fmaxf(mt, sc[15]) * p.scale_log2e;
+  };
+  // RT == 1 only: rescale the row state when the maximum jumps.  `pending` are probabilities that were taken
+  // against the old maximum and whose output product has not been issued yet: they are rescaled as well.
+  auto raise_max = [&](float mt, bf16x8v* pending) {
+    if (__any(mt > m[0] + kVerifyMargin)) {
+      const float mx = fmaxf(mt, __shfl_xor(mt, 32, 64));
+      const float mn = fmaxf(m[0], mx);
+      const float alpha = __builtin_amdgcn_exp2f(m[0] - mn);
+      l[0] *= alpha;
+#pragma unroll
+      for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) oacc[0][dt][i] *= alpha;
+      if (pending) {
+#pragma unroll
+        for (int kk = 0; kk < 2; ++kk)
+#pragma unroll
+          for (int e = 0; e < 8; ++e) pending[kk][e] = (__bf16)(static_cast<float>(pending[kk][e]) * alpha);
+      }
+      m[0] = mn;
+    }
+  };
+  auto exps = [&](const float16v& sc, bf16x8v (&pb)[2]) {
+    float ps0 = 0.f, ps1 = 0.f;
+    const float negm = -m[0];
+#pragma unroll
+    for (int i = 0; i < 16; i += 2) {
+      const float p0 = __builtin_amdgcn_exp2f(fmaf(sc[i], p.scale_log2e, negm));
+      const float p1 = __builtin_amdgcn_exp2f(fmaf(sc[i + 1], p.scale_log2e, negm));
+      ps0 += p0;
+      ps1 += p1;
+      pb[i >> 3][i & 7] = (__bf16)p0;
+      pb[i >> 3][(i & 7) + 1] = (__bf16)p1;
+    }
+    l[0] += ps0 + ps1;
+  };
+  auto interleave = [&]() {                      // 8 x (a few vector instructions, then one matrix instruction), then 16 LDS reads
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      __builtin_amdgcn_sched_group_barrier(0x002, 8, 0);
+      __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+    }
+    __builtin_amdgcn_sched_group_barrier(0x002, 16, 0);
+    __builtin_amdgcn_sched_group_barrier(0x100, 16, 0);
+  };
+  auto mask_edge = [&](int ts, float16v& sc) {   // a slice that touches the window or the end of the chunk
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+      const int tok = ts + 8 * (i >> 2) + 4 * hh + (i & 3);
+      const bool ok = tok < t_end && (tok < N || tok - N <= iw[0]);
+      sc[i] = ok ? sc[i] : -INFINITY;
+    }
+  };
+  // The two-slice form (SUB == 2, RT == 1: every wave has rows), one code path for every tile: the only
+  // difference at the edge of the chunk is a mask on the scores (a slice entirely past the end is masked
+  // out as a whole and adds zeros).
+  auto compute_pair = [&](int j) {
+    const int ts0 = t_begin + j * TT;
+    const bool edge = ts0 + TT > min(N, t_end);
+    bf16x8v kb[8], vb[2][4], pA[2], pB[2];
+    float16v sA, sB;
+    read_k(j, 0, kb);
+#pragma unroll
+    for (int i = 0; i < 16; ++i) sA[i] = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) sA = mfma32(kb[ks], qb[0][ks], sA);
+    read_k(j, 1, kb);                            // lands while the maximum of slice A is taken
+    __builtin_amdgcn_sched_barrier(0);
+    if (edge) mask_edge(ts0, sA);
+    raise_max(row_max(sA), nullptr);
+    __builtin_amdgcn_sched_barrier(0);
+    // scores of slice B  |  exponentials of slice A; then the V^T reads of slice A (into the registers K left)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) sB[i] = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) sB = mfma32(kb[ks], qb[0][ks], sB);
+    exps(sA, pA);
+    read_v(j, 0, vb);
+    interleave();
+    __builtin_amdgcn_sched_barrier(0);
+    if (edge) mask_edge(ts0 + 32, sB);
+    raise_max(row_max(sB), pA);
+    __builtin_amdgcn_sched_barrier(0);
+    // output products of slice A  |  exponentials of slice B; then the V^T reads of slice B
+#pragma unroll
+    for (int kk = 0; kk < 2; ++kk)
+#pragma unroll
+      for (int dt = 0; dt < 4; ++dt) oacc[0][dt] = mfma32(vb[kk][dt], pA[kk], oacc[0][dt]);
+    exps(sB, pB);
+    read_v(j, 1, vb);
+    interleave();
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int kk = 0; kk < 2; ++kk)
+#pragma unroll
+      for (int dt = 0; dt < 4; ++dt) oacc[0][dt] = mfma32(vb[kk][dt], pB[kk], oacc[0][dt]);
   };
 
   // ---- ring: tile j is requested DEPTH iterations before it is used ----
@@ -311,7 +425,11 @@ __device__ __forceinline__ void verify_body(const VerifyParams& p, char* smem, i
     else wait_vm<(DEPTH > 6 ? 6 : 0) * 2 * LPT>();
     __syncthreads();                            // every wave's share of tile j is in LDS; tile j-1 is no longer read
     if (j + DEPTH < ntiles) issue(j + DEPTH);   // into the stage tile j-1 just left
-    compute(j);
+    if constexpr (SUB == 2 && RT == 1 && NTG == 1) {
+      if (wave_rows) compute_pair(j);
+    } else {
+      compute(j);
+    }
   }
 
   // With two token slices per tile, the two waves that share a row group merge their states
