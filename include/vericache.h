@@ -58,7 +58,8 @@ const char* vc_version(void);
  * between the calls of one streamed verify, is the caller's error.  Names:
  *   VC_DRAFT_BF16_WGS, VC_DRAFT_QUANT_WGS   workgroups a draft launch is cut for
  *   VC_DRAFT_MIN_TOK, VC_DRAFT_MIN_BLK      shortest split (tokens / block records)
- *   VC_DRAFT_TAPER                          1: the last splits of a list of records are cut shorter
+ *   VC_DRAFT_FLAT                           0: ragged batches of at most 64 sequences are launched
+ *                                           like larger ones (a grid over the longest sequence's splits)
  *   VC_VERIFY_WGS, VC_VERIFY_MIN_TOK        workgroups a verify launch is cut for, shortest chunk
  *   VC_VERIFY_WORKLIST, VC_VERIFY_LIST_MIN, VC_VERIFY_TAPER, VC_VERIFY_QUEUE_WGS   the work-list
  *                                           launch of large ragged batches

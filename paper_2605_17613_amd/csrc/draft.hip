@@ -13,6 +13,33 @@
 
 namespace vc {
 
+// Flat launch (at most 64 sequences): workgroup x of the launch is split x of the list of all the
+// splits that exist, sequence after sequence.  Every wave finds its sequence by itself - lane i holds
+// the split count of sequence i, a prefix sum over the lanes, one ballot - so a ragged batch launches
+// no workgroup per (sequence, split of the longest sequence) that finds nothing to do.  `cu` holds
+// the n_seqs + 1 prefix sums of the units (rows or records), `per` the units per split.  Returns
+// false when x is beyond the last split.
+__device__ __forceinline__ bool flat_split(const int* cu, int n_seqs, int per, int x, int& b, int& sp) {
+  const int lane = threadIdx.x & 63;
+  int cnt = 0;
+  if (lane < n_seqs) {
+    const int s = cu[lane], e = cu[lane + 1];
+    cnt = e > s ? (e - s + per - 1) / per : 0;
+  }
+  int scan = cnt;
+#pragma unroll
+  for (int d = 1; d < 64; d <<= 1) {
+    const int t = __shfl_up(scan, d);
+    if (lane >= d) scan += t;
+  }
+  const unsigned long long hit = __ballot(scan > x);
+  if (hit == 0ull) return false;
+  const int l = __ffsll(hit) - 1;
+  b = __builtin_amdgcn_readfirstlane(l);
+  sp = __builtin_amdgcn_readfirstlane(x - (__shfl(scan, l) - __shfl(cnt, l)));
+  return true;
+}
+
 // --------------------------------------------------------------------------------------------
 // bf16 rows (kept-index gather, contiguous pool, or tail)
 // --------------------------------------------------------------------------------------------
@@ -26,6 +53,7 @@ struct DraftBf16Params {
   float* ws;
   int n_q_heads, n_kv_heads, g;
   int split_tok, slot0, ns;
+  int n_seqs, flat;     // flat: see flat_split
   float scale_log2e;
 };
 
@@ -67,7 +95,13 @@ __global__ __launch_bounds__(NW * 64, 1) void draft_bf16_kernel(DraftBf16Params 
   constexpr int NT = kRowsStep / 16;                            // 16-token score tiles per step
   constexpr int NLD = kRowsStep / 4;                            // wave loads per matrix per step
   extern __shared__ __attribute__((aligned(1024))) char ring[];
-  const int b = blockIdx.z, kvh = blockIdx.y, sp = blockIdx.x;
+  int b, kvh, sp;
+  if (p.flat) {
+    kvh = blockIdx.x % p.n_kv_heads;   // heads vary fastest: the workgroups beyond the last split come last
+    if (!flat_split(GATHER ? p.cu_keep : p.cu_rows, p.n_seqs, p.split_tok, blockIdx.x / p.n_kv_heads, b, sp)) return;
+  } else {
+    b = blockIdx.z; kvh = blockIdx.y; sp = blockIdx.x;
+  }
   const int row0 = p.cu_rows[b];
   const int count = GATHER ? (p.cu_keep[b + 1] - p.cu_keep[b]) : (p.cu_rows[b + 1] - row0);
   const int start = sp * p.split_tok;
@@ -309,6 +343,7 @@ struct DraftQuantParams {
   float* ws;
   int n_q_heads, n_kv_heads, g, npass;
   int bps, slot0, ns;
+  int n_seqs, flat;   // flat: see flat_split
   float scale_log2e;
 };
 
@@ -388,8 +423,16 @@ __global__ __launch_bounds__(256, 3) void draft_quant_kernel(DraftQuantParams p)
   constexpr int GPS = NG > NSLOT ? NG / NSLOT : 1;   // channel groups a slot carries
   constexpr int TPG = 8 / NG;                 // 16-channel output tiles per channel group
   extern __shared__ __attribute__((aligned(1024))) char ring[];
-  const int b = blockIdx.z, sp = blockIdx.x;
-  const int kvh = blockIdx.y / p.npass, pass = blockIdx.y % p.npass;
+  int b, sp, yy;
+  if (p.flat) {
+    // heads vary fastest, so the workgroups beyond the last split are the last ones dispatched
+    const int ny = p.n_kv_heads * p.npass;
+    yy = blockIdx.x % ny;
+    if (!flat_split(p.cu_blk, p.n_seqs, p.bps, blockIdx.x / ny, b, sp)) return;
+  } else {
+    b = blockIdx.z; sp = blockIdx.x; yy = blockIdx.y;
+  }
+  const int kvh = yy / p.npass, pass = yy % p.npass;
   const int nb = p.cu_blk[b + 1] - p.cu_blk[b];
   const int blk0 = sp * p.bps;
   if (blk0 >= nb) return;
@@ -924,6 +967,7 @@ __global__ __launch_bounds__(128 * kMergeGroups) void draft_merge_kernel(DraftMe
 struct DraftPlan {
   int split_a, s1;   // bf16 pool source: tokens per split, splits of the longest sequence
   int bps, s2;       // block records: records per split, splits of the longest sequence
+  bool flat_a, flat_b;   // launches that hold only the splits that exist (flat_split)
   int ns;
 };
 
@@ -957,14 +1001,24 @@ static DraftPlan make_plan(const vc_comp_kv* kv) {
     return sum <= 0 || static_cast<int64_t>(mx) * kv->n_seqs * 10 <= static_cast<int64_t>(sum) * 11;
   };
   const int target_a = tunable(kTunDraftBf16Wgs, uniform(kv->sum_keep, kv->max_keep) ? 256 : 512, 1, 1 << 20);
-  const int target_b = tunable(kTunDraftQuantWgs, uniform(kv->sum_blk, kv->max_blk) ? 768 : 1536, 1, 1 << 20);
+  // (a handful of lists - one long sequence - does better with one workgroup per CU: 256 against 768 measured
+  // 29.8 against 31.8 us for the record kernel and 5.4 against 7.4 us for the merge at 8 lists of 4096 records)
+  const int npass_b = ceil_div(g, heads_per_pass(kv->bits, g));
+  const int target_b = tunable(kTunDraftQuantWgs, lists * npass_b < 32 ? 256 : uniform(kv->sum_blk, kv->max_blk) ? 768 : 1536, 1, 1 << 20);
   pl.split_a = pick_chunk(static_cast<int64_t>(kv->sum_keep) * kv->n_kv_heads, kv->max_keep, lists, 128,
                           tunable(kTunDraftMinTok, 256, 128, 1 << 20), target_a);
   pl.s1 = has_a ? ceil_div(kv->max_keep, pl.split_a) : 0;
-  const int npass = ceil_div(g, heads_per_pass(kv->bits, g));
+  const int npass = npass_b;
   pl.bps = pick_chunk(static_cast<int64_t>(kv->sum_blk) * kv->n_kv_heads * npass, kv->max_blk, lists * npass, 4,
                       tunable(kTunDraftMinBlk, 16, 4, 1 << 20), target_b);
   pl.s2 = has_b ? ceil_div(kv->max_blk, pl.bps) : 0;
+  // a ragged batch of at most 64 sequences launches only the splits that exist (config 4: 178 -> 165 us
+  // with the record kernel launched so)
+  const bool flat_ok = tunable(kTunDraftFlat, 1, 0, 1) != 0 && kv->n_seqs <= 64;
+  pl.flat_a = flat_ok && has_a && !uniform(kv->sum_keep, kv->max_keep) &&
+              static_cast<int64_t>(pl.s1) * lists <= (1ll << 30);
+  pl.flat_b = flat_ok && has_b && !uniform(kv->sum_blk, kv->max_blk) &&
+              static_cast<int64_t>(pl.s2) * lists * npass <= (1ll << 30);
   pl.ns = pl.s1 + pl.s2;
   if (pl.ns == 0) pl.ns = 1;
   return pl;
@@ -1069,7 +1123,9 @@ static vc_status draft_attn_impl(const char* who, vc_ctx* ctx, const vc_comp_kv*
     bp.n_q_heads = kv->n_q_heads; bp.n_kv_heads = kv->n_kv_heads; bp.g = g;
     bp.split_tok = pl.split_a; bp.slot0 = 0; bp.ns = pl.ns;
     bp.scale_log2e = sl2;
+    bp.n_seqs = kv->n_seqs; bp.flat = pl.flat_a;
     dim3 grid(pl.s1, kv->n_kv_heads, kv->n_seqs);
+    if (pl.flat_a) grid = dim3(static_cast<unsigned>(pl.s1) * kv->n_seqs * kv->n_kv_heads, 1, 1);
     // 32-token steps, 4 waves (16-token steps with 8 waves measured the same: the gather itself binds)
     constexpr int kLds = rows_lds(32, 4);
     if (kv->keep_idx) hipLaunchKernelGGL((draft_bf16_kernel<true, 32, 4>), grid, dim3(256), kLds, st, bp);
@@ -1086,7 +1142,10 @@ static vc_status draft_attn_impl(const char* who, vc_ctx* ctx, const vc_comp_kv*
     qp.npass = ceil_div(g, hpw);
     qp.bps = pl.bps; qp.slot0 = pl.s1; qp.ns = pl.ns;
     qp.scale_log2e = sl2;
+    qp.n_seqs = kv->n_seqs; qp.flat = pl.flat_b;
+    // flat: every sequence has at most s2 splits, all heads of a split are neighbours in the launch
     dim3 grid(pl.s2, kv->n_kv_heads * qp.npass, kv->n_seqs);
+    if (pl.flat_b) grid = dim3(static_cast<unsigned>(pl.s2) * kv->n_seqs * kv->n_kv_heads * qp.npass, 1, 1);
     if (kv->bits == 4 && hpw == 4) hipLaunchKernelGGL((draft_quant_kernel<4, 4>), grid, dim3(256), kQuantRingBytes, st, qp);
     else if (kv->bits == 4) hipLaunchKernelGGL((draft_quant_kernel<4, 8>), grid, dim3(256), kQuantRingBytes, st, qp);
     else if (hpw == 4) hipLaunchKernelGGL((draft_quant_kernel<2, 4>), grid, dim3(256), kQuantRingBytes, st, qp);

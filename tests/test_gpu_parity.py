@@ -20,8 +20,9 @@ def ctx(lib):
     c.close()
 
 
-def check_draft(lib, ctx, lay, tag, lse_tol=H.LSE_TOL, **sel):
+def check_draft(lib, ctx, lay, tag, lse_tol=H.LSE_TOL, hints=None, **sel):
     kw = H.draft_kwargs(lay, **sel)
+    kw.update(hints or {})      # sum_keep / sum_blk: they steer the launch shape only
     print(f"[draft] {tag} {sel}", flush=True)
     out, lse = H.gpu_draft(lib, ctx, lay, **kw)
     ref, ref_lse = H.oracle_draft(lay, kw)
@@ -82,6 +83,38 @@ def test_draft_long_tails_in_both_merge_variants(lib, ctx, nseq):
     check_draft(lib, ctx, lay, f"long tails, {nseq} sequences", bits=4, use_tail=True)
     lay = synth.make_layer(70 + nseq, DEV, ctx_len=lens, n_q_heads=8, n_kv_heads=2, tail_len=tails)
     check_draft(lib, ctx, lay, f"tail only, {nseq} sequences", use_tail=True)     # no split at all: the merge does everything
+
+
+@pytest.mark.parametrize("nseq", [5, 64, 65])
+def test_draft_ragged_mixed_batch_with_length_hints(lib, ctx, tunables, nseq):
+    """A ragged batch whose descriptor carries the sums of its list lengths: up to 64 sequences both
+    split kernels are launched over the splits that exist (every wave finds its sequence from the
+    prefix arrays), beyond that over a grid sized by the longest sequence.  The splits are the same
+    either way, so the two launches must agree bit for bit, and both with the oracle."""
+    rng = np.random.default_rng(900 + nseq)
+    lens = [int(x) for x in rng.integers(1, 1500, nseq)]
+    lens[nseq // 2] = 6000                       # one long sequence makes the batch ragged
+    lens[0] = 40
+    keep = [int(rng.integers(0, n + 1)) if i % 3 else 0 for i, n in enumerate(lens)]
+    keep[nseq // 2] = 2500
+    first = [min(k, 2) for k in keep]
+    last = [min(k - f, 3) for k, f in zip(keep, first)]
+    lay = synth.make_layer(90 + nseq, DEV, ctx_len=lens, n_q_heads=8, n_kv_heads=2, keep=keep, keep_first=first,
+                           keep_last=last, quant_bits=(4,), tail_len=[int(x) for x in rng.integers(0, 20, nseq)])
+    outs = []
+    for flat in (1, 0):
+        tunables.set("VC_DRAFT_FLAT", flat)
+        # small splits so that even these short lists are cut several times
+        tunables.set("VC_DRAFT_MIN_TOK", 128)
+        tunables.set("VC_DRAFT_MIN_BLK", 4)
+        tunables.set("VC_DRAFT_BF16_WGS", 300)
+        tunables.set("VC_DRAFT_QUANT_WGS", 500)
+        o1 = check_draft(lib, ctx, lay, f"hints rows, {nseq} sequences, flat {flat}", use_pool=True, use_keep=True,
+                         use_tail=True, hints=dict(sum_keep=int(lay.cu_keep[-1])))
+        o2 = check_draft(lib, ctx, lay, f"hints records, {nseq} sequences, flat {flat}", bits=4, use_tail=True,
+                         hints=dict(sum_blk=int(lay.cu_blk[4][-1])))
+        outs.append((o1.clone(), o2.clone()))
+    assert torch.equal(outs[0][0], outs[1][0]) and torch.equal(outs[0][1], outs[1][1])
 
 
 @pytest.mark.parametrize("bits", [4, 2])
