@@ -63,6 +63,7 @@ const char* vc_version(void);
  *   VC_VERIFY_WGS, VC_VERIFY_MIN_TOK        workgroups a verify launch is cut for, shortest chunk
  *   VC_VERIFY_WORKLIST, VC_VERIFY_LIST_MIN, VC_VERIFY_TAPER, VC_VERIFY_QUEUE_WGS   the work-list
  *                                           launch of large ragged batches
+ *   VC_ACCEPT_FUSED                         0: the accept call finishes in a second launch
  * Unknown names return VC_ERR_INVALID_ARG. */
 vc_status vc_set_tunable(const char* name, int32_t value);
 vc_status vc_get_tunable(const char* name, int32_t* value, int32_t* is_set);
@@ -263,7 +264,10 @@ vc_status vc_verify_finish(vc_ctx* ctx, const vc_full_kv* kv, const int32_t* cu_
  *               index wins a tie
  *   accept_len  device int32 [n_seqs]: first j with draft_ids[j] != argmax(row j), else w_b
  *   next_token  device int32 [n_seqs]: argmax(row accept_len) - the correction, or the bonus
- *               token when everything matched and the bonus row exists; -1 if that row is absent */
+ *               token when everything matched and the bonus row exists; -1 if that row is absent
+ * A short scan (up to 2048 segments of 8192 logits) is one launch whose last workgroup finishes the batch; it counts on one
+ * of 16 sets of counters the context owns (call i uses set i mod 16), so at most 16 calls made through
+ * one context may be in flight, or captured in graphs that run, at the same time. */
 vc_status vc_accept_workspace_bytes(int32_t total_rows, int32_t vocab, size_t* bytes);
 vc_status vc_accept_len(vc_ctx* ctx, const float* logits, int32_t vocab, const int32_t* cu_rows,
                         int32_t total_rows, const int32_t* draft_ids, const int32_t* cu_win,

@@ -6,8 +6,12 @@
 //   key = (order-preserving image of the float) << 32 | ~index
 // and stores it in the row's slot for that segment; the largest key of a row is the largest value
 // and, among equal values, the lowest index.  The finishing kernel takes the maximum over a row's
-// segments (a dozen keys) before it compares with the drafted ids, so a call is two launches and
-// needs neither atomics nor a cleared workspace.
+// segments (a dozen keys) before it compares with the drafted ids.  In a short scan (up to
+// kFusedMaxWgs workgroups) the finish runs inside the scan: every workgroup counts itself on a counter of its row (memory the
+// context owns) after it has published its key; the one that completes a row takes the row's arg-max
+// and counts the row; the one that completes the launch walks the drafted ids of every sequence.
+// Counters go back to zero as they complete - one launch, no workspace that must be cleared.  Longer
+// scans (and VC_ACCEPT_FUSED 0) take the finish as a second launch.
 #include "common.h"
 
 namespace vc {
@@ -25,8 +29,51 @@ __device__ __forceinline__ unsigned long long make_key(float v, int idx) {
   return (static_cast<unsigned long long>(float_order(v)) << 32) | static_cast<uint32_t>(~static_cast<uint32_t>(idx));
 }
 
+constexpr int kFusedMaxRows = vc_ctx::kAcceptMaxRows;
+constexpr int kFusedMaxWgs = 2048;
+
+__device__ __forceinline__ int key_index(unsigned long long key) { return static_cast<int>(~static_cast<uint32_t>(key)); }
+
+struct FinishParams {
+  unsigned int* counter;   // NULL: the finish is a launch of its own
+  const int* cu_rows;
+  const int* draft_ids;
+  const int* cu_win;
+  int* accept_len;
+  int* next_token;
+  int* argmax_ids;
+  int n_seqs, total_rows;
+};
+
+// The compare of one sequence (section 4.1 step 3), by one wave: lane j holds drafted id j against
+// the arg-max of row j, a ballot finds the first mismatch.  accept_len = drafted ids that equal the
+// arg-max of their row, from the first row on; next_token = the arg-max of the first row that
+// disagrees (or of the bonus row), -1 when the sequence has no such row.  id_at(r) = arg-max of row r.
+template <typename IdAt>
+__device__ __forceinline__ void accept_wave(int b, const int* cu_rows, const int* draft_ids, const int* cu_win, IdAt id_at,
+                                            int* accept_len, int* next_token) {
+  const int lane = threadIdx.x & 63;
+  const int r0 = cu_rows[b], r1 = cu_rows[b + 1];
+  const int w0 = cu_win[b], w = cu_win[b + 1] - w0;
+  int a = w;
+  for (int j0 = 0; j0 < w; j0 += 64) {
+    const int j = j0 + lane;
+    const bool miss = j < w && draft_ids[w0 + j] != id_at(r0 + j);
+    const unsigned long long m = __ballot(miss);
+    if (m != 0ull) {
+      a = j0 + __ffsll(m) - 1;
+      break;
+    }
+  }
+  if (lane == 0) {
+    accept_len[b] = a;
+    next_token[b] = (r0 + a < r1) ? id_at(r0 + a) : -1;
+  }
+}
+
 __global__ __launch_bounds__(kAcceptThreads) void argmax_segment_kernel(const float* __restrict__ logits, int vocab,
-                                                                       unsigned long long* __restrict__ keys) {
+                                                                       unsigned long long* __restrict__ keys,
+                                                                       FinishParams fp) {
   const int row = blockIdx.y;
   const int seg0 = blockIdx.x * kSegElems;
   const int seg1 = min(vocab, seg0 + kSegElems);
@@ -62,15 +109,55 @@ __global__ __launch_bounds__(kAcceptThreads) void argmax_segment_kernel(const fl
     key = o > key ? o : key;
   }
   __shared__ unsigned long long wk[kAcceptThreads / 64];
+  __shared__ int last;
   if ((threadIdx.x & 63) == 0) wk[threadIdx.x >> 6] = key;
   __syncthreads();
   if (threadIdx.x == 0) {
     for (int w = 1; w < kAcceptThreads / 64; ++w) key = wk[w] > key ? wk[w] : key;
-    keys[static_cast<size_t>(row) * gridDim.x + blockIdx.x] = key;   // 0 (below every real key) for an empty segment
+    unsigned long long* slot = keys + static_cast<size_t>(row) * gridDim.x + blockIdx.x;
+    if (fp.counter == nullptr) {
+      *slot = key;   // 0 (below every real key) for an empty segment
+    } else {
+      // The key is written through to device-coherent memory (the workgroup that reads it may sit on
+      // another XCD, behind another L2) and has arrived there before the count is taken.  A release
+      // fence would do the same and also write this XCD's whole L2 back, once per workgroup (measured:
+      // 368 against 49 us per call at 8448 workgroups); the key is the only store there is to order.
+      // Counting is in two levels - the segments of a row on the row's counter, the rows on the
+      // launch's - because thousands of atomics on one address serialise (124 us per call).
+      __hip_atomic_store(slot, key, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      const unsigned int nseg = gridDim.x;
+      unsigned int* row_counter = fp.counter + (1 + row) * vc_ctx::kAcceptCounterStride;
+      if (__hip_atomic_fetch_add(row_counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == nseg - 1u) {
+        // last segment of its row: every key of the row has been published
+        __hip_atomic_store(row_counter, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // for the next call
+        const unsigned long long* k = keys + static_cast<size_t>(row) * nseg;
+        unsigned long long best = 0ull;
+        for (unsigned int sgm = 0; sgm < nseg; ++sgm) {
+          const unsigned long long o = __hip_atomic_load(k + sgm, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          best = o > best ? o : best;
+        }
+        __hip_atomic_store(fp.argmax_ids + row, key_index(best), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        last = __hip_atomic_fetch_add(fp.counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == gridDim.y - 1u;
+        if (last) __hip_atomic_store(fp.counter, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      } else {
+        last = 0;
+      }
+    }
   }
+  if (fp.counter == nullptr) return;
+  __syncthreads();
+  if (!last) return;
+  // ---- the workgroup that arrived last: the arg-max of every row has been published ----
+  // all of them are fetched at once (each is a trip to device-coherent memory), then compared from LDS
+  __shared__ int ids[kFusedMaxRows];
+  for (int r = threadIdx.x; r < fp.total_rows; r += kAcceptThreads)
+    ids[r] = __hip_atomic_load(fp.argmax_ids + r, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  __syncthreads();
+  for (int b = threadIdx.x >> 6; b < fp.n_seqs; b += kAcceptThreads / 64)
+    accept_wave(b, fp.cu_rows, fp.draft_ids, fp.cu_win, [&](int r) { return ids[r]; }, fp.accept_len, fp.next_token);
 }
-
-__device__ __forceinline__ int key_index(unsigned long long key) { return static_cast<int>(~static_cast<uint32_t>(key)); }
 
 __device__ __forceinline__ int row_argmax(const unsigned long long* __restrict__ keys, int nseg, int row) {
   const unsigned long long* k = keys + static_cast<size_t>(row) * nseg;
@@ -80,7 +167,7 @@ __device__ __forceinline__ int row_argmax(const unsigned long long* __restrict__
 }
 
 // One workgroup per sequence: its threads take the arg-max of the sequence's rows in parallel
-// (written to argmax_ids), then one thread walks the drafted ids to the first mismatch.
+// (written to argmax_ids), then one wave compares them with the drafted ids.
 __global__ __launch_bounds__(128) void accept_finish_kernel(const unsigned long long* __restrict__ keys, int nseg,
                                                             const int* __restrict__ cu_rows,
                                                             const int* __restrict__ draft_ids,
@@ -88,17 +175,10 @@ __global__ __launch_bounds__(128) void accept_finish_kernel(const unsigned long 
                                                             int* __restrict__ next_token, int* __restrict__ argmax_ids) {
   const int b = blockIdx.x;
   const int r0 = cu_rows[b], r1 = cu_rows[b + 1];
-  const int w0 = cu_win[b], w = cu_win[b + 1] - w0;
   for (int r = r0 + threadIdx.x; r < r1; r += blockDim.x) argmax_ids[r] = row_argmax(keys, nseg, r);
-  __syncthreads();                            // the ids written above are read below by thread 0
-  if (threadIdx.x == 0) {
-    int a = w;
-    for (int j = 0; j < w; ++j) {
-      if (draft_ids[w0 + j] != argmax_ids[r0 + j]) { a = j; break; }
-    }
-    accept_len[b] = a;
-    next_token[b] = (r0 + a < r1) ? argmax_ids[r0 + a] : -1;
-  }
+  __syncthreads();                            // the ids written above are read below by wave 0
+  if (threadIdx.x < 64)
+    accept_wave(b, cu_rows, draft_ids, cu_win, [&](int r) { return argmax_ids[r]; }, accept_len, next_token);
 }
 
 // keep = [0, len) minus dropped.  A workgroup owns kKeepSpan consecutive positions [p0, p1) of one
@@ -198,12 +278,28 @@ extern "C" vc_status vc_accept_len(vc_ctx* ctx, const float* logits, int32_t voc
   hipStream_t st = static_cast<hipStream_t>(stream);
   unsigned long long* keys = static_cast<unsigned long long*>(workspace);
   const int nseg = ceil_div(vocab, kSegElems);
+  FinishParams fp{};
+  // One launch while the scan is short (the second launch is then a fifth of the call: 14.8 -> 11.5 us
+  // at 36 rows of 128256 logits).  A workgroup of a fused launch ends with two trips to device-coherent
+  // memory; with dozens of workgroups per compute unit those add up to more than the launch they save
+  // (8448 workgroups: 57.6 against 47.3 us), so larger scans keep the finish as a launch of its own.
+  const bool fused = total_rows > 0 && total_rows <= kFusedMaxRows &&
+                     static_cast<int64_t>(total_rows) * nseg <= kFusedMaxWgs && ctx->accept_counters != nullptr &&
+                     tunable(kTunAcceptFused, 1, 0, 1) != 0;
+  if (fused) {
+    // calls in flight at the same time (other streams, captured graphs) each count on a counter of their own
+    fp.counter = ctx->accept_counters + (ctx->accept_calls++ % vc_ctx::kAcceptCounters) * vc_ctx::kAcceptSlotWords;
+    fp.cu_rows = cu_rows; fp.draft_ids = draft_ids; fp.cu_win = cu_win;
+    fp.accept_len = accept_len; fp.next_token = next_token; fp.argmax_ids = argmax_ids;
+    fp.n_seqs = n_seqs; fp.total_rows = total_rows;
+  }
   if (total_rows > 0) {
     dim3 grid(nseg, total_rows);
-    hipLaunchKernelGGL(argmax_segment_kernel, grid, dim3(kAcceptThreads), 0, st, logits, vocab, keys);
+    hipLaunchKernelGGL(argmax_segment_kernel, grid, dim3(kAcceptThreads), 0, st, logits, vocab, keys, fp);
   }
-  hipLaunchKernelGGL(accept_finish_kernel, dim3(n_seqs), dim3(128), 0, st, keys, nseg, cu_rows, draft_ids, cu_win,
-                     accept_len, next_token, argmax_ids);
+  if (!fused)
+    hipLaunchKernelGGL(accept_finish_kernel, dim3(n_seqs), dim3(128), 0, st, keys, nseg, cu_rows, draft_ids, cu_win,
+                       accept_len, next_token, argmax_ids);
   VC_HIP(hipGetLastError());
   return VC_OK;
 }

@@ -58,6 +58,7 @@ __device__ __forceinline__ void st_stream(uint4* p, const uint4& v) {
 enum Tunable {
   kTunDraftBf16Wgs, kTunDraftQuantWgs, kTunDraftMinTok, kTunDraftMinBlk, kTunDraftFlat,
   kTunVerifyWgs, kTunVerifyMinTok, kTunVerifyWorklist, kTunVerifyListMin, kTunVerifyTaper, kTunVerifyQueueWgs,
+  kTunAcceptFused,
   kNumTunables
 };
 int tunable(Tunable t, int dflt, int lo, int hi);
@@ -83,6 +84,13 @@ struct vc_ctx {
   static constexpr int kMarkRing = 1024;
   hipEvent_t mark_events[kMarkRing];
   int64_t marks_issued;
+  // vc_accept_len: counters (zero between calls) on which the workgroups of a fused launch count
+  // themselves: call i uses slot i % kAcceptCounters = one counter for the launch and one per row,
+  // each on a cache line of its own
+  static constexpr int kAcceptCounters = 16, kAcceptCounterStride = 16, kAcceptMaxRows = 2048;
+  static constexpr int kAcceptSlotWords = (1 + kAcceptMaxRows) * kAcceptCounterStride;
+  unsigned int* accept_counters;
+  uint64_t accept_calls;
 };
 
 namespace vc {

@@ -35,7 +35,8 @@ vc_status hip_fail(hipError_t e, const char* what) {
 namespace {
 const char* const kTunableNames[kNumTunables] = {
     "VC_DRAFT_BF16_WGS", "VC_DRAFT_QUANT_WGS", "VC_DRAFT_MIN_TOK", "VC_DRAFT_MIN_BLK", "VC_DRAFT_FLAT",
-    "VC_VERIFY_WGS", "VC_VERIFY_MIN_TOK", "VC_VERIFY_WORKLIST", "VC_VERIFY_LIST_MIN", "VC_VERIFY_TAPER", "VC_VERIFY_QUEUE_WGS"};
+    "VC_VERIFY_WGS", "VC_VERIFY_MIN_TOK", "VC_VERIFY_WORKLIST", "VC_VERIFY_LIST_MIN", "VC_VERIFY_TAPER", "VC_VERIFY_QUEUE_WGS",
+    "VC_ACCEPT_FUSED"};
 constexpr int kUnset = INT_MIN;
 
 struct TunableTable {
@@ -104,7 +105,14 @@ extern "C" vc_status vc_create(int device, vc_ctx** out) {
     if (e != hipSuccess) st = hip_fail(e, "hipDeviceGetAttribute");
     c->n_cu = cus;
   }
+  if (st == VC_OK) {
+    const size_t bytes = sizeof(unsigned int) * vc_ctx::kAcceptCounters * vc_ctx::kAcceptSlotWords;
+    e = hipMalloc(reinterpret_cast<void**>(&c->accept_counters), bytes);
+    if (e == hipSuccess) e = hipMemset(c->accept_counters, 0, bytes);   // synchronous: done before any call
+    if (e != hipSuccess) st = hip_fail(e, "vc_create: accept counters");
+  }
   if (st != VC_OK) {
+    if (c->accept_counters) (void)hipFree(c->accept_counters);
     (void)hipStreamDestroy(c->copy_stream);
     free(c->events);
     free(c);
@@ -159,6 +167,7 @@ extern "C" vc_status vc_destroy(vc_ctx* c) {
   for (int i = 0; i < vc_ctx::kMarkRing; ++i)
     if (c->mark_events[i]) (void)hipEventDestroy(c->mark_events[i]);
   (void)hipStreamDestroy(c->copy_stream);
+  if (c->accept_counters) (void)hipFree(c->accept_counters);
   free(c->events);
   free(c);
   return VC_OK;

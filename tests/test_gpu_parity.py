@@ -213,7 +213,15 @@ def test_verify_window_of_one_equals_draft(lib, ctx):
 
 
 # ------------------------------------------------------------------ accept / keep
-def test_accept_planted_ties_bonus(lib, ctx):
+@pytest.fixture(params=[1, 0], ids=["one-launch", "two-launches"])
+def accept_launches(request, tunables):
+    """Short scans finish inside the scan launch; VC_ACCEPT_FUSED 0 forces the second launch that
+    long scans take.  Every accept case runs both ways."""
+    tunables.set("VC_ACCEPT_FUSED", request.param)
+    return request.param
+
+
+def test_accept_planted_ties_bonus(lib, ctx, accept_launches):
     lay = synth.make_layer(50, DEV, ctx_len=[8] * 6, n_q_heads=4, n_kv_heads=2, win=[5, 5, 3, 1, 64, 7], vocab=32000,
                            bonus_row=True, prefix_len=[0, 5, 2, 1, 64, 3])
     lay.logits[3, 100] = 10.0; lay.logits[3, 31999] = 10.0       # ties: lowest index must win
@@ -224,7 +232,7 @@ def test_accept_planted_ties_bonus(lib, ctx):
     assert np.array_equal(am, ram) and np.array_equal(a, ra) and np.array_equal(n, rn)
 
 
-def test_accept_signed_zero_ties_across_segments(lib, ctx):
+def test_accept_signed_zero_ties_across_segments(lib, ctx, accept_launches):
     """Row maximum 0 held by -0.0 at a low index and +0.0 in another thread / another 8192-logit
     segment (and the other way round): the lower index wins, as in the oracle."""
     lay = synth.make_layer(52, DEV, ctx_len=[8] * 2, n_q_heads=4, n_kv_heads=2, win=[3, 2], vocab=32000)
@@ -241,12 +249,26 @@ def test_accept_signed_zero_ties_across_segments(lib, ctx):
 
 
 @pytest.mark.parametrize("vocab", [128256, 32000, 1001, 7])
-def test_accept_vocab_sizes(lib, ctx, vocab):
+def test_accept_vocab_sizes(lib, ctx, vocab, accept_launches):
     lay = synth.make_layer(51, DEV, ctx_len=[8] * 5, n_q_heads=4, n_kv_heads=2, win=[4, 9, 1, 0, 33], vocab=vocab)
     a, n, am = H.gpu_accept(lib, ctx, lay)
     ra, rn, ram = H.oracle_accept(lay)
     assert np.array_equal(am, ram) and np.array_equal(a, ra) and np.array_equal(n, rn)
     assert a.tolist() == lay.prefix_len or vocab == 7
+
+
+def test_accept_many_calls_reuse_the_contexts_counters(lib, ctx):
+    """The one-launch form counts workgroups on counters the context owns, 16 sets used in turn and
+    left at zero by the call that used them: 40 calls in a row over batches of different shapes, each
+    checked against the oracle."""
+    lays = [synth.make_layer(53 + i, DEV, ctx_len=[8] * n, n_q_heads=4, n_kv_heads=2, win=win, vocab=vocab, bonus_row=bonus)
+            for i, (n, win, vocab, bonus) in enumerate([(3, [4, 1, 7], 32000, True), (1, [2], 128256, False),
+                                                        (6, [1, 0, 3, 5, 2, 64], 9000, True)])]
+    refs = [H.oracle_accept(lay) for lay in lays]
+    for i in range(40):
+        lay, (ra, rn, ram) = lays[i % 3], refs[i % 3]
+        a, n, am = H.gpu_accept(lib, ctx, lay)
+        assert np.array_equal(am, ram) and np.array_equal(a, ra) and np.array_equal(n, rn), f"call {i}"
 
 
 def test_keep_from_dropped(lib, ctx):
