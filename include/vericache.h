@@ -60,6 +60,8 @@ const char* vc_version(void);
  *   VC_DRAFT_MIN_TOK, VC_DRAFT_MIN_BLK      shortest split (tokens / block records)
  *   VC_DRAFT_FLAT                           0: ragged batches of at most 64 sequences are launched
  *                                           like larger ones (a grid over the longest sequence's splits)
+ *   VC_DRAFT_ROW_WAVES                      2 or 4 waves per workgroup of the bf16 row kernel (default: 2 for
+ *                                           ragged batches - two workgroups share a compute unit - else 4)
  *   VC_VERIFY_WGS, VC_VERIFY_MIN_TOK        workgroups a verify launch is cut for, shortest chunk
  *   VC_VERIFY_WORKLIST, VC_VERIFY_LIST_MIN, VC_VERIFY_TAPER, VC_VERIFY_QUEUE_WGS   the work-list
  *                                           launch of large ragged batches

@@ -56,7 +56,7 @@ __device__ __forceinline__ void st_stream(uint4* p, const uint4& v) {
 // library first needs one (thread safe), and can be overridden with vc_set_tunable; the hot path
 // only reads an atomic integer.  tunable() returns the set value if it lies in [lo, hi], else `dflt`.
 enum Tunable {
-  kTunDraftBf16Wgs, kTunDraftQuantWgs, kTunDraftMinTok, kTunDraftMinBlk, kTunDraftFlat,
+  kTunDraftBf16Wgs, kTunDraftQuantWgs, kTunDraftMinTok, kTunDraftMinBlk, kTunDraftFlat, kTunDraftRowWaves,
   kTunVerifyWgs, kTunVerifyMinTok, kTunVerifyWorklist, kTunVerifyListMin, kTunVerifyTaper, kTunVerifyQueueWgs,
   kTunAcceptFused,
   kNumTunables

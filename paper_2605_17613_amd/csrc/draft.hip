@@ -89,7 +89,7 @@ __device__ __forceinline__ float4v mfma16_bf16_k16(short4v a, short4v b, float4v
 // kRowsStep: tokens per step (32: the second product is one 16x16x32 per output tile; 16: one
 // 16x16x16, whose k-slots are exactly the 4 tokens a lane holds); NW: waves per workgroup.
 template <bool GATHER, int kRowsStep, int NW>
-__global__ __launch_bounds__(NW * 64, 1) void draft_bf16_kernel(DraftBf16Params p) {
+__global__ __launch_bounds__(NW * 64, 4 / NW) void draft_bf16_kernel(DraftBf16Params p) {
   constexpr int kRowsStage = kRowsStep * 512;                   // K rows then V rows
   constexpr int kRowsWaveLds = rows_wave_lds(kRowsStep);
   constexpr int NT = kRowsStep / 16;                            // 16-token score tiles per step
@@ -968,6 +968,7 @@ struct DraftPlan {
   int split_a, s1;   // bf16 pool source: tokens per split, splits of the longest sequence
   int bps, s2;       // block records: records per split, splits of the longest sequence
   bool flat_a, flat_b;   // launches that hold only the splits that exist (flat_split)
+  int row_waves;         // waves per workgroup of the row kernel (4, or 2: two workgroups per compute unit)
   int ns;
 };
 
@@ -1000,7 +1001,13 @@ static DraftPlan make_plan(const vc_comp_kv* kv) {
   auto uniform = [&](int sum, int mx) {
     return sum <= 0 || static_cast<int64_t>(mx) * kv->n_seqs * 10 <= static_cast<int64_t>(sum) * 11;
   };
-  const int target_a = tunable(kTunDraftBf16Wgs, uniform(kv->sum_keep, kv->max_keep) ? 256 : 512, 1, 1 << 20);
+  // ragged: workgroups of two waves, two per compute unit - the same rows in flight, but the launch ends
+  // in pieces half as long (config 4, 576 pieces over 16 lists of 228 ... 12710 rows: 48.2 -> 39.3 us).
+  // A uniform batch gains nothing from that (one piece per compute unit either way: 72.7 / 73.1 us) and
+  // loses when its lists are cut finer (78.6 us): fewer, longer row streams suit the memory better.
+  const bool ragged_a = !uniform(kv->sum_keep, kv->max_keep);
+  pl.row_waves = tunable(kTunDraftRowWaves, ragged_a ? 2 : 4, 2, 4) == 2 ? 2 : 4;
+  const int target_a = tunable(kTunDraftBf16Wgs, ragged_a ? 512 : 256, 1, 1 << 20);
   // (a handful of lists - one long sequence - does better with one workgroup per CU: 256 against 768 measured
   // 29.8 against 31.8 us for the record kernel and 5.4 against 7.4 us for the merge at 8 lists of 4096 records)
   const int npass_b = ceil_div(g, heads_per_pass(kv->bits, g));
@@ -1070,11 +1077,14 @@ vc_status draft_init_device() {
     VC_HIP(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
     scratch_ptr[dev].store(ptr, std::memory_order_release);
   }
-  constexpr int kLds = rows_lds(32, 4);
   VC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(draft_bf16_kernel<true, 32, 4>),
-                             hipFuncAttributeMaxDynamicSharedMemorySize, kLds));
+                             hipFuncAttributeMaxDynamicSharedMemorySize, rows_lds(32, 4)));
   VC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(draft_bf16_kernel<false, 32, 4>),
-                             hipFuncAttributeMaxDynamicSharedMemorySize, kLds));
+                             hipFuncAttributeMaxDynamicSharedMemorySize, rows_lds(32, 4)));
+  VC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(draft_bf16_kernel<true, 32, 2>),
+                             hipFuncAttributeMaxDynamicSharedMemorySize, rows_lds(32, 2)));
+  VC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(draft_bf16_kernel<false, 32, 2>),
+                             hipFuncAttributeMaxDynamicSharedMemorySize, rows_lds(32, 2)));
   return VC_OK;
 }
 
@@ -1126,10 +1136,15 @@ static vc_status draft_attn_impl(const char* who, vc_ctx* ctx, const vc_comp_kv*
     bp.n_seqs = kv->n_seqs; bp.flat = pl.flat_a;
     dim3 grid(pl.s1, kv->n_kv_heads, kv->n_seqs);
     if (pl.flat_a) grid = dim3(static_cast<unsigned>(pl.s1) * kv->n_seqs * kv->n_kv_heads, 1, 1);
-    // 32-token steps, 4 waves (16-token steps with 8 waves measured the same: the gather itself binds)
-    constexpr int kLds = rows_lds(32, 4);
-    if (kv->keep_idx) hipLaunchKernelGGL((draft_bf16_kernel<true, 32, 4>), grid, dim3(256), kLds, st, bp);
-    else hipLaunchKernelGGL((draft_bf16_kernel<false, 32, 4>), grid, dim3(256), kLds, st, bp);
+    // 32-token steps (16-token steps with 8 waves measured the same: the gather itself binds); 4 waves
+    // per workgroup, or 2 so that two workgroups share a compute unit (pl.row_waves)
+    if (pl.row_waves == 2) {
+      if (kv->keep_idx) hipLaunchKernelGGL((draft_bf16_kernel<true, 32, 2>), grid, dim3(128), rows_lds(32, 2), st, bp);
+      else hipLaunchKernelGGL((draft_bf16_kernel<false, 32, 2>), grid, dim3(128), rows_lds(32, 2), st, bp);
+    } else {
+      if (kv->keep_idx) hipLaunchKernelGGL((draft_bf16_kernel<true, 32, 4>), grid, dim3(256), rows_lds(32, 4), st, bp);
+      else hipLaunchKernelGGL((draft_bf16_kernel<false, 32, 4>), grid, dim3(256), rows_lds(32, 4), st, bp);
+    }
   }
   if (pl.s2 > 0) {
     DraftQuantParams qp{};

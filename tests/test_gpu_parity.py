@@ -55,6 +55,18 @@ def test_draft_bf16_many_splits(lib, ctx):
     check_draft(lib, ctx, lay, "gather splits", use_pool=True, use_keep=True)
 
 
+def test_draft_bf16_two_wave_workgroups(lib, ctx, tunables):
+    """The row kernel's form for ragged batches (two waves per workgroup), forced on small inputs:
+    contiguous pool, gathered rows, 16 heads per KV head."""
+    tunables.set("VC_DRAFT_ROW_WAVES", 2)
+    tunables.set("VC_DRAFT_MIN_TOK", 128)
+    lay = synth.make_layer(14, DEV, ctx_len=[700, 1, 333, 64, 65], n_q_heads=16, n_kv_heads=1)
+    check_draft(lib, ctx, lay, "two waves, contiguous", use_pool=True)
+    lay = synth.make_layer(15, DEV, ctx_len=[5000, 90], n_q_heads=8, n_kv_heads=2, keep=[3001, 33], keep_first=[64, 2],
+                           keep_last=[256, 3], tail_len=[5, 0])
+    check_draft(lib, ctx, lay, "two waves, gather", use_pool=True, use_keep=True, use_tail=True)
+
+
 # ------------------------------------------------------------------ draft, block records
 @pytest.mark.parametrize("bits", [4, 2])
 @pytest.mark.parametrize("hq,hkv", [(8, 2), (2, 2), (16, 2), (6, 2), (10, 2), (32, 2), (14, 2)])
