@@ -267,7 +267,7 @@ vc_status vc_verify_finish(vc_ctx* ctx, const vc_full_kv* kv, const int32_t* cu_
  *   accept_len  device int32 [n_seqs]: first j with draft_ids[j] != argmax(row j), else w_b
  *   next_token  device int32 [n_seqs]: argmax(row accept_len) - the correction, or the bonus
  *               token when everything matched and the bonus row exists; -1 if that row is absent
- * A short scan (up to 2048 segments of 8192 logits) is one launch whose last workgroup finishes the batch; it counts on one
+ * A short scan (up to 2048 segments of 8192 logits, up to 128 sequences) is one launch whose last workgroup finishes the batch; it counts on one
  * of 16 sets of counters the context owns (call i uses set i mod 16), so at most 16 calls made through
  * one context may be in flight, or captured in graphs that run, at the same time. */
 vc_status vc_accept_workspace_bytes(int32_t total_rows, int32_t vocab, size_t* bytes);

@@ -31,6 +31,7 @@ __device__ __forceinline__ unsigned long long make_key(float v, int idx) {
 
 constexpr int kFusedMaxRows = vc_ctx::kAcceptMaxRows;
 constexpr int kFusedMaxWgs = 2048;
+constexpr int kFusedMaxSeqs = 128;
 
 __device__ __forceinline__ int key_index(unsigned long long key) { return static_cast<int>(~static_cast<uint32_t>(key)); }
 
@@ -283,7 +284,8 @@ extern "C" vc_status vc_accept_len(vc_ctx* ctx, const float* logits, int32_t voc
   // at 36 rows of 128256 logits).  A workgroup of a fused launch ends with two trips to device-coherent
   // memory; with dozens of workgroups per compute unit those add up to more than the launch they save
   // (8448 workgroups: 57.6 against 47.3 us), so larger scans keep the finish as a launch of its own.
-  const bool fused = total_rows > 0 && total_rows <= kFusedMaxRows &&
+  // (the workgroup that finishes compares the sequences four at a time: not for batches of hundreds)
+  const bool fused = total_rows > 0 && total_rows <= kFusedMaxRows && n_seqs <= kFusedMaxSeqs &&
                      static_cast<int64_t>(total_rows) * nseg <= kFusedMaxWgs && ctx->accept_counters != nullptr &&
                      tunable(kTunAcceptFused, 1, 0, 1) != 0;
   if (fused) {
