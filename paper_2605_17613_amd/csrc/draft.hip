@@ -329,9 +329,9 @@ __global__ __launch_bounds__(NW * 64, 4 / NW) void draft_bf16_kernel(DraftBf16Pa
 //                                                  value scale of channel group `slot`
 //   The four column slots carry the four (two for int2) value channel groups, so one pass of the
 //   probabilities serves all groups and each output tile picks the slot of its own group.
-//   The zero points never touch the codes: the key zero is one extra product with an all-ones A
-//   operand (sum_d q[d]*zK[d], the same for every token of the block), the value zero likewise
-//   (sum_t p[t]*zV[t]).
+//   The zero points never touch the codes: the key zero is one extra product whose A operand is
+//   the zero points themselves in every row (sum_d zK[d]*q[d], the same for every token of the
+//   block), the value zero a product of an all-ones A operand with p[t]*zV[t].
 //   Codes reach the matrix core as fp16 1024 + f*code, built with one and-or per two codes
 //   (0x6400 is fp16 1024; f is 1, 4, 16 or 64 depending on where the field sits in its byte).
 //   1/f is folded into the operand on the other side of the product once, outside the loop, and
@@ -515,7 +515,7 @@ __global__ __launch_bounds__(256, 3) void draft_quant_kernel(DraftQuantParams p)
   // int4: token e of a word -> pair e/2 -> f = 16 if (e/2) odd;  int2: pair r = e/2, f = 4^(r&3)
   // register index i of score tile T is token 4*T' + i of the word, see below
   float m_run = -INFINITY;                    // running maximum of this column's head (log2 domain)
-  float l_part = 0.f;                         // this lane's share of sum 2^(s - m_run)
+  float4v lacc = {0.f, 0.f, 0.f, 0.f};        // sum 2^(s - m_run) of this column, in every row of the tile
   float4v oacc[8], ozero[GPS];
 #pragma unroll
   for (int dt = 0; dt < 8; ++dt) oacc[dt] = float4v{0.f, 0.f, 0.f, 0.f};
@@ -593,18 +593,18 @@ __global__ __launch_bounds__(256, 3) void draft_quant_kernel(DraftQuantParams p)
     if (it + kQuantSlots < nrec) request(it + kQuantSlots);
 
     // ---------------- scores ----------------
-    uint32_t qf[16], qz[16];
+    uint32_t qf[16];
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      qf[i] = as_u32(as_half2(qn[i]) * as_half2(ksc[i]));                            // q * sK / f
-      qz[i] = as_u32(as_half2(qnf[i]) * as_half2(kzr[i]));                           // q * zK
-    }
+    for (int i = 0; i < 16; ++i) qf[i] = as_u32(as_half2(qn[i]) * as_half2(ksc[i]));    // q * sK / f
     float4v init = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int s = 0; s < 4; ++s) {
-      const uint32_t bz[4] = {qz[4 * s], qz[4 * s + 1], qz[4 * s + 2], qz[4 * s + 3]};
+      // the key zeros are the A operand themselves (every row the same: a lane's k-slots are its channels
+      // 32j + 8s .., exactly the ones its query registers cover), so they cost no multiply
+      const uint32_t az[4] = {kzr[4 * s], kzr[4 * s + 1], kzr[4 * s + 2], kzr[4 * s + 3]};
+      const uint32_t bq[4] = {qnf[4 * s], qnf[4 * s + 1], qnf[4 * s + 2], qnf[4 * s + 3]};
       const uint32_t bf[4] = {qf[4 * s], qf[4 * s + 1], qf[4 * s + 2], qf[4 * s + 3]};
-      init = mfma16(ones, bz, init);       // + sum_d q[d] zK[d]
+      init = mfma16(az, bq, init);         // + sum_d zK[d] q[d]
       init = mfma16(m1024, bf, init);      // - 1024 * sum_d q'[d]: cancels the code offset
     }
     float4v sacc[NT];
@@ -652,7 +652,7 @@ __global__ __launch_bounds__(256, 3) void draft_quant_kernel(DraftQuantParams p)
       mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
       const float mn = fmaxf(m_run, mx);
       const float alpha = exp2_diff(m_run, mn);
-      l_part *= alpha;
+      lacc *= alpha;
 #pragma unroll
       for (int dt = 0; dt < 8; ++dt) oacc[dt] *= alpha;
 #pragma unroll
@@ -670,9 +670,7 @@ __global__ __launch_bounds__(256, 3) void draft_quant_kernel(DraftQuantParams p)
         const int T = 2 * a + (e >> 2), i = e & 3;
         const int r = (BITS == 4) ? (e >> 1) : ((8 * a + e) >> 1);
         const float lf = (BITS == 4) ? ((r & 1) ? 4.f : 0.f) : 2.f * (r & 3);     // log2 f
-        const float f = (BITS == 4) ? ((r & 1) ? 16.f : 1.f) : ((r & 3) == 0 ? 1.f : (r & 3) == 1 ? 4.f : (r & 3) == 2 ? 16.f : 64.f);
         pe[e] = __builtin_amdgcn_exp2f(sacc[T][i] - (m_run + lf));
-        l_part = fmaf(pe[e], f, l_part);
       }
 #pragma unroll
       for (int k = 0; k < 4; ++k) pb[a][k] = pack_half2(pe[2 * k], pe[2 * k + 1]);
@@ -681,19 +679,29 @@ __global__ __launch_bounds__(256, 3) void draft_quant_kernel(DraftQuantParams p)
     // ---------------- output ----------------
     uint32_t pg[NKS][GPS][4];
 #pragma unroll
-    for (int a = 0; a < NKS; ++a)
+    for (int a = 0; a < NKS; ++a) {
+      // the probabilities with their field factor undone, as rounded to fp16: the value-zero product takes
+      // them, and so does the denominator - a product with an all-ones operand sums them over the 32
+      // tokens of the k-step for every column (16 multiply-adds per lane and record otherwise)
+      uint32_t pf[4];
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        const int r = (BITS == 4) ? k : (4 * a + k);
+        pf[k] = as_u32(as_half2(pb[a][k]) * as_half2(finv[(BITS == 4) ? (r & 1) : (r & 3)]));
+      }
+      lacc = mfma16(ones, pf, lacc);
 #pragma unroll
       for (int gi = 0; gi < GPS; ++gi) {
         uint32_t pz[4];
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
-          pg[a][gi][k] = as_u32(as_half2(pb[a][k]) * as_half2(vsc[a][gi][k]));                            // p * sV / f
-          const int r = (BITS == 4) ? k : (4 * a + k);
-          pz[k] = as_u32(as_half2(pb[a][k]) * as_half2(finv[(BITS == 4) ? (r & 1) : (r & 3)]) * as_half2(vzr[a][gi][k]));   // p * zV
+          pg[a][gi][k] = as_u32(as_half2(pb[a][k]) * as_half2(vsc[a][gi][k]));   // p * sV / f
+          pz[k] = as_u32(as_half2(pf[k]) * as_half2(vzr[a][gi][k]));             // p * zV
         }
         ozero[gi] = mfma16(ones, pz, ozero[gi]);           // + sum_t p[t] zV[t][G]
         ozero[gi] = mfma16(m1024, pg[a][gi], ozero[gi]);   // - 1024 * sum_t p'[t]: cancels the code offset
       }
+    }
 #pragma unroll
     for (int c = 0; c < 2; ++c) {
 #pragma unroll
@@ -723,10 +731,8 @@ __global__ __launch_bounds__(256, 3) void draft_quant_kernel(DraftQuantParams p)
   float* st = reinterpret_cast<float*>(ring);                 // [wave][head][kPartialFloats], each wave in its own ring
   {
     float* mine = st + wave * kWaveFloats + hq * kPartialFloats;
-    // the lanes of a head agree on m_run; sum l over the row blocks j (slots are replicas)
-    float lsum = l_part;
-    lsum += __shfl_xor(lsum, 16, 64);
-    lsum += __shfl_xor(lsum, 32, 64);
+    // the lanes of a head agree on m_run; the all-ones product has summed l over all tokens (slots are replicas)
+    const float lsum = lacc[0];
     if (j == 0 && slot == 0) {
       mine[0] = m_run;
       mine[1] = lsum;
