@@ -62,6 +62,8 @@ const char* vc_version(void);
  *                                           like larger ones (a grid over the longest sequence's splits)
  *   VC_DRAFT_ROW_WAVES                      2 or 4 waves per workgroup of the bf16 row kernel (default: 2 for
  *                                           ragged batches - two workgroups share a compute unit - else 4)
+ *   VC_DRAFT_FUSED                          largest launch (workgroups) of a single-source draft call that finishes
+ *                                           inside its split kernel instead of in a merge launch (default 64; 0: none)
  *   VC_VERIFY_WGS, VC_VERIFY_MIN_TOK        workgroups a verify launch is cut for, shortest chunk
  *   VC_VERIFY_WORKLIST, VC_VERIFY_LIST_MIN, VC_VERIFY_TAPER, VC_VERIFY_QUEUE_WGS   the work-list
  *                                           launch of large ragged batches

@@ -56,7 +56,7 @@ __device__ __forceinline__ void st_stream(uint4* p, const uint4& v) {
 // library first needs one (thread safe), and can be overridden with vc_set_tunable; the hot path
 // only reads an atomic integer.  tunable() returns the set value if it lies in [lo, hi], else `dflt`.
 enum Tunable {
-  kTunDraftBf16Wgs, kTunDraftQuantWgs, kTunDraftMinTok, kTunDraftMinBlk, kTunDraftFlat, kTunDraftRowWaves,
+  kTunDraftBf16Wgs, kTunDraftQuantWgs, kTunDraftMinTok, kTunDraftMinBlk, kTunDraftFlat, kTunDraftRowWaves, kTunDraftFused,
   kTunVerifyWgs, kTunVerifyMinTok, kTunVerifyWorklist, kTunVerifyListMin, kTunVerifyTaper, kTunVerifyQueueWgs,
   kTunAcceptFused,
   kNumTunables
@@ -91,6 +91,10 @@ struct vc_ctx {
   static constexpr int kAcceptSlotWords = (1 + kAcceptMaxRows) * kAcceptCounterStride;
   unsigned int* accept_counters;
   uint64_t accept_calls;
+  // vc_draft_attn: the same for the fused finish of small launches: one counter per (sequence, KV head)
+  static constexpr int kDraftCounterSets = 16, kDraftMaxLists = 256, kDraftCounterStride = 16;
+  unsigned int* draft_counters;
+  uint64_t draft_calls;
 };
 
 namespace vc {

@@ -34,7 +34,7 @@ vc_status hip_fail(hipError_t e, const char* what) {
 
 namespace {
 const char* const kTunableNames[kNumTunables] = {
-    "VC_DRAFT_BF16_WGS", "VC_DRAFT_QUANT_WGS", "VC_DRAFT_MIN_TOK", "VC_DRAFT_MIN_BLK", "VC_DRAFT_FLAT", "VC_DRAFT_ROW_WAVES",
+    "VC_DRAFT_BF16_WGS", "VC_DRAFT_QUANT_WGS", "VC_DRAFT_MIN_TOK", "VC_DRAFT_MIN_BLK", "VC_DRAFT_FLAT", "VC_DRAFT_ROW_WAVES", "VC_DRAFT_FUSED",
     "VC_VERIFY_WGS", "VC_VERIFY_MIN_TOK", "VC_VERIFY_WORKLIST", "VC_VERIFY_LIST_MIN", "VC_VERIFY_TAPER", "VC_VERIFY_QUEUE_WGS",
     "VC_ACCEPT_FUSED"};
 constexpr int kUnset = INT_MIN;
@@ -111,8 +111,15 @@ extern "C" vc_status vc_create(int device, vc_ctx** out) {
     if (e == hipSuccess) e = hipMemset(c->accept_counters, 0, bytes);   // synchronous: done before any call
     if (e != hipSuccess) st = hip_fail(e, "vc_create: accept counters");
   }
+  if (st == VC_OK) {
+    const size_t bytes = sizeof(unsigned int) * vc_ctx::kDraftCounterSets * vc_ctx::kDraftMaxLists * vc_ctx::kDraftCounterStride;
+    e = hipMalloc(reinterpret_cast<void**>(&c->draft_counters), bytes);
+    if (e == hipSuccess) e = hipMemset(c->draft_counters, 0, bytes);
+    if (e != hipSuccess) st = hip_fail(e, "vc_create: draft counters");
+  }
   if (st != VC_OK) {
     if (c->accept_counters) (void)hipFree(c->accept_counters);
+    if (c->draft_counters) (void)hipFree(c->draft_counters);
     (void)hipStreamDestroy(c->copy_stream);
     free(c->events);
     free(c);
@@ -168,6 +175,7 @@ extern "C" vc_status vc_destroy(vc_ctx* c) {
     if (c->mark_events[i]) (void)hipEventDestroy(c->mark_events[i]);
   (void)hipStreamDestroy(c->copy_stream);
   if (c->accept_counters) (void)hipFree(c->accept_counters);
+  if (c->draft_counters) (void)hipFree(c->draft_counters);
   free(c->events);
   free(c);
   return VC_OK;

@@ -40,6 +40,64 @@ __device__ __forceinline__ bool flat_split(const int* cu, int n_seqs, int per, i
   return true;
 }
 
+struct DraftMergeParams {
+  const float* ws;
+  const uint16_t* q;
+  uint16_t* out;
+  float* lse;
+  const int* cu_a;      // bf16 source: cu_keep (gather) or cu_ctx (contiguous), or NULL
+  const int* cu_blk;    // or NULL
+  const uint16_t* tail_k;  // or NULL
+  const uint16_t* tail_v;
+  const int* cu_tail;
+  int n_q_heads, n_kv_heads, g, ns;
+  int split_a, s1, bps;
+  float scale_log2e;
+};
+
+// The merge of one (sequence, query head) by 128 threads (defined with the merge kernels below).  The split
+// kernels call it too: in a small launch the workgroup that delivers the last partial of a (sequence, KV
+// head) finishes its heads on the spot (see finish_if_last).
+template <bool COHERENT, int CHUNK>
+__device__ __forceinline__ void merge_head(const DraftMergeParams& p, int b, int h, int d, float* probs);
+
+// Fused finish of small launches.  Every workgroup of a split kernel has written its partials through to
+// device-coherent memory (the reader may sit on another XCD, behind another L2) and waited for those stores;
+// one thread then counts the workgroup on the counter of its (sequence, KV head).  The workgroup that
+// brings the count to `expected` finds every partial of the pair complete: it puts the counter back to
+// zero for the next call and merges the pair's g heads, 128 threads each, reading the
+// partials with device-coherent loads, all of a head's at once.  No fence: a release fence would write the
+// whole L2 back once per workgroup.  `lds` is the workgroup's ring, idle by now.
+struct DraftFuse {
+  unsigned int* counters;   // one per (sequence, KV head) of the launch, zero between calls; NULL: the merge is a launch of its own
+  int expected_mul;         // workgroups per split (passes of the record kernel)
+};
+__device__ __forceinline__ void st_partial(float* p, float v, bool coherent) {
+  if (coherent) __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  else *p = v;
+}
+__device__ __forceinline__ void finish_if_last(const DraftFuse& f, const DraftMergeParams& mp, int b, int kvh, int nsplits,
+                                               char* lds) {
+  __shared__ int last;
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();                              // every thread's partial stores have arrived; the ring is no longer read
+  if (threadIdx.x == 0) {
+    unsigned int* c = f.counters + (static_cast<size_t>(b) * mp.n_kv_heads + kvh) * vc_ctx::kDraftCounterStride;
+    const unsigned int expected = static_cast<unsigned int>(nsplits) * f.expected_mul;
+    last = expected <= 1u || __hip_atomic_fetch_add(c, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == expected - 1u;
+    if (last && expected > 1u) __hip_atomic_store(c, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+  __syncthreads();
+  if (!last) return;
+  float* probs = reinterpret_cast<float*>(lds) + (threadIdx.x >> 6) * 64;   // a strip of 64 floats per wave
+  const int per_pass = blockDim.x >> 7;          // heads merged at a time
+  for (int hp = 0; hp < mp.g; hp += per_pass) {
+    const int hl = hp + (threadIdx.x >> 7);
+    if (hl < mp.g) merge_head<true, 16>(mp, b, kvh * mp.g + hl, threadIdx.x & 127, probs);
+  }
+}
+
+
 // --------------------------------------------------------------------------------------------
 // bf16 rows (kept-index gather, contiguous pool, or tail)
 // --------------------------------------------------------------------------------------------
@@ -88,8 +146,10 @@ __device__ __forceinline__ float4v mfma16_bf16_k16(short4v a, short4v b, float4v
 
 // kRowsStep: tokens per step (32: the second product is one 16x16x32 per output tile; 16: one
 // 16x16x16, whose k-slots are exactly the 4 tokens a lane holds); NW: waves per workgroup.
-template <bool GATHER, int kRowsStep, int NW>
-__global__ __launch_bounds__(NW * 64, 4 / NW) void draft_bf16_kernel(DraftBf16Params p) {
+// FUSED: the instantiation for small launches, which carries the merge (finish_if_last); the plain one
+// stays free of its registers.
+template <bool GATHER, int kRowsStep, int NW, bool FUSED>
+__global__ __launch_bounds__(NW * 64, 4 / NW) void draft_bf16_kernel(DraftBf16Params p, DraftMergeParams mp, DraftFuse fz) {
   constexpr int kRowsStage = kRowsStep * 512;                   // K rows then V rows
   constexpr int kRowsWaveLds = rows_wave_lds(kRowsStep);
   constexpr int NT = kRowsStep / 16;                            // 16-token score tiles per step
@@ -105,7 +165,14 @@ __global__ __launch_bounds__(NW * 64, 4 / NW) void draft_bf16_kernel(DraftBf16Pa
   const int row0 = p.cu_rows[b];
   const int count = GATHER ? (p.cu_keep[b + 1] - p.cu_keep[b]) : (p.cu_rows[b + 1] - row0);
   const int start = sp * p.split_tok;
-  if (start >= count) return;
+  constexpr bool fused = FUSED;
+  if (start >= count) {
+    // fused: the first workgroup of a list without rows still has the list's heads to finish (tail only, or zeros)
+    if constexpr (FUSED) {
+      if (sp == 0) finish_if_last(fz, mp, b, kvh, 0, ring);
+    }
+    return;
+  }
   const int end = min(count, start + p.split_tok);
   const int* idx = GATHER ? p.keep_idx + (static_cast<size_t>(p.cu_keep[b]) * p.n_kv_heads + static_cast<size_t>(kvh) * count)
                           : nullptr;
@@ -307,12 +374,13 @@ __global__ __launch_bounds__(NW * 64, 4 / NW) void draft_bf16_kernel(DraftBf16Pa
       lsum = fmaf(a, s0[w * kWaveFloats + 1], lsum);
     }
     float* dst = p.ws + ((static_cast<size_t>(b) * p.n_q_heads + kvh * p.g + hq) * p.ns + slot) * kPartialFloats;
-    dst[2 + d] = acc;
+    st_partial(dst + 2 + d, acc, fused);
     if (d == 0) {
-      dst[0] = mm;
-      dst[1] = lsum;
+      st_partial(dst, mm, fused);
+      st_partial(dst + 1, lsum, fused);
     }
   }
+  if constexpr (FUSED) finish_if_last(fz, mp, b, kvh, ceil_div_dev(count, p.split_tok), ring);
 }
 
 // --------------------------------------------------------------------------------------------
@@ -413,8 +481,10 @@ constexpr int kQuantRingBytes = 4 * kQuantSlots * kRecordBytes;   // per workgro
 // use 4 heads x 4 slots, one slot per value channel group (int2 has two groups: slots repeat);
 // ratios of 5 to 8 use 8 heads x 2 slots so that the records are still read once for all heads -
 // for int4 a slot then carries two channel groups and scales its probabilities once per group.
-template <int BITS, int HPW>
-__global__ __launch_bounds__(256, 3) void draft_quant_kernel(DraftQuantParams p) {
+// FUSED: as for the row kernel; that instantiation runs two workgroups per CU (it is only used for launches
+// that do not fill the GPU anyway).
+template <int BITS, int HPW, bool FUSED>
+__global__ __launch_bounds__(256, FUSED ? 2 : 3) void draft_quant_kernel(DraftQuantParams p, DraftMergeParams mp, DraftFuse fz) {
   constexpr int TB = (BITS == 4) ? 32 : 64;   // tokens per block record
   constexpr int NT = TB / 16;                 // 16-token score tiles per record
   constexpr int NKS = TB / 32;                // 32-token k-steps of the output product per record
@@ -435,7 +505,14 @@ __global__ __launch_bounds__(256, 3) void draft_quant_kernel(DraftQuantParams p)
   const int kvh = yy / p.npass, pass = yy % p.npass;
   const int nb = p.cu_blk[b + 1] - p.cu_blk[b];
   const int blk0 = sp * p.bps;
-  if (blk0 >= nb) return;
+  constexpr bool fused = FUSED;
+  if (blk0 >= nb) {
+    // fused: the first workgroup of a list without records still has the list's heads to finish
+    if constexpr (FUSED) {
+      if (sp == 0 && pass == 0) finish_if_last(fz, mp, b, kvh, 0, ring);
+    }
+    return;
+  }
   const int blk1 = min(nb, blk0 + p.bps);
   const uint8_t* rec_base =
       p.blocks + (static_cast<size_t>(p.cu_blk[b]) * p.n_kv_heads + static_cast<size_t>(kvh) * nb) * kRecordBytes;
@@ -763,31 +840,18 @@ __global__ __launch_bounds__(256, 3) void draft_quant_kernel(DraftQuantParams p)
       lsum = fmaf(a, s0[w * kWaveFloats + 1], lsum);
     }
     float* dst = p.ws + ((static_cast<size_t>(b) * p.n_q_heads + kvh * p.g + hl) * p.ns + oslot) * kPartialFloats;
-    dst[2 + d] = acc;
+    st_partial(dst + 2 + d, acc, fused);
     if (d == 0) {
-      dst[0] = mm;
-      dst[1] = lsum;
+      st_partial(dst, mm, fused);
+      st_partial(dst + 1, lsum, fused);
     }
   }
+  if constexpr (FUSED) finish_if_last(fz, mp, b, kvh, ceil_div_dev(nb, p.bps), ring);
 }
 
 // --------------------------------------------------------------------------------------------
 // merge of the split partials, fused with the attention over the bf16 tail -> bf16 output (+ LSE)
 // --------------------------------------------------------------------------------------------
-struct DraftMergeParams {
-  const float* ws;
-  const uint16_t* q;
-  uint16_t* out;
-  float* lse;
-  const int* cu_a;      // bf16 source: cu_keep (gather) or cu_ctx (contiguous), or NULL
-  const int* cu_blk;    // or NULL
-  const uint16_t* tail_k;  // or NULL
-  const uint16_t* tail_v;
-  const int* cu_tail;
-  int n_q_heads, n_kv_heads, g, ns;
-  int split_a, s1, bps;
-  float scale_log2e;
-};
 
 // One workgroup of 512 threads per (sequence, query head): four groups of 128 threads; thread d of a
 // group owns output channel d.  Group k merges the splits k, k+4, ... and accumulates the tail
@@ -984,10 +1048,13 @@ __device__ __forceinline__ float dot8_bf16(const uint4& a, const uint4& b, float
   return c;
 }
 
-__global__ __launch_bounds__(128) void draft_merge_one_kernel(DraftMergeParams p) {
+// COHERENT: the partials were written by other workgroups of the launch that is still running (fused
+// finish): read them with device-coherent loads.  CHUNK: partials requested at once.  `probs`: the calling
+// wave's strip of 64 floats in LDS.
+template <bool COHERENT, int CHUNK>
+__device__ __forceinline__ void merge_head(const DraftMergeParams& p, int b, int h, int d, float* probs) {
   constexpr int kPre = 32;                       // value rows requested up front
-  const int b = blockIdx.y, h = blockIdx.x;
-  const int d = threadIdx.x, lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63;
   const int half = lane & 1, tk = lane >> 1;     // this lane scores channels 64*half .. +63 of tokens tk and 32 + tk of a chunk
   const int n1 = p.cu_a ? ceil_div_dev(p.cu_a[b + 1] - p.cu_a[b], p.split_a) : 0;
   const int n2 = p.cu_blk ? ceil_div_dev(p.cu_blk[b + 1] - p.cu_blk[b], p.bps) : 0;
@@ -999,7 +1066,6 @@ __global__ __launch_bounds__(128) void draft_merge_one_kernel(DraftMergeParams p
   }
   const int kvh = h / p.g;
   const size_t row_stride = static_cast<size_t>(p.n_kv_heads) * kHeadDim;
-  __shared__ float probs[2][64];
 
   // ---- requests for the tail first (they are consumed last) ----
   uint4 qraw[8], kraw[2][8];
@@ -1020,28 +1086,31 @@ __global__ __launch_bounds__(128) void draft_merge_one_kernel(DraftMergeParams p
     for (int i = 0; i < kPre; ++i) vpre[i] = vcol[static_cast<size_t>(min(i, nt - 1)) * row_stride];
   }
 
-  // ---- the split partials, eight at a time ----
+  // ---- the split partials, CHUNK at a time ----
   const float* base = p.ws + (static_cast<size_t>(b) * p.n_q_heads + h) * p.ns * kPartialFloats;
+  auto ld = [](const float* q) {
+    return COHERENT ? __hip_atomic_load(q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : *q;
+  };
   float mm = -INFINITY, acc = 0.f, lsum = 0.f;
-  for (int s0 = 0; s0 < nsl; s0 += 8) {
-    float m8[8], l8[8], o8[8];
+  for (int s0 = 0; s0 < nsl; s0 += CHUNK) {
+    float m8[CHUNK], l8[CHUNK], o8[CHUNK];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
+    for (int i = 0; i < CHUNK; ++i) {
       const int si = s0 + i;
       const int sl = min(si, nsl - 1);
       const float* pp = base + static_cast<size_t>(sl < n1 ? sl : p.s1 + (sl - n1)) * kPartialFloats;
-      m8[i] = si < nsl ? pp[0] : -INFINITY;
-      l8[i] = pp[1];
-      o8[i] = pp[2 + d];
+      m8[i] = si < nsl ? ld(pp) : -INFINITY;
+      l8[i] = ld(pp + 1);
+      o8[i] = ld(pp + 2 + d);
     }
     float mn = mm;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) mn = fmaxf(mn, m8[i]);
+    for (int i = 0; i < CHUNK; ++i) mn = fmaxf(mn, m8[i]);
     const float alpha = exp2_diff(mm, mn);
     acc *= alpha;
     lsum *= alpha;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
+    for (int i = 0; i < CHUNK; ++i) {
       const float a = exp2_diff(m8[i], mn);
       acc = fmaf(a, o8[i], acc);
       lsum = fmaf(a, l8[i], lsum);
@@ -1073,8 +1142,8 @@ __global__ __launch_bounds__(128) void draft_merge_one_kernel(DraftMergeParams p
     // LDS operations of one wave are carried out in order, so the reads below see these writes, and the
     // writes of the next chunk come after this chunk's reads: no barrier, the wave is alone on its strip
     if (half == 0) {
-      probs[wv][tk] = exp2_diff(sc[0], mn);
-      probs[wv][32 + tk] = exp2_diff(sc[1], mn);
+      probs[tk] = exp2_diff(sc[0], mn);
+      probs[32 + tk] = exp2_diff(sc[1], mn);
     }
     __builtin_amdgcn_wave_barrier();
     tacc *= alpha;
@@ -1083,7 +1152,7 @@ __global__ __launch_bounds__(128) void draft_merge_one_kernel(DraftMergeParams p
     if (c0 == 0) {
 #pragma unroll
       for (; i < kPre; ++i) {
-        const float pv = i < cn ? probs[wv][i] : 0.f;
+        const float pv = i < cn ? probs[i] : 0.f;
         tacc = fmaf(pv, bf16_bits_to_float(vpre[i]), tacc);
         tl += pv;
       }
@@ -1094,7 +1163,7 @@ __global__ __launch_bounds__(128) void draft_merge_one_kernel(DraftMergeParams p
       for (int k = 0; k < 8; ++k) v8[k] = vcol[static_cast<size_t>(c0 + min(i + k, cn - 1)) * row_stride];
 #pragma unroll
       for (int k = 0; k < 8; ++k) {
-        const float pv = i + k < cn ? probs[wv][i + k] : 0.f;
+        const float pv = i + k < cn ? probs[i + k] : 0.f;
         tacc = fmaf(pv, bf16_bits_to_float(v8[k]), tacc);
         tl += pv;
       }
@@ -1111,6 +1180,11 @@ __global__ __launch_bounds__(128) void draft_merge_one_kernel(DraftMergeParams p
   if (p.lse && d == 0) p.lse[static_cast<size_t>(b) * p.n_q_heads + h] = den > 0.f ? (M + log2f(den)) * kLn2 : -INFINITY;
 }
 
+__global__ __launch_bounds__(128) void draft_merge_one_kernel(DraftMergeParams p) {
+  __shared__ float probs[2][64];
+  merge_head<false, 8>(p, blockIdx.y, blockIdx.x, threadIdx.x, probs[threadIdx.x >> 6]);
+}
+
 // --------------------------------------------------------------------------------------------
 // host side
 // --------------------------------------------------------------------------------------------
@@ -1118,6 +1192,7 @@ struct DraftPlan {
   int split_a, s1;   // bf16 pool source: tokens per split, splits of the longest sequence
   int bps, s2;       // block records: records per split, splits of the longest sequence
   bool flat_a, flat_b;   // launches that hold only the splits that exist (flat_split)
+  bool fused;            // the split kernel's last workgroup per (sequence, KV head) merges: no merge launch
   int row_waves;         // waves per workgroup of the row kernel (4, or 2: two workgroups per compute unit)
   int ns;
 };
@@ -1176,6 +1251,15 @@ static DraftPlan make_plan(const vc_comp_kv* kv) {
               static_cast<int64_t>(pl.s1) * lists <= (1ll << 30);
   pl.flat_b = flat_ok && has_b && !uniform(kv->sum_blk, kv->max_blk) &&
               static_cast<int64_t>(pl.s2) * lists * npass <= (1ll << 30);
+  // A tiny launch from one source finishes inside its split kernel (finish_if_last): 13.3 -> 11.4 us per call
+  // for one sequence of 4096 tokens (16 workgroups).  From a few hundred workgroups on the merge launch is
+  // faster: every trip of the finishing workgroup to device-coherent memory (count, partials) takes about as
+  // long as a launch, and the pairs all complete at the end of the launch together (256 workgroups: 16.8 ->
+  // 17.8 us at 8 sequences x 2048 kept rows, 75.5 -> 89.4 ms for the 2048 calls of a 131072-token horizon;
+  // config 2: 3 - 15 us slower per call).
+  const int64_t wgs = has_a ? static_cast<int64_t>(pl.s1) * lists : static_cast<int64_t>(pl.s2) * lists * npass;
+  pl.fused = has_a != has_b && lists <= vc_ctx::kDraftMaxLists && wgs <= tunable(kTunDraftFused, 64, 0, 1 << 20);
+  if (pl.fused) pl.flat_a = pl.flat_b = false;   // every list needs its first workgroup, rows or not
   pl.ns = pl.s1 + pl.s2;
   if (pl.ns == 0) pl.ns = 1;
   return pl;
@@ -1219,6 +1303,27 @@ constexpr int kMaxDevices = 64;
 static std::atomic<void*> scratch_ptr[kMaxDevices];
 
 // the row kernel's ring needs more dynamic LDS than the default limit: a per-device function attribute
+// The split kernels exist in two instantiations each: with the fused finish (small launches: fz.counters
+// set) and without.
+template <bool GATHER, int NW>
+static void launch_rows(dim3 grid, hipStream_t st, const DraftBf16Params& bp, const DraftMergeParams& mp, const DraftFuse& fz) {
+  if (fz.counters) hipLaunchKernelGGL((draft_bf16_kernel<GATHER, 32, NW, true>), grid, dim3(NW * 64), rows_lds(32, NW), st, bp, mp, fz);
+  else hipLaunchKernelGGL((draft_bf16_kernel<GATHER, 32, NW, false>), grid, dim3(NW * 64), rows_lds(32, NW), st, bp, mp, fz);
+}
+template <int BITS, int HPW>
+static void launch_records(dim3 grid, hipStream_t st, const DraftQuantParams& qp, const DraftMergeParams& mp, const DraftFuse& fz) {
+  if (fz.counters) hipLaunchKernelGGL((draft_quant_kernel<BITS, HPW, true>), grid, dim3(256), kQuantRingBytes, st, qp, mp, fz);
+  else hipLaunchKernelGGL((draft_quant_kernel<BITS, HPW, false>), grid, dim3(256), kQuantRingBytes, st, qp, mp, fz);
+}
+template <bool GATHER, int NW>
+static vc_status rows_attributes() {
+  VC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(draft_bf16_kernel<GATHER, 32, NW, false>),
+                             hipFuncAttributeMaxDynamicSharedMemorySize, rows_lds(32, NW)));
+  VC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(draft_bf16_kernel<GATHER, 32, NW, true>),
+                             hipFuncAttributeMaxDynamicSharedMemorySize, rows_lds(32, NW)));
+  return VC_OK;
+}
+
 vc_status draft_init_device() {
   int dev = -1;
   VC_HIP(hipGetDevice(&dev));
@@ -1227,14 +1332,11 @@ vc_status draft_init_device() {
     VC_HIP(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
     scratch_ptr[dev].store(ptr, std::memory_order_release);
   }
-  VC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(draft_bf16_kernel<true, 32, 4>),
-                             hipFuncAttributeMaxDynamicSharedMemorySize, rows_lds(32, 4)));
-  VC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(draft_bf16_kernel<false, 32, 4>),
-                             hipFuncAttributeMaxDynamicSharedMemorySize, rows_lds(32, 4)));
-  VC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(draft_bf16_kernel<true, 32, 2>),
-                             hipFuncAttributeMaxDynamicSharedMemorySize, rows_lds(32, 2)));
-  VC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(draft_bf16_kernel<false, 32, 2>),
-                             hipFuncAttributeMaxDynamicSharedMemorySize, rows_lds(32, 2)));
+  vc_status st = rows_attributes<true, 4>();
+  if (st == VC_OK) st = rows_attributes<false, 4>();
+  if (st == VC_OK) st = rows_attributes<true, 2>();
+  if (st == VC_OK) st = rows_attributes<false, 2>();
+  if (st != VC_OK) return st;
   return VC_OK;
 }
 
@@ -1270,6 +1372,28 @@ static vc_status draft_attn_impl(const char* who, vc_ctx* ctx, const vc_comp_kv*
   const float sl2 = softmax_scale * kLog2e;
   float* ws = static_cast<float*>(workspace);
 
+  DraftMergeParams mp{};
+  mp.ws = ws;
+  mp.q = static_cast<const uint16_t*>(q);
+  mp.out = static_cast<uint16_t*>(out);
+  mp.lse = lse;
+  mp.cu_a = pl.s1 > 0 ? (kv->keep_idx ? kv->cu_keep : kv->cu_ctx) : nullptr;
+  mp.cu_blk = pl.s2 > 0 ? kv->cu_blk : nullptr;
+  const bool has_t = kv->tail_k != nullptr && kv->max_tail > 0;
+  mp.tail_k = has_t ? static_cast<const uint16_t*>(kv->tail_k) : nullptr;
+  mp.tail_v = has_t ? static_cast<const uint16_t*>(kv->tail_v) : nullptr;
+  mp.cu_tail = kv->cu_tail;
+  mp.n_q_heads = kv->n_q_heads; mp.n_kv_heads = kv->n_kv_heads; mp.g = g; mp.ns = pl.ns;
+  mp.split_a = pl.split_a; mp.s1 = pl.s1; mp.bps = pl.bps;
+  mp.scale_log2e = sl2;
+  DraftFuse fz{};
+  if (pl.fused && ctx->draft_counters != nullptr) {
+    // calls in flight at the same time (other streams, captured graphs) count on sets of their own
+    fz.counters = ctx->draft_counters + (ctx->draft_calls++ % vc_ctx::kDraftCounterSets) *
+                                            (static_cast<size_t>(vc_ctx::kDraftMaxLists) * vc_ctx::kDraftCounterStride);
+    fz.expected_mul = 1;
+  }
+
   mark_begin(ctx, st);
   if (pl.s1 > 0) {
     DraftBf16Params bp{};
@@ -1289,11 +1413,11 @@ static vc_status draft_attn_impl(const char* who, vc_ctx* ctx, const vc_comp_kv*
     // 32-token steps (16-token steps with 8 waves measured the same: the gather itself binds); 4 waves
     // per workgroup, or 2 so that two workgroups share a compute unit (pl.row_waves)
     if (pl.row_waves == 2) {
-      if (kv->keep_idx) hipLaunchKernelGGL((draft_bf16_kernel<true, 32, 2>), grid, dim3(128), rows_lds(32, 2), st, bp);
-      else hipLaunchKernelGGL((draft_bf16_kernel<false, 32, 2>), grid, dim3(128), rows_lds(32, 2), st, bp);
+      if (kv->keep_idx) launch_rows<true, 2>(grid, st, bp, mp, fz);
+      else launch_rows<false, 2>(grid, st, bp, mp, fz);
     } else {
-      if (kv->keep_idx) hipLaunchKernelGGL((draft_bf16_kernel<true, 32, 4>), grid, dim3(256), rows_lds(32, 4), st, bp);
-      else hipLaunchKernelGGL((draft_bf16_kernel<false, 32, 4>), grid, dim3(256), rows_lds(32, 4), st, bp);
+      if (kv->keep_idx) launch_rows<true, 4>(grid, st, bp, mp, fz);
+      else launch_rows<false, 4>(grid, st, bp, mp, fz);
     }
   }
   if (pl.s2 > 0) {
@@ -1308,29 +1432,20 @@ static vc_status draft_attn_impl(const char* who, vc_ctx* ctx, const vc_comp_kv*
     qp.bps = pl.bps; qp.slot0 = pl.s1; qp.ns = pl.ns;
     qp.scale_log2e = sl2;
     qp.n_seqs = kv->n_seqs; qp.flat = pl.flat_b;
+    fz.expected_mul = qp.npass;
     // flat: every sequence has at most s2 splits, all heads of a split are neighbours in the launch
     dim3 grid(pl.s2, kv->n_kv_heads * qp.npass, kv->n_seqs);
     if (pl.flat_b) grid = dim3(static_cast<unsigned>(pl.s2) * kv->n_seqs * kv->n_kv_heads * qp.npass, 1, 1);
-    if (kv->bits == 4 && hpw == 4) hipLaunchKernelGGL((draft_quant_kernel<4, 4>), grid, dim3(256), kQuantRingBytes, st, qp);
-    else if (kv->bits == 4) hipLaunchKernelGGL((draft_quant_kernel<4, 8>), grid, dim3(256), kQuantRingBytes, st, qp);
-    else if (hpw == 4) hipLaunchKernelGGL((draft_quant_kernel<2, 4>), grid, dim3(256), kQuantRingBytes, st, qp);
-    else hipLaunchKernelGGL((draft_quant_kernel<2, 8>), grid, dim3(256), kQuantRingBytes, st, qp);
+    if (kv->bits == 4 && hpw == 4) launch_records<4, 4>(grid, st, qp, mp, fz);
+    else if (kv->bits == 4) launch_records<4, 8>(grid, st, qp, mp, fz);
+    else if (hpw == 4) launch_records<2, 4>(grid, st, qp, mp, fz);
+    else launch_records<2, 8>(grid, st, qp, mp, fz);
   }
   mark_end(ctx, st);
-  DraftMergeParams mp{};
-  mp.ws = ws;
-  mp.q = static_cast<const uint16_t*>(q);
-  mp.out = static_cast<uint16_t*>(out);
-  mp.lse = lse;
-  mp.cu_a = pl.s1 > 0 ? (kv->keep_idx ? kv->cu_keep : kv->cu_ctx) : nullptr;
-  mp.cu_blk = pl.s2 > 0 ? kv->cu_blk : nullptr;
-  const bool has_t = kv->tail_k != nullptr && kv->max_tail > 0;
-  mp.tail_k = has_t ? static_cast<const uint16_t*>(kv->tail_k) : nullptr;
-  mp.tail_v = has_t ? static_cast<const uint16_t*>(kv->tail_v) : nullptr;
-  mp.cu_tail = kv->cu_tail;
-  mp.n_q_heads = kv->n_q_heads; mp.n_kv_heads = kv->n_kv_heads; mp.g = g; mp.ns = pl.ns;
-  mp.split_a = pl.split_a; mp.s1 = pl.s1; mp.bps = pl.bps;
-  mp.scale_log2e = sl2;
+  if (fz.counters != nullptr) {
+    VC_HIP(hipGetLastError());
+    return VC_OK;
+  }
   if (static_cast<int64_t>(kv->n_seqs) * kv->n_q_heads < 256)
     hipLaunchKernelGGL(draft_merge_kernel<4>, dim3(kv->n_q_heads, kv->n_seqs), dim3(512), 0, st, mp);
   else

@@ -20,6 +20,14 @@ def ctx(lib):
     c.close()
 
 
+@pytest.fixture(params=[100000, 0], ids=["finish-in-kernel", "merge-launch"])
+def draft_finish(request, tunables):
+    """Tiny single-source launches finish inside the split kernel (by default up to 64 workgroups); here
+    VC_DRAFT_FUSED makes every single-source launch do so, or none.  The draft cases run both ways."""
+    tunables.set("VC_DRAFT_FUSED", request.param)
+    return request.param
+
+
 def check_draft(lib, ctx, lay, tag, lse_tol=H.LSE_TOL, hints=None, **sel):
     kw = H.draft_kwargs(lay, **sel)
     kw.update(hints or {})      # sum_keep / sum_blk: they steer the launch shape only
@@ -36,12 +44,12 @@ def check_draft(lib, ctx, lay, tag, lse_tol=H.LSE_TOL, hints=None, **sel):
 
 # ------------------------------------------------------------------ draft, bf16 rows
 @pytest.mark.parametrize("hq,hkv", [(8, 2), (4, 4), (8, 4), (16, 2), (16, 1)])
-def test_draft_bf16_contiguous_gqa(lib, ctx, hq, hkv):
+def test_draft_bf16_contiguous_gqa(lib, ctx, hq, hkv, draft_finish):
     lay = synth.make_layer(11, DEV, ctx_len=[700, 1, 333], n_q_heads=hq, n_kv_heads=hkv)
     check_draft(lib, ctx, lay, f"bf16 g={hq // hkv}", use_pool=True)
 
 
-def test_draft_bf16_gather_ragged_with_tail_and_empty(lib, ctx):
+def test_draft_bf16_gather_ragged_with_tail_and_empty(lib, ctx, draft_finish):
     lay = synth.make_layer(12, DEV, ctx_len=[900, 70, 2000, 64], n_q_heads=8, n_kv_heads=2,
                            keep=[257, 70, 0, 5], keep_first=[4, 2, 0, 1], keep_last=[9, 3, 0, 2],
                            tail_len=[3, 0, 17, 0])
@@ -50,12 +58,12 @@ def test_draft_bf16_gather_ragged_with_tail_and_empty(lib, ctx):
     # sequence 2 keeps nothing and has no tail in the second call: out = 0, lse = -inf there
 
 
-def test_draft_bf16_many_splits(lib, ctx):
+def test_draft_bf16_many_splits(lib, ctx, draft_finish):
     lay = synth.make_layer(13, DEV, ctx_len=[5000], n_q_heads=8, n_kv_heads=2, keep=[3001], keep_first=64, keep_last=256)
     check_draft(lib, ctx, lay, "gather splits", use_pool=True, use_keep=True)
 
 
-def test_draft_bf16_two_wave_workgroups(lib, ctx, tunables):
+def test_draft_bf16_two_wave_workgroups(lib, ctx, tunables, draft_finish):
     """The row kernel's form for ragged batches (two waves per workgroup), forced on small inputs:
     contiguous pool, gathered rows, 16 heads per KV head."""
     tunables.set("VC_DRAFT_ROW_WAVES", 2)
@@ -70,7 +78,7 @@ def test_draft_bf16_two_wave_workgroups(lib, ctx, tunables):
 # ------------------------------------------------------------------ draft, block records
 @pytest.mark.parametrize("bits", [4, 2])
 @pytest.mark.parametrize("hq,hkv", [(8, 2), (2, 2), (16, 2), (6, 2), (10, 2), (32, 2), (14, 2)])
-def test_draft_quant(lib, ctx, bits, hq, hkv):
+def test_draft_quant(lib, ctx, bits, hq, hkv, draft_finish):
     tb = synth.tokens_per_block(bits)
     lay = synth.make_layer(20 + bits, DEV, ctx_len=[tb * 37, tb, tb * 8 + 5], n_q_heads=hq, n_kv_heads=hkv,
                            quant_bits=(bits,), outlier_channels=3)
@@ -78,14 +86,14 @@ def test_draft_quant(lib, ctx, bits, hq, hkv):
 
 
 @pytest.mark.parametrize("bits", [4, 2])
-def test_draft_quant_long_with_tail(lib, ctx, bits):
+def test_draft_quant_long_with_tail(lib, ctx, bits, draft_finish):
     lay = synth.make_layer(30 + bits, DEV, ctx_len=[20000 + 13, 4096], n_q_heads=8, n_kv_heads=2, quant_bits=(bits,),
                            tail_len=[63, 1])
     check_draft(lib, ctx, lay, f"int{bits} long", bits=bits, use_tail=True)
 
 
 @pytest.mark.parametrize("nseq", [2, 32])
-def test_draft_long_tails_in_both_merge_variants(lib, ctx, nseq):
+def test_draft_long_tails_in_both_merge_variants(lib, ctx, nseq, draft_finish):
     """Tails beyond 128 tokens take the merge kernel's chunk loop; a small batch runs its four-group
     variant, a batch of 256 (sequence, head) pairs the one-group variant."""
     rng = np.random.default_rng(nseq)
@@ -114,6 +122,7 @@ def test_draft_ragged_mixed_batch_with_length_hints(lib, ctx, tunables, nseq):
     lay = synth.make_layer(90 + nseq, DEV, ctx_len=lens, n_q_heads=8, n_kv_heads=2, keep=keep, keep_first=first,
                            keep_last=last, quant_bits=(4,), tail_len=[int(x) for x in rng.integers(0, 20, nseq)])
     outs = []
+    tunables.set("VC_DRAFT_FUSED", 0)            # (a launch that finishes in the kernel is never flat)
     for flat in (1, 0):
         tunables.set("VC_DRAFT_FLAT", flat)
         # small splits so that even these short lists are cut several times

@@ -3,7 +3,7 @@
 records, bf16 tail or none), verify windows, launch-shape tunables and host hints, and compares the
 draft, verify and accept entry points with the oracle.  The point is the host logic that turns such a
 batch into launches - split lengths, flat and grid launches, two- and four-wave workgroups, the
-one-launch accept, row blocks - at combinations no hand-written case lists."""
+finish inside the split kernel, the one-launch accept, row blocks - at combinations no hand-written case lists."""
 import numpy as np
 import pytest
 import torch
@@ -69,6 +69,7 @@ def test_random_batch(lib, ctx, tunables, seed):
     tunables.set("VC_VERIFY_MIN_TOK", int(rng.choice([64, 256, 1024])))
     tunables.set("VC_VERIFY_WGS", int(rng.choice([4, 64, 256])))
     tunables.set("VC_ACCEPT_FUSED", int(rng.integers(0, 2)))
+    tunables.set("VC_DRAFT_FUSED", int(rng.choice([0, 64, 512])))
     hints = bool(rng.random() < 0.7)
 
     def check(tag, hint, **sel):
