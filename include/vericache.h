@@ -150,7 +150,10 @@ typedef struct {
  *   q    device bf16 [n_seqs, n_q_heads, 128]
  *   out  device bf16 [n_seqs, n_q_heads, 128]
  *   lse  device fp32 [n_seqs, n_q_heads] or NULL: natural-log sum of exp(s_j)
- * A sequence with no keys at all gets out = 0 and lse = -inf. */
+ * A sequence with no keys at all gets out = 0 and lse = -inf.
+ * Tiny single-source calls (up to 64 workgroups, see VC_DRAFT_FUSED) are one launch that counts its
+ * workgroups on one of 16 sets of counters the context owns (call i uses set i mod 16): at most 16 such
+ * calls made through one context may be in flight, or captured in graphs that run, at the same time. */
 vc_status vc_draft_workspace_bytes(const vc_comp_kv* kv, size_t* bytes);
 vc_status vc_draft_attn(vc_ctx* ctx, const vc_comp_kv* kv, const void* q, float softmax_scale,
                         void* out, float* lse, void* workspace, size_t workspace_bytes,
