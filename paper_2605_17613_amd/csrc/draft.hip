@@ -862,8 +862,9 @@ __global__ __launch_bounds__(256, FUSED ? 2 : 3) void draft_quant_kernel(DraftQu
 // the first value rows, then eight partials at a time - and the work of a head is spread over the
 // groups so that even a single-sequence batch, whose heads each own ~100 splits, needs only a few
 // memory round trips.
-// kMergeGroups = 4 when the batch has few (sequence, head) pairs (latency is everything), 1 when it
-// has hundreds (the groups' barriers and idle lanes then cost more than they save).
+// This grouped form (kMergeGroups = 4) serves batches of few (sequence, head) pairs, where latency is
+// everything; batches of hundreds of pairs take draft_merge_one_kernel below (the groups' barriers and idle
+// lanes then cost more than they save).
 template <int kMergeGroups>
 __global__ __launch_bounds__(128 * kMergeGroups) void draft_merge_kernel(DraftMergeParams p) {
   constexpr int kTailPrefetch = 64 / kMergeGroups > 32 ? 32 : 64 / kMergeGroups;   // value rows per group requested up front
