@@ -27,7 +27,6 @@ struct QuantGeom {
   static constexpr int LEVELS = (1 << BITS) - 1;
   static constexpr int E = 32 / BITS;                // codes per 32-bit word
   static constexpr int NL = TB / 4;                  // wave loads per matrix (4 token rows each)
-  static constexpr int STAGE_ROW = TB + 16;          // bytes per channel row of the value staging tile
 };
 
 // bit position of element e of a code word
@@ -50,10 +49,20 @@ __device__ __forceinline__ void group_meta(float mn, float mx, _Float16& sh, _Fl
   inv = sf > 0.f ? __fdiv_rn(1.0f, sf) : 0.f;      // a constant group: every code 0
 }
 
+// (the conversion instruction rounds to nearest even and saturates at 0 and 255 by itself, and puts the
+// result into a byte of choice of a word: rounding, lower clamp, conversion and packing in one)
 template <int LEVELS>
-__device__ __forceinline__ uint32_t code_of(float x, float zf, float inv) {
-  const float c = fminf(fmaxf(rintf((x - zf) * inv), 0.f), static_cast<float>(LEVELS));
-  return static_cast<uint32_t>(c);
+__device__ __forceinline__ uint32_t code_into(float x, float zf, float inv, uint32_t byte, uint32_t word) {
+  return __builtin_amdgcn_cvt_pk_u8_f32(fminf((x - zf) * inv, static_cast<float>(LEVELS)), byte, word);
+}
+template <int LEVELS>
+__device__ __forceinline__ uint32_t code_of(float x, float zf, float inv) { return code_into<LEVELS>(x, zf, inv, 0u, 0u); }
+
+// Four 2-bit codes, one per byte of x -> one byte (code of byte k at bits 2k)
+__device__ __forceinline__ uint32_t squeeze2(uint32_t x) {
+  x |= x >> 6;       // bytes 0 and 2: two codes each
+  x |= x >> 12;      // byte 0: four codes
+  return x & 0xFFu;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -64,26 +73,30 @@ __device__ __forceinline__ uint32_t code_of(float x, float zf, float inv) {
 template <int BITS>
 __global__ __launch_bounds__(256) void compress_quant_kernel(QuantParams p) {
   using G = QuantGeom<BITS>;
-  constexpr int TB = G::TB, LEVELS = G::LEVELS, E = G::E, NL = G::NL, SR = G::STAGE_ROW;
-  __shared__ __attribute__((aligned(16))) uint8_t stage_all[4][kHeadDim * SR];   // value codes, [channel][token]
+  constexpr int TB = G::TB, LEVELS = G::LEVELS, NL = G::NL;
+  static_assert(G::E == NL, "a lane's NL consecutive tokens are exactly the tokens of one value code word");
+  __shared__ __attribute__((aligned(16))) uint32_t words_all[4][512];            // value code words, in record order
   __shared__ __attribute__((aligned(16))) uint16_t vmeta_all[4][256];            // value scale[g][t], zero[g][t]
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63, lg = lane >> 4, lc = lane & 15;
   const int b = blockIdx.z, kvh = blockIdx.x, blk = blockIdx.y * 4 + wave;
   const int nb = p.cu_blk[b + 1] - p.cu_blk[b];
-  const bool live = blk < nb;                        // the barriers below are reached by every wave
-  uint8_t* stage = stage_all[wave];
+  const bool live = blk < nb;                        // the barrier below is reached by every wave
+  uint32_t* words = words_all[wave];
   uint16_t* vmeta = vmeta_all[wave];
   const size_t rs = static_cast<size_t>(p.n_kv_heads) * kHeadDim;
   const size_t row0 = (static_cast<size_t>(p.cu_ctx[b]) + static_cast<size_t>(live ? blk : 0) * TB) * rs +
                       static_cast<size_t>(kvh) * kHeadDim + 8 * lc;
   uint8_t* rec = p.blocks_out + (static_cast<size_t>(p.cu_blk[b]) * p.n_kv_heads + static_cast<size_t>(kvh) * nb +
                                  (live ? blk : 0)) * kRecordBytes;
+  // Lane (lg, lc) owns channels 8*lc .. +7 of the NL consecutive tokens lg*NL .. lg*NL + NL - 1 (a wave load
+  // still fetches four whole rows).  Those tokens are the ones a value code word holds for one channel, so
+  // the lane packs its eight value words by itself; nothing is transposed through memory.
   uint4 kraw[NL], vraw[NL];
   if (live) {
 #pragma unroll
     for (int i = 0; i < NL; ++i) {
-      kraw[i] = ld_stream(reinterpret_cast<const uint4*>(p.k + row0 + static_cast<size_t>(4 * i + lg) * rs));
-      vraw[i] = ld_stream(reinterpret_cast<const uint4*>(p.v + row0 + static_cast<size_t>(4 * i + lg) * rs));
+      kraw[i] = ld_stream(reinterpret_cast<const uint4*>(p.k + row0 + static_cast<size_t>(lg * NL + i) * rs));
+      vraw[i] = ld_stream(reinterpret_cast<const uint4*>(p.v + row0 + static_cast<size_t>(lg * NL + i) * rs));
     }
     // ---- keys: one group per channel over the TB tokens
     float mn[8], mx[8];
@@ -111,28 +124,38 @@ __global__ __launch_bounds__(256) void compress_quant_kernel(QuantParams p) {
       *reinterpret_cast<uint4*>(rec + 4096 + 16 * lc) = make_uint4(sw[0], sw[1], sw[2], sw[3]);
       *reinterpret_cast<uint4*>(rec + 4352 + 16 * lc) = make_uint4(zw[0], zw[1], zw[2], zw[3]);
     }
+    // Element e of a code word sits at bit 16*(e & 1) + BITS*(e >> 1): the even elements fill the low half
+    // of the word, the odd ones the high half.  Codes are converted straight into the bytes of words that
+    // collect the even and the odd elements, and squeezed together from there - a few operations per word
+    // instead of a shift and an or per code.
 #pragma unroll
     for (int i = 0; i < NL; ++i) {
       float x[8];
       unpack8(kraw[i], x);
-      const int tk = 4 * i + lg;
-      uint32_t w = 0;
-      if (BITS == 4) {
+      const int tk = lg * NL + i;
+      uint32_t ev = 0, od = 0;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) w |= code_of<LEVELS>(x[e], zf[e], inv[e]) << field_shift<BITS>(e);
-        *reinterpret_cast<uint32_t*>(rec + tk * 64 + 4 * lc) = w;
+      for (int e = 0; e < 8; e += 2) {
+        ev = code_into<LEVELS>(x[e], zf[e], inv[e], e >> 1, ev);
+        od = code_into<LEVELS>(x[e + 1], zf[e + 1], inv[e + 1], e >> 1, od);
+      }
+      if (BITS == 4) {
+        const uint32_t te = ev | (ev >> 4), to = od | (od >> 4);   // bytes 0 and 2: two codes each
+        *reinterpret_cast<uint32_t*>(rec + tk * 64 + 4 * lc) = __builtin_amdgcn_perm(to, te, 0x06040200u);
       } else {
         // 16 channels per word: this lane holds elements 8*(lc & 1) .. +7, its neighbour the rest
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-          const uint32_t c = code_of<LEVELS>(x[e], zf[e], inv[e]);
-          w |= (lc & 1) ? c << field_shift<BITS>(8 + e) : c << field_shift<BITS>(e);
-        }
+        uint32_t w = (squeeze2(ev) | (squeeze2(od) << 16)) << (8 * (lc & 1));
         w |= __shfl_xor(w, 1, 64);
         if ((lc & 1) == 0) *reinterpret_cast<uint32_t*>(rec + tk * 32 + 4 * (lc >> 1)) = w;
       }
     }
-    // ---- values: one group per token over TB consecutive channels (TB / 8 lanes)
+    // ---- values: one group per token over TB consecutive channels (TB / 8 lanes); the codes of channel
+    // 8*lc + e over this lane's tokens collect in vev / vod [e] (even / odd tokens, four per word)
+    uint32_t vev[8][NL / 8], vod[8][NL / 8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e)
+#pragma unroll
+      for (int h = 0; h < NL / 8; ++h) { vev[e][h] = 0; vod[e][h] = 0; }
 #pragma unroll
     for (int i = 0; i < NL; ++i) {
       float x[8];
@@ -148,46 +171,41 @@ __global__ __launch_bounds__(256) void compress_quant_kernel(QuantParams p) {
       _Float16 sh, zh;
       float zfv, invv;
       group_meta<LEVELS>(lo, hi, sh, zh, zfv, invv);
-      const int tk = 4 * i + lg;
+      const int tk = lg * NL + i;
       const int grp = (8 * lc) / TB;
       if ((8 * lc) % TB == 0) {
         vmeta[grp * TB + tk] = __builtin_bit_cast(uint16_t, sh);
         vmeta[128 + grp * TB + tk] = __builtin_bit_cast(uint16_t, zh);
       }
 #pragma unroll
-      for (int e = 0; e < 8; ++e) stage[(8 * lc + e) * SR + tk] = static_cast<uint8_t>(code_of<LEVELS>(x[e], zfv, invv));
+      for (int e = 0; e < 8; ++e) {
+        if (i & 1) vod[e][i >> 3] = code_into<LEVELS>(x[e], zfv, invv, (i >> 1) & 3, vod[e][i >> 3]);
+        else vev[e][i >> 3] = code_into<LEVELS>(x[e], zfv, invv, (i >> 1) & 3, vev[e][i >> 3]);
+      }
+    }
+    // value code words: word W = 4 * slot + q, slot = 64c + 16j + n, holds channel 64c + 16q + n of the
+    // tokens E*j .. E*j + E - 1 - here j = lg
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const int ch = 8 * lc + e;
+      const int W = 4 * (64 * (ch >> 6) + 16 * lg + (ch & 15)) + ((ch >> 4) & 3);
+      uint32_t w;
+      if (BITS == 4) {
+        const uint32_t te = vev[e][0] | (vev[e][0] >> 4), to = vod[e][0] | (vod[e][0] >> 4);
+        w = __builtin_amdgcn_perm(to, te, 0x06040200u);
+      } else {
+        w = (squeeze2(vev[e][0]) | (squeeze2(vev[e][NL / 8 - 1]) << 8)) |
+            ((squeeze2(vod[e][0]) | (squeeze2(vod[e][NL / 8 - 1]) << 8)) << 16);
+      }
+      words[W] = w;
     }
   }
   __syncthreads();
   if (live) {
-    // value code words: word W = 4 * slot + q, slot = 64c + 16j + n, channel 64c + 16q + n,
-    // tokens E*j .. E*j+E-1, which are E consecutive bytes of the staging tile
+    // the 2048 bytes of value code words and the 512 bytes of value scales / zeros leave as 16-byte stores
 #pragma unroll
-    for (int m = 0; m < 8; ++m) {
-      const int W = 64 * m + lane;
-      const int slot = W >> 2, q = W & 3;
-      const int c = slot >> 6, j = (slot >> 4) & 3, n = slot & 15;
-      const uint8_t* src = stage + (64 * c + 16 * q + n) * SR + E * j;
-      uint32_t w = 0;
-      if (BITS == 4) {
-        const uint2 by = *reinterpret_cast<const uint2*>(src);
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          w |= ((by.x >> (8 * e)) & 0xFFu) << field_shift<BITS>(e);
-          w |= ((by.y >> (8 * e)) & 0xFFu) << field_shift<BITS>(4 + e);
-        }
-      } else {
-        const uint4 by = *reinterpret_cast<const uint4*>(src);
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          w |= ((by.x >> (8 * e)) & 0xFFu) << field_shift<BITS>(e);
-          w |= ((by.y >> (8 * e)) & 0xFFu) << field_shift<BITS>(4 + e);
-          w |= ((by.z >> (8 * e)) & 0xFFu) << field_shift<BITS>(8 + e);
-          w |= ((by.w >> (8 * e)) & 0xFFu) << field_shift<BITS>(12 + e);
-        }
-      }
-      *reinterpret_cast<uint32_t*>(rec + 2048 + 4 * W) = w;
-    }
+    for (int m = 0; m < 2; ++m)
+      *reinterpret_cast<uint4*>(rec + 2048 + 16 * (64 * m + lane)) = *reinterpret_cast<const uint4*>(words + 4 * (64 * m + lane));
     *reinterpret_cast<uint2*>(rec + 4608 + 8 * lane) = *reinterpret_cast<const uint2*>(vmeta + 4 * lane);
   }
 }
