@@ -85,14 +85,26 @@ __global__ __launch_bounds__(kAcceptThreads) void argmax_segment_kernel(const fl
   if (vec_ok) {
     const int nvec = (seg1 - seg0) >> 2;
     const float4* b4 = reinterpret_cast<const float4*>(base + seg0);
-    for (int i = threadIdx.x; i < nvec; i += kAcceptThreads) {
-      float4 x = ld_stream(b4 + i);
-      int e = seg0 + 4 * i;
-      // ascending index order inside a thread, strict '>' keeps the first of equal values
-      if (x.x > best || bidx == 0x7fffffff) { best = x.x; bidx = e; }
-      if (x.y > best) { best = x.y; bidx = e + 1; }
-      if (x.z > best) { best = x.z; bidx = e + 2; }
-      if (x.w > best) { best = x.w; bidx = e + 3; }
+    // a segment is at most kSegElems / 4 = 8 vectors per thread: all requested before the first compare
+    constexpr int kVecPerThread = kSegElems / 4 / kAcceptThreads;
+    float4 xs[kVecPerThread];
+#pragma unroll
+    for (int u = 0; u < kVecPerThread; ++u) {
+      const int i = threadIdx.x + u * kAcceptThreads;
+      xs[u] = i < nvec ? ld_stream(b4 + i) : make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
+    }
+#pragma unroll
+    for (int u = 0; u < kVecPerThread; ++u) {
+      const int i = threadIdx.x + u * kAcceptThreads;
+      if (i < nvec) {
+        const float4 x = xs[u];
+        const int e = seg0 + 4 * i;
+        // ascending index order inside a thread, strict '>' keeps the first of equal values
+        if (x.x > best || bidx == 0x7fffffff) { best = x.x; bidx = e; }
+        if (x.y > best) { best = x.y; bidx = e + 1; }
+        if (x.z > best) { best = x.z; bidx = e + 2; }
+        if (x.w > best) { best = x.w; bidx = e + 3; }
+      }
     }
     for (int e = seg0 + 4 * nvec + threadIdx.x; e < seg1; e += kAcceptThreads) {
       float x = ld_stream(base + e);
