@@ -9,7 +9,9 @@
  *     frees nor keeps it beyond the call (vc_swap_in keeps src/dst until the tickets complete).
  *   - Scratch memory is a caller-provided device workspace, sized by the *_workspace_bytes query.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Calls enqueue work
- *     and return; they never synchronise the device and never allocate device memory.
+ *     and return; they never synchronise the device and never allocate device memory (vc_create
+ *     alone allocates: the context's counter arrays, about 2.3 MB, freed by vc_destroy).
+ *   - A context is used by one host thread at a time; contexts are independent of each other.
  *   - Errors are return codes; vc_last_error() gives a message for the last failing call on the
  *     calling thread.  Arguments are validated on the host in O(1) (null pointers, 16-byte
  *     alignment, head_dim == 128, group geometry); data-dependent contents (index ranges,
@@ -41,7 +43,8 @@ typedef enum {
   VC_ERR_NOT_READY = 5     /* vc_swap_query: the ticket's copy has not finished yet           */
 } vc_status;
 
-typedef struct vc_ctx vc_ctx; /* opaque: owns one copy stream and the chunk events, nothing else */
+typedef struct vc_ctx vc_ctx; /* opaque: owns one copy stream, the chunk and mark events, and the counter
+                                 arrays of the one-launch forms of vc_accept_len and vc_draft_attn */
 
 /* Create / destroy a context bound to HIP device `device`. */
 vc_status vc_create(int device, vc_ctx** out);
