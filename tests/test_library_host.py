@@ -149,3 +149,44 @@ def test_tunables_are_a_process_table_not_the_environment(monkeypatch):
         vc.vc_set_tunable("VC_NO_SUCH_THING", 1)
     assert lib.vc_stream_status(None, None) == B.VC_ERR_INVALID_ARG
     assert lib.vc_validate_comp_kv(None, None, None, None) == B.VC_ERR_INVALID_ARG
+
+
+def test_every_documented_tunable_is_known_and_the_reverse():
+    """The header's tunable list and the library's name table are the same set: every VC_* name in the
+    header's tunable comment can be set and read back, and no other VC_DRAFT_ / VC_VERIFY_ / VC_ACCEPT_
+    name is accepted."""
+    import re
+    text = open(os.path.join(ROOT, "include", "vericache.h")).read()
+    block = text[text.index("Launch-shape tunables"):text.index("vc_status vc_set_tunable")]
+    names = sorted(set(re.findall(r"VC_(?:DRAFT|VERIFY|ACCEPT)_[A-Z0-9_]+", block)))
+    assert len(names) >= 14, names
+    for n in names:
+        assert vc.vc_get_tunable(n) is None, n
+        vc.vc_set_tunable(n, 3)
+        assert vc.vc_get_tunable(n) == 3, n
+        vc.vc_set_tunable(n, -1)
+        assert vc.vc_get_tunable(n) is None, n
+    for bogus in ("VC_DRAFT_TAPER", "VC_DRAFT_", "VC_VERIFY_WGS2", "vc_draft_flat", ""):
+        with pytest.raises(vc.VcError):
+            vc.vc_set_tunable(bogus, 1)
+
+
+def test_draft_plan_reacts_to_its_launch_shape_tunables():
+    """The workspace of a draft call holds one partial per split: cutting a launch for more workgroups,
+    or allowing shorter splits, must grow it, and the defaults must come back afterwards."""
+    def ws(**kw):
+        d = B.vc_comp_kv()
+        d.n_seqs, d.n_q_heads, d.n_kv_heads, d.head_dim = 16, 32, 8, 128
+        d.bits, d.blocks, d.cu_blk, d.max_blk, d.sum_blk = 4, 0x1000, 0x2000, 2048, 16 * 2048
+        n = C.c_size_t()
+        assert vc.load().vc_draft_workspace_bytes(C.byref(d), C.byref(n)) == B.VC_OK
+        return n.value
+    base = ws()
+    try:
+        vc.vc_set_tunable("VC_DRAFT_QUANT_WGS", 3072)
+        assert ws() > base
+        vc.vc_set_tunable("VC_DRAFT_QUANT_WGS", 128)
+        assert ws() < base
+    finally:
+        vc.vc_set_tunable("VC_DRAFT_QUANT_WGS", -1)
+    assert ws() == base
