@@ -84,3 +84,45 @@ def test_captured_draft_and_verify_replays_equal_eager(lib, ctx):
         assert torch.equal(vout.view(torch.int16), want[2].view(torch.int16)), rep
         assert torch.equal(out_b.view(torch.int16), want[3].view(torch.int16)), rep
         assert torch.isfinite(scratch)
+
+
+def test_captured_accept_replays_equal_eager(lib, ctx):
+    """The one-launch accept counts its workgroups on counters of the context that it leaves at zero:
+    a captured call is replayed with eager calls (which use other counter sets, and after 16 of them the
+    same one) in between, drafted ids changed in place."""
+    dev = "cuda:0"
+    lay = synth.make_layer(synth.SEED_BASE + 92, dev, ctx_len=[8] * 4, n_q_heads=4, n_kv_heads=2, win=[5, 1, 9, 3],
+                           vocab=32000, bonus_row=True, prefix_len=[5, 0, 4, 3])
+    nseq, rows = 4, lay.logits.shape[0]
+    ids = lay.draft_ids.clone()
+    acc, nxt = (torch.full((nseq,), -7, dtype=torch.int32, device=dev) for _ in range(2))
+    amax = torch.full((rows,), -7, dtype=torch.int32, device=dev)
+    ws = torch.empty(max(vc.vc_accept_workspace_bytes(rows, 32000), 16), dtype=torch.uint8, device=dev)
+
+    def step():
+        vc.vc_accept_len(ctx, lay.logits, lay.cu_rows, ids, lay.cu_win, acc, nxt, amax, workspace=ws)
+
+    step()
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            step()
+    torch.cuda.synchronize()
+    g = torch.Generator(device=dev)
+    g.manual_seed(3)
+    for rep in range(4):
+        ids.copy_(lay.draft_ids)
+        if rep:
+            flip = torch.randint(0, ids.numel(), (2,), generator=g, device=dev)
+            ids[flip] += 1                                       # a mismatch somewhere else every time
+        for _ in range(5 + 6 * rep):                             # eager calls walk through the counter sets
+            step()
+        torch.cuda.synchronize()
+        want = (acc.clone(), nxt.clone(), amax.clone())
+        acc.fill_(-7); nxt.fill_(-7); amax.fill_(-7)
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(acc, want[0]) and torch.equal(nxt, want[1]) and torch.equal(amax, want[2]), rep
+    assert acc.tolist() != [-7] * nseq
