@@ -400,10 +400,11 @@ __global__ __launch_bounds__(NW * 64, 4 / NW) void draft_bf16_kernel(DraftBf16Pa
 //   The zero points never touch the codes: the key zero is one extra product whose A operand is
 //   the zero points themselves in every row (sum_d zK[d]*q[d], the same for every token of the
 //   block), the value zero a product of an all-ones A operand with p[t]*zV[t].
-//   Codes reach the matrix core as fp16 1024 + f*code, built with one and-or per two codes
-//   (0x6400 is fp16 1024; f is 1, 4, 16 or 64 depending on where the field sits in its byte).
-//   1/f is folded into the operand on the other side of the product once, outside the loop, and
-//   the 1024 offset is cancelled by a product with a constant -1024 A operand.
+//   Codes reach the matrix core as the fp16 subnormals 2^-24 * f * code that their masked bit fields
+//   already are, one and per two codes (f is 1, 4, 16 or 64 depending on where the field sits in
+//   its byte).  1/f is folded into the operand on the other side of the product once, outside the
+//   loop; 2^24 is applied to the fp32 results (inside the multiply-add that forms the exponent for
+//   the scores, once per split for the outputs).
 struct DraftQuantParams {
   const uint16_t* q;
   const uint8_t* blocks;
@@ -429,30 +430,34 @@ __device__ __forceinline__ uint32_t pack_half2(float a, float b) {
   return as_u32(h);
 }
 
-// (x & mask) | magic in one VALU op; magic lives in a VGPR so that only one literal is needed
-__device__ __forceinline__ uint32_t and_or(uint32_t x, uint32_t mask, uint32_t magic) { return (x & mask) | magic; }
+// A code field masked out of its word IS an fp16 number: a subnormal (or, from mantissa bit 10 on, nothing
+// we use) whose value is 2^-24 * f * code, f = 2^(position of the field in its 16-bit half).  The matrix
+// core takes fp16 subnormals exactly (checked on the device: sums of products of such operands come out to
+// the last bit), so one v_and_b32 per two codes is the whole dequantisation: f is folded into the operand on
+// the other side of the product outside the loop, 2^24 into the fp32 results.
+constexpr float kCodeScale = 16777216.f;   // 2^24
 
 // Eight 4-bit codes of one word (element e at bit 16*(e&1) + 4*(e>>1)) -> four fp16 pairs in element
-// order holding 1024 + code (pairs 0, 2) or 1024 + 16*code (pairs 1, 3).
-__device__ __forceinline__ void unpack_i4(uint32_t x, uint32_t magic, uint32_t (&out)[4]) {
+// order holding 2^-24 * code (pairs 0, 2) or 2^-24 * 16 * code (pairs 1, 3).
+__device__ __forceinline__ void unpack_i4(uint32_t x, uint32_t (&out)[4]) {
   const uint32_t y = x >> 8;
-  out[0] = and_or(x, 0x000F000Fu, magic);
-  out[1] = and_or(x, 0x00F000F0u, magic);
-  out[2] = and_or(y, 0x000F000Fu, magic);
-  out[3] = and_or(y, 0x00F000F0u, magic);
+  out[0] = x & 0x000F000Fu;
+  out[1] = x & 0x00F000F0u;
+  out[2] = y & 0x000F000Fu;
+  out[3] = y & 0x00F000F0u;
 }
 // Sixteen 2-bit codes (element e at bit 16*(e&1) + 2*(e>>1)) -> eight fp16 pairs holding
-// 1024 + 4^(r&3) * code for pair r.
-__device__ __forceinline__ void unpack_i2(uint32_t x, uint32_t magic, uint32_t (&out)[8]) {
+// 2^-24 * 4^(r&3) * code for pair r.
+__device__ __forceinline__ void unpack_i2(uint32_t x, uint32_t (&out)[8]) {
   const uint32_t y = x >> 8;
-  out[0] = and_or(x, 0x00030003u, magic);
-  out[1] = and_or(x, 0x000C000Cu, magic);
-  out[2] = and_or(x, 0x00300030u, magic);
-  out[3] = and_or(x, 0x00C000C0u, magic);
-  out[4] = and_or(y, 0x00030003u, magic);
-  out[5] = and_or(y, 0x000C000Cu, magic);
-  out[6] = and_or(y, 0x00300030u, magic);
-  out[7] = and_or(y, 0x00C000C0u, magic);
+  out[0] = x & 0x00030003u;
+  out[1] = x & 0x000C000Cu;
+  out[2] = x & 0x00300030u;
+  out[3] = x & 0x00C000C0u;
+  out[4] = y & 0x00030003u;
+  out[5] = y & 0x000C000Cu;
+  out[6] = y & 0x00300030u;
+  out[7] = y & 0x00C000C0u;
 }
 
 __device__ __forceinline__ float4v mfma16(const uint32_t (&a)[4], const uint32_t (&b)[4], float4v c) {
@@ -556,9 +561,6 @@ __global__ __launch_bounds__(256, FUSED ? 2 : 3) void draft_quant_kernel(DraftQu
   const int hloc = pass * HPW + hq;
   const bool head_ok = hloc < p.g;
 
-  uint32_t magic = 0x64006400u;
-  asm volatile("" : "+v"(magic));             // keep it in a VGPR (see and_or)
-
   // query as B operand of the score product: channels 32j .. 32j+31 in natural fp16 pairs, with the
   // softmax scale, log2(e) and the 1/f of the code field each channel meets folded in
   uint32_t qn[16];
@@ -586,7 +588,6 @@ __global__ __launch_bounds__(256, FUSED ? 2 : 3) void draft_quant_kernel(DraftQu
     finv[k] = pack_half2(f, f);
   }
   const uint32_t ones[4] = {0x3C003C00u, 0x3C003C00u, 0x3C003C00u, 0x3C003C00u};      // fp16 1.0
-  const uint32_t m1024[4] = {0xE400E400u, 0xE400E400u, 0xE400E400u, 0xE400E400u};     // fp16 -1024.0
 
   // log2 of the field factor f of each probability register (token position inside its word)
   // int4: token e of a word -> pair e/2 -> f = 16 if (e/2) odd;  int2: pair r = e/2, f = 4^(r&3)
@@ -680,19 +681,17 @@ __global__ __launch_bounds__(256, FUSED ? 2 : 3) void draft_quant_kernel(DraftQu
       // 32j + 8s .., exactly the ones its query registers cover), so they cost no multiply
       const uint32_t az[4] = {kzr[4 * s], kzr[4 * s + 1], kzr[4 * s + 2], kzr[4 * s + 3]};
       const uint32_t bq[4] = {qnf[4 * s], qnf[4 * s + 1], qnf[4 * s + 2], qnf[4 * s + 3]};
-      const uint32_t bf[4] = {qf[4 * s], qf[4 * s + 1], qf[4 * s + 2], qf[4 * s + 3]};
-      init = mfma16(az, bq, init);         // + sum_d zK[d] q[d]
-      init = mfma16(m1024, bf, init);      // - 1024 * sum_d q'[d]: cancels the code offset
+      init = mfma16(az, bq, init);         // sum_d zK[d] q[d]: the zero-point part of every score of the record
     }
     float4v sacc[NT];
 #pragma unroll
     for (int T = 0; T < NT; ++T) {
-      float4v acc = init;
+      float4v acc = {0.f, 0.f, 0.f, 0.f};     // 2^-24 * the code part of the scores
       if constexpr (BITS == 4) {
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
           uint32_t ka[4];
-          unpack_i4(kw[T][s], magic, ka);
+          unpack_i4(kw[T][s], ka);
           const uint32_t bf[4] = {qf[4 * s], qf[4 * s + 1], qf[4 * s + 2], qf[4 * s + 3]};
           acc = mfma16(ka, bf, acc);
         }
@@ -700,7 +699,7 @@ __global__ __launch_bounds__(256, FUSED ? 2 : 3) void draft_quant_kernel(DraftQu
 #pragma unroll
         for (int h2 = 0; h2 < 2; ++h2) {
           uint32_t k8[8];
-          unpack_i2(kw[T][h2], magic, k8);
+          unpack_i2(kw[T][h2], k8);
 #pragma unroll
           for (int a2 = 0; a2 < 2; ++a2) {
             const int s = 2 * h2 + a2;
@@ -715,11 +714,13 @@ __global__ __launch_bounds__(256, FUSED ? 2 : 3) void draft_quant_kernel(DraftQu
     // lane (n, j) now holds, for column n, register i of tile T = token (TB/4)*j + 4T + i
 
     // ---------------- softmax with a lazily updated maximum ----------------
+    const float zpart = init[0];              // (every row of the tile holds the same sum)
     float smax = sacc[0][0];
 #pragma unroll
     for (int T = 0; T < NT; ++T)
 #pragma unroll
       for (int i = 0; i < 4; ++i) smax = fmaxf(smax, sacc[T][i]);
+    smax = fmaf(smax, kCodeScale, zpart);      // the largest score of this lane
     if (__any(smax > m_run + kLazyMargin)) {
       // agree on the new maximum among the lanes of this head (all slots, all row blocks)
       float mx = smax;
@@ -747,7 +748,7 @@ __global__ __launch_bounds__(256, FUSED ? 2 : 3) void draft_quant_kernel(DraftQu
         const int T = 2 * a + (e >> 2), i = e & 3;
         const int r = (BITS == 4) ? (e >> 1) : ((8 * a + e) >> 1);
         const float lf = (BITS == 4) ? ((r & 1) ? 4.f : 0.f) : 2.f * (r & 3);     // log2 f
-        pe[e] = __builtin_amdgcn_exp2f(sacc[T][i] - (m_run + lf));
+        pe[e] = __builtin_amdgcn_exp2f(fmaf(sacc[T][i], kCodeScale, zpart - (m_run + lf)));
       }
 #pragma unroll
       for (int k = 0; k < 4; ++k) pb[a][k] = pack_half2(pe[2 * k], pe[2 * k + 1]);
@@ -775,8 +776,7 @@ __global__ __launch_bounds__(256, FUSED ? 2 : 3) void draft_quant_kernel(DraftQu
           pg[a][gi][k] = as_u32(as_half2(pb[a][k]) * as_half2(vsc[a][gi][k]));   // p * sV / f
           pz[k] = as_u32(as_half2(pf[k]) * as_half2(vzr[a][gi][k]));             // p * zV
         }
-        ozero[gi] = mfma16(ones, pz, ozero[gi]);           // + sum_t p[t] zV[t][G]
-        ozero[gi] = mfma16(m1024, pg[a][gi], ozero[gi]);   // - 1024 * sum_t p'[t]: cancels the code offset
+        ozero[gi] = mfma16(ones, pz, ozero[gi]);           // sum_t p[t] zV[t][G]
       }
     }
 #pragma unroll
@@ -787,11 +787,11 @@ __global__ __launch_bounds__(256, FUSED ? 2 : 3) void draft_quant_kernel(DraftQu
         const int gi = index_in_slot(dt / TPG);   // which of its groups a column uses for this tile
         if constexpr (BITS == 4) {
           uint32_t va[4];
-          unpack_i4(vsl[c][qq], magic, va);
+          unpack_i4(vsl[c][qq], va);
           oacc[dt] = mfma16(va, pg[0][gi], oacc[dt]);
         } else {
           uint32_t v8[8];
-          unpack_i2(vsl[c][qq], magic, v8);
+          unpack_i2(vsl[c][qq], v8);
 #pragma unroll
           for (int a = 0; a < NKS; ++a) {
             const uint32_t va[4] = {v8[4 * a], v8[4 * a + 1], v8[4 * a + 2], v8[4 * a + 3]};
@@ -820,7 +820,7 @@ __global__ __launch_bounds__(256, FUSED ? 2 : 3) void draft_quant_kernel(DraftQu
       const int Gd = dt / TPG;
       if (slot == slot_of(Gd)) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) mine[2 + 16 * dt + 4 * j + i] = oacc[dt][i] + ozero[index_in_slot(Gd)][i];
+        for (int i = 0; i < 4; ++i) mine[2 + 16 * dt + 4 * j + i] = fmaf(oacc[dt][i], kCodeScale, ozero[index_in_slot(Gd)][i]);
       }
     }
   }
