@@ -67,6 +67,8 @@ const char* vc_version(void);
  *                                           ragged batches - two workgroups share a compute unit - else 4)
  *   VC_DRAFT_FUSED                          largest launch (workgroups) of a single-source draft call that finishes
  *                                           inside its split kernel instead of in a merge launch (default 64; 0: none)
+ *   VC_DRAFT_TAIL_SPLIT                     0: the merge launch attends to the bf16 tail itself (default 1: workgroups
+ *                                           of the split launch do, and hand the merge one more partial)
  *   VC_VERIFY_WGS, VC_VERIFY_MIN_TOK        workgroups a verify launch is cut for, shortest chunk
  *   VC_VERIFY_WORKLIST, VC_VERIFY_LIST_MIN, VC_VERIFY_TAPER, VC_VERIFY_QUEUE_WGS   the work-list
  *                                           launch of large ragged batches

@@ -57,6 +57,7 @@ __device__ __forceinline__ void st_stream(uint4* p, const uint4& v) {
 // only reads an atomic integer.  tunable() returns the set value if it lies in [lo, hi], else `dflt`.
 enum Tunable {
   kTunDraftBf16Wgs, kTunDraftQuantWgs, kTunDraftMinTok, kTunDraftMinBlk, kTunDraftFlat, kTunDraftRowWaves, kTunDraftFused,
+  kTunDraftTailSplit,
   kTunVerifyWgs, kTunVerifyMinTok, kTunVerifyWorklist, kTunVerifyListMin, kTunVerifyTaper, kTunVerifyQueueWgs,
   kTunAcceptFused,
   kNumTunables

@@ -35,6 +35,7 @@ vc_status hip_fail(hipError_t e, const char* what) {
 namespace {
 const char* const kTunableNames[kNumTunables] = {
     "VC_DRAFT_BF16_WGS", "VC_DRAFT_QUANT_WGS", "VC_DRAFT_MIN_TOK", "VC_DRAFT_MIN_BLK", "VC_DRAFT_FLAT", "VC_DRAFT_ROW_WAVES", "VC_DRAFT_FUSED",
+    "VC_DRAFT_TAIL_SPLIT",
     "VC_VERIFY_WGS", "VC_VERIFY_MIN_TOK", "VC_VERIFY_WORKLIST", "VC_VERIFY_LIST_MIN", "VC_VERIFY_TAPER", "VC_VERIFY_QUEUE_WGS",
     "VC_ACCEPT_FUSED"};
 constexpr int kUnset = INT_MIN;

@@ -2,10 +2,11 @@
 // step 1; section 4.2.1: the step is bounded by HBM bandwidth, so every kernel here streams its
 // source exactly once with 128-bit loads and does the arithmetic in registers).
 //
-// Three sources (retained bf16 rows, int4/int2 block records, bf16 tail) are each cut into splits
-// over their tokens; one workgroup turns one split of one (sequence, KV head) into a partial
-// (m, l, O) for the g query heads of that KV head (GQA packing: K/V are read once for all of them)
-// and a merge kernel combines the partials of all sources.
+// Two sources (retained bf16 rows, int4/int2 block records) are each cut into splits over their
+// tokens; one workgroup turns one split of one (sequence, KV head) into a partial (m, l, O) for the
+// g query heads of that KV head (GQA packing: K/V are read once for all of them).  The short bf16
+// tail is one more partial, made by extra workgroups of the same launch, and a merge kernel
+// combines the partials of all sources.
 #include <atomic>
 
 #include "attn_common.h"
@@ -18,7 +19,7 @@ namespace vc {
 // the split count of sequence i, a prefix sum over the lanes, one ballot - so a ragged batch launches
 // no workgroup per (sequence, split of the longest sequence) that finds nothing to do.  `cu` holds
 // the n_seqs + 1 prefix sums of the units (rows or records), `per` the units per split.  Returns
-// false when x is beyond the last split.
+// false when x is beyond the last split, with `b` = how far beyond (0 for the first such x).
 __device__ __forceinline__ bool flat_split(const int* cu, int n_seqs, int per, int x, int& b, int& sp) {
   const int lane = threadIdx.x & 63;
   int cnt = 0;
@@ -33,7 +34,10 @@ __device__ __forceinline__ bool flat_split(const int* cu, int n_seqs, int per, i
     if (lane >= d) scan += t;
   }
   const unsigned long long hit = __ballot(scan > x);
-  if (hit == 0ull) return false;
+  if (hit == 0ull) {
+    b = x - __builtin_amdgcn_readfirstlane(__shfl(scan, 63));
+    return false;
+  }
   const int l = __ffsll(hit) - 1;
   b = __builtin_amdgcn_readfirstlane(l);
   sp = __builtin_amdgcn_readfirstlane(x - (__shfl(scan, l) - __shfl(cnt, l)));
@@ -52,6 +56,7 @@ struct DraftMergeParams {
   const int* cu_tail;
   int n_q_heads, n_kv_heads, g, ns;
   int split_a, s1, bps;
+  int tail_slot;        // >= 0: the tail's partial sits in this slot (tail_partial, run by workgroups of the split launch)
   float scale_log2e;
 };
 
@@ -97,6 +102,112 @@ __device__ __forceinline__ void finish_if_last(const DraftFuse& f, const DraftMe
   }
 }
 
+// The bf16 tail as one more partial.  In launches that keep the merge as a launch of its own, the split
+// kernel carries one extra workgroup per (sequence, KV head) that attends the pair's g query heads over the
+// tail tokens and writes (m, l, O) into slot `tail_slot`; the merge then only combines partials.  The tail
+// work runs beside the splits instead of behind them (a merge that also scores the tail takes 6 us, one that
+// does not 4 us).  One wave per head at a time: two lanes per token for the scores (64 channels each, packed
+// bf16 dot products against the query row), maximum and exponentials inside the wave, probabilities through
+// the wave's own strip of LDS, and every lane accumulates output channels 2*lane and 2*lane + 1.
+__device__ __forceinline__ float dot8_bf16(const uint4& a, const uint4& b, float c);
+struct TailLane {          // what a lane needs to address the tail of (sequence b, KV head kvh)
+  const uint16_t* kcol;    // its 64 channels of the first tail key row
+  const uint16_t* vcol;    // its two channels of the first tail value row
+  size_t row_stride;
+  float* probs;            // the wave's strip of 32 floats in LDS
+  int nt, half, tk;
+};
+struct TailChunk {         // one chunk of 32 tokens as it comes from memory
+  uint4 k[8];
+  uint32_t v[32];
+};
+__device__ __forceinline__ TailLane tail_lane(const DraftMergeParams& p, int b, int kvh, float* probs_lds) {
+  TailLane g;
+  const int lane = threadIdx.x & 63;
+  g.half = lane & 1;
+  g.tk = lane >> 1;
+  g.probs = probs_lds + (threadIdx.x >> 6) * 32;
+  const int t0 = p.cu_tail[b];
+  g.nt = p.cu_tail[b + 1] - t0;
+  g.row_stride = static_cast<size_t>(p.n_kv_heads) * kHeadDim;
+  g.kcol = p.tail_k + static_cast<size_t>(t0) * g.row_stride + static_cast<size_t>(kvh) * kHeadDim + 64 * g.half;
+  g.vcol = p.tail_v + static_cast<size_t>(t0) * g.row_stride + static_cast<size_t>(kvh) * kHeadDim + 2 * lane;
+  return g;
+}
+__device__ __forceinline__ void tail_request_q(const DraftMergeParams& p, const TailLane& g, int b, int h, uint4 (&q)[8]) {
+  const uint16_t* qp = p.q + (static_cast<size_t>(b) * p.n_q_heads + h) * kHeadDim + 64 * g.half;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) q[i] = *reinterpret_cast<const uint4*>(qp + 8 * i);
+}
+// everything a chunk needs is requested before anything of it is consumed: one trip to memory per chunk
+// (the tails of a speculation horizon are one chunk).  Only called with tokens left (c0 < nt).
+__device__ __forceinline__ void tail_request(const TailLane& g, int c0, TailChunk& c) {
+  const int cn = min(32, g.nt - c0);
+  const uint16_t* kr = g.kcol + static_cast<size_t>(c0 + min(g.tk, cn - 1)) * g.row_stride;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) c.k[i] = *reinterpret_cast<const uint4*>(kr + 8 * i);
+#pragma unroll
+  for (int i = 0; i < 32; ++i)
+    c.v[i] = *reinterpret_cast<const uint32_t*>(g.vcol + static_cast<size_t>(c0 + min(i, cn - 1)) * g.row_stride);
+}
+struct TailAcc { float mt, a0, a1, tl; };
+__device__ __forceinline__ void tail_consume(const DraftMergeParams& p, const TailLane& g, int c0, const uint4 (&q)[8],
+                                             const TailChunk& c, TailAcc& r) {
+  const int cn = min(32, g.nt - c0);
+  float a = 0.f;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) a = dot8_bf16(c.k[i], q[i], a);
+  a += __shfl_xor(a, 1, 64);
+  const float sc = g.tk < cn ? a * p.scale_log2e : -INFINITY;
+  const float mn = fmaxf(r.mt, wave_max(sc));
+  const float alpha = exp2_diff(r.mt, mn);
+  // LDS operations of one wave are carried out in order: the reads below see this write, and the next
+  // chunk's write comes after this chunk's reads - the wave is alone on its strip, no barrier
+  if (g.half == 0) g.probs[g.tk] = exp2_diff(sc, mn);
+  __builtin_amdgcn_wave_barrier();
+  r.a0 *= alpha;
+  r.a1 *= alpha;
+  r.tl *= alpha;
+#pragma unroll
+  for (int i = 0; i < 32; ++i) {
+    const float pv = g.probs[i];               // 0 beyond the chunk's last token
+    r.a0 = fmaf(pv, bf16_lo(c.v[i]), r.a0);
+    r.a1 = fmaf(pv, bf16_hi(c.v[i]), r.a1);
+    r.tl += pv;
+  }
+  r.mt = mn;
+  __builtin_amdgcn_wave_barrier();
+}
+// chunks from c0 on, then the partial of head h
+__device__ __forceinline__ void tail_finish(const DraftMergeParams& p, const TailLane& g, int b, int h, const uint4 (&q)[8],
+                                            int c0, TailAcc r) {
+  for (; c0 < g.nt; c0 += 32) {
+    TailChunk c;
+    tail_request(g, c0, c);
+    tail_consume(p, g, c0, q, c, r);
+  }
+  const int lane = threadIdx.x & 63;
+  float* dst = const_cast<float*>(p.ws) + ((static_cast<size_t>(b) * p.n_q_heads + h) * p.ns + p.tail_slot) * kPartialFloats;
+  *reinterpret_cast<float2*>(dst + 2 + 2 * lane) = make_float2(r.a0, r.a1);
+  if (lane == 0) {
+    dst[0] = r.mt;
+    dst[1] = r.tl;
+  }
+}
+// heads hl0, hl0 + NWAVES, ... of the KV head, one after the other
+template <int NWAVES>
+__device__ __forceinline__ void tail_heads(const DraftMergeParams& p, const TailLane& g, int b, int kvh, int hl0) {
+  for (int hl = hl0; hl < p.g; hl += NWAVES) {
+    uint4 q[8];
+    if (g.nt > 0) tail_request_q(p, g, b, kvh * p.g + hl, q);
+    tail_finish(p, g, b, kvh * p.g + hl, q, 0, TailAcc{-INFINITY, 0.f, 0.f, 0.f});
+  }
+}
+template <int NWAVES>
+__device__ __forceinline__ void tail_partial(const DraftMergeParams& p, int b, int kvh, char* lds) {
+  const TailLane g = tail_lane(p, b, kvh, reinterpret_cast<float*>(lds));
+  tail_heads<NWAVES>(p, g, b, kvh, threadIdx.x >> 6);
+}
 
 // --------------------------------------------------------------------------------------------
 // bf16 rows (kept-index gather, contiguous pool, or tail)
@@ -112,6 +223,7 @@ struct DraftBf16Params {
   int n_q_heads, n_kv_heads, g;
   int split_tok, slot0, ns;
   int n_seqs, flat;     // flat: see flat_split
+  int tail;             // the launch carries the tail's workgroups (tail_partial), behind the splits' in launch order
   float scale_log2e;
 };
 
@@ -158,9 +270,23 @@ __global__ __launch_bounds__(NW * 64, 4 / NW) void draft_bf16_kernel(DraftBf16Pa
   int b, kvh, sp;
   if (p.flat) {
     kvh = blockIdx.x % p.n_kv_heads;   // heads vary fastest: the workgroups beyond the last split come last
-    if (!flat_split(GATHER ? p.cu_keep : p.cu_rows, p.n_seqs, p.split_tok, blockIdx.x / p.n_kv_heads, b, sp)) return;
+    if (!flat_split(GATHER ? p.cu_keep : p.cu_rows, p.n_seqs, p.split_tok, blockIdx.x / p.n_kv_heads, b, sp)) {
+      // the first n_seqs workgroups (per head) beyond the last split take the tails
+      if constexpr (!FUSED) {
+        if (p.tail && b < p.n_seqs) tail_partial<NW>(mp, b, kvh, ring);
+      }
+      return;
+    }
   } else {
     b = blockIdx.z; kvh = blockIdx.y; sp = blockIdx.x;
+    if constexpr (!FUSED) {
+      if (b >= p.n_seqs) {
+        // the slices behind the last sequence's: one workgroup per (sequence, KV head) for the tails
+        b = (b - p.n_seqs) * static_cast<int>(gridDim.x) + sp;
+        if (p.tail && b < p.n_seqs) tail_partial<NW>(mp, b, kvh, ring);
+        return;
+      }
+    }
   }
   const int row0 = p.cu_rows[b];
   const int count = GATHER ? (p.cu_keep[b + 1] - p.cu_keep[b]) : (p.cu_rows[b + 1] - row0);
@@ -413,6 +539,7 @@ struct DraftQuantParams {
   int n_q_heads, n_kv_heads, g, npass;
   int bps, slot0, ns;
   int n_seqs, flat;   // flat: see flat_split
+  int tail;           // the launch carries the tail's workgroups, as in DraftBf16Params
   float scale_log2e;
 };
 
@@ -503,9 +630,21 @@ __global__ __launch_bounds__(256, FUSED ? 2 : 3) void draft_quant_kernel(DraftQu
     // heads vary fastest, so the workgroups beyond the last split are the last ones dispatched
     const int ny = p.n_kv_heads * p.npass;
     yy = blockIdx.x % ny;
-    if (!flat_split(p.cu_blk, p.n_seqs, p.bps, blockIdx.x / ny, b, sp)) return;
+    if (!flat_split(p.cu_blk, p.n_seqs, p.bps, blockIdx.x / ny, b, sp)) {
+      if constexpr (!FUSED) {
+        if (p.tail && b < p.n_seqs && yy % p.npass == 0) tail_partial<4>(mp, b, yy / p.npass, ring);
+      }
+      return;
+    }
   } else {
     b = blockIdx.z; sp = blockIdx.x; yy = blockIdx.y;
+    if constexpr (!FUSED) {
+      if (b >= p.n_seqs) {
+        b = (b - p.n_seqs) * static_cast<int>(gridDim.x) + sp;
+        if (p.tail && b < p.n_seqs && yy % p.npass == 0) tail_partial<4>(mp, b, yy / p.npass, ring);
+        return;
+      }
+    }
   }
   const int kvh = yy / p.npass, pass = yy % p.npass;
   const int nb = p.cu_blk[b + 1] - p.cu_blk[b];
@@ -872,9 +1011,9 @@ __global__ __launch_bounds__(128 * kMergeGroups) void draft_merge_kernel(DraftMe
   const int d = threadIdx.x & 127, grp = threadIdx.x >> 7;
   const int n1 = p.cu_a ? ceil_div_dev(p.cu_a[b + 1] - p.cu_a[b], p.split_a) : 0;
   const int n2 = p.cu_blk ? ceil_div_dev(p.cu_blk[b + 1] - p.cu_blk[b], p.bps) : 0;
-  const int nsl = n1 + n2;
+  const int nsl = n1 + n2 + (p.tail_slot >= 0 ? 1 : 0);   // the tail's partial, when the split launch made one, comes last
   int t0 = 0, nt = 0;
-  if (p.tail_k) {
+  if (p.tail_k && p.tail_slot < 0) {
     t0 = p.cu_tail[b];
     nt = p.cu_tail[b + 1] - t0;
   }
@@ -912,7 +1051,7 @@ __global__ __launch_bounds__(128 * kMergeGroups) void draft_merge_kernel(DraftMe
     for (int i = 0; i < 8; ++i) {
       const int si = s0 + kMergeGroups * i;
       const int s = min(si, nsl - 1);
-      const float* pp = base + static_cast<size_t>(s < n1 ? s : p.s1 + (s - n1)) * kPartialFloats;
+      const float* pp = base + static_cast<size_t>(s < n1 ? s : s < n1 + n2 ? p.s1 + (s - n1) : p.tail_slot) * kPartialFloats;
       m8[i] = si < nsl ? pp[0] : -INFINITY;
       l8[i] = pp[1];
       o8[i] = pp[2 + d];
@@ -1059,9 +1198,9 @@ __device__ __forceinline__ void merge_head(const DraftMergeParams& p, int b, int
   const int half = lane & 1, tk = lane >> 1;     // this lane scores channels 64*half .. +63 of tokens tk and 32 + tk of a chunk
   const int n1 = p.cu_a ? ceil_div_dev(p.cu_a[b + 1] - p.cu_a[b], p.split_a) : 0;
   const int n2 = p.cu_blk ? ceil_div_dev(p.cu_blk[b + 1] - p.cu_blk[b], p.bps) : 0;
-  const int nsl = n1 + n2;
+  const int nsl = n1 + n2 + (p.tail_slot >= 0 ? 1 : 0);   // the tail's partial, when the split launch made one, comes last
   int t0 = 0, nt = 0;
-  if (p.tail_k) {
+  if (p.tail_k && p.tail_slot < 0) {
     t0 = p.cu_tail[b];
     nt = p.cu_tail[b + 1] - t0;
   }
@@ -1099,7 +1238,7 @@ __device__ __forceinline__ void merge_head(const DraftMergeParams& p, int b, int
     for (int i = 0; i < CHUNK; ++i) {
       const int si = s0 + i;
       const int sl = min(si, nsl - 1);
-      const float* pp = base + static_cast<size_t>(sl < n1 ? sl : p.s1 + (sl - n1)) * kPartialFloats;
+      const float* pp = base + static_cast<size_t>(sl < n1 ? sl : sl < n1 + n2 ? p.s1 + (sl - n1) : p.tail_slot) * kPartialFloats;
       m8[i] = si < nsl ? ld(pp) : -INFINITY;
       l8[i] = ld(pp + 1);
       o8[i] = ld(pp + 2 + d);
@@ -1195,6 +1334,7 @@ struct DraftPlan {
   bool flat_a, flat_b;   // launches that hold only the splits that exist (flat_split)
   bool fused;            // the split kernel's last workgroup per (sequence, KV head) merges: no merge launch
   int row_waves;         // waves per workgroup of the row kernel (4, or 2: two workgroups per compute unit)
+  bool tail_split;       // the tail is one more partial, made by extra workgroups of the first split launch (tail_partial)
   int ns;
 };
 
@@ -1261,7 +1401,11 @@ static DraftPlan make_plan(const vc_comp_kv* kv) {
   const int64_t wgs = has_a ? static_cast<int64_t>(pl.s1) * lists : static_cast<int64_t>(pl.s2) * lists * npass;
   pl.fused = has_a != has_b && lists <= vc_ctx::kDraftMaxLists && wgs <= tunable(kTunDraftFused, 64, 0, 1 << 20);
   if (pl.fused) pl.flat_a = pl.flat_b = false;   // every list needs its first workgroup, rows or not
-  pl.ns = pl.s1 + pl.s2;
+  // With a merge launch of its own, the tail is attended to beside the splits, not in the merge
+  // (its workgroups sit in grid slices behind the sequences': the grid's z extent stays below 65536)
+  pl.tail_split = !pl.fused && (has_a || has_b) && kv->tail_k != nullptr && kv->max_tail > 0 && kv->n_seqs <= 32767 &&
+                  tunable(kTunDraftTailSplit, 1, 0, 1) != 0;
+  pl.ns = pl.s1 + pl.s2 + (pl.tail_split ? 1 : 0);
   if (pl.ns == 0) pl.ns = 1;
   return pl;
 }
@@ -1386,6 +1530,7 @@ static vc_status draft_attn_impl(const char* who, vc_ctx* ctx, const vc_comp_kv*
   mp.cu_tail = kv->cu_tail;
   mp.n_q_heads = kv->n_q_heads; mp.n_kv_heads = kv->n_kv_heads; mp.g = g; mp.ns = pl.ns;
   mp.split_a = pl.split_a; mp.s1 = pl.s1; mp.bps = pl.bps;
+  mp.tail_slot = pl.tail_split ? pl.s1 + pl.s2 : -1;
   mp.scale_log2e = sl2;
   DraftFuse fz{};
   if (pl.fused && ctx->draft_counters != nullptr) {
@@ -1409,8 +1554,12 @@ static vc_status draft_attn_impl(const char* who, vc_ctx* ctx, const vc_comp_kv*
     bp.split_tok = pl.split_a; bp.slot0 = 0; bp.ns = pl.ns;
     bp.scale_log2e = sl2;
     bp.n_seqs = kv->n_seqs; bp.flat = pl.flat_a;
-    dim3 grid(pl.s1, kv->n_kv_heads, kv->n_seqs);
-    if (pl.flat_a) grid = dim3(static_cast<unsigned>(pl.s1) * kv->n_seqs * kv->n_kv_heads, 1, 1);
+    // one more workgroup per (sequence, KV head) for the tails, behind the splits' in launch order.  (Handing a
+    // list's tail to the workgroup of its last split instead, requested ahead of that workgroup's ring, was
+    // slower: the row loop lost 1.3 us to the registers held across it - 16 x 6554 kept rows, 74.8 against 73.4 us.)
+    bp.tail = pl.tail_split ? 1 : 0;
+    dim3 grid(pl.s1, kv->n_kv_heads, kv->n_seqs + (bp.tail ? ceil_div(kv->n_seqs, pl.s1) : 0));
+    if (pl.flat_a) grid = dim3(static_cast<unsigned>(pl.s1 + bp.tail) * kv->n_seqs * kv->n_kv_heads, 1, 1);
     // 32-token steps (16-token steps with 8 waves measured the same: the gather itself binds); 4 waves
     // per workgroup, or 2 so that two workgroups share a compute unit (pl.row_waves)
     if (pl.row_waves == 2) {
@@ -1433,10 +1582,11 @@ static vc_status draft_attn_impl(const char* who, vc_ctx* ctx, const vc_comp_kv*
     qp.bps = pl.bps; qp.slot0 = pl.s1; qp.ns = pl.ns;
     qp.scale_log2e = sl2;
     qp.n_seqs = kv->n_seqs; qp.flat = pl.flat_b;
+    qp.tail = pl.tail_split && pl.s1 == 0 ? 1 : 0;   // the row launch carries them when there is one
     fz.expected_mul = qp.npass;
     // flat: every sequence has at most s2 splits, all heads of a split are neighbours in the launch
-    dim3 grid(pl.s2, kv->n_kv_heads * qp.npass, kv->n_seqs);
-    if (pl.flat_b) grid = dim3(static_cast<unsigned>(pl.s2) * kv->n_seqs * kv->n_kv_heads * qp.npass, 1, 1);
+    dim3 grid(pl.s2, kv->n_kv_heads * qp.npass, kv->n_seqs + (qp.tail ? ceil_div(kv->n_seqs, pl.s2) : 0));
+    if (pl.flat_b) grid = dim3(static_cast<unsigned>(pl.s2 + qp.tail) * kv->n_seqs * kv->n_kv_heads * qp.npass, 1, 1);
     if (kv->bits == 4 && hpw == 4) launch_records<4, 4>(grid, st, qp, mp, fz);
     else if (kv->bits == 4) launch_records<4, 8>(grid, st, qp, mp, fz);
     else if (hpw == 4) launch_records<2, 4>(grid, st, qp, mp, fz);

@@ -20,12 +20,15 @@ def ctx(lib):
     c.close()
 
 
-@pytest.fixture(params=[100000, 0], ids=["finish-in-kernel", "merge-launch"])
+@pytest.fixture(params=[(100000, 1), (0, 1), (0, 0)], ids=["finish-in-kernel", "merge-launch", "merge-attends-tail"])
 def draft_finish(request, tunables):
     """Tiny single-source launches finish inside the split kernel (by default up to 64 workgroups); here
-    VC_DRAFT_FUSED makes every single-source launch do so, or none.  The draft cases run both ways."""
-    tunables.set("VC_DRAFT_FUSED", request.param)
-    return request.param
+    VC_DRAFT_FUSED makes every single-source launch do so, or none.  With a merge launch, the bf16 tail is
+    attended to by workgroups of the split launch (one more partial; the default) or by the merge itself
+    (VC_DRAFT_TAIL_SPLIT = 0).  The draft cases run all three ways."""
+    tunables.set("VC_DRAFT_FUSED", request.param[0])
+    tunables.set("VC_DRAFT_TAIL_SPLIT", request.param[1])
+    return request.param[0]
 
 
 def check_draft(lib, ctx, lay, tag, lse_tol=H.LSE_TOL, hints=None, **sel):

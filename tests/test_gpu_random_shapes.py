@@ -3,7 +3,7 @@
 records, bf16 tail or none), verify windows, launch-shape tunables and host hints, and compares the
 draft, verify and accept entry points with the oracle.  The point is the host logic that turns such a
 batch into launches - split lengths, flat and grid launches, two- and four-wave workgroups, the
-finish inside the split kernel, the one-launch accept, row blocks - at combinations no hand-written case lists."""
+finish inside the split kernel, the tail as a partial of the split launch, the one-launch accept, row blocks - at combinations no hand-written case lists."""
 import numpy as np
 import pytest
 import torch
@@ -71,6 +71,7 @@ def test_random_batch(lib, ctx, tunables, seed):
     tunables.set("VC_ACCEPT_FUSED", int(rng.integers(0, 2)))
     tunables.set("VC_DRAFT_FUSED", int(rng.choice([0, 64, 512])))
     hints = bool(rng.random() < 0.7)
+    tunables.set("VC_DRAFT_TAIL_SPLIT", int(rng.integers(0, 2)))
 
     def check(tag, hint, **sel):
         kw = H.draft_kwargs(lay, **sel)

@@ -63,10 +63,21 @@ def test_draft_workspace_grows_with_work_and_covers_every_split():
                          max_keep=1000))[1]
     assert small >= 2 * 8 * 130 * 4 and big > small and both > small
     assert small % (130 * 4) == 0
-    # the tail is attended to inside the merge kernel: it needs no partial slots
+    # a launch this small finishes inside its split kernel, tail included: the tail needs no partial slot
     tail = ws_bytes(desc(blocks=0x1000, cu_blk=0x2000, max_blk=64, tail_k=0x3000, tail_v=0x4000, cu_tail=0x5000,
                          max_tail=63))[1]
     assert tail == small
+    # with a merge launch, the tail is one more partial per (sequence, query head), made by workgroups of the
+    # split launch - unless VC_DRAFT_TAIL_SPLIT = 0 leaves it to the merge
+    big_tail = ws_bytes(desc(blocks=0x1000, cu_blk=0x2000, max_blk=1 << 16, tail_k=0x3000, tail_v=0x4000, cu_tail=0x5000,
+                             max_tail=63))[1]
+    assert big_tail == big + 2 * 8 * 130 * 4
+    try:
+        vc.vc_set_tunable("VC_DRAFT_TAIL_SPLIT", 0)
+        assert ws_bytes(desc(blocks=0x1000, cu_blk=0x2000, max_blk=1 << 16, tail_k=0x3000, tail_v=0x4000, cu_tail=0x5000,
+                             max_tail=63))[1] == big
+    finally:
+        vc.vc_set_tunable("VC_DRAFT_TAIL_SPLIT", -1)
     # the sum hint changes the chunking (load balance), never below one slot per list
     hinted = ws_bytes(desc(blocks=0x1000, cu_blk=0x2000, max_blk=1 << 16, sum_blk=1 << 16))[1]
     assert hinted >= big
