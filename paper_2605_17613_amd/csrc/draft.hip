@@ -1334,7 +1334,7 @@ struct DraftPlan {
   bool flat_a, flat_b;   // launches that hold only the splits that exist (flat_split)
   bool fused;            // the split kernel's last workgroup per (sequence, KV head) merges: no merge launch
   int row_waves;         // waves per workgroup of the row kernel (4, or 2: two workgroups per compute unit)
-  bool tail_split;       // the tail is one more partial, made by extra workgroups of the first split launch (tail_partial)
+  bool tail_split;       // the tail is one more partial, made by extra workgroups of a split launch (tail_partial)
   int ns;
 };
 
@@ -1557,7 +1557,7 @@ static vc_status draft_attn_impl(const char* who, vc_ctx* ctx, const vc_comp_kv*
     // one more workgroup per (sequence, KV head) for the tails, behind the splits' in launch order.  (Handing a
     // list's tail to the workgroup of its last split instead, requested ahead of that workgroup's ring, was
     // slower: the row loop lost 1.3 us to the registers held across it - 16 x 6554 kept rows, 74.8 against 73.4 us.)
-    bp.tail = pl.tail_split ? 1 : 0;
+    bp.tail = pl.tail_split && pl.s2 == 0 ? 1 : 0;   // (a record launch of the same call carries them instead: it hides them)
     dim3 grid(pl.s1, kv->n_kv_heads, kv->n_seqs + (bp.tail ? ceil_div(kv->n_seqs, pl.s1) : 0));
     if (pl.flat_a) grid = dim3(static_cast<unsigned>(pl.s1 + bp.tail) * kv->n_seqs * kv->n_kv_heads, 1, 1);
     // 32-token steps (16-token steps with 8 waves measured the same: the gather itself binds); 4 waves
@@ -1582,7 +1582,10 @@ static vc_status draft_attn_impl(const char* who, vc_ctx* ctx, const vc_comp_kv*
     qp.bps = pl.bps; qp.slot0 = pl.s1; qp.ns = pl.ns;
     qp.scale_log2e = sl2;
     qp.n_seqs = kv->n_seqs; qp.flat = pl.flat_b;
-    qp.tail = pl.tail_split && pl.s1 == 0 ? 1 : 0;   // the row launch carries them when there is one
+    // the tail's workgroups travel with the record launch whenever the call has one: three workgroups share a
+    // compute unit there and the launch drains over some microseconds, which hides them; the row launch, one
+    // resident round of workgroups that fill the LDS, ends 1.6 us later with them
+    qp.tail = pl.tail_split ? 1 : 0;
     fz.expected_mul = qp.npass;
     // flat: every sequence has at most s2 splits, all heads of a split are neighbours in the launch
     dim3 grid(pl.s2, kv->n_kv_heads * qp.npass, kv->n_seqs + (qp.tail ? ceil_div(kv->n_seqs, pl.s2) : 0));
