@@ -318,6 +318,13 @@ def main():
         except Exception as e:
             loop32 = {"error": f"{type(e).__name__}: {e}"}
 
+    compact = None
+    if not args.no_compressor and not args.only:
+        try:
+            compact = measure_compact_rows(vc, ctx, lay, torch, keep_out, HQ, HKV, B, keep_n, out, ws)
+        except Exception as e:
+            compact = {"error": f"{type(e).__name__}: {e}"}
+
     cpu = None
     if not args.no_cpu_baseline:
         cpu = cpu_baseline(lay, torch, np, HQ, HKV, N)
@@ -355,7 +362,7 @@ def main():
                    "step": f"keep-index + {W} draft steps x (bf16 gather, int4, int2) + verify + accept"},
         "legs": res,
         "verify_TFLOPs": res.get("verify", {}).get("TFLOPs"),
-        "roofline": roofline, "verify_series": series, "swap": swap, "compressor": comp, "layer_loop": loop32, "config0_config1": small, "config3_round": round3, "config4_ragged": ragged,
+        "roofline": roofline, "verify_series": series, "swap": swap, "compressor": comp, "layer_loop": loop32, "compact_rows": compact, "config0_config1": small, "config3_round": round3, "config4_ragged": ragged,
         "clocks_after_run": device_clocks(),
         "cpu_baseline": cpu,
     }
@@ -394,6 +401,37 @@ def measure_verify_series(vc, ctx, torch, verify, draft):
     res["after_32_int4_draft_calls_each_us"] = run(12, before=lambda: [draft() for _ in range(32)])
     res["after_5ms_idle_each_us"] = run(12, before=idle)
     return res
+
+
+def measure_compact_rows(vc, ctx, lay, torch, keep_idx, HQ, HKV, B, keep_n, out, ws, reps=40):
+    """The d1 leg's kept rows stored compactly - row r of a sequence's pool holds, for every KV head, that
+    head's r-th kept token (all heads keep the same count) - and read through the contiguous path of
+    vc_draft_attn: what a deployment that evicts the dropped tokens from HBM would hold.  Same rows, same
+    bytes as d1 without its index lists; not part of `value`."""
+    dev = lay.q.device
+    idx = keep_idx.view(B, HKV, keep_n).long() + lay.cu_ctx[:-1].view(B, 1, 1).long()       # pool rows
+    head = torch.arange(HKV, device=dev).view(1, HKV, 1)
+    ck = lay.k_full[idx, head].permute(0, 2, 1, 3).reshape(B * keep_n, HKV, 128).contiguous()
+    cv = lay.v_full[idx, head].permute(0, 2, 1, 3).reshape(B * keep_n, HKV, 128).contiguous()
+    cu = torch.arange(0, (B + 1) * keep_n, keep_n, dtype=torch.int32, device=dev)
+    kw = dict(pool_k=ck, pool_v=cv, cu_ctx=cu, max_keep=keep_n, sum_keep=keep_n * B)
+    ref = torch.empty_like(out)
+    vc.vc_draft_attn(ctx, lay.q, lay.scale, ref, n_kv_heads=HKV, workspace=ws, pool_k=lay.k_full, pool_v=lay.v_full,
+                     cu_ctx=lay.cu_ctx, keep_idx=keep_idx, cu_keep=cu, max_keep=keep_n, sum_keep=keep_n * B)
+    for _ in range(5):
+        vc.vc_draft_attn(ctx, lay.q, lay.scale, out, n_kv_heads=HKV, workspace=ws, **kw)
+    torch.cuda.synchronize()
+    same = bool(torch.equal(out.view(torch.int16), ref.view(torch.int16)))
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        vc.vc_draft_attn(ctx, lay.q, lay.scale, out, n_kv_heads=HKV, workspace=ws, **kw)
+    e1.record()
+    torch.cuda.synchronize()
+    us = e0.elapsed_time(e1) * 1e3 / reps
+    nbytes = draft_bytes(B, HQ, HKV, kept=keep_n, tail=0) - B * HKV * keep_n * 4      # no index lists
+    return {"us": us, "GBps": nbytes / us / 1e3, "frac_hbm": nbytes / us / 1e3 / HBM_PEAK_GBPS,
+            "same_bits_as_gather": same, "note": "kept rows stored compactly, contiguous path, no tail; back-to-back calls"}
 
 
 def measure_layer_loop(vc, ctx, lay, torch, HQ, HKV, N, B, layers=32, reps=3):
