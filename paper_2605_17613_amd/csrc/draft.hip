@@ -605,7 +605,9 @@ __device__ __forceinline__ void u4_to_arr(const uint4& v, uint32_t (&a)[4]) {
 //   int4: chunk 64*T + lane           <- key bytes of token 8*(n>>2) + 4*T + (n&3), chunk j
 //   int2: chunk 32*T + 2*n + m        <- key bytes of token 16*(n>>2) + 4*T + (n&3), chunk m
 //         (lane (n, j) then reads the 8 bytes at 512*T + 32*n + 8*j: a linear, conflict-free sweep)
-// (three slots at two workgroups per CU measured 2-3 % slower than two slots at three)
+// (three slots at two workgroups per CU measured 2-3 % slower than two slots at three; four slots: int4 203.5 ->
+// 206 us and int2 113 -> 125 us at 16 x 65536 tokens, and no gain for one sequence of 131072 tokens at one
+// workgroup per CU either - 2048 calls 69 -> 74 ms - so the bytes in flight are not what holds small launches back)
 constexpr int kQuantSlots = 2;
 constexpr int kQuantRingBytes = 4 * kQuantSlots * kRecordBytes;   // per workgroup of 4 waves
 
