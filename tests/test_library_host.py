@@ -72,6 +72,9 @@ def test_draft_workspace_grows_with_work_and_covers_every_split():
     big_tail = ws_bytes(desc(blocks=0x1000, cu_blk=0x2000, max_blk=1 << 16, tail_k=0x3000, tail_v=0x4000, cu_tail=0x5000,
                              max_tail=63))[1]
     assert big_tail == big + 2 * 8 * 130 * 4
+    # (its workgroups sit in grid slices behind the sequences': beyond 32767 sequences the merge keeps the tail)
+    many = dict(blocks=0x1000, cu_blk=0x2000, max_blk=64, n_seqs=40000)
+    assert ws_bytes(desc(tail_k=0x3000, tail_v=0x4000, cu_tail=0x5000, max_tail=63, **many))[1] == ws_bytes(desc(**many))[1]
     try:
         vc.vc_set_tunable("VC_DRAFT_TAIL_SPLIT", 0)
         assert ws_bytes(desc(blocks=0x1000, cu_blk=0x2000, max_blk=1 << 16, tail_k=0x3000, tail_v=0x4000, cu_tail=0x5000,
