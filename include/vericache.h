@@ -287,9 +287,9 @@ vc_status vc_accept_len(vc_ctx* ctx, const float* logits, int32_t vocab, const i
                         int32_t* argmax_ids, void* workspace, size_t workspace_bytes,
                         void* stream);
 
-/* Sampling-based acceptance (the footnote of paper section 4.1: the method "extends to
- * sampling-based decoding via standard rejection sampling"; the paper gives no further text, so
- * this is the textbook speculative-sampling rule, with every random number an input).
+/* Sampling-based acceptance (the footnote of paper section 4.1 says that the method carries over to
+ * sampled decoding through the usual rejection-sampling rule and gives no further text, so this is
+ * the textbook speculative-sampling rule, with every random number an input).
  *   p_j = softmax(target row j / T)   full-KV distribution for drafted position j
  *   q_j = softmax(draft row j / T)    the distribution drafted token t_j was sampled from
  *   position j is accepted iff u_accept[j] * q_j(t_j) < p_j(t_j); accept_len = first rejected
