@@ -375,8 +375,8 @@ vc_status vc_swap_in_rows(vc_ctx* ctx, const void* host_packed_k, const void* ho
 
 /* Kept-index lists from the compressor's dropped-index lists (section 6,
  * CompressedKV.dropped_indices): keep = [0, len_b) minus dropped, ascending.
- *   dropped  device int32: list (b, h) is dropped[(cu_drop[b]*n_kv_heads + h*nd) + i], ascending,
- *            i < nd = cu_drop[b+1]-cu_drop[b]
+ *   dropped  device int32, 16-byte aligned, cu_drop[n_seqs]*n_kv_heads entries: list (b, h) is
+ *            dropped[(cu_drop[b]*n_kv_heads + h*nd) + i], ascending, i < nd = cu_drop[b+1]-cu_drop[b]
  *   cu_ctx   device int32 [n_seqs+1]: len_b = cu_ctx[b+1]-cu_ctx[b];  max_ctx host
  *   keep_idx device int32, written in the layout vc_comp_kv.keep_idx describes
  *   cu_keep  device int32 [n_seqs+1], written: prefix sums of len_b - nd */

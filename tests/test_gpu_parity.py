@@ -307,6 +307,38 @@ def test_keep_from_dropped(lib, ctx):
     assert np.array_equal(keep.cpu().numpy(), ref_keep)
 
 
+def test_keep_from_dropped_gap_shapes(lib, ctx):
+    """The kernel writes the gaps between neighbouring dropped entries: lists with nothing dropped (one gap that
+    is the whole sequence), everything dropped, one position, long kept runs in the middle, lengths at and around
+    the 1024 gaps a workgroup takes, a different list per head."""
+    rng = np.random.default_rng(77)
+    hkv = 3
+    lens = [4096, 1, 1, 1023, 1024, 1025, 3000, 2048, 10000, 0, 517]
+    ndrop = [0, 0, 1, 1023, 1000, 1024, 1500, 2047, 9000, 0, 200]
+    lists, cu_drop = [], [0]
+    for n, nd in zip(lens, ndrop):
+        for h in range(hkv):
+            if n == 3000:        # two long kept runs: positions 100..899 and 2000..2699 are never dropped
+                pool = np.array([p for p in range(n) if not (100 <= p < 900 or 2000 <= p < 2700)])
+            else:
+                pool = np.arange(n)
+            lists.append(np.sort(rng.choice(pool, size=nd, replace=False)).astype(np.int32))
+        cu_drop.append(cu_drop[-1] + nd)
+    dropped = np.concatenate(lists) if lists else np.zeros(0, np.int32)
+    cu_ctx = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    cu_drop = np.array(cu_drop, dtype=np.int32)
+    ref_keep, ref_cu = O.keep_from_dropped(dropped, cu_drop, lens, hkv)
+    keep = torch.full((len(ref_keep) + 8,), -1, dtype=torch.int32, device=DEV)     # 8 guard entries behind the lists
+    cu = torch.full((len(lens) + 1,), -1, dtype=torch.int32, device=DEV)
+    lib.vc_keep_from_dropped(ctx, torch.from_numpy(np.concatenate([dropped, np.zeros(4, np.int32)])).to(DEV),
+                             torch.from_numpy(cu_drop).to(DEV), torch.from_numpy(cu_ctx).to(DEV), hkv, max(lens), keep, cu)
+    torch.cuda.synchronize()
+    assert np.array_equal(cu.cpu().numpy(), ref_cu)
+    got = keep.cpu().numpy()
+    assert np.array_equal(got[:len(ref_keep)], ref_keep)
+    assert (got[len(ref_keep):] == -1).all(), "stores behind the last list"
+
+
 # ------------------------------------------------------------------ swap-in
 def test_swap_in_bytes_tickets_and_wait(lib, ctx):
     n = 8 << 20
