@@ -142,6 +142,44 @@ def test_draft_ragged_mixed_batch_with_length_hints(lib, ctx, tunables, nseq):
 
 
 @pytest.mark.parametrize("bits", [4, 2])
+def test_draft_flat_launch_with_two_head_passes_and_tails(lib, ctx, tunables, bits):
+    """Sixteen query heads per KV head take two passes of the record kernel; in a flat launch of a ragged
+    batch the workgroups behind the last split attend to the tails, once per (sequence, KV head) - not once per
+    pass - and a sequence without records still gets its tail."""
+    tb = synth.tokens_per_block(bits)
+    lens = [tb * 50 + 3, tb * 2, 7, tb * 9 + 1, tb * 160]          # sequence 2 has no full block: tail only
+    lay = synth.make_layer(120 + bits, DEV, ctx_len=lens, n_q_heads=32, n_kv_heads=2, quant_bits=(bits,),
+                           tail_len=[5, 0, 0, 40, 70])
+    tunables.set("VC_DRAFT_FUSED", 0)
+    tunables.set("VC_DRAFT_MIN_BLK", 4)
+    tunables.set("VC_DRAFT_QUANT_WGS", 200)
+    outs = []
+    for flat in (1, 0):
+        tunables.set("VC_DRAFT_FLAT", flat)
+        outs.append(check_draft(lib, ctx, lay, f"int{bits}, 16 heads per KV head, flat {flat}", bits=bits, use_tail=True,
+                                hints=dict(sum_blk=int(lay.cu_blk[bits][-1]))).clone())
+    assert torch.equal(outs[0], outs[1])
+
+
+def test_draft_rows_flat_launch_sixteen_heads_with_tails(lib, ctx, tunables):
+    """The row kernel's tail workgroups with more query heads than waves: two-wave workgroups of a ragged
+    batch take eight heads of a KV head each, tails of 0, 1, 33 and 100 tokens (one and four chunks)."""
+    lens = [3000, 40, 900, 5, 260]
+    keep = [1500, 40, 0, 5, 130]
+    lay = synth.make_layer(130, DEV, ctx_len=lens, n_q_heads=16, n_kv_heads=1, keep=keep, keep_first=[8, 2, 0, 1, 4],
+                           keep_last=[16, 3, 0, 2, 8], tail_len=[33, 0, 100, 1, 64])
+    tunables.set("VC_DRAFT_FUSED", 0)
+    tunables.set("VC_DRAFT_MIN_TOK", 128)
+    tunables.set("VC_DRAFT_BF16_WGS", 64)
+    outs = []
+    for flat in (1, 0):
+        tunables.set("VC_DRAFT_FLAT", flat)
+        outs.append(check_draft(lib, ctx, lay, f"rows, 16 heads per KV head, flat {flat}", use_pool=True, use_keep=True,
+                                use_tail=True, hints=dict(sum_keep=int(lay.cu_keep[-1]))).clone())
+    assert torch.equal(outs[0], outs[1])
+
+
+@pytest.mark.parametrize("bits", [4, 2])
 def test_draft_quant_just_inside_the_fp16_range_limits(lib, ctx, bits):
     """The header's number range for block records: value scale and |value zero| up to 4094, key
     metadata times the scaled query inside fp16.  Key outlier channels x100 (key zero points of
