@@ -90,8 +90,8 @@ vc_status vc_stream_status(vc_ctx* ctx, void* stream);
 vc_status vc_time_main_kernel(vc_ctx* ctx, void* begin_event, void* end_event);
 
 /* ------------------------------------------------------------------------------------------
- * Compressed KV of one attention layer for a ragged batch (paper section 6: a compressed cache
- * is "which positions are dropped" plus "bits per element").  The drafted token of sequence b
+ * Compressed KV of one attention layer for a ragged batch (paper section 6: all the runtime needs
+ * to know of a compressed cache is its set of dropped positions and its element width).  The drafted token of sequence b
  * attends to the union of three sources, each of which may be absent or empty:
  *
  *  (1) bf16 rows of a pool, either all rows of the sequence or the rows a kept-index list names
