@@ -316,8 +316,11 @@ __global__ __launch_bounds__(NW * 64, 4 / NW) void draft_bf16_kernel(DraftBf16Pa
       qb[ks] = __builtin_bit_cast(bf16x8v, raw);
     }
   }
+
   // the query loads must have landed before the ring starts (a wait for them inside the loop
-  // would also drain the rows in flight)
+  // would also drain the rows in flight).  (Pinning them behind the ring's first requests instead, so that
+  // query and first rows are one trip to memory, measured 1.6 us slower per call at 16 x 6554 kept rows; the
+  // record kernel, below, gains a little from that order.)
 #pragma unroll
   for (int ks = 0; ks < 4; ++ks) asm volatile("" : "+v"(qb[ks]));
 
@@ -702,6 +705,13 @@ __global__ __launch_bounds__(256, FUSED ? 2 : 3) void draft_quant_kernel(DraftQu
   const int hloc = pass * HPW + hq;
   const bool head_ok = hloc < p.g;
 
+  // the ring's first records are requested before the query is even loaded: the wait for the query (which the
+  // conversions below need) then covers them too - one trip to memory before the loop, not two in a row
+  // (0.3 - 0.6 us per call at 16 x 65536 tokens)
+#pragma unroll
+  for (int i = 0; i < kQuantSlots; ++i)
+    if (i < nrec) request(i);
+
   // query as B operand of the score product: channels 32j .. 32j+31 in natural fp16 pairs, with the
   // softmax scale, log2(e) and the 1/f of the code field each channel meets folded in
   uint32_t qn[16];
@@ -746,13 +756,10 @@ __global__ __launch_bounds__(256, FUSED ? 2 : 3) void draft_quant_kernel(DraftQu
 #pragma unroll
   for (int i = 0; i < 16; ++i) qnf[i] = as_u32(as_half2(qn[i]) * as_half2(finv[i & 3]));
 
-  // the query loads above must have landed before the ring starts: a wait for them inside the
-  // loop would also drain the records in flight
+  // the query must be complete before the loop: a wait for its loads inside the loop would also drain
+  // the records in flight at every step
 #pragma unroll
   for (int i = 0; i < 16; ++i) asm volatile("" : "+v"(qn[i]));
-#pragma unroll
-  for (int i = 0; i < kQuantSlots; ++i)
-    if (i < nrec) request(i);
 
   for (int it = 0; it < nrec; ++it) {
     // this record has landed once only the younger requests are outstanding
