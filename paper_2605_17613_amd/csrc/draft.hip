@@ -528,7 +528,7 @@ __global__ __launch_bounds__(NW * 64, 4 / NW) void draft_bf16_kernel(DraftBf16Pa
 //   probabilities serves all groups and each output tile picks the slot of its own group.
 //   The zero points never touch the codes: the key zero is one extra product whose A operand is
 //   the zero points themselves in every row (sum_d zK[d]*q[d], the same for every token of the
-//   block), the value zero a product of an all-ones A operand with p[t]*zV[t].
+//   block), the value zero a product of a constant A operand with p[t]*zV[t].
 //   Codes reach the matrix core as the fp16 subnormals 2^-24 * f * code that their masked bit fields
 //   already are, one and per two codes (f is 1, 4, 16 or 64 depending on where the field sits in
 //   its byte).  1/f is folded into the operand on the other side of the product once, outside the
@@ -738,7 +738,8 @@ __global__ __launch_bounds__(256, FUSED ? 2 : 3) void draft_quant_kernel(DraftQu
     const float f = (BITS == 4) ? ((k & 1) ? 16.f : 1.f) : (k == 0 ? 1.f : k == 1 ? 4.f : k == 2 ? 16.f : 64.f);
     finv[k] = pack_half2(f, f);
   }
-  const uint32_t ones[4] = {0x3C003C00u, 0x3C003C00u, 0x3C003C00u, 0x3C003C00u};      // fp16 1.0
+  // (finv doubles as an A operand - the field factor of every k-slot pair, the same in every row: pair k of a
+  // probability register quadruple meets f = 1, 16, 1, 16 (int4) or 1, 4, 16, 64 (int2))
 
   // log2 of the field factor f of each probability register (token position inside its word)
   // int4: token e of a word -> pair e/2 -> f = 16 if (e/2) odd;  int2: pair r = e/2, f = 4^(r&3)
@@ -906,25 +907,20 @@ __global__ __launch_bounds__(256, FUSED ? 2 : 3) void draft_quant_kernel(DraftQu
     uint32_t pg[NKS][GPS][4];
 #pragma unroll
     for (int a = 0; a < NKS; ++a) {
-      // the probabilities with their field factor undone, as rounded to fp16: the value-zero product takes
-      // them, and so does the denominator - a product with an all-ones operand sums them over the 32
-      // tokens of the k-step for every column (16 multiply-adds per lane and record otherwise)
-      uint32_t pf[4];
-#pragma unroll
-      for (int k = 0; k < 4; ++k) {
-        const int r = (BITS == 4) ? k : (4 * a + k);
-        pf[k] = as_u32(as_half2(pb[a][k]) * as_half2(finv[(BITS == 4) ? (r & 1) : (r & 3)]));
-      }
-      lacc = mfma16(ones, pf, lacc);
+      // the denominator and the value-zero term need the probabilities with their field factor undone: both are
+      // products with a constant A operand that holds the factor of each k-slot (in every row), which sums
+      // f * (p / f) [* zV] over the 32 tokens of the k-step for every column - no multiply to undo the factor
+      // (8 per lane and record), no multiply-adds for the denominator (16)
+      lacc = mfma16(finv, pb[a], lacc);
 #pragma unroll
       for (int gi = 0; gi < GPS; ++gi) {
         uint32_t pz[4];
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
           pg[a][gi][k] = as_u32(as_half2(pb[a][k]) * as_half2(vsc[a][gi][k]));   // p * sV / f
-          pz[k] = as_u32(as_half2(pf[k]) * as_half2(vzr[a][gi][k]));             // p * zV
+          pz[k] = as_u32(as_half2(pb[a][k]) * as_half2(vzr[a][gi][k]));          // p * zV / f
         }
-        ozero[gi] = mfma16(ones, pz, ozero[gi]);           // sum_t p[t] zV[t][G]
+        ozero[gi] = mfma16(finv, pz, ozero[gi]);           // sum_t p[t] zV[t][G]
       }
     }
 #pragma unroll
@@ -956,7 +952,7 @@ __global__ __launch_bounds__(256, FUSED ? 2 : 3) void draft_quant_kernel(DraftQu
   float* st = reinterpret_cast<float*>(ring);                 // [wave][head][kPartialFloats], each wave in its own ring
   {
     float* mine = st + wave * kWaveFloats + hq * kPartialFloats;
-    // the lanes of a head agree on m_run; the all-ones product has summed l over all tokens (slots are replicas)
+    // the lanes of a head agree on m_run; the constant-operand product has summed l over all tokens (slots are replicas)
     const float lsum = lacc[0];
     if (j == 0 && slot == 0) {
       mine[0] = m_run;
