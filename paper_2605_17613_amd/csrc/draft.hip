@@ -1325,9 +1325,11 @@ __device__ __forceinline__ void merge_head(const DraftMergeParams& p, int b, int
   if (p.lse && d == 0) p.lse[static_cast<size_t>(b) * p.n_q_heads + h] = den > 0.f ? (M + log2f(den)) * kLn2 : -INFINITY;
 }
 
-__global__ __launch_bounds__(128) void draft_merge_one_kernel(DraftMergeParams p) {
-  __shared__ float probs[2][64];
-  merge_head<false, 8>(p, blockIdx.y, blockIdx.x, threadIdx.x, probs[threadIdx.x >> 6]);
+// (two heads per workgroup: 0.3 us per call faster than one at 512 heads, four slower again)
+__global__ __launch_bounds__(256) void draft_merge_one_kernel(DraftMergeParams p) {
+  __shared__ float probs[4][64];
+  const int h = 2 * blockIdx.x + (threadIdx.x >> 7);
+  if (h < p.n_q_heads) merge_head<false, 8>(p, blockIdx.y, h, threadIdx.x & 127, probs[threadIdx.x >> 6]);
 }
 
 // --------------------------------------------------------------------------------------------
@@ -1608,7 +1610,7 @@ static vc_status draft_attn_impl(const char* who, vc_ctx* ctx, const vc_comp_kv*
   if (static_cast<int64_t>(kv->n_seqs) * kv->n_q_heads < 256)
     hipLaunchKernelGGL(draft_merge_kernel<4>, dim3(kv->n_q_heads, kv->n_seqs), dim3(512), 0, st, mp);
   else
-    hipLaunchKernelGGL(draft_merge_one_kernel, dim3(kv->n_q_heads, kv->n_seqs), dim3(128), 0, st, mp);
+    hipLaunchKernelGGL(draft_merge_one_kernel, dim3((kv->n_q_heads + 1) / 2, kv->n_seqs), dim3(256), 0, st, mp);
   VC_HIP(hipGetLastError());
   return VC_OK;
 }
