@@ -83,7 +83,8 @@ __device__ __forceinline__ void load_to_lds(const uint8_t* gbase_uniform, uint32
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2 nt"
                : : "s"(lds_addr), "v"(lane_off), "s"(gbase_uniform) : "memory");
 }
-// Same, four bytes per lane: lane i's word lands at lds_addr + 4*i.
+// Same, four bytes per lane: lane i's word lands at lds_addr + 4*i.  (Default cache policy: the kept-index
+// lists it brings in measured 0.4 us per call slower with the non-temporal hint.)
 __device__ __forceinline__ void load_to_lds_b32(const int* gsrc, uint32_t lds_addr) {
   asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, off" : : "s"(lds_addr), "v"(gsrc) : "memory");
 }

@@ -1329,7 +1329,10 @@ __device__ __forceinline__ void merge_head(const DraftMergeParams& p, int b, int
 __global__ __launch_bounds__(256) void draft_merge_one_kernel(DraftMergeParams p) {
   __shared__ float probs[4][64];
   const int h = 2 * blockIdx.x + (threadIdx.x >> 7);
-  if (h < p.n_q_heads) merge_head<false, 8>(p, blockIdx.y, h, threadIdx.x & 127, probs[threadIdx.x >> 6]);
+  if (h >= p.n_q_heads) return;
+  // (a head of at most four partials asks for four at once, not eight)
+  if (p.ns <= 4) merge_head<false, 4>(p, blockIdx.y, h, threadIdx.x & 127, probs[threadIdx.x >> 6]);
+  else merge_head<false, 8>(p, blockIdx.y, h, threadIdx.x & 127, probs[threadIdx.x >> 6]);
 }
 
 // --------------------------------------------------------------------------------------------
