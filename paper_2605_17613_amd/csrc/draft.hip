@@ -327,7 +327,6 @@ __global__ __launch_bounds__(NW * 64, 4 / NW) void draft_bf16_kernel(DraftBf16Pa
   const size_t row_stride = static_cast<size_t>(p.n_kv_heads) * kHeadDim;
   const uint16_t* kbase = p.pk + static_cast<size_t>(row0) * row_stride + static_cast<size_t>(kvh) * kHeadDim;
   const uint16_t* vbase = p.pv + static_cast<size_t>(row0) * row_stride + static_cast<size_t>(kvh) * kHeadDim;
-  const uint16_t* dummy = p.q + static_cast<size_t>(b) * p.n_q_heads * kHeadDim;   // any valid 16 bytes
 
   // steps of this wave: step `it` covers tokens tok0(it) .. tok0(it) + 31 of the list
   auto tok0 = [&](int it) { return start + kRowsStep * (wave + NW * it); };
@@ -337,12 +336,13 @@ __global__ __launch_bounds__(NW * 64, 4 / NW) void draft_bf16_kernel(DraftBf16Pa
   const int ts = lane >> 4, c = lane & 15;    // direct loads: 16 lanes per row, lane c brings one 16-byte chunk
 
   auto request_idx = [&](int it) {            // kept positions of step `it` -> index stage it % 4 (one load)
+    if (it > nst) return;                     // (step nst is still requested: it keeps the wait counts below uniform)
     if constexpr (GATHER) {
       const int t = it < nst ? min(tok0(it) + (lane & (kRowsStep - 1)), end - 1) : end - 1;
       load_to_lds_b32(idx + t, idx_lds + (it & 3) * kRowsIdxStage);
     }
   };
-  auto request_rows = [&](int it) {           // rows of step `it` -> stage it % 2 (16 loads, real or dummy)
+  auto request_rows = [&](int it) {           // rows of step `it` -> stage it % 2 (16 loads); nothing past the last step
     const uint32_t stage = wave_lds + (it & 1) * kRowsStage;
     if (it < nst) {
 #pragma unroll
@@ -359,9 +359,6 @@ __global__ __launch_bounds__(NW * 64, 4 / NW) void draft_bf16_kernel(DraftBf16Pa
         load_to_lds(kbase + off, stage + i * 1024);
         load_to_lds(vbase + off, stage + kRowsStep * 256 + i * 1024);
       }
-    } else {
-#pragma unroll
-      for (int i = 0; i < 2 * NLD; ++i) load_to_lds(dummy, stage + i * 1024);
     }
   };
 
@@ -397,7 +394,11 @@ __global__ __launch_bounds__(NW * 64, 4 / NW) void draft_bf16_kernel(DraftBf16Pa
   request_rows(1);
 
   for (int it = 0; it < nst; ++it) {
-    wait_vm<kYounger>();                      // rows(it) have landed
+    // rows(it) have landed once only the younger requests are outstanding: rows(it + 1) and idx(it + 2), which
+    // exist together or (in the wave's last step) not at all - no loads are issued just to keep the count, so
+    // the last step ends without a trip to memory to wait for
+    if (it + 1 < nst) wait_vm<kYounger>();
+    else wait_vm<0>();
     const uint32_t stage = wave_lds + (it & 1) * kRowsStage;
     // ---------------- scores ----------------
     float4v sacc[NT];
@@ -464,8 +465,10 @@ __global__ __launch_bounds__(NW * 64, 4 / NW) void draft_bf16_kernel(DraftBf16Pa
     // the stage is free once those reads have returned: request the rows two steps ahead
     wait_lds_reads();
     request_idx(it + 3);
-    if constexpr (GATHER) wait_vm<kYounger>();   // idx(it + 2) has landed (younger: rows(it + 1), idx(it + 3))
-    request_rows(it + 2);
+    if (it + 2 < nst) {
+      if constexpr (GATHER) wait_vm<kYounger>();   // idx(it + 2) has landed (younger: rows(it + 1), idx(it + 3))
+      request_rows(it + 2);
+    }
   }
   wait_vm<0>();                               // nothing may land in the ring any more: it is reused below
 
